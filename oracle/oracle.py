@@ -1,0 +1,199 @@
+"""ctypes/numpy front end of the CPU oracle (mc_oracle.c).
+
+TEST INFRASTRUCTURE: imported only by tests/, the smoke check and the
+benchmark's cpu_baseline leg.  Nothing here touches the HIP library.
+
+All functions work on ONE merged group given as a flat fp32 numpy vector (the
+concatenation of the group's tensors, Section 4.1 of the paper).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mc_oracle.c")
+_LIB = os.path.join(_HERE, "libmc_oracle.so")
+
+EFSIGN, TOPK, DGC, QSGD, TERNGRAD, FP16 = 1, 2, 3, 4, 5, 6
+ALGO_NAMES = {EFSIGN: "efsign", TOPK: "topk", DGC: "dgc", QSGD: "qsgd", TERNGRAD: "terngrad", FP16: "fp16"}
+PART_EVEN_COUNT, PART_EVEN_ELEMS, PART_USER = 0, 1, 2
+HDR = 64
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc: no contraction to FMA, no fast-math."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+class _Cfg(C.Structure):
+    _fields_ = [("algo", C.c_int32), ("use_ef", C.c_int32), ("ratio_ppm", C.c_uint32),
+                ("qsgd_bits", C.c_int32), ("dgc_momentum", C.c_float), ("seed", C.c_uint64)]
+
+
+@dataclass
+class Config:
+    algo: int
+    use_ef: int = 1
+    ratio_ppm: int = 10000
+    qsgd_bits: int = 8
+    dgc_momentum: float = 0.9
+    seed: int = 0
+
+    def c(self) -> _Cfg:
+        return _Cfg(self.algo, self.use_ef, self.ratio_ppm, self.qsgd_bits, self.dgc_momentum, self.seed)
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = C.CDLL(build())
+        L.orc_philox4x32_10.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        L.orc_philox4x32_10.restype = None
+        L.orc_uniform.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint64]
+        L.orc_uniform.restype = C.c_float
+        L.orc_partition.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        L.orc_partition.restype = C.c_int
+        L.orc_topk_count.argtypes = [C.c_int64, C.c_uint32]
+        L.orc_topk_count.restype = C.c_int64
+        L.orc_payload_bytes.argtypes = [C.POINTER(_Cfg), C.c_int64]
+        L.orc_payload_bytes.restype = C.c_int64
+        L.orc_state_floats.argtypes = [C.POINTER(_Cfg), C.c_int64]
+        L.orc_state_floats.restype = C.c_int64
+        L.orc_f32_to_f16.argtypes = [C.c_void_p, C.c_void_p, C.c_int64]
+        L.orc_f16_to_f32.argtypes = [C.c_void_p, C.c_void_p, C.c_int64]
+        L.orc_compress.argtypes = [C.POINTER(_Cfg), C.c_int64, C.c_uint64, C.c_uint32, C.c_uint64,
+                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.orc_compress.restype = C.c_int
+        L.orc_decode.argtypes = [C.c_void_p, C.c_int64, C.c_void_p]
+        L.orc_decode.restype = C.c_int
+        L.orc_decompress_sum.argtypes = [C.c_int64, C.c_void_p, C.c_int32, C.c_float, C.c_void_p]
+        L.orc_decompress_sum.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def philox4x32_10(ctr: Sequence[int], key: Sequence[int]) -> np.ndarray:
+    c = np.array(ctr, dtype=np.uint32)
+    k = np.array(key, dtype=np.uint32)
+    out = np.zeros(4, dtype=np.uint32)
+    lib().orc_philox4x32_10(_ptr(c), _ptr(k), _ptr(out))
+    return out
+
+
+def uniform(seed: int, worker: int, it: int, global_index: int) -> float:
+    return float(lib().orc_uniform(seed, worker, it, global_index))
+
+
+def partition(numel: Sequence[int], y: int, policy: int = PART_EVEN_ELEMS,
+              user_bounds: Optional[Sequence[int]] = None) -> np.ndarray:
+    nm = np.ascontiguousarray(numel, dtype=np.int64)
+    ub = None if user_bounds is None else np.ascontiguousarray(user_bounds, dtype=np.int32)
+    out = np.zeros(max(y, 0) + 1, dtype=np.int32)
+    rc = lib().orc_partition(_ptr(nm), len(nm), y, policy, _ptr(ub), _ptr(out))
+    if rc:
+        raise ValueError(f"orc_partition failed: {rc}")
+    return out
+
+
+def topk_count(n: int, ppm: int) -> int:
+    return int(lib().orc_topk_count(n, ppm))
+
+
+def payload_bytes(cfg: Config, n: int) -> int:
+    c = cfg.c()
+    return int(lib().orc_payload_bytes(C.byref(c), n))
+
+
+def state_floats(cfg: Config, n: int) -> int:
+    c = cfg.c()
+    return int(lib().orc_state_floats(C.byref(c), n))
+
+
+def new_state(cfg: Config, n: int) -> np.ndarray:
+    return np.zeros(state_floats(cfg, n), dtype=np.float32)
+
+
+def compress(cfg: Config, g: np.ndarray, state: Optional[np.ndarray], *, group_off: int = 0, worker: int = 0,
+             it: int = 0, scale_in: Optional[float] = None) -> Tuple[np.ndarray, float]:
+    """Returns (payload bytes, group scalar computed by the oracle); state is updated in place."""
+    g = np.ascontiguousarray(g, dtype=np.float32)
+    n = g.size
+    if state is not None:
+        assert state.dtype == np.float32 and state.flags.c_contiguous and state.size == state_floats(cfg, n)
+    payload = np.zeros(payload_bytes(cfg, n), dtype=np.uint8)
+    c = cfg.c()
+    sin = None if scale_in is None else np.array([scale_in], dtype=np.float32)
+    sout = np.zeros(1, dtype=np.float32)
+    rc = lib().orc_compress(C.byref(c), n, group_off, worker, it, _ptr(g), _ptr(state), _ptr(payload),
+                            _ptr(sin), _ptr(sout))
+    if rc:
+        raise ValueError(f"orc_compress failed: {rc}")
+    return payload, float(sout[0])
+
+
+def decode(payload: np.ndarray, n: int) -> np.ndarray:
+    d = np.zeros(n, dtype=np.float32)
+    rc = lib().orc_decode(_ptr(payload), n, _ptr(d))
+    if rc:
+        raise ValueError(f"orc_decode failed: {rc}")
+    return d
+
+
+def decompress_sum(payloads: List[np.ndarray], n: int, alpha: float = 1.0) -> np.ndarray:
+    arr = (C.c_void_p * len(payloads))(*[p.ctypes.data for p in payloads])
+    out = np.zeros(n, dtype=np.float32)
+    rc = lib().orc_decompress_sum(n, arr, len(payloads), alpha, _ptr(out))
+    if rc:
+        raise ValueError(f"orc_decompress_sum failed: {rc}")
+    return out
+
+
+def f32_to_f16_bits(x: np.ndarray) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    h = np.zeros(x.size, dtype=np.uint16)
+    lib().orc_f32_to_f16(_ptr(x), _ptr(h), x.size)
+    return h
+
+
+def f16_bits_to_f32(h: np.ndarray) -> np.ndarray:
+    h = np.ascontiguousarray(h, dtype=np.uint16)
+    x = np.zeros(h.size, dtype=np.float32)
+    lib().orc_f16_to_f32(_ptr(h), _ptr(x), h.size)
+    return x
+
+
+# ---- payload views (layout: 64-byte header, then the body) -----------------
+def header(payload: np.ndarray) -> dict:
+    b = payload[:HDR].tobytes()
+    return {
+        "magic": int(np.frombuffer(b, np.uint32, 1, 0)[0]),
+        "algo": int(np.frombuffer(b, np.uint32, 1, 4)[0]),
+        "n": int(np.frombuffer(b, np.uint64, 1, 8)[0]),
+        "k": int(np.frombuffer(b, np.uint64, 1, 16)[0]),
+        "scale": float(np.frombuffer(b, np.float32, 1, 24)[0]),
+        "levels": int(np.frombuffer(b, np.uint32, 1, 28)[0]),
+    }
+
+
+def sparse_view(payload: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    k = header(payload)["k"]
+    idx = payload[HDR:HDR + 4 * k].view(np.uint32)
+    val = payload[HDR + 4 * k:HDR + 8 * k].view(np.float32)
+    return idx, val

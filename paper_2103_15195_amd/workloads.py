@@ -1,0 +1,185 @@
+"""Seeded synthetic gradient workloads shaped like the paper's models.
+
+This module holds ONLY input generation: tensor-shape lists of the five
+benchmark configurations and the seeded random values that fill them.  It
+contains none of the compression method's arithmetic, so both the test oracle
+and the HIP path may be fed from it without sharing any of the method's code.
+
+The paper (Section 5, "Workloads") trains ResNet50 / ResNet101 / Mask R-CNN on
+CIFAR10 / ImageNet / COCO.  Those datasets are not needed here: the hot path
+only sees gradient *tensors*, so the stand-in is a list of fp32 tensors with
+the architectures' parameter shapes (161 tensors for ResNet50 and 314 for
+ResNet101, as the caption of Figure 3 states) filled with seeded random
+values.  Tensor lists are returned in gradient-ready order, i.e. the reverse of
+forward order, which is the order wait-free back-propagation produces them in
+(Section 2.2).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List, Sequence, Tuple
+
+import numpy as np
+
+Shape = Tuple[int, ...]
+
+
+# --------------------------------------------------------------------------
+# shape lists (forward order inside the helpers; reversed on return)
+# --------------------------------------------------------------------------
+def _bn(c: int) -> List[Shape]:
+    return [(c,), (c,)]  # gamma, beta
+
+
+def mlp_shapes() -> List[Shape]:
+    """784-256-256-10 perceptron: weight and bias of three linear layers."""
+    fwd = [(784, 256), (256,), (256, 256), (256,), (256, 10), (10,)]
+    return fwd[::-1]
+
+
+def resnet20_shapes() -> List[Shape]:
+    """CIFAR ResNet-20: 3x3 stem, three stages of three basic blocks
+    (16/32/64 channels), 1x1 projection shortcut with BN on the two
+    down-sampling blocks, FC 64x10 with bias."""
+    fwd: List[Shape] = [(16, 3, 3, 3)] + _bn(16)
+    cin = 16
+    for cout in (16, 32, 64):
+        for b in range(3):
+            fwd += [(cout, cin, 3, 3)] + _bn(cout)
+            fwd += [(cout, cout, 3, 3)] + _bn(cout)
+            if b == 0 and cin != cout:
+                fwd += [(cout, cin, 1, 1)] + _bn(cout)
+            cin = cout
+    fwd += [(10, 64), (10,)]
+    return fwd[::-1]
+
+
+def _bottleneck_backbone(blocks: Sequence[int]) -> List[Shape]:
+    fwd: List[Shape] = [(64, 3, 7, 7)] + _bn(64)
+    cin = 64
+    for stage, nb in enumerate(blocks):
+        mid = 64 << stage
+        cout = mid * 4
+        for b in range(nb):
+            fwd += [(mid, cin, 1, 1)] + _bn(mid)
+            fwd += [(mid, mid, 3, 3)] + _bn(mid)
+            fwd += [(cout, mid, 1, 1)] + _bn(cout)
+            if b == 0:
+                fwd += [(cout, cin, 1, 1)] + _bn(cout)
+            cin = cout
+    return fwd
+
+
+def resnet50_shapes() -> List[Shape]:
+    """ImageNet ResNet-50 (3-4-6-3 bottlenecks) with FC 2048x1000 + bias."""
+    fwd = _bottleneck_backbone((3, 4, 6, 3)) + [(1000, 2048), (1000,)]
+    return fwd[::-1]
+
+
+def resnet101_shapes() -> List[Shape]:
+    """ImageNet ResNet-101 (3-4-23-3 bottlenecks) with FC 2048x1000 + bias."""
+    fwd = _bottleneck_backbone((3, 4, 23, 3)) + [(1000, 2048), (1000,)]
+    return fwd[::-1]
+
+
+def maskrcnn_shapes() -> List[Shape]:
+    """Mask R-CNN with a ResNet-50-FPN backbone, 91 classes: backbone (BN
+    affine parameters counted), FPN lateral 1x1 and output 3x3 256-channel
+    convolutions, RPN head, two-FC box head (12544x1024, 1024x1024) with
+    91/364-way predictors, four-conv mask head with 2x2 deconvolution and a
+    91-way 1x1 predictor."""
+    fwd = _bottleneck_backbone((3, 4, 6, 3))
+    for cin in (256, 512, 1024, 2048):          # FPN lateral
+        fwd += [(256, cin, 1, 1), (256,)]
+    for _ in range(4):                          # FPN output
+        fwd += [(256, 256, 3, 3), (256,)]
+    fwd += [(256, 256, 3, 3), (256,), (3, 256, 1, 1), (3,), (12, 256, 1, 1), (12,)]  # RPN
+    fwd += [(1024, 12544), (1024,), (1024, 1024), (1024,)]                         # box head
+    fwd += [(91, 1024), (91,), (364, 1024), (364,)]                                # box predictors
+    for _ in range(4):                          # mask head
+        fwd += [(256, 256, 3, 3), (256,)]
+    fwd += [(256, 256, 2, 2), (256,), (91, 256, 1, 1), (91,)]
+    return fwd[::-1]
+
+
+# --------------------------------------------------------------------------
+# configurations
+# --------------------------------------------------------------------------
+@dataclass(frozen=True)
+class Workload:
+    cfg: int                 # index into the benchmark configuration list
+    name: str
+    shapes: Tuple[Shape, ...]
+    dist: str                # "normal_fixed" | "normal_loguniform" | "student_t3"
+    workers: int
+    ys: Tuple[int, ...]
+
+    @property
+    def numel(self) -> np.ndarray:
+        return np.array([int(np.prod(s)) for s in self.shapes], dtype=np.int64)
+
+    @property
+    def total(self) -> int:
+        return int(self.numel.sum())
+
+
+def workload(cfg: int) -> Workload:
+    if cfg == 0:
+        return Workload(0, "mlp", tuple(mlp_shapes()), "normal_fixed", 4, (2,))
+    if cfg == 1:
+        return Workload(1, "resnet20", tuple(resnet20_shapes()), "normal_loguniform", 8, (1, 2, 4, 8, 16))
+    if cfg == 2:
+        return Workload(2, "resnet50", tuple(resnet50_shapes()), "normal_loguniform", 8, (1, 2, 3, 4))
+    if cfg == 3:
+        return Workload(3, "resnet101", tuple(resnet101_shapes()), "normal_loguniform", 16, (1, 2, 4))
+    if cfg == 4:
+        return Workload(4, "maskrcnn_r50fpn", tuple(maskrcnn_shapes()), "student_t3", 8, (1, 2, 4))
+    raise ValueError(f"unknown workload config {cfg}")
+
+
+def synthetic_workload(numel: Sequence[int], dist: str = "normal_loguniform", workers: int = 2,
+                       cfg: int = 99, name: str = "custom") -> Workload:
+    """A workload over an arbitrary list of tensor sizes (edge-case tests)."""
+    return Workload(cfg, name, tuple((int(n),) for n in numel), dist, workers, (1,))
+
+
+# --------------------------------------------------------------------------
+# values
+# --------------------------------------------------------------------------
+def tensor_std(wl: Workload) -> np.ndarray:
+    """Per-tensor standard deviation: a property of the model, shared by all
+    workers and iterations.  Fixed 0.01 for the MLP; otherwise log-uniform in
+    [1e-4, 1e-1]."""
+    n = len(wl.shapes)
+    if wl.dist == "normal_fixed":
+        return np.full(n, 0.01, dtype=np.float64)
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([0, wl.cfg, 0xFFFF])))
+    return 10.0 ** rng.uniform(-4.0, -1.0, size=n)
+
+
+def gradients(wl: Workload, worker: int, it: int, shared_fraction: float = 0.0) -> List[np.ndarray]:
+    """One worker's fp32 gradient tensors (flattened, list order = wl.shapes).
+
+    Workers are independent by default; with shared_fraction = f the value is
+    sqrt(f) * common + sqrt(1 - f) * private so that large entries overlap
+    between workers (exercises index collisions in the sparse decompress)."""
+    std = tensor_std(wl)
+    numel = wl.numel
+
+    def draw(seed_words) -> List[np.ndarray]:
+        rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence(seed_words)))
+        out = []
+        for t, n in enumerate(numel):
+            if wl.dist == "student_t3":
+                x = rng.standard_t(3.0, size=int(n))
+            else:
+                x = rng.standard_normal(size=int(n))
+            out.append(x * std[t])
+        return out
+
+    private = draw([0, wl.cfg, worker, it])
+    if shared_fraction > 0.0:
+        common = draw([0, wl.cfg, 0xC0FFEE, it])
+        a, b = np.sqrt(shared_fraction), np.sqrt(1.0 - shared_fraction)
+        private = [a * c + b * p for c, p in zip(common, private)]
+    return [x.astype(np.float32) for x in private]
