@@ -1,0 +1,184 @@
+/*
+ * mergecomp.h -- C ABI of the MI355X (gfx950) MergeComp hot path.
+ *
+ * The library implements the two per-group steps of the paper's Algorithm 1,
+ *     delta = C(g)                      -> mc_compress
+ *     g~    = aggregate(C^-1(Delta))    -> mc_decompress_sum
+ * for a model whose N gradient tensors have been partitioned into y contiguous
+ * groups (Section 4.1: tensors of a group are merged and compressed together in
+ * one compression operation; Section 4.3: a partition X_y = {x_1..x_y}), plus
+ * the partition helper itself (mc_partition).
+ *
+ * Conventions
+ *   - "host" / "device" is stated for every pointer.  The library never takes
+ *     ownership of a caller buffer.  It owns only the context (small device
+ *     tables and scratch allocated in mc_ctx_create, freed in mc_ctx_destroy).
+ *   - mc_compress / mc_decompress_sum only enqueue kernels on the caller's HIP
+ *     stream (void* = hipStream_t, NULL = the default stream).  They allocate
+ *     nothing, never synchronise the host with the device and read nothing
+ *     back.  All calls that use one context must be issued in stream order
+ *     (one stream, or streams the caller has ordered with events): the context
+ *     scratch and its cached pointer tables are shared between calls.
+ *   - A group is addressed as the flat fp32 vector obtained by concatenating
+ *     its tensors in list order, each tensor contiguous; nothing is copied to
+ *     build it, kernels walk a segment table.  Flat index i of group j has the
+ *     model-global index  (elements of groups 0..j-1) + i.
+ *   - fp32 element arithmetic is IEEE binary32, round-to-nearest-even, without
+ *     fused multiply-add; group reductions are accumulated in fp64.
+ *   - Return value: 0 on success, a negative mc_status otherwise.  No call
+ *     throws or aborts.  Non-finite gradient values give unspecified codes.
+ *
+ * Payload layout (little endian), identical for every algorithm up to the body:
+ *   byte  0  uint32  magic 0x3150434D
+ *   byte  4  uint32  algorithm id (mc_algo)
+ *   byte  8  uint64  n, elements of the group
+ *   byte 16  uint64  k, kept entries (sparsifiers; 0 otherwise)
+ *   byte 24  float   group scalar: EF-Sign scale, QSGD norm, TernGrad max (0 otherwise)
+ *   byte 28  uint32  QSGD levels s (0 otherwise)
+ *   byte 32..63      zero
+ *   byte 64  body:
+ *     EF-Sign   ceil(n/32) uint32; element i <-> bit (i%32) of word i/32, 1 = non-negative; pad bits 0
+ *     TernGrad  non-zero plane ceil(n/32) uint32, then negative plane, same bit order
+ *     QSGD      n int8 codes in [-s, s], zero-padded to a multiple of 4 bytes
+ *     FP16      n binary16, zero-padded to a multiple of 4 bytes
+ *     Top-k/DGC idx[k] uint32 ascending group-relative indices, then val[k] float
+ *   Payload buffers must be 16-byte aligned.
+ */
+#ifndef MERGECOMP_H
+#define MERGECOMP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mc_ctx mc_ctx;
+
+/* Compression algorithms (Section 2.1 and Table 1 name them; the paper gives no
+ * formulas, the definitions of the cited original works are used). */
+typedef enum {
+    MC_ALGO_EFSIGN = 1,   /* 1-bit sign with per-group scale mean|p| and error feedback       */
+    MC_ALGO_TOPK = 2,     /* exact top-k of |p|, ties broken towards the lower index          */
+    MC_ALGO_DGC = 3,      /* momentum correction + exact top-k + momentum factor masking      */
+    MC_ALGO_QSGD = 4,     /* stochastic rounding to s levels of |p|/||p||_2 (Section 5: 8 bit) */
+    MC_ALGO_TERNGRAD = 5, /* ternary {-s,0,+s}, s = max|p|, Bernoulli(|p|/s)                   */
+    MC_ALGO_FP16 = 6      /* binary16 cast, round to nearest even                              */
+} mc_algo;
+
+/* Partition policies for mc_partition. */
+typedef enum {
+    MC_PART_EVEN_COUNT = 0, /* the "naive" strategy of Section 5.2: even by number of tensors   */
+    MC_PART_EVEN_ELEMS = 1, /* even by number of elements                                        */
+    MC_PART_USER = 2        /* caller-supplied boundaries (what Algorithm 2 would return)        */
+} mc_part_policy;
+
+typedef enum {
+    MC_OK = 0,
+    MC_ERR_INVALID_ARG = -1, /* null pointer, unknown algo/policy, bad config value             */
+    MC_ERR_RANGE = -2,       /* y > N, group with >= 2^32 - 2^24 elements, bounds not increasing */
+    MC_ERR_ALLOC = -3,       /* host or device allocation failed in mc_ctx_create                */
+    MC_ERR_DEVICE = -4,      /* a HIP runtime call failed                                        */
+    MC_ERR_PAYLOAD = -5      /* a payload header did not match the context (device-side check)   */
+} mc_status;
+
+typedef struct {
+    int32_t algo;        /* mc_algo                                                             */
+    int32_t use_ef;      /* 1: p = g + e and the residual e is updated; 0: p = g, state unused   */
+    uint32_t ratio_ppm;  /* sparsifiers: kept fraction in parts per million (Section 5: 10000)   */
+    int32_t qsgd_bits;   /* QSGD code width incl. sign, 2..8; levels s = 2^(bits-1) - 1          */
+    float dgc_momentum;  /* DGC momentum m                                                       */
+    uint32_t reserved;   /* must be 0                                                            */
+    uint64_t seed;       /* Philox key of the stochastic quantizers                              */
+} mc_config;
+
+/*
+ * Partition a list of N tensors into y contiguous groups (Section 4.3; Lemma 1
+ * counts exactly these partitions).  Host-only, touches no device.
+ *   numel        host, N tensor sizes in elements (>= 0)
+ *   user_bounds  host, y+1 boundaries for MC_PART_USER, otherwise ignored (may be NULL)
+ *   bounds_out   host, y+1 entries: 0 = b[0] < b[1] < ... < b[y] = N; group j = tensors [b[j], b[j+1])
+ * Errors: MC_ERR_INVALID_ARG (null, N < 1, y < 1, negative size, unknown policy),
+ *         MC_ERR_RANGE (y > N, user bounds not strictly increasing from 0 to N).
+ */
+int mc_partition(const int64_t *numel, int32_t n_tensors, int32_t y, int32_t policy,
+                 const int32_t *user_bounds, int32_t *bounds_out);
+
+/*
+ * Create a context for one (config, tensor list, partition) on the current HIP
+ * device.  All arrays are host memory and are copied.  Allocates the device
+ * segment tables and scratch for every group.
+ */
+int mc_ctx_create(mc_ctx **out, const mc_config *cfg, const int64_t *numel, int32_t n_tensors,
+                  const int32_t *bounds, int32_t y);
+int mc_ctx_destroy(mc_ctx *ctx);
+
+/* Elements n of a group / kept entries k = min(n, max(1, floor(n*ppm/1e6))) of a
+ * sparsifier (0 for other algorithms) / number of tensors of the group. */
+int64_t mc_group_numel(const mc_ctx *ctx, int32_t group);
+int64_t mc_group_k(const mc_ctx *ctx, int32_t group);
+int32_t mc_group_tensors(const mc_ctx *ctx, int32_t group);
+
+/* Exact size of a group's payload (static: k is exact, so no size read-back) and
+ * of its error-feedback memory.  0 for an invalid group. */
+size_t mc_payload_bytes(const mc_ctx *ctx, int32_t group);
+size_t mc_state_bytes(const mc_ctx *ctx, int32_t group);
+
+/*
+ * delta = C(g) for one group of one worker (Algorithm 1), fused with the
+ * error-feedback update (Section 3.2: error feedback costs another decode).
+ *   worker, iter  only select the random stream of QSGD / TernGrad
+ *   grad_ptrs     host array, one DEVICE pointer per tensor of the group (fp32, contiguous,
+ *                 4-byte aligned; 16-byte alignment enables the fastest path); read only
+ *   state         device, mc_state_bytes() bytes, 16-byte aligned, zero-filled by the caller
+ *                 before the first iteration and otherwise opaque: a 64-byte header followed by
+ *                 n floats (DGC: 2n, v then u).  For EF-Sign the floats hold p = g + e of the
+ *                 last call and the header its scale, from which the residual is re-derived;
+ *                 use mc_state_export_residual to read e.  May be NULL when use_ef = 0.
+ *   payload_out   device, mc_payload_bytes() bytes, 16-byte aligned; fully overwritten
+ */
+int mc_compress(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter,
+                const float *const *grad_ptrs, void *state, void *payload_out, void *stream);
+
+/*
+ * g~ = aggregate(C^-1(Delta)) for one group (Algorithm 1): decode the W workers'
+ * payloads and write  out_i = alpha * (((0 + d_0,i) + d_1,i) + ... + d_{W-1,i})  in fp32.
+ *   payloads   host array of W DEVICE pointers to payloads of this group
+ *   out_ptrs   host array, one DEVICE pointer per tensor of the group; fully overwritten
+ * A payload whose header does not match (magic, algorithm, n, k) is reported through
+ * mc_last_device_status; out-of-range sparse indices are ignored, never written.
+ */
+int mc_decompress_sum(mc_ctx *ctx, int32_t group, const void *const *payloads, int32_t W, float alpha,
+                      float *const *out_ptrs, void *stream);
+
+/*
+ * Convert between the opaque state and plain error-feedback memory
+ * (n floats e; DGC: v[n] then u[n]), both DEVICE pointers.  Import of a residual
+ * followed by export returns the same bits.
+ */
+int mc_state_export_residual(mc_ctx *ctx, int32_t group, const void *state, float *e_out, void *stream);
+int mc_state_import_residual(mc_ctx *ctx, int32_t group, const float *e_in, void *state, void *stream);
+
+/* Synchronises the context's device and returns MC_OK or MC_ERR_PAYLOAD if any
+ * mc_decompress_sum since the last call saw a mismatching header; clears the flag. */
+int mc_last_device_status(mc_ctx *ctx);
+
+/*
+ * Per-kernel timing with HIP events recorded on the caller's stream around each
+ * launch (off by default).  mc_profile_read synchronises the recorded events.
+ *   mc_profile_kernels   number of kernel slots
+ *   mc_profile_read      name (static string), launches and total milliseconds of slot `id`
+ */
+int mc_profile_enable(mc_ctx *ctx, int32_t on);
+int mc_profile_reset(mc_ctx *ctx);
+int32_t mc_profile_kernels(void);
+int mc_profile_read(mc_ctx *ctx, int32_t id, const char **name, int64_t *launches, double *total_ms);
+
+const char *mc_strerror(int status);
+const char *mc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MERGECOMP_H */

@@ -1,0 +1,187 @@
+"""Thin ctypes binding of libmergecomp.so (the C ABI in include/mergecomp.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels.
+PyTorch is used for device memory and streams; tensors are passed by
+``data_ptr()``.  There is no CPU fallback: if the library has not been built the
+import fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmergecomp.so")
+
+MC_ALGO_EFSIGN, MC_ALGO_TOPK, MC_ALGO_DGC, MC_ALGO_QSGD, MC_ALGO_TERNGRAD, MC_ALGO_FP16 = 1, 2, 3, 4, 5, 6
+ALGO_IDS = {"efsign": 1, "topk": 2, "dgc": 3, "qsgd": 4, "terngrad": 5, "fp16": 6}
+MC_PART_EVEN_COUNT, MC_PART_EVEN_ELEMS, MC_PART_USER = 0, 1, 2
+MC_OK, MC_ERR_INVALID_ARG, MC_ERR_RANGE, MC_ERR_ALLOC, MC_ERR_DEVICE, MC_ERR_PAYLOAD = 0, -1, -2, -3, -4, -5
+
+EXPORTS = [
+    "mc_partition", "mc_ctx_create", "mc_ctx_destroy", "mc_group_numel", "mc_group_k", "mc_group_tensors",
+    "mc_payload_bytes", "mc_state_bytes", "mc_compress", "mc_decompress_sum", "mc_state_export_residual",
+    "mc_state_import_residual", "mc_last_device_status", "mc_profile_enable", "mc_profile_reset",
+    "mc_profile_kernels", "mc_profile_read", "mc_strerror", "mc_version",
+]
+
+
+class McConfig(C.Structure):
+    _fields_ = [("algo", C.c_int32), ("use_ef", C.c_int32), ("ratio_ppm", C.c_uint32), ("qsgd_bits", C.c_int32),
+                ("dgc_momentum", C.c_float), ("reserved", C.c_uint32), ("seed", C.c_uint64)]
+
+
+class McError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {lib().mc_strerror(status).decode()} ({status})")
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                              "(or paper_2103_15195_amd/build.py) first")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, u32, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_uint64
+        L.mc_partition.argtypes = [vp, i32, i32, i32, vp, vp]
+        L.mc_ctx_create.argtypes = [C.POINTER(vp), C.POINTER(McConfig), vp, i32, vp, i32]
+        L.mc_ctx_destroy.argtypes = [vp]
+        for f in (L.mc_group_numel, L.mc_group_k):
+            f.argtypes = [vp, i32]
+            f.restype = i64
+        L.mc_group_tensors.argtypes = [vp, i32]
+        L.mc_group_tensors.restype = i32
+        for f in (L.mc_payload_bytes, L.mc_state_bytes):
+            f.argtypes = [vp, i32]
+            f.restype = C.c_size_t
+        L.mc_compress.argtypes = [vp, i32, u32, u64, vp, vp, vp, vp]
+        L.mc_decompress_sum.argtypes = [vp, i32, vp, i32, C.c_float, vp, vp]
+        L.mc_state_export_residual.argtypes = [vp, i32, vp, vp, vp]
+        L.mc_state_import_residual.argtypes = [vp, i32, vp, vp, vp]
+        L.mc_last_device_status.argtypes = [vp]
+        L.mc_profile_enable.argtypes = [vp, i32]
+        L.mc_profile_reset.argtypes = [vp]
+        L.mc_profile_kernels.argtypes = []
+        L.mc_profile_kernels.restype = i32
+        L.mc_profile_read.argtypes = [vp, i32, C.POINTER(C.c_char_p), C.POINTER(i64), C.POINTER(C.c_double)]
+        L.mc_strerror.argtypes = [C.c_int]
+        L.mc_strerror.restype = C.c_char_p
+        L.mc_version.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(status: int, what: str) -> None:
+    if status != MC_OK:
+        raise McError(status, what)
+
+
+def _ptr_array(tensors: Sequence) -> C.Array:
+    return (C.c_void_p * max(len(tensors), 1))(*[t.data_ptr() if t is not None else None for t in tensors])
+
+
+def _stream_handle(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def mc_partition(numel: Sequence[int], y: int, policy: int = MC_PART_EVEN_ELEMS,
+                 user_bounds: Optional[Sequence[int]] = None) -> List[int]:
+    """Partition N tensors into y contiguous groups; host-only (needs no GPU)."""
+    n = len(numel)
+    nm = (C.c_int64 * max(n, 1))(*[int(x) for x in numel])
+    ub = None if user_bounds is None else (C.c_int32 * len(user_bounds))(*[int(x) for x in user_bounds])
+    out = (C.c_int32 * (max(y, 0) + 1))()
+    _check(lib().mc_partition(nm, n, y, policy, ub, out), "mc_partition")
+    return list(out)
+
+
+class Context:
+    """One (config, tensor list, partition) on the current device: wraps mc_ctx."""
+
+    def __init__(self, algo, numel: Sequence[int], bounds: Sequence[int], *, use_ef: int = 1, ratio_ppm: int = 10000,
+                 qsgd_bits: int = 8, dgc_momentum: float = 0.9, seed: int = 0):
+        algo = ALGO_IDS.get(algo, algo)
+        self.algo = int(algo)
+        self.numel = [int(x) for x in numel]
+        self.bounds = [int(b) for b in bounds]
+        self.y = len(self.bounds) - 1
+        self.cfg = McConfig(self.algo, use_ef, ratio_ppm, qsgd_bits, dgc_momentum, 0, seed)
+        nm = (C.c_int64 * max(len(self.numel), 1))(*self.numel)
+        bd = (C.c_int32 * len(self.bounds))(*self.bounds)
+        self._h = C.c_void_p()
+        _check(lib().mc_ctx_create(C.byref(self._h), C.byref(self.cfg), nm, len(self.numel), bd, self.y), "mc_ctx_create")
+
+    def close(self) -> None:
+        if getattr(self, "_h", None):
+            lib().mc_ctx_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # sizes -----------------------------------------------------------------
+    def group_numel(self, group: int) -> int:
+        return int(lib().mc_group_numel(self._h, group))
+
+    def group_k(self, group: int) -> int:
+        return int(lib().mc_group_k(self._h, group))
+
+    def group_tensors(self, group: int) -> range:
+        return range(self.bounds[group], self.bounds[group + 1])
+
+    def payload_bytes(self, group: int) -> int:
+        return int(lib().mc_payload_bytes(self._h, group))
+
+    def state_bytes(self, group: int) -> int:
+        return int(lib().mc_state_bytes(self._h, group))
+
+    # the two hot calls --------------------------------------------------------
+    def mc_compress(self, group: int, worker: int, it: int, grads: Sequence, state, payload, stream=None) -> None:
+        _check(lib().mc_compress(self._h, group, worker, it, _ptr_array(grads),
+                                 None if state is None else state.data_ptr(), payload.data_ptr(),
+                                 _stream_handle(stream)), "mc_compress")
+
+    def mc_decompress_sum(self, group: int, payloads: Sequence, alpha: float, outs: Sequence, stream=None) -> None:
+        _check(lib().mc_decompress_sum(self._h, group, _ptr_array(payloads), len(payloads), alpha, _ptr_array(outs),
+                                       _stream_handle(stream)), "mc_decompress_sum")
+
+    # state helpers --------------------------------------------------------------
+    def mc_state_export_residual(self, group: int, state, e_out, stream=None) -> None:
+        _check(lib().mc_state_export_residual(self._h, group, state.data_ptr(), e_out.data_ptr(),
+                                              _stream_handle(stream)), "mc_state_export_residual")
+
+    def mc_state_import_residual(self, group: int, e_in, state, stream=None) -> None:
+        _check(lib().mc_state_import_residual(self._h, group, e_in.data_ptr(), state.data_ptr(),
+                                              _stream_handle(stream)), "mc_state_import_residual")
+
+    def mc_last_device_status(self) -> int:
+        return int(lib().mc_last_device_status(self._h))
+
+    # profiling ------------------------------------------------------------------
+    def profile_enable(self, on: bool) -> None:
+        _check(lib().mc_profile_enable(self._h, 1 if on else 0), "mc_profile_enable")
+
+    def profile_reset(self) -> None:
+        _check(lib().mc_profile_reset(self._h), "mc_profile_reset")
+
+    def profile_read(self) -> dict:
+        out = {}
+        for i in range(lib().mc_profile_kernels()):
+            name, cnt, ms = C.c_char_p(), C.c_int64(), C.c_double()
+            _check(lib().mc_profile_read(self._h, i, C.byref(name), C.byref(cnt), C.byref(ms)), "mc_profile_read")
+            if cnt.value:
+                out[name.value.decode()] = {"launches": cnt.value, "total_ms": ms.value}
+        return out

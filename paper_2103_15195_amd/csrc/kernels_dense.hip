@@ -1,0 +1,494 @@
+// Dense-code compressors (EF-Sign, QSGD, TernGrad, FP16) and their
+// decompress-and-sum, for gfx950.  One launch covers a whole merged group
+// (Section 4.1 of the paper: the tensors of a group are compressed in one
+// operation); tensors are reached through the segment table, nothing is copied.
+//
+// All kernels are HBM-streaming: each operand is touched once per pass with
+// lane-consecutive 4-byte accesses (256 contiguous bytes per wave instruction),
+// sign / ternary planes are packed with 64-lane ballots, group scalars are
+// reduced per block in LDS and combined by a one-block finalize kernel.
+#include "mc_internal.h"
+
+namespace mc {
+
+// ---------------------------------------------------------------------------
+// pointer-table upload: the per-call list of tensor addresses travels in the
+// kernel argument buffer, so no host staging memory has to outlive the call.
+// ---------------------------------------------------------------------------
+__global__ void upload_ptrs_k(PtrChunk chunk, uintptr_t *dst, uint32_t count)
+{
+    uint32_t i = threadIdx.x;
+    if (i < count) dst[i] = chunk.p[i];
+}
+
+void launch_upload_ptrs(const LaunchCtx &lc, const uintptr_t *host, uintptr_t *dev, uint32_t count)
+{
+    for (uint32_t done = 0; done < count; done += 256) {
+        PtrChunk ch;
+        uint32_t m = count - done < 256 ? count - done : 256;
+        for (uint32_t i = 0; i < 256; ++i) ch.p[i] = i < m ? host[done + i] : 0;
+        prof_begin(lc, K_UPLOAD);
+        hipLaunchKernelGGL(upload_ptrs_k, dim3(1), dim3(256), 0, lc.stream, ch, dev + done, m);
+        prof_end(lc, K_UPLOAD);
+    }
+}
+
+static inline uint32_t tiles_of(uint32_t n) { return (uint32_t)(((uint64_t)n + kTile - 1) / kTile); }
+
+// ---------------------------------------------------------------------------
+// EF-Sign, single pass.  delta = (||p||_1 / n) sign(p), p = g + e, e <- p - delta.
+// The sign bits do not depend on the scale, so the residual is not written:
+// the state keeps p and the scale of the call that produced it, and the
+// residual of the previous call is re-derived on the fly as
+//     e = p_prev - (p_prev >= 0 ? s_prev : -s_prev)
+// with the same fp32 operations an explicit update would have used.
+// Traffic per element: read g, read p_prev, write p, 1/8 byte of sign bits.
+// ---------------------------------------------------------------------------
+template <bool EF>
+__global__ __launch_bounds__(kBlock) void efsign_compress_k(GroupView g, float *st, const float *scale_prev,
+                                                            uint32_t *words, uint32_t nwords, double *partial)
+{
+    __shared__ uint64_t stage[kWavesPerBlock][kSteps];
+    __shared__ double red[kWavesPerBlock];
+    const Chunk c = my_chunk(g.n);
+    double acc = 0.0;
+    if (c.base < g.n) {
+        float p[kSteps];
+        load_seg(g, c, p);
+        if (EF) {
+            const float sp = *scale_prev;
+            float q[kSteps];
+            load_flat(st, c, g.n, q, 0.0f);
+#pragma unroll
+            for (int j = 0; j < kSteps; ++j) {
+                float d = q[j] >= 0.0f ? sp : -sp;
+                float e = q[j] - d;
+                p[j] = p[j] + e;
+            }
+            store_flat(st, c, g.n, p);
+        }
+        uint64_t b[kSteps];
+#pragma unroll
+        for (int j = 0; j < kSteps; ++j) {
+            bool valid = c.full || (c.base + 64 * j + c.lane < g.n);
+            b[j] = __builtin_amdgcn_ballot_w64(valid && p[j] >= 0.0f);
+            acc += valid ? fabs((double)p[j]) : 0.0;
+        }
+        store_plane(words, nwords, c, b, stage[threadIdx.x >> 6]);
+    }
+    double t = block_sum(acc, red);
+    if (threadIdx.x == 0) partial[blockIdx.x] = t;
+}
+
+void launch_efsign_compress(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, const float *scale_prev,
+                            uint32_t *words, uint32_t nwords, double *partial)
+{
+    if (g.n == 0) return;
+    dim3 grid(tiles_of(g.n)), block(kBlock);
+    prof_begin(lc, K_EFSIGN_COMPRESS);
+    if (ef) hipLaunchKernelGGL(efsign_compress_k<true>, grid, block, 0, lc.stream, g, state_f, scale_prev, words, nwords, partial);
+    else hipLaunchKernelGGL(efsign_compress_k<false>, grid, block, 0, lc.stream, g, state_f, scale_prev, words, nwords, partial);
+    prof_end(lc, K_EFSIGN_COMPRESS);
+}
+
+// ---------------------------------------------------------------------------
+// One block: combine the per-block partials in a fixed order (bit-reproducible
+// whatever the launch geometry of the producer was), derive the group scalar,
+// write the payload header (and, for EF-Sign, the scale kept in the state).
+//   RED_MEAN_ABS: scale = (float)(sum / n)      RED_L2: norm = (float)sqrt(sum)
+//   RED_MAX_ABS : max of the partials (exact)   mode < 0: header only
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void scalar_finalize_k(const double *partial, uint32_t nblocks, int mode, uint32_t n,
+                                                            PayloadHeader *hdr, uint32_t algo, uint64_t k, uint32_t levels,
+                                                            float *state_scale)
+{
+    __shared__ double red[kBlock];
+    double acc = 0.0;
+    if (mode >= 0) {
+        for (uint32_t i = threadIdx.x; i < nblocks; i += kBlock) {
+            double v = partial[i];
+            acc = mode == RED_MAX_ABS ? fmax(acc, v) : acc + v;
+        }
+    }
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    for (int s = kBlock / 2; s >= 1; s >>= 1) {
+        if ((int)threadIdx.x < s) {
+            double a = red[threadIdx.x], b = red[threadIdx.x + s];
+            red[threadIdx.x] = mode == RED_MAX_ABS ? fmax(a, b) : a + b;
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        double S = red[0];
+        float scale = 0.0f;
+        if (n > 0) {
+            if (mode == RED_MEAN_ABS) scale = (float)(S / (double)n);
+            else if (mode == RED_L2) scale = (float)sqrt(S);
+            else if (mode == RED_MAX_ABS) scale = (float)S;
+        }
+        PayloadHeader h;
+        h.magic = kMagic; h.algo = algo; h.n = n; h.k = k; h.scale = scale; h.levels = levels;
+        for (int i = 0; i < 8; ++i) h.pad[i] = 0;
+        *hdr = h;
+        if (state_scale) *state_scale = scale;
+    }
+}
+
+void launch_scalar_finalize(const LaunchCtx &lc, const double *partial, uint32_t nblocks, int mode, uint32_t n,
+                            PayloadHeader *hdr, uint32_t algo, uint64_t k, uint32_t levels, float *state_scale)
+{
+    prof_begin(lc, K_SCALAR_FINALIZE);
+    hipLaunchKernelGGL(scalar_finalize_k, dim3(1), dim3(kBlock), 0, lc.stream, partial, nblocks, mode, n, hdr, algo, k,
+                       levels, state_scale);
+    prof_end(lc, K_SCALAR_FINALIZE);
+}
+
+// ---------------------------------------------------------------------------
+// Pass A of the two-pass quantizers: p = g + e (kept in the state in place of
+// e), per-block partial of sum p^2 (QSGD) or max |p| (TernGrad).
+// ---------------------------------------------------------------------------
+template <bool EF, int MODE>
+__global__ __launch_bounds__(kBlock) void accum_reduce_k(GroupView g, float *st, double *partial)
+{
+    __shared__ double red[kWavesPerBlock];
+    __shared__ float redf[kWavesPerBlock];
+    const Chunk c = my_chunk(g.n);
+    double acc = 0.0;
+    float mx = 0.0f;
+    if (c.base < g.n) {
+        float p[kSteps];
+        load_seg(g, c, p);
+        if (EF) {
+            float e[kSteps];
+            load_flat(st, c, g.n, e, 0.0f);
+#pragma unroll
+            for (int j = 0; j < kSteps; ++j) p[j] = p[j] + e[j];
+            store_flat(st, c, g.n, p);
+        }
+#pragma unroll
+        for (int j = 0; j < kSteps; ++j) {   // elements past n were loaded as 0 and add nothing
+            if (MODE == RED_L2) acc += (double)p[j] * (double)p[j];
+            else mx = fmaxf(mx, fabsf(p[j]));
+        }
+    }
+    if (MODE == RED_L2) {
+        double t = block_sum(acc, red);
+        if (threadIdx.x == 0) partial[blockIdx.x] = t;
+    } else {
+        float t = block_max(mx, redf);
+        if (threadIdx.x == 0) partial[blockIdx.x] = (double)t;
+    }
+}
+
+void launch_accum_reduce(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, int mode, double *partial)
+{
+    if (g.n == 0) return;
+    dim3 grid(tiles_of(g.n)), block(kBlock);
+    prof_begin(lc, K_ACCUM_REDUCE);
+    if (mode == RED_L2) {
+        if (ef) hipLaunchKernelGGL((accum_reduce_k<true, RED_L2>), grid, block, 0, lc.stream, g, state_f, partial);
+        else hipLaunchKernelGGL((accum_reduce_k<false, RED_L2>), grid, block, 0, lc.stream, g, state_f, partial);
+    } else {
+        if (ef) hipLaunchKernelGGL((accum_reduce_k<true, RED_MAX_ABS>), grid, block, 0, lc.stream, g, state_f, partial);
+        else hipLaunchKernelGGL((accum_reduce_k<false, RED_MAX_ABS>), grid, block, 0, lc.stream, g, state_f, partial);
+    }
+    prof_end(lc, K_ACCUM_REDUCE);
+}
+
+// p of pass B: from the state (where pass A left it) or, without error feedback, the gradient itself
+template <bool EF>
+__device__ __forceinline__ void load_p(const GroupView &g, const float *st, const Chunk &c, float (&p)[kSteps])
+{
+    if (EF) load_flat(st, c, g.n, p, 0.0f);
+    else load_seg(g, c, p);
+}
+
+// Store one narrow code per element (int8 / binary16) of a chunk.  Codes are
+// staged through LDS so that each lane writes 16 contiguous bytes.
+template <typename T>
+__device__ __forceinline__ void store_codes(T *codes, uint32_t n, uint32_t n_padded, const Chunk &c,
+                                            const T (&v)[kSteps], T *stage /* kChunk entries, wave-private */)
+{
+    if (c.full) {
+#pragma unroll
+        for (int j = 0; j < kSteps; ++j) stage[64 * j + c.lane] = v[j];
+        __builtin_amdgcn_wave_barrier();
+        constexpr int kVec = (int)(kChunk * sizeof(T) / 16 / kWave);     // 16-byte vectors per lane
+        const uint4 *src = reinterpret_cast<const uint4 *>(stage);
+        uint4 *dst = reinterpret_cast<uint4 *>(codes + c.base);
+#pragma unroll
+        for (int r = 0; r < kVec; ++r) dst[r * 64 + c.lane] = src[r * 64 + c.lane];
+        __builtin_amdgcn_wave_barrier();
+    } else {
+#pragma unroll
+        for (int j = 0; j < kSteps; ++j) {
+            uint32_t i = c.base + 64 * j + c.lane;
+            if (i < n) codes[i] = v[j];
+            else if (i < n_padded) codes[i] = (T)0;      // zero padding up to a multiple of 4 bytes
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// QSGD pass B.  With a = |p| s / norm:  level = floor(a) + [u < a - floor(a)],
+// code = sgn(p) level, decode d = code * (norm / s), e <- p - d.
+// The two per-group divisions are taken in fp64 and rounded once, which equals
+// the correctly rounded fp32 quotient of two fp32 numbers.
+// ---------------------------------------------------------------------------
+template <bool EF>
+__global__ __launch_bounds__(kBlock) void qsgd_encode_k(GroupView g, float *st, const PayloadHeader *hdr, int8_t *codes,
+                                                        uint32_t levels, uint64_t seed, uint32_t worker, uint32_t iter_lo)
+{
+    __shared__ __attribute__((aligned(16))) int8_t stage[kWavesPerBlock][kChunk];
+    const Chunk c = my_chunk(g.n);
+    if (c.base >= g.n) return;
+    const float norm = hdr->scale;
+    const float sf = (float)levels;
+    const float r = norm > 0.0f ? (float)((double)sf / (double)norm) : 0.0f;
+    const float q = (float)((double)norm / (double)sf);
+    float p[kSteps];
+    load_p<EF>(g, st, c, p);
+    int8_t code[kSteps];
+    float e[kSteps];
+#pragma unroll
+    for (int j = 0; j < kSteps; ++j) {
+        uint32_t i = c.base + 64 * j + c.lane;
+        int xi = 0;
+        if (norm > 0.0f) {
+            float a = fabsf(p[j]) * r;
+            if (a < sf) {
+                float l = floorf(a);
+                float f = a - l;
+                float u = philox_uniform(seed, worker, iter_lo, g.goff + i);
+                xi = (int)l + (u < f ? 1 : 0);
+                xi = xi > (int)levels ? (int)levels : xi;
+            } else xi = (int)levels;
+        }
+        int cd = p[j] < 0.0f ? -xi : xi;
+        code[j] = (int8_t)cd;
+        float d = (float)cd * q;
+        e[j] = p[j] - d;
+    }
+    if (EF) store_flat(st, c, g.n, e);
+    store_codes<int8_t>(codes, g.n, (g.n + 3u) & ~3u, c, code, stage[threadIdx.x >> 6]);
+}
+
+void launch_qsgd_encode(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, const PayloadHeader *hdr,
+                        int8_t *codes, uint32_t levels, uint64_t seed, uint32_t worker, uint32_t iter_lo)
+{
+    if (g.n == 0) return;
+    dim3 grid(tiles_of(g.n)), block(kBlock);
+    prof_begin(lc, K_QSGD_ENCODE);
+    if (ef) hipLaunchKernelGGL(qsgd_encode_k<true>, grid, block, 0, lc.stream, g, state_f, hdr, codes, levels, seed, worker, iter_lo);
+    else hipLaunchKernelGGL(qsgd_encode_k<false>, grid, block, 0, lc.stream, g, state_f, hdr, codes, levels, seed, worker, iter_lo);
+    prof_end(lc, K_QSGD_ENCODE);
+}
+
+// ---------------------------------------------------------------------------
+// TernGrad pass B.  nz = [u * smax < |p|] (Bernoulli(|p|/smax) without a
+// division), neg = nz and p < 0, d = +-smax or 0, e <- p - d.  Two bit planes.
+// ---------------------------------------------------------------------------
+template <bool EF>
+__global__ __launch_bounds__(kBlock) void tern_encode_k(GroupView g, float *st, const PayloadHeader *hdr, uint32_t *planes,
+                                                        uint32_t nwords, uint64_t seed, uint32_t worker, uint32_t iter_lo)
+{
+    __shared__ uint64_t stage[kWavesPerBlock][kSteps];
+    const Chunk c = my_chunk(g.n);
+    if (c.base >= g.n) return;
+    const float smax = hdr->scale;
+    float p[kSteps];
+    load_p<EF>(g, st, c, p);
+    uint64_t bnz[kSteps], bng[kSteps];
+    float e[kSteps];
+#pragma unroll
+    for (int j = 0; j < kSteps; ++j) {
+        uint32_t i = c.base + 64 * j + c.lane;
+        bool valid = c.full || i < g.n;
+        float u = philox_uniform(seed, worker, iter_lo, g.goff + i);
+        bool nz = valid && (u * smax < fabsf(p[j]));
+        bool neg = nz && p[j] < 0.0f;
+        bnz[j] = __builtin_amdgcn_ballot_w64(nz);
+        bng[j] = __builtin_amdgcn_ballot_w64(neg);
+        float d = nz ? (neg ? -smax : smax) : 0.0f;
+        e[j] = p[j] - d;
+    }
+    if (EF) store_flat(st, c, g.n, e);
+    store_plane(planes, nwords, c, bnz, stage[threadIdx.x >> 6]);
+    store_plane(planes + nwords, nwords, c, bng, stage[threadIdx.x >> 6]);
+}
+
+void launch_tern_encode(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, const PayloadHeader *hdr,
+                        uint32_t *planes, uint32_t nwords, uint64_t seed, uint32_t worker, uint32_t iter_lo)
+{
+    if (g.n == 0) return;
+    dim3 grid(tiles_of(g.n)), block(kBlock);
+    prof_begin(lc, K_TERN_ENCODE);
+    if (ef) hipLaunchKernelGGL(tern_encode_k<true>, grid, block, 0, lc.stream, g, state_f, hdr, planes, nwords, seed, worker, iter_lo);
+    else hipLaunchKernelGGL(tern_encode_k<false>, grid, block, 0, lc.stream, g, state_f, hdr, planes, nwords, seed, worker, iter_lo);
+    prof_end(lc, K_TERN_ENCODE);
+}
+
+// ---------------------------------------------------------------------------
+// FP16, single pass: h = binary16(p) round-to-nearest-even, e <- p - (float)h.
+// ---------------------------------------------------------------------------
+template <bool EF>
+__global__ __launch_bounds__(kBlock) void fp16_compress_k(GroupView g, float *st, uint16_t *halves)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t stage[kWavesPerBlock][kChunk];
+    const Chunk c = my_chunk(g.n);
+    if (c.base >= g.n) return;
+    float p[kSteps];
+    load_seg(g, c, p);
+    if (EF) {
+        float e[kSteps];
+        load_flat(st, c, g.n, e, 0.0f);
+#pragma unroll
+        for (int j = 0; j < kSteps; ++j) p[j] = p[j] + e[j];
+    }
+    uint16_t h[kSteps];
+    float e[kSteps];
+#pragma unroll
+    for (int j = 0; j < kSteps; ++j) {
+        _Float16 hv = (_Float16)p[j];                 // v_cvt_f16_f32: round to nearest even, keeps subnormals
+        h[j] = __builtin_bit_cast(uint16_t, hv);
+        e[j] = p[j] - (float)hv;
+    }
+    if (EF) store_flat(st, c, g.n, e);
+    store_codes<uint16_t>(halves, g.n, (g.n + 1u) & ~1u, c, h, stage[threadIdx.x >> 6]);
+}
+
+void launch_fp16_compress(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, PayloadHeader *hdr,
+                          uint16_t *halves)
+{
+    (void)hdr;
+    if (g.n == 0) return;
+    dim3 grid(tiles_of(g.n)), block(kBlock);
+    prof_begin(lc, K_FP16_COMPRESS);
+    if (ef) hipLaunchKernelGGL(fp16_compress_k<true>, grid, block, 0, lc.stream, g, state_f, halves);
+    else hipLaunchKernelGGL(fp16_compress_k<false>, grid, block, 0, lc.stream, g, state_f, halves);
+    prof_end(lc, K_FP16_COMPRESS);
+}
+
+// ---------------------------------------------------------------------------
+// Decompress-and-sum of dense codes (Algorithm 1: g~ = aggregate(C^-1(Delta))):
+// out_i = alpha * (((0 + d_0,i) + d_1,i) + ...), workers in ascending order, one
+// pass, every payload read once, the dense result written once through the
+// segment table.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void check_header(const PayloadHeader *h, uint32_t algo, uint32_t n, int *status)
+{
+    if (h->magic != kMagic || h->algo != algo || h->n != (uint64_t)n) *status = 1;
+}
+
+template <int ALGO>
+__global__ __launch_bounds__(kBlock) void dense_decompress_k(GroupView out, PayloadPtrs pl, int W, float alpha,
+                                                             uint32_t levels, int *status)
+{
+    const Chunk c = my_chunk(out.n);
+    if (blockIdx.x == 0 && (int)threadIdx.x < W)
+        check_header(reinterpret_cast<const PayloadHeader *>(pl.p[threadIdx.x]), ALGO, out.n, status);
+    if (c.base >= out.n) return;
+    const uint32_t nwords = (out.n + 31u) >> 5;
+    float acc[kSteps];
+#pragma unroll
+    for (int j = 0; j < kSteps; ++j) acc[j] = 0.0f;
+    for (int w = 0; w < W; ++w) {
+        const uint8_t *pay = pl.p[w];
+        const float scale = reinterpret_cast<const PayloadHeader *>(pay)->scale;
+        const uint8_t *body = pay + kHeaderBytes;
+        if (ALGO == MC_ALGO_EFSIGN) {
+            // lanes 0..31 fetch the chunk's 32 words once; step j uses words 2j and 2j+1
+            const uint32_t *words = reinterpret_cast<const uint32_t *>(body);
+            uint32_t wi = (c.base >> 5) + (c.lane & 31u);
+            uint32_t mine = wi < nwords ? ld_stream(words + wi) : 0u;
+#pragma unroll
+            for (int j = 0; j < kSteps; ++j) {
+                uint32_t lo = __builtin_amdgcn_readlane(mine, 2 * j), hi = __builtin_amdgcn_readlane(mine, 2 * j + 1);
+                uint32_t word = c.lane < 32 ? lo : hi;
+                float d = ((word >> (c.lane & 31u)) & 1u) ? scale : -scale;
+                acc[j] = acc[j] + d;
+            }
+        } else if (ALGO == MC_ALGO_TERNGRAD) {
+            const uint32_t *nzp = reinterpret_cast<const uint32_t *>(body), *ngp = nzp + nwords;
+            uint32_t wi = (c.base >> 5) + (c.lane & 31u);
+            uint32_t mnz = wi < nwords ? ld_stream(nzp + wi) : 0u;
+            uint32_t mng = wi < nwords ? ld_stream(ngp + wi) : 0u;
+#pragma unroll
+            for (int j = 0; j < kSteps; ++j) {
+                uint32_t nzl = __builtin_amdgcn_readlane(mnz, 2 * j), nzh = __builtin_amdgcn_readlane(mnz, 2 * j + 1);
+                uint32_t ngl = __builtin_amdgcn_readlane(mng, 2 * j), ngh = __builtin_amdgcn_readlane(mng, 2 * j + 1);
+                uint32_t nz = ((c.lane < 32 ? nzl : nzh) >> (c.lane & 31u)) & 1u;
+                uint32_t ng = ((c.lane < 32 ? ngl : ngh) >> (c.lane & 31u)) & 1u;
+                float d = nz ? (ng ? -scale : scale) : 0.0f;
+                acc[j] = acc[j] + d;
+            }
+        } else if (ALGO == MC_ALGO_QSGD) {
+            const int8_t *codes = reinterpret_cast<const int8_t *>(body);
+            const float q = (float)((double)scale / (double)(float)levels);
+            int8_t cd[kSteps];
+            load_flat<int8_t>(codes, c, out.n, cd, (int8_t)0);
+#pragma unroll
+            for (int j = 0; j < kSteps; ++j) acc[j] = acc[j] + (float)cd[j] * q;
+        } else {   // FP16
+            const _Float16 *h = reinterpret_cast<const _Float16 *>(body);
+            _Float16 hv[kSteps];
+            load_flat<_Float16>(h, c, out.n, hv, (_Float16)0.0f);
+#pragma unroll
+            for (int j = 0; j < kSteps; ++j) acc[j] = acc[j] + (float)hv[j];
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < kSteps; ++j) acc[j] = alpha * acc[j];
+    store_seg(out, c, acc);
+}
+
+void launch_dense_decompress(const LaunchCtx &lc, int algo, const GroupView &out, const PayloadPtrs &pl, int W,
+                             float alpha, uint32_t levels, int *status)
+{
+    if (out.n == 0) return;
+    dim3 grid(tiles_of(out.n)), block(kBlock);
+    prof_begin(lc, K_DENSE_DECOMPRESS);
+    switch (algo) {
+    case MC_ALGO_EFSIGN: hipLaunchKernelGGL(dense_decompress_k<MC_ALGO_EFSIGN>, grid, block, 0, lc.stream, out, pl, W, alpha, levels, status); break;
+    case MC_ALGO_TERNGRAD: hipLaunchKernelGGL(dense_decompress_k<MC_ALGO_TERNGRAD>, grid, block, 0, lc.stream, out, pl, W, alpha, levels, status); break;
+    case MC_ALGO_QSGD: hipLaunchKernelGGL(dense_decompress_k<MC_ALGO_QSGD>, grid, block, 0, lc.stream, out, pl, W, alpha, levels, status); break;
+    default: hipLaunchKernelGGL(dense_decompress_k<MC_ALGO_FP16>, grid, block, 0, lc.stream, out, pl, W, alpha, levels, status); break;
+    }
+    prof_end(lc, K_DENSE_DECOMPRESS);
+}
+
+// ---------------------------------------------------------------------------
+// State <-> plain residual.  Only EF-Sign keeps something other than the
+// residual itself (p and the last scale); the other algorithms copy.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void state_convert_k(int algo, int to_residual, uint32_t nfloats, const uint8_t *src, uint8_t *dst)
+{
+    uint32_t i = blockIdx.x * kBlock + threadIdx.x;
+    if (to_residual) {
+        const StateHeader *h = reinterpret_cast<const StateHeader *>(src);
+        const float *f = reinterpret_cast<const float *>(src + kHeaderBytes);
+        float *e = reinterpret_cast<float *>(dst);
+        if (i < nfloats) {
+            float v = f[i];
+            if (algo == MC_ALGO_EFSIGN) { float sp = h->scale; v = v - (v >= 0.0f ? sp : -sp); }
+            e[i] = v;
+        }
+    } else {
+        const float *e = reinterpret_cast<const float *>(src);
+        float *f = reinterpret_cast<float *>(dst + kHeaderBytes);
+        if (i < nfloats) f[i] = e[i];       // EF-Sign: p = e with scale 0 re-derives exactly e
+        if (i < kHeaderBytes / 4) reinterpret_cast<uint32_t *>(dst)[i] = 0u;
+    }
+}
+
+void launch_state_convert(const LaunchCtx &lc, int algo, bool to_residual, uint32_t nfloats, const void *src, void *dst)
+{
+    uint32_t work = nfloats > 16 ? nfloats : 16;
+    prof_begin(lc, K_STATE_CONVERT);
+    hipLaunchKernelGGL(state_convert_k, dim3((work + kBlock - 1) / kBlock), dim3(kBlock), 0, lc.stream, algo,
+                       to_residual ? 1 : 0, nfloats, (const uint8_t *)src, (uint8_t *)dst);
+    prof_end(lc, K_STATE_CONVERT);
+}
+
+}  // namespace mc

@@ -1,0 +1,476 @@
+// Host side of the C ABI declared in include/mergecomp.h: partition policies,
+// the context (segment tables, scratch, pointer-table cache), argument checks
+// and the per-algorithm launch sequences.  Nothing here computes on gradient
+// values; every step of the path runs in the kernels.
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "mc_internal.h"
+
+using namespace mc;
+
+namespace {
+
+constexpr uint64_t kMaxGroupElems = (1ull << 32) - (1ull << 24);
+constexpr int kPtrSlots = 64;            // cached device copies of per-call tensor address lists
+
+struct Group {
+    int32_t t0 = 0, t1 = 0;              // tensor range [t0, t1) of the model's list
+    std::vector<int32_t> live;           // tensors of the group that hold at least one element
+    uint32_t n = 0;
+    uint64_t goff = 0;
+    uint64_t k = 0;
+    uint32_t *d_seg_off = nullptr;       // live.size() + 1 flat offsets
+};
+
+struct PtrSlot {
+    int32_t group = -1;
+    uint64_t stamp = 0;
+    std::vector<uintptr_t> host;
+    uintptr_t *dev = nullptr;
+};
+
+struct ProfEvent { int id; hipEvent_t a, b; };
+
+struct Profiler {
+    bool on = false;
+    std::vector<ProfEvent> pending;
+    std::vector<hipEvent_t> pool;
+    int64_t launches[K_COUNT] = {};
+    double ms[K_COUNT] = {};
+    hipEvent_t current = nullptr;
+};
+
+}  // namespace
+
+struct mc_ctx {
+    mc_config cfg{};
+    int device = 0;
+    std::vector<Group> groups;
+    uint32_t max_tiles = 0;
+    size_t max_live = 0;
+    double *d_partial = nullptr;
+    SparseScratch sparse{};
+    int *d_status = nullptr;
+    std::vector<PtrSlot> slots;
+    uint64_t clock = 0;
+    Profiler prof;
+};
+
+namespace mc {
+void prof_begin(const LaunchCtx &lc, int id)
+{
+    Profiler *p = static_cast<Profiler *>(lc.prof);
+    if (!p || !p->on) return;
+    (void)id;
+    hipEvent_t a = nullptr;
+    if (!p->pool.empty()) { a = p->pool.back(); p->pool.pop_back(); }
+    else if (hipEventCreate(&a) != hipSuccess) { p->current = nullptr; return; }
+    (void)hipEventRecord(a, lc.stream);
+    p->current = a;
+}
+void prof_end(const LaunchCtx &lc, int id)
+{
+    Profiler *p = static_cast<Profiler *>(lc.prof);
+    if (!p || !p->on || !p->current) return;
+    hipEvent_t b = nullptr;
+    if (!p->pool.empty()) { b = p->pool.back(); p->pool.pop_back(); }
+    else if (hipEventCreate(&b) != hipSuccess) { p->pool.push_back(p->current); p->current = nullptr; return; }
+    (void)hipEventRecord(b, lc.stream);
+    p->pending.push_back({id, p->current, b});
+    p->current = nullptr;
+}
+}  // namespace mc
+
+static const char *kKernelNames[K_COUNT] = {
+    "upload_ptrs", "efsign_compress", "scalar_finalize", "accum_reduce", "qsgd_encode", "tern_encode",
+    "fp16_compress", "dense_decompress", "sparse_accum", "select_bin", "sparse_hist", "sparse_count",
+    "sparse_scan", "sparse_emit", "sparse_decompress", "state_convert"};
+
+static void prof_drain(Profiler &p)
+{
+    for (ProfEvent &e : p.pending) {
+        float ms = 0.0f;
+        if (hipEventSynchronize(e.b) == hipSuccess && hipEventElapsedTime(&ms, e.a, e.b) == hipSuccess) {
+            p.launches[e.id] += 1;
+            p.ms[e.id] += ms;
+        }
+        p.pool.push_back(e.a);
+        p.pool.push_back(e.b);
+    }
+    p.pending.clear();
+}
+
+static uint64_t topk_count(uint64_t n, uint32_t ppm)
+{
+    if (n == 0) return 0;
+    unsigned __int128 prod = (unsigned __int128)n * ppm;
+    uint64_t k = (uint64_t)(prod / 1000000u);
+    if (k < 1) k = 1;
+    if (k > n) k = n;
+    return k;
+}
+
+static bool is_sparse(int algo) { return algo == MC_ALGO_TOPK || algo == MC_ALGO_DGC; }
+
+extern "C" {
+
+const char *mc_version(void) { return "mergecomp-gfx950 0.1"; }
+
+const char *mc_strerror(int status)
+{
+    switch (status) {
+    case MC_OK: return "ok";
+    case MC_ERR_INVALID_ARG: return "invalid argument";
+    case MC_ERR_RANGE: return "value out of range";
+    case MC_ERR_ALLOC: return "allocation failed";
+    case MC_ERR_DEVICE: return "HIP runtime error";
+    case MC_ERR_PAYLOAD: return "payload header does not match the context";
+    default: return "unknown status";
+    }
+}
+
+int mc_partition(const int64_t *numel, int32_t n_tensors, int32_t y, int32_t policy, const int32_t *user_bounds,
+                 int32_t *bounds_out)
+{
+    if (!numel || !bounds_out || n_tensors < 1 || y < 1) return MC_ERR_INVALID_ARG;
+    for (int32_t t = 0; t < n_tensors; ++t) if (numel[t] < 0) return MC_ERR_INVALID_ARG;
+    if (policy != MC_PART_EVEN_COUNT && policy != MC_PART_EVEN_ELEMS && policy != MC_PART_USER) return MC_ERR_INVALID_ARG;
+    if (policy == MC_PART_USER && !user_bounds) return MC_ERR_INVALID_ARG;
+    if (y > n_tensors) return MC_ERR_RANGE;
+    const int32_t N = n_tensors;
+    if (policy == MC_PART_EVEN_COUNT) {
+        for (int32_t j = 0; j <= y; ++j) bounds_out[j] = (int32_t)(((int64_t)j * N) / y);
+        return MC_OK;
+    }
+    if (policy == MC_PART_USER) {
+        if (user_bounds[0] != 0 || user_bounds[y] != N) return MC_ERR_RANGE;
+        for (int32_t j = 0; j < y; ++j) if (user_bounds[j + 1] <= user_bounds[j]) return MC_ERR_RANGE;
+        std::copy(user_bounds, user_bounds + y + 1, bounds_out);
+        return MC_OK;
+    }
+    // even by elements: one sweep over the prefix sums; boundary j is the first tensor
+    // count whose prefix reaches j/y of the model, kept inside [previous + 1, N - (y - j)]
+    unsigned __int128 D = 0;
+    for (int32_t t = 0; t < N; ++t) D += (uint64_t)numel[t];
+    bounds_out[0] = 0;
+    bounds_out[y] = N;
+    unsigned __int128 prefix = 0;
+    int32_t t = 0;
+    for (int32_t j = 1; j < y; ++j) {
+        while (t < N && prefix * (unsigned)y < D * (unsigned)j) prefix += (uint64_t)numel[t++];
+        int32_t b = std::min(std::max(t, bounds_out[j - 1] + 1), N - (y - j));
+        bounds_out[j] = b;
+    }
+    return MC_OK;
+}
+
+int mc_ctx_destroy(mc_ctx *ctx)
+{
+    if (!ctx) return MC_ERR_INVALID_ARG;
+    int prev = 0;
+    bool switched = hipGetDevice(&prev) == hipSuccess && prev != ctx->device && hipSetDevice(ctx->device) == hipSuccess;
+    (void)hipDeviceSynchronize();
+    prof_drain(ctx->prof);
+    for (hipEvent_t e : ctx->prof.pool) (void)hipEventDestroy(e);
+    for (Group &g : ctx->groups) if (g.d_seg_off) (void)hipFree(g.d_seg_off);
+    for (PtrSlot &s : ctx->slots) if (s.dev) (void)hipFree(s.dev);
+    if (ctx->d_partial) (void)hipFree(ctx->d_partial);
+    if (ctx->sparse.hist) (void)hipFree(ctx->sparse.hist);
+    if (ctx->sparse.sel) (void)hipFree(ctx->sparse.sel);
+    if (ctx->sparse.tile_gt) (void)hipFree(ctx->sparse.tile_gt);
+    if (ctx->sparse.tile_eq) (void)hipFree(ctx->sparse.tile_eq);
+    if (ctx->d_status) (void)hipFree(ctx->d_status);
+    if (switched) (void)hipSetDevice(prev);
+    delete ctx;
+    return MC_OK;
+}
+
+int mc_ctx_create(mc_ctx **out, const mc_config *cfg, const int64_t *numel, int32_t n_tensors, const int32_t *bounds,
+                  int32_t y)
+{
+    if (!out) return MC_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!cfg || !numel || !bounds || n_tensors < 1 || y < 1) return MC_ERR_INVALID_ARG;
+    if (cfg->algo < MC_ALGO_EFSIGN || cfg->algo > MC_ALGO_FP16 || cfg->reserved != 0) return MC_ERR_INVALID_ARG;
+    if (cfg->use_ef != 0 && cfg->use_ef != 1) return MC_ERR_INVALID_ARG;
+    if (cfg->algo == MC_ALGO_DGC && cfg->use_ef != 1) return MC_ERR_INVALID_ARG;
+    if (cfg->algo == MC_ALGO_QSGD && (cfg->qsgd_bits < 2 || cfg->qsgd_bits > 8)) return MC_ERR_INVALID_ARG;
+    if (is_sparse(cfg->algo) && (cfg->ratio_ppm < 1 || cfg->ratio_ppm > 1000000u)) return MC_ERR_INVALID_ARG;
+    if (y > n_tensors) return MC_ERR_RANGE;
+    if (bounds[0] != 0 || bounds[y] != n_tensors) return MC_ERR_RANGE;
+    for (int32_t j = 0; j < y; ++j) if (bounds[j + 1] <= bounds[j]) return MC_ERR_RANGE;
+    for (int32_t t = 0; t < n_tensors; ++t) if (numel[t] < 0) return MC_ERR_INVALID_ARG;
+    for (int32_t j = 0; j < y; ++j) {      // flat indices of a group are 32-bit
+        uint64_t n = 0;
+        for (int32_t t = bounds[j]; t < bounds[j + 1]; ++t) {
+            if ((uint64_t)numel[t] >= kMaxGroupElems) return MC_ERR_RANGE;
+            n += (uint64_t)numel[t];
+            if (n >= kMaxGroupElems) return MC_ERR_RANGE;
+        }
+    }
+
+    mc_ctx *ctx = new (std::nothrow) mc_ctx();
+    if (!ctx) return MC_ERR_ALLOC;
+    ctx->cfg = *cfg;
+    if (hipGetDevice(&ctx->device) != hipSuccess) { delete ctx; return MC_ERR_DEVICE; }
+    int rc = MC_OK;
+    try {
+        ctx->groups.resize(y);
+        uint64_t goff = 0;
+        for (int32_t j = 0; j < y && rc == MC_OK; ++j) {
+            Group &g = ctx->groups[j];
+            g.t0 = bounds[j]; g.t1 = bounds[j + 1]; g.goff = goff;
+            std::vector<uint32_t> off;
+            uint64_t n = 0;
+            for (int32_t t = g.t0; t < g.t1; ++t) {
+                if (numel[t] == 0) continue;
+                g.live.push_back(t - g.t0);
+                off.push_back((uint32_t)n);
+                n += (uint64_t)numel[t];
+            }
+            off.push_back((uint32_t)n);
+            g.n = (uint32_t)n;
+            g.k = is_sparse(cfg->algo) ? topk_count(n, cfg->ratio_ppm) : 0;
+            goff += n;
+            if (hipMalloc(&g.d_seg_off, off.size() * sizeof(uint32_t)) != hipSuccess) { rc = MC_ERR_ALLOC; break; }
+            if (hipMemcpy(g.d_seg_off, off.data(), off.size() * sizeof(uint32_t), hipMemcpyHostToDevice) != hipSuccess) { rc = MC_ERR_DEVICE; break; }
+            ctx->max_tiles = std::max<uint32_t>(ctx->max_tiles, (uint32_t)((n + kTile - 1) / kTile));
+            ctx->max_live = std::max(ctx->max_live, g.live.size());
+        }
+        const size_t tiles = std::max<size_t>(ctx->max_tiles, 1);
+        if (rc == MC_OK && hipMalloc(&ctx->d_partial, tiles * sizeof(double)) != hipSuccess) rc = MC_ERR_ALLOC;
+        if (rc == MC_OK && hipMalloc(&ctx->d_status, sizeof(int)) != hipSuccess) rc = MC_ERR_ALLOC;
+        if (rc == MC_OK && hipMemset(ctx->d_status, 0, sizeof(int)) != hipSuccess) rc = MC_ERR_DEVICE;
+        if (rc == MC_OK && is_sparse(cfg->algo)) {
+            const size_t hist_bytes = (2048 + 1024 + 1024) * sizeof(uint32_t);
+            if (hipMalloc(&ctx->sparse.hist, hist_bytes) != hipSuccess ||
+                hipMalloc(&ctx->sparse.sel, sizeof(SelectState)) != hipSuccess ||
+                hipMalloc(&ctx->sparse.tile_gt, tiles * sizeof(uint32_t)) != hipSuccess ||
+                hipMalloc(&ctx->sparse.tile_eq, tiles * sizeof(uint32_t)) != hipSuccess) rc = MC_ERR_ALLOC;
+            else if (hipMemset(ctx->sparse.hist, 0, hist_bytes) != hipSuccess ||
+                     hipMemset(ctx->sparse.sel, 0, sizeof(SelectState)) != hipSuccess) rc = MC_ERR_DEVICE;
+        }
+        if (rc == MC_OK) {
+            ctx->slots.resize(kPtrSlots);
+            for (PtrSlot &s : ctx->slots) {
+                if (hipMalloc(&s.dev, std::max<size_t>(ctx->max_live, 1) * sizeof(uintptr_t)) != hipSuccess) { rc = MC_ERR_ALLOC; break; }
+                s.host.reserve(ctx->max_live);
+            }
+        }
+        if (rc == MC_OK && hipDeviceSynchronize() != hipSuccess) rc = MC_ERR_DEVICE;
+    } catch (const std::bad_alloc &) {
+        rc = MC_ERR_ALLOC;
+    }
+    if (rc != MC_OK) { mc_ctx_destroy(ctx); return rc; }
+    *out = ctx;
+    return MC_OK;
+}
+
+static const Group *group_of(const mc_ctx *ctx, int32_t group)
+{
+    if (!ctx || group < 0 || (size_t)group >= ctx->groups.size()) return nullptr;
+    return &ctx->groups[group];
+}
+
+int64_t mc_group_numel(const mc_ctx *ctx, int32_t group) { const Group *g = group_of(ctx, group); return g ? (int64_t)g->n : -1; }
+int64_t mc_group_k(const mc_ctx *ctx, int32_t group) { const Group *g = group_of(ctx, group); return g ? (int64_t)g->k : -1; }
+int32_t mc_group_tensors(const mc_ctx *ctx, int32_t group) { const Group *g = group_of(ctx, group); return g ? g->t1 - g->t0 : -1; }
+
+size_t mc_payload_bytes(const mc_ctx *ctx, int32_t group)
+{
+    const Group *g = group_of(ctx, group);
+    if (!g) return 0;
+    const uint64_t n = g->n, words = (n + 31) / 32;
+    switch (ctx->cfg.algo) {
+    case MC_ALGO_EFSIGN: return kHeaderBytes + 4 * words;
+    case MC_ALGO_TERNGRAD: return kHeaderBytes + 8 * words;
+    case MC_ALGO_QSGD: return kHeaderBytes + (n + 3) / 4 * 4;
+    case MC_ALGO_FP16: return kHeaderBytes + (2 * n + 3) / 4 * 4;
+    default: return kHeaderBytes + 8 * g->k;
+    }
+}
+
+size_t mc_state_bytes(const mc_ctx *ctx, int32_t group)
+{
+    const Group *g = group_of(ctx, group);
+    if (!g) return 0;
+    return kHeaderBytes + sizeof(float) * (size_t)g->n * (ctx->cfg.algo == MC_ALGO_DGC ? 2 : 1);
+}
+
+// Device copy of a per-call tensor address list (only tensors that hold elements).
+// Lists seen before are served from the cache; a new list replaces the least
+// recently used slot and is uploaded through a kernel's argument buffer, in
+// stream order with the kernels that will read it.
+static const uintptr_t *device_ptrs(mc_ctx *ctx, const LaunchCtx &lc, int32_t group, const Group &g, const void *const *ptrs)
+{
+    static thread_local std::vector<uintptr_t> want;
+    want.clear();
+    for (int32_t rel : g.live) want.push_back(reinterpret_cast<uintptr_t>(ptrs[rel]));
+    PtrSlot *victim = &ctx->slots[0];
+    for (PtrSlot &s : ctx->slots) {
+        if (s.group == group && s.host.size() == want.size() &&
+            std::memcmp(s.host.data(), want.data(), want.size() * sizeof(uintptr_t)) == 0) {
+            s.stamp = ++ctx->clock;
+            return s.dev;
+        }
+        if (s.stamp < victim->stamp) victim = &s;
+    }
+    victim->group = group;
+    victim->stamp = ++ctx->clock;
+    victim->host = want;
+    if (!want.empty()) launch_upload_ptrs(lc, want.data(), victim->dev, (uint32_t)want.size());
+    return victim->dev;
+}
+
+static int check_launch() { return hipGetLastError() == hipSuccess ? MC_OK : MC_ERR_DEVICE; }
+
+int mc_compress(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter, const float *const *grad_ptrs, void *state,
+                void *payload_out, void *stream)
+{
+    const Group *gp = group_of(ctx, group);
+    if (!gp || !payload_out) return MC_ERR_INVALID_ARG;
+    const Group &G = *gp;
+    const mc_config &cfg = ctx->cfg;
+    const bool ef = cfg.use_ef != 0;
+    if (ef && !state) return MC_ERR_INVALID_ARG;
+    if (G.t1 > G.t0 && !grad_ptrs) return MC_ERR_INVALID_ARG;
+    for (int32_t rel : G.live) if (!grad_ptrs[rel] || (reinterpret_cast<uintptr_t>(grad_ptrs[rel]) & 3u)) return MC_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(payload_out) & 15u) || (reinterpret_cast<uintptr_t>(state) & 15u)) return MC_ERR_INVALID_ARG;
+
+    LaunchCtx lc{static_cast<hipStream_t>(stream), &ctx->prof};
+    (void)hipGetLastError();
+    PayloadHeader *hdr = static_cast<PayloadHeader *>(payload_out);
+    uint8_t *body = static_cast<uint8_t *>(payload_out) + kHeaderBytes;
+    StateHeader *sh = static_cast<StateHeader *>(state);
+    float *sf = state ? reinterpret_cast<float *>(static_cast<uint8_t *>(state) + kHeaderBytes) : nullptr;
+    const uint32_t n = G.n, nwords = (uint32_t)(((uint64_t)n + 31) / 32);
+    const uint32_t tiles = (uint32_t)(((uint64_t)n + kTile - 1) / kTile);
+    const uint32_t levels = cfg.algo == MC_ALGO_QSGD ? (1u << (cfg.qsgd_bits - 1)) - 1u : 0u;
+
+    if (n == 0) {   // nothing to encode: the payload is its header
+        launch_scalar_finalize(lc, ctx->d_partial, 0, -1, 0, hdr, (uint32_t)cfg.algo, 0, levels, nullptr);
+        return check_launch();
+    }
+    GroupView gv{G.d_seg_off, device_ptrs(ctx, lc, group, G, reinterpret_cast<const void *const *>(grad_ptrs)),
+                 (uint32_t)G.live.size(), n, G.goff};
+    switch (cfg.algo) {
+    case MC_ALGO_EFSIGN:
+        launch_efsign_compress(lc, gv, ef, sf, ef ? &sh->scale : nullptr, reinterpret_cast<uint32_t *>(body), nwords, ctx->d_partial);
+        launch_scalar_finalize(lc, ctx->d_partial, tiles, RED_MEAN_ABS, n, hdr, MC_ALGO_EFSIGN, 0, 0, ef ? &sh->scale : nullptr);
+        break;
+    case MC_ALGO_QSGD:
+        launch_accum_reduce(lc, gv, ef, sf, RED_L2, ctx->d_partial);
+        launch_scalar_finalize(lc, ctx->d_partial, tiles, RED_L2, n, hdr, MC_ALGO_QSGD, 0, levels, nullptr);
+        launch_qsgd_encode(lc, gv, ef, sf, hdr, reinterpret_cast<int8_t *>(body), levels, cfg.seed, worker, (uint32_t)iter);
+        break;
+    case MC_ALGO_TERNGRAD:
+        launch_accum_reduce(lc, gv, ef, sf, RED_MAX_ABS, ctx->d_partial);
+        launch_scalar_finalize(lc, ctx->d_partial, tiles, RED_MAX_ABS, n, hdr, MC_ALGO_TERNGRAD, 0, 0, nullptr);
+        launch_tern_encode(lc, gv, ef, sf, hdr, reinterpret_cast<uint32_t *>(body), nwords, cfg.seed, worker, (uint32_t)iter);
+        break;
+    case MC_ALGO_FP16:
+        launch_scalar_finalize(lc, ctx->d_partial, 0, -1, n, hdr, MC_ALGO_FP16, 0, 0, nullptr);
+        launch_fp16_compress(lc, gv, ef, sf, hdr, reinterpret_cast<uint16_t *>(body));
+        break;
+    case MC_ALGO_TOPK:
+    case MC_ALGO_DGC:
+        launch_sparse_compress(lc, cfg.algo, gv, ef, sf, cfg.dgc_momentum, G.k, hdr, ctx->sparse);
+        break;
+    default: return MC_ERR_INVALID_ARG;
+    }
+    return check_launch();
+}
+
+int mc_decompress_sum(mc_ctx *ctx, int32_t group, const void *const *payloads, int32_t W, float alpha,
+                      float *const *out_ptrs, void *stream)
+{
+    const Group *gp = group_of(ctx, group);
+    if (!gp || !payloads || W < 1) return MC_ERR_INVALID_ARG;
+    if (W > kMaxWorkers) return MC_ERR_RANGE;
+    const Group &G = *gp;
+    if (G.t1 > G.t0 && !out_ptrs) return MC_ERR_INVALID_ARG;
+    for (int32_t rel : G.live) if (!out_ptrs[rel] || (reinterpret_cast<uintptr_t>(out_ptrs[rel]) & 3u)) return MC_ERR_INVALID_ARG;
+    PayloadPtrs pl{};
+    for (int32_t w = 0; w < W; ++w) {
+        if (!payloads[w] || (reinterpret_cast<uintptr_t>(payloads[w]) & 15u)) return MC_ERR_INVALID_ARG;
+        pl.p[w] = static_cast<const uint8_t *>(payloads[w]);
+    }
+    if (G.n == 0) return MC_OK;
+    LaunchCtx lc{static_cast<hipStream_t>(stream), &ctx->prof};
+    (void)hipGetLastError();
+    GroupView gv{G.d_seg_off, device_ptrs(ctx, lc, group, G, reinterpret_cast<const void *const *>(out_ptrs)),
+                 (uint32_t)G.live.size(), G.n, G.goff};
+    const mc_config &cfg = ctx->cfg;
+    if (is_sparse(cfg.algo)) launch_sparse_decompress(lc, cfg.algo, gv, pl, W, alpha, G.k, ctx->d_status);
+    else {
+        const uint32_t levels = cfg.algo == MC_ALGO_QSGD ? (1u << (cfg.qsgd_bits - 1)) - 1u : 0u;
+        launch_dense_decompress(lc, cfg.algo, gv, pl, W, alpha, levels, ctx->d_status);
+    }
+    return check_launch();
+}
+
+static int state_convert(mc_ctx *ctx, int32_t group, const void *src, void *dst, bool to_residual, void *stream)
+{
+    const Group *g = group_of(ctx, group);
+    if (!g) return MC_ERR_INVALID_ARG;
+    const uint32_t nf = g->n * (ctx->cfg.algo == MC_ALGO_DGC ? 2u : 1u);
+    // an empty group has no residual: the plain side may be null, the opaque side never
+    if (!(to_residual ? src : dst) || (nf > 0 && !(to_residual ? dst : src))) return MC_ERR_INVALID_ARG;
+    if (nf == 0 && to_residual) return MC_OK;
+    LaunchCtx lc{static_cast<hipStream_t>(stream), &ctx->prof};
+    (void)hipGetLastError();
+    launch_state_convert(lc, ctx->cfg.algo, to_residual, nf, src, dst);
+    return check_launch();
+}
+
+int mc_state_export_residual(mc_ctx *ctx, int32_t group, const void *state, float *e_out, void *stream)
+{
+    return state_convert(ctx, group, state, e_out, true, stream);
+}
+
+int mc_state_import_residual(mc_ctx *ctx, int32_t group, const float *e_in, void *state, void *stream)
+{
+    return state_convert(ctx, group, e_in, state, false, stream);
+}
+
+int mc_last_device_status(mc_ctx *ctx)
+{
+    if (!ctx) return MC_ERR_INVALID_ARG;
+    int flag = 0;
+    if (hipDeviceSynchronize() != hipSuccess) return MC_ERR_DEVICE;
+    if (hipMemcpy(&flag, ctx->d_status, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess) return MC_ERR_DEVICE;
+    if (flag && hipMemset(ctx->d_status, 0, sizeof(int)) != hipSuccess) return MC_ERR_DEVICE;
+    return flag ? MC_ERR_PAYLOAD : MC_OK;
+}
+
+int mc_profile_enable(mc_ctx *ctx, int32_t on)
+{
+    if (!ctx) return MC_ERR_INVALID_ARG;
+    ctx->prof.on = on != 0;
+    return MC_OK;
+}
+
+int mc_profile_reset(mc_ctx *ctx)
+{
+    if (!ctx) return MC_ERR_INVALID_ARG;
+    prof_drain(ctx->prof);
+    for (int i = 0; i < K_COUNT; ++i) { ctx->prof.launches[i] = 0; ctx->prof.ms[i] = 0.0; }
+    return MC_OK;
+}
+
+int32_t mc_profile_kernels(void) { return K_COUNT; }
+
+int mc_profile_read(mc_ctx *ctx, int32_t id, const char **name, int64_t *launches, double *total_ms)
+{
+    if (!ctx || id < 0 || id >= K_COUNT) return MC_ERR_INVALID_ARG;
+    prof_drain(ctx->prof);
+    if (name) *name = kKernelNames[id];
+    if (launches) *launches = ctx->prof.launches[id];
+    if (total_ms) *total_ms = ctx->prof.ms[id];
+    return MC_OK;
+}
+
+}  // extern "C"

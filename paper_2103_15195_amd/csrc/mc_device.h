@@ -1,0 +1,233 @@
+// Device-side building blocks shared by the gfx950 kernels: the wave-chunk
+// element mapping, segment-table addressing, reductions and Philox.
+//
+// Element mapping.  A block of 256 threads (4 wavefronts of 64) owns a tile of
+// 4096 consecutive flat elements of a merged group; wavefront w owns the
+// 1024-element chunk starting at tile + 1024 w, and in step j (0..15) lane l
+// holds flat element  chunk + 64 j + l.  A wave instruction therefore touches 256
+// contiguous bytes whatever the alignment of the tensors behind the flat index,
+// and a 64-bit ballot of step j is exactly two consecutive 32-bit words of a
+// packed bit plane.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mc {
+
+constexpr int kBlock = 256;
+constexpr int kWave = 64;
+constexpr int kSteps = 16;                  // elements per lane per chunk
+constexpr int kChunk = kWave * kSteps;      // 1024 elements per wavefront
+constexpr int kTile = kBlock * kSteps;      // 4096 elements per block
+constexpr int kWavesPerBlock = kBlock / kWave;
+
+// A merged group as the kernels see it: the flat index space [0, n) laid over
+// `nseg` non-empty tensors.  seg_off[s] is the flat index of the first element
+// of tensor s (strictly increasing, seg_off[nseg] = n); ptrs[s] its address.
+struct GroupView {
+    const uint32_t *seg_off;
+    const uintptr_t *ptrs;
+    uint32_t nseg;
+    uint32_t n;
+    uint64_t goff;   // model-global flat index of element 0 (random streams only)
+};
+
+struct Chunk {
+    uint32_t base;   // flat index of the chunk's first element (wave-uniform)
+    uint32_t lane;
+    bool full;       // the whole chunk lies below n
+};
+
+__device__ __forceinline__ Chunk my_chunk(uint32_t n)
+{
+    Chunk c;
+    uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    c.base = blockIdx.x * (uint32_t)kTile + wave * (uint32_t)kChunk;
+    c.lane = threadIdx.x & 63u;
+    c.full = c.base < n && n - c.base >= (uint32_t)kChunk;
+    return c;
+}
+
+template <typename T>
+__device__ __forceinline__ T ld_stream(const T *p) { return __builtin_nontemporal_load(p); }
+template <typename T>
+__device__ __forceinline__ void st_stream(T *p, T v) { __builtin_nontemporal_store(v, p); }
+
+// largest s with seg_off[s] <= i, for i < n
+__device__ __forceinline__ uint32_t seg_find(const uint32_t *off, uint32_t nseg, uint32_t i)
+{
+    uint32_t lo = 0, hi = nseg;
+    while (hi - lo > 1) {
+        uint32_t mid = (lo + hi) >> 1;
+        if (off[mid] <= i) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// ---- flat (contiguous) buffers -------------------------------------------
+template <typename T>
+__device__ __forceinline__ void load_flat(const T *buf, const Chunk &c, uint32_t n, T (&v)[kSteps], T fill)
+{
+    const T *p = buf + c.base + c.lane;
+    if (c.full) {
+#pragma unroll
+        for (int j = 0; j < kSteps; ++j) v[j] = ld_stream(p + 64 * j);
+    } else {
+#pragma unroll
+        for (int j = 0; j < kSteps; ++j) v[j] = (c.base + 64 * j + c.lane < n) ? p[64 * j] : fill;
+    }
+}
+
+template <typename T>
+__device__ __forceinline__ void store_flat(T *buf, const Chunk &c, uint32_t n, const T (&v)[kSteps])
+{
+    T *p = buf + c.base + c.lane;
+    if (c.full) {
+#pragma unroll
+        for (int j = 0; j < kSteps; ++j) st_stream(p + 64 * j, v[j]);
+    } else {
+#pragma unroll
+        for (int j = 0; j < kSteps; ++j) if (c.base + 64 * j + c.lane < n) p[64 * j] = v[j];
+    }
+}
+
+// ---- segmented (per-tensor) buffers ------------------------------------------
+// Fast path: the chunk lies inside one tensor.  Otherwise every lane walks the
+// segment table forward from the chunk's first tensor (flat indices of a lane
+// only grow with j, so the cursor never moves back).
+__device__ __forceinline__ void load_seg(const GroupView &g, const Chunk &c, float (&v)[kSteps])
+{
+    uint32_t s = seg_find(g.seg_off, g.nseg, c.base);
+    uint32_t beg = g.seg_off[s], end = g.seg_off[s + 1];
+    if (c.full && end - c.base >= (uint32_t)kChunk) {
+        const float *p = reinterpret_cast<const float *>(g.ptrs[s]) + (c.base - beg) + c.lane;
+#pragma unroll
+        for (int j = 0; j < kSteps; ++j) v[j] = ld_stream(p + 64 * j);
+    } else {
+        const float *p = reinterpret_cast<const float *>(g.ptrs[s]);
+#pragma unroll
+        for (int j = 0; j < kSteps; ++j) {
+            uint32_t i = c.base + 64 * j + c.lane;
+            float x = 0.0f;
+            if (i < g.n) {
+                while (i >= end) { ++s; beg = end; end = g.seg_off[s + 1]; p = reinterpret_cast<const float *>(g.ptrs[s]); }
+                x = p[i - beg];
+            }
+            v[j] = x;
+        }
+    }
+}
+
+__device__ __forceinline__ void store_seg(const GroupView &g, const Chunk &c, const float (&v)[kSteps])
+{
+    uint32_t s = seg_find(g.seg_off, g.nseg, c.base);
+    uint32_t beg = g.seg_off[s], end = g.seg_off[s + 1];
+    if (c.full && end - c.base >= (uint32_t)kChunk) {
+        float *p = reinterpret_cast<float *>(g.ptrs[s]) + (c.base - beg) + c.lane;
+#pragma unroll
+        for (int j = 0; j < kSteps; ++j) st_stream(p + 64 * j, v[j]);
+    } else {
+        float *p = reinterpret_cast<float *>(g.ptrs[s]);
+#pragma unroll
+        for (int j = 0; j < kSteps; ++j) {
+            uint32_t i = c.base + 64 * j + c.lane;
+            if (i < g.n) {
+                while (i >= end) { ++s; beg = end; end = g.seg_off[s + 1]; p = reinterpret_cast<float *>(g.ptrs[s]); }
+                p[i - beg] = v[j];
+            }
+        }
+    }
+}
+
+// ---- packed bit planes -------------------------------------------------------
+// Store the 16 ballots of a chunk (32 words) to a plane of `nwords` words.
+// `stage` is 16 uint64 of LDS private to the calling wavefront.
+__device__ __forceinline__ void store_plane(uint32_t *plane, uint32_t nwords, const Chunk &c,
+                                            const uint64_t (&ballots)[kSteps], uint64_t *stage)
+{
+#pragma unroll
+    for (int j = 0; j < kSteps; ++j) if (c.lane == (uint32_t)j) stage[j] = ballots[j];
+    __builtin_amdgcn_wave_barrier();
+    if (c.lane < 32) {
+        uint32_t w = (c.base >> 5) + c.lane;
+        if (w < nwords) plane[w] = reinterpret_cast<const uint32_t *>(stage)[c.lane];
+    }
+    __builtin_amdgcn_wave_barrier();
+}
+
+// word holding the bit of flat element i, for the chunk mapping: lanes 0..31 of
+// step j read word 2j, lanes 32..63 word 2j+1 of the chunk
+__device__ __forceinline__ uint32_t plane_word(const uint32_t *plane, uint32_t i) { return plane[i >> 5]; }
+
+// ---- reductions ----------------------------------------------------------------
+__device__ __forceinline__ double wave_sum(double x)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) x += __shfl_xor(x, m, 64);
+    return x;
+}
+__device__ __forceinline__ float wave_max(float x)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) x = fmaxf(x, __shfl_xor(x, m, 64));
+    return x;
+}
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) x += __shfl_xor(x, m, 64);
+    return x;
+}
+
+// all threads of the block get the block total; fixed combination order
+__device__ __forceinline__ double block_sum(double x, double *lds4)
+{
+    x = wave_sum(x);
+    if ((threadIdx.x & 63) == 0) lds4[threadIdx.x >> 6] = x;
+    __syncthreads();
+    double t = (lds4[0] + lds4[1]) + (lds4[2] + lds4[3]);
+    __syncthreads();
+    return t;
+}
+__device__ __forceinline__ float block_max(float x, float *lds4)
+{
+    x = wave_max(x);
+    if ((threadIdx.x & 63) == 0) lds4[threadIdx.x >> 6] = x;
+    __syncthreads();
+    float t = fmaxf(fmaxf(lds4[0], lds4[1]), fmaxf(lds4[2], lds4[3]));
+    __syncthreads();
+    return t;
+}
+
+// number of set bits of a ballot below this lane
+__device__ __forceinline__ uint32_t lanes_below(uint64_t ballot)
+{
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ballot, 0u));
+}
+
+// ---- Philox-4x32-10 (Salmon et al., SC'11) --------------------------------------
+// Counter = (J lo, J hi, worker, iteration), J = global element index / 4, key =
+// seed; the element takes output word (index % 4).  Returns the top 24 bits
+// scaled to [0, 1).
+__device__ __forceinline__ float philox_uniform(uint64_t seed, uint32_t worker, uint32_t iter_lo, uint64_t gidx)
+{
+    uint64_t J = gidx >> 2;
+    uint32_t c0 = (uint32_t)J, c1 = (uint32_t)(J >> 32), c2 = worker, c3 = iter_lo;
+    uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        c0 = hi1 ^ c1 ^ k0;
+        c1 = lo1;
+        c2 = hi0 ^ c3 ^ k1;
+        c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    uint32_t lane = (uint32_t)gidx & 3u;
+    uint32_t x = lane == 0 ? c0 : lane == 1 ? c1 : lane == 2 ? c2 : c3;
+    return (float)(x >> 8) * 5.9604644775390625e-8f;
+}
+
+}  // namespace mc

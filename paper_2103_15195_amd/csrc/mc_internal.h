@@ -1,0 +1,86 @@
+// Host <-> kernel-launcher interface of the library (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/mergecomp.h"
+#include "mc_device.h"
+
+namespace mc {
+
+constexpr uint32_t kMagic = 0x3150434Du;
+constexpr int kHeaderBytes = 64;
+constexpr int kMaxWorkers = 64;
+
+struct PayloadHeader {          // 64 bytes, see the layout in mergecomp.h
+    uint32_t magic, algo;
+    uint64_t n, k;
+    float scale;
+    uint32_t levels;
+    uint32_t pad[8];
+};
+static_assert(sizeof(PayloadHeader) == kHeaderBytes, "payload header is 64 bytes");
+
+struct StateHeader {            // 64 bytes in front of the error-feedback floats
+    float scale;                // EF-Sign: scale of the last call (0 after zero-fill / import)
+    uint32_t pad[15];
+};
+static_assert(sizeof(StateHeader) == kHeaderBytes, "state header is 64 bytes");
+
+struct PayloadPtrs { const uint8_t *p[kMaxWorkers]; };
+struct PtrChunk { uintptr_t p[256]; };
+
+// radix-select state carried between the passes of the exact top-k
+struct SelectState {
+    uint32_t prefix;     // bits of the threshold key decided so far
+    uint32_t pad0;
+    uint64_t need;       // entries still to take among keys that match the prefix
+};
+
+// profiling slots
+enum KernelId {
+    K_UPLOAD = 0, K_EFSIGN_COMPRESS, K_SCALAR_FINALIZE, K_ACCUM_REDUCE, K_QSGD_ENCODE, K_TERN_ENCODE,
+    K_FP16_COMPRESS, K_DENSE_DECOMPRESS, K_SPARSE_ACCUM, K_SELECT_BIN, K_SPARSE_HIST, K_SPARSE_COUNT,
+    K_SPARSE_SCAN, K_SPARSE_EMIT, K_SPARSE_DECOMPRESS, K_STATE_CONVERT, K_COUNT
+};
+
+// reduction kinds of the two-pass quantizers
+enum ReduceMode { RED_MEAN_ABS = 0, RED_L2 = 1, RED_MAX_ABS = 2 };
+
+struct LaunchCtx {               // what a launcher needs besides its arguments
+    hipStream_t stream;
+    void *prof;                  // opaque: profiling recorder or null
+};
+void prof_begin(const LaunchCtx &lc, int id);
+void prof_end(const LaunchCtx &lc, int id);
+
+// ---- dense kernels (kernels_dense.hip) -----------------------------------------
+void launch_upload_ptrs(const LaunchCtx &lc, const uintptr_t *host, uintptr_t *dev, uint32_t count);
+void launch_efsign_compress(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, const float *scale_prev,
+                            uint32_t *words, uint32_t nwords, double *partial);
+void launch_scalar_finalize(const LaunchCtx &lc, const double *partial, uint32_t nblocks, int mode, uint32_t n,
+                            PayloadHeader *hdr, uint32_t algo, uint64_t k, uint32_t levels, float *state_scale);
+void launch_accum_reduce(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, int mode, double *partial);
+void launch_qsgd_encode(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, const PayloadHeader *hdr,
+                        int8_t *codes, uint32_t levels, uint64_t seed, uint32_t worker, uint32_t iter_lo);
+void launch_tern_encode(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, const PayloadHeader *hdr,
+                        uint32_t *planes, uint32_t nwords, uint64_t seed, uint32_t worker, uint32_t iter_lo);
+void launch_fp16_compress(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, PayloadHeader *hdr,
+                          uint16_t *halves);
+void launch_dense_decompress(const LaunchCtx &lc, int algo, const GroupView &out, const PayloadPtrs &pl, int W,
+                             float alpha, uint32_t levels, int *status);
+void launch_state_convert(const LaunchCtx &lc, int algo, bool to_residual, uint32_t nfloats, const void *src, void *dst);
+
+// ---- sparse kernels (kernels_sparse.hip) ----------------------------------------
+struct SparseScratch {
+    uint32_t *hist;        // 2048 + 1024 + 1024 bins, zero between calls
+    SelectState *sel;
+    uint32_t *tile_gt;     // per tile: entries above the threshold (then exclusive prefix)
+    uint32_t *tile_eq;     // per tile: entries equal to the threshold (then exclusive prefix)
+};
+void launch_sparse_compress(const LaunchCtx &lc, int algo, const GroupView &g, bool ef, float *state_f, float momentum,
+                            uint64_t k, PayloadHeader *hdr, const SparseScratch &sc);
+void launch_sparse_decompress(const LaunchCtx &lc, int algo, const GroupView &out, const PayloadPtrs &pl, int W,
+                              float alpha, uint64_t k, int *status);
+
+}  // namespace mc

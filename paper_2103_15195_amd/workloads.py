@@ -157,29 +157,41 @@ def tensor_std(wl: Workload) -> np.ndarray:
     return 10.0 ** rng.uniform(-4.0, -1.0, size=n)
 
 
-def gradients(wl: Workload, worker: int, it: int, shared_fraction: float = 0.0) -> List[np.ndarray]:
-    """One worker's fp32 gradient tensors (flattened, list order = wl.shapes).
+def gradients_flat(wl: Workload, worker: int, it: int, shared_fraction: float = 0.0) -> np.ndarray:
+    """One worker's gradients as one flat fp32 vector (tensors in list order).
 
     Workers are independent by default; with shared_fraction = f the value is
     sqrt(f) * common + sqrt(1 - f) * private so that large entries overlap
     between workers (exercises index collisions in the sparse decompress)."""
-    std = tensor_std(wl)
+    std = tensor_std(wl).astype(np.float32)
     numel = wl.numel
+    total = int(numel.sum())
 
-    def draw(seed_words) -> List[np.ndarray]:
+    def draw(seed_words) -> np.ndarray:
         rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence(seed_words)))
-        out = []
-        for t, n in enumerate(numel):
-            if wl.dist == "student_t3":
-                x = rng.standard_t(3.0, size=int(n))
-            else:
-                x = rng.standard_normal(size=int(n))
-            out.append(x * std[t])
-        return out
+        if wl.dist == "student_t3":
+            x = rng.standard_t(3.0, size=total).astype(np.float32)
+        else:
+            x = rng.standard_normal(size=total, dtype=np.float32)
+        return x
 
-    private = draw([0, wl.cfg, worker, it])
+    x = draw([0, wl.cfg, worker, it])
     if shared_fraction > 0.0:
         common = draw([0, wl.cfg, 0xC0FFEE, it])
-        a, b = np.sqrt(shared_fraction), np.sqrt(1.0 - shared_fraction)
-        private = [a * c + b * p for c, p in zip(common, private)]
-    return [x.astype(np.float32) for x in private]
+        x = np.float32(np.sqrt(shared_fraction)) * common + np.float32(np.sqrt(1.0 - shared_fraction)) * x
+    off = 0
+    for t, n in enumerate(numel):
+        x[off:off + int(n)] *= std[t]
+        off += int(n)
+    return x
+
+
+def split(wl: Workload, flat: np.ndarray) -> List[np.ndarray]:
+    """Views of a flat vector, one per tensor of the workload."""
+    offs = np.concatenate([[0], np.cumsum(wl.numel)])
+    return [flat[int(offs[t]):int(offs[t + 1])] for t in range(len(wl.shapes))]
+
+
+def gradients(wl: Workload, worker: int, it: int, shared_fraction: float = 0.0) -> List[np.ndarray]:
+    """One worker's fp32 gradient tensors (flattened, list order = wl.shapes)."""
+    return split(wl, gradients_flat(wl, worker, it, shared_fraction))

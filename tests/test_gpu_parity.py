@@ -1,0 +1,243 @@
+"""GPU-vs-oracle parity through the C ABI (run with -m gpu on an MI355X).
+
+Small configurations (the MLP and ResNet-20-shaped sets, and hand-made edge
+cases) are compared element by element for every (iteration, group, worker).
+The full-size configurations live in test_gpu_fullsize.py.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as O
+from paper_2103_15195_amd import binding as B
+from paper_2103_15195_amd import workloads as WL
+
+import harness as H
+
+pytestmark = pytest.mark.gpu
+
+ALL = ["efsign", "topk", "dgc", "qsgd", "terngrad", "fp16"]
+_cache = {}
+
+
+def normal_grads(total, seed, scale=0.01):
+    def fn(w, it):
+        rng = np.random.default_rng([seed, w, it])
+        return (rng.standard_normal(total, dtype=np.float32) * np.float32(scale))
+    return fn
+
+
+# ---- BASELINE configs[0]: MLP, y=2, W=4, EF-Sign and Top-k 1 %, 3 iterations ----------
+@pytest.mark.parametrize("algo", ["efsign", "topk"])
+def test_config0_mlp(algo):
+    wl = WL.workload(0)
+    st = H.run_parity(wl.numel, algo, 2, 4, 3, H.workload_grads(wl, cache=_cache), ratio_ppm=10000)
+    assert st.compress_checks == 3 * 2 * 4 and st.decompress_checks == 2
+    print(f"[config0 {algo}] conditional re-encodes: {st.conditional}")
+
+
+# ---- BASELINE configs[1]: ResNet-20 shapes, y in {1,2,4,8,16}, W=8, all algorithms ------
+@pytest.mark.parametrize("y", [1, 2, 4, 8, 16])
+@pytest.mark.parametrize("algo", ALL)
+def test_config1_resnet20(algo, y):
+    wl = WL.workload(1)
+    st = H.run_parity(wl.numel, algo, y, 8, 2, H.workload_grads(wl, cache=_cache), ratio_ppm=10000, seed=1234)
+    assert st.compress_checks == 2 * y * 8 and st.decompress_checks == y
+    print(f"[config1 {algo} y={y}] conditional re-encodes: {st.conditional}")
+
+
+def test_config1_even_count_partition_and_shared_entries():
+    wl = WL.workload(1)
+    for algo in ("topk", "dgc", "efsign"):
+        H.run_parity(wl.numel, algo, 4, 8, 2, H.workload_grads(wl, shared_fraction=0.8), policy=B.MC_PART_EVEN_COUNT,
+                     ratio_ppm=1000 if algo == "dgc" else 10000)
+
+
+# ---- ragged sizes, tile boundaries, tiny tensors, unaligned tensors -------------------------
+RAGGED = [
+    [1], [63], [64], [65], [1023], [1024], [1025], [4095], [4096], [4097], [12289],
+    [3, 1, 1, 2], [10, 2560, 256, 65536, 7, 1000, 91], [5, 0, 0, 1031, 0, 2],
+    [33] * 130,                    # many small tensors inside one chunk
+    [4096, 1, 4095, 8191],
+]
+
+
+@pytest.mark.parametrize("algo", ALL)
+@pytest.mark.parametrize("layout", ["separate", "misaligned"])
+def test_ragged_and_unaligned(algo, layout):
+    for numel in RAGGED:
+        total = sum(numel)
+        for y in sorted({1, min(2, len(numel)), len(numel) if len(numel) <= 6 else 3}):
+            H.run_parity(numel, algo, y, 3, 2, normal_grads(total, seed=total + y), layout=layout,
+                         ratio_ppm=100000, seed=99, alpha=0.5)
+
+
+@pytest.mark.parametrize("algo", ALL)
+def test_groups_made_of_empty_tensors(algo):
+    numel = [0, 0, 100, 0, 5000, 0]
+    H.run_parity(numel, algo, 3, 2, 2, normal_grads(5100, seed=3), user_bounds=[0, 2, 4, 6], policy=B.MC_PART_USER,
+                 ratio_ppm=20000)
+
+
+# ---- degenerate values ------------------------------------------------------------------------
+def special_grads(total, kind):
+    def fn(w, it):
+        rng = np.random.default_rng([17, w, it])
+        if kind == "zeros":
+            return np.zeros(total, np.float32)
+        if kind == "all_equal":
+            return np.full(total, 0.25 * (1 if (w + it) % 2 else -1), np.float32)
+        if kind == "ties":
+            return rng.integers(-3, 4, total).astype(np.float32) * np.float32(0.125)
+        if kind == "tiny":        # fp32 subnormals and values below the smallest fp16 subnormal
+            return (rng.standard_normal(total, dtype=np.float32) * np.float32(1e-41)).astype(np.float32)
+        if kind == "fp16_edges":
+            base = np.array([65504.0, 65519.9, 65520.0, -65520.0, 1e9, 2.0 ** -14, 2.0 ** -24, 2.0 ** -25, 3 * 2.0 ** -25,
+                             2.0 ** -26, 1.0009765625, 1.00048828125, 1.00146484375, 6.1e-5, -5.97e-8, 0.0, -0.0], np.float32)
+            return np.resize(base, total) * np.float32(1 if it == 0 else 0.5)
+        if kind == "wide":        # magnitudes over 30 decades
+            return (rng.standard_normal(total, dtype=np.float32) * (10.0 ** rng.uniform(-25, 5, total)).astype(np.float32))
+        raise ValueError(kind)
+    return fn
+
+
+@pytest.mark.parametrize("kind", ["zeros", "all_equal", "ties", "tiny", "wide"])
+@pytest.mark.parametrize("algo", ALL)
+def test_degenerate_values(algo, kind):
+    numel = [3000, 17, 5000, 1200]
+    H.run_parity(numel, algo, 2, 3, 3, special_grads(sum(numel), kind), ratio_ppm=30000, seed=5)
+
+
+def test_fp16_edge_values():
+    H.run_parity([4099], "fp16", 1, 2, 2, special_grads(4099, "fp16_edges"))
+
+
+@pytest.mark.parametrize("ppm", [1, 500, 500000, 1000000])
+@pytest.mark.parametrize("algo", ["topk", "dgc"])
+def test_sparsifier_ratios(algo, ppm):
+    numel = [20000, 333, 4096]
+    H.run_parity(numel, algo, 1, 3, 2, special_grads(sum(numel), "ties" if ppm >= 500000 else "wide"), ratio_ppm=ppm)
+    H.run_parity(numel, algo, 2, 2, 2, normal_grads(sum(numel), seed=ppm), ratio_ppm=ppm)
+
+
+@pytest.mark.parametrize("algo", ["topk", "qsgd", "terngrad", "efsign", "fp16"])
+def test_without_error_feedback(algo):
+    numel = [7000, 129, 4096]
+    H.run_parity(numel, algo, 2, 3, 2, normal_grads(sum(numel), seed=8), use_ef=0, ratio_ppm=20000, seed=11)
+
+
+@pytest.mark.parametrize("bits", [2, 4, 7])
+def test_qsgd_code_widths(bits):
+    H.run_parity([9000, 100], "qsgd", 1, 2, 2, normal_grads(9100, seed=bits), qsgd_bits=bits, seed=21)
+
+
+def test_dgc_momentum_values():
+    for m in (0.0, 0.5, 0.99):
+        H.run_parity([9000, 100, 3000], "dgc", 2, 2, 4, normal_grads(12100, seed=4), dgc_momentum=m, ratio_ppm=5000)
+
+
+@pytest.mark.parametrize("W", [1, 2, 17, 64])
+@pytest.mark.parametrize("algo", ALL)
+def test_worker_counts(algo, W):
+    H.run_parity([5000, 77], algo, 1, W, 1, normal_grads(5077, seed=W), ratio_ppm=50000, alpha=1.0 / W)
+
+
+# ---- determinism, state conversion, error reporting ------------------------------------------
+@pytest.mark.parametrize("algo", ALL)
+def test_bit_reproducible_runs(algo):
+    wl = WL.workload(1)
+    numel = wl.numel.tolist()
+    flat = WL.gradients_flat(wl, 0, 0)
+    results = []
+    for rep in range(2):
+        ctx = B.Context(algo, numel, B.mc_partition(numel, 2), ratio_ppm=10000, seed=3)
+        dev = H.device_tensors(flat, numel)
+        out = []
+        states = [torch.zeros(ctx.state_bytes(g), dtype=torch.uint8, device=H.DEV) for g in range(2)]
+        for it in range(2):
+            for j in range(2):
+                pay = torch.zeros(ctx.payload_bytes(j), dtype=torch.uint8, device=H.DEV)
+                ctx.mc_compress(j, 0, it, dev[ctx.bounds[j]:ctx.bounds[j + 1]], states[j], pay)
+                out.append(pay.cpu().numpy())
+        out += [s.cpu().numpy() for s in states]
+        results.append(out)
+        ctx.close()
+    for a, b in zip(*results):
+        assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("algo", ALL)
+def test_state_import_export_roundtrip(algo):
+    n = 10007
+    ctx = B.Context(algo, [n], [0, 1], ratio_ppm=10000)
+    nf = n * (2 if algo == "dgc" else 1)
+    rng = np.random.default_rng(1)
+    e = rng.standard_normal(nf, dtype=np.float32)
+    e[:4] = [0.0, -0.0, 1e-42, -1e-42]
+    state = torch.full((ctx.state_bytes(0),), 0x55, dtype=torch.uint8, device=H.DEV)
+    back = torch.zeros(nf, dtype=torch.float32, device=H.DEV)
+    ctx.mc_state_import_residual(0, torch.from_numpy(e).to(H.DEV), state)
+    ctx.mc_state_export_residual(0, state, back)
+    assert H.same_bits(back.cpu().numpy(), e)
+    # a compress that starts from an imported residual equals the oracle started from that residual
+    g = rng.standard_normal(n, dtype=np.float32)
+    ocfg = O.Config(H.ALGOS[algo], ratio_ppm=10000)
+    ost = e.copy()
+    op, _ = O.compress(ocfg, g, ost, worker=1, it=7)
+    pay = torch.zeros(ctx.payload_bytes(0), dtype=torch.uint8, device=H.DEV)
+    ctx.mc_compress(0, 1, 7, [torch.from_numpy(g).to(H.DEV)], state, pay)
+    ctx.mc_state_export_residual(0, state, back)
+    if O.header(pay.cpu().numpy())["scale"] == O.header(op)["scale"]:
+        assert np.array_equal(pay.cpu().numpy(), op) and H.same_bits(back.cpu().numpy(), ost)
+    ctx.close()
+
+
+def test_payload_mismatch_is_reported_not_fatal():
+    n = 5000
+    ctx = B.Context("efsign", [n], [0, 1])
+    other = B.Context("topk", [n], [0, 1])
+    g = torch.randn(n, device=H.DEV)
+    st = torch.zeros(ctx.state_bytes(0), dtype=torch.uint8, device=H.DEV)
+    pay = torch.zeros(ctx.payload_bytes(0), dtype=torch.uint8, device=H.DEV)
+    ctx.mc_compress(0, 0, 0, [g], st, pay)
+    out = torch.zeros(n, device=H.DEV)
+    ctx.mc_decompress_sum(0, [pay], 1.0, [out])
+    assert ctx.mc_last_device_status() == B.MC_OK
+    # a sparse context fed an EF-Sign payload: flagged; garbage indices are never written out of bounds
+    big = torch.zeros(max(other.payload_bytes(0), ctx.payload_bytes(0)), dtype=torch.uint8, device=H.DEV)
+    big[:pay.numel()] = pay
+    guard = torch.full((n + 64,), 7.0, device=H.DEV)
+    other.mc_decompress_sum(0, [big], 1.0, [guard[32:32 + n]])
+    assert other.mc_last_device_status() == B.MC_ERR_PAYLOAD
+    assert other.mc_last_device_status() == B.MC_OK            # the flag is cleared by reading it
+    assert torch.all(guard[:32] == 7.0) and torch.all(guard[32 + n:] == 7.0)
+    # host-side argument checks
+    L = B.lib()
+    assert L.mc_compress(ctx._h, 3, 0, 0, None, None, None, None) == B.MC_ERR_INVALID_ARG
+    with pytest.raises(B.McError):
+        ctx.mc_compress(0, 0, 0, [g], None, pay)               # use_ef = 1 needs a state
+    with pytest.raises(B.McError):
+        ctx.mc_decompress_sum(0, [pay] * 65, 1.0, [out])       # more than 64 payloads
+    with pytest.raises(B.McError):
+        ctx.mc_compress(0, 0, 0, [g], st, pay[4:])             # payload not 16-byte aligned
+    ctx.close(); other.close()
+
+
+def test_profile_hooks_count_launches():
+    n = 100000
+    ctx = B.Context("efsign", [n], [0, 1])
+    g = torch.randn(n, device=H.DEV)
+    st = torch.zeros(ctx.state_bytes(0), dtype=torch.uint8, device=H.DEV)
+    pay = torch.zeros(ctx.payload_bytes(0), dtype=torch.uint8, device=H.DEV)
+    ctx.profile_enable(True)
+    for it in range(3):
+        ctx.mc_compress(0, 0, it, [g], st, pay)
+    prof = ctx.profile_read()
+    assert prof["efsign_compress"]["launches"] == 3 and prof["scalar_finalize"]["launches"] == 3
+    assert prof["efsign_compress"]["total_ms"] > 0
+    assert prof["upload_ptrs"]["launches"] == 1                # the tensor address list is cached after the first call
+    ctx.profile_reset()
+    ctx.profile_enable(False)
+    ctx.mc_compress(0, 0, 3, [g], st, pay)
+    assert ctx.profile_read() == {}
+    ctx.close()
