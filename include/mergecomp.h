@@ -167,10 +167,12 @@ int mc_last_device_status(mc_ctx *ctx);
 /*
  * Per-kernel timing with HIP events recorded on the caller's stream around each
  * launch (off by default).  mc_profile_read synchronises the recorded events.
+ *   mc_profile_select    bit i of the mask: time kernel slot i while enabled (default: all slots)
  *   mc_profile_kernels   number of kernel slots
  *   mc_profile_read      name (static string), launches and total milliseconds of slot `id`
  */
 int mc_profile_enable(mc_ctx *ctx, int32_t on);
+int mc_profile_select(mc_ctx *ctx, uint64_t kernel_mask);
 int mc_profile_reset(mc_ctx *ctx);
 int32_t mc_profile_kernels(void);
 int mc_profile_read(mc_ctx *ctx, int32_t id, const char **name, int64_t *launches, double *total_ms);

@@ -22,7 +22,7 @@ MC_OK, MC_ERR_INVALID_ARG, MC_ERR_RANGE, MC_ERR_ALLOC, MC_ERR_DEVICE, MC_ERR_PAY
 EXPORTS = [
     "mc_partition", "mc_ctx_create", "mc_ctx_destroy", "mc_group_numel", "mc_group_k", "mc_group_tensors",
     "mc_payload_bytes", "mc_state_bytes", "mc_compress", "mc_decompress_sum", "mc_state_export_residual",
-    "mc_state_import_residual", "mc_last_device_status", "mc_profile_enable", "mc_profile_reset",
+    "mc_state_import_residual", "mc_last_device_status", "mc_profile_enable", "mc_profile_select", "mc_profile_reset",
     "mc_profile_kernels", "mc_profile_read", "mc_strerror", "mc_version",
 ]
 
@@ -67,6 +67,7 @@ def lib():
         L.mc_state_import_residual.argtypes = [vp, i32, vp, vp, vp]
         L.mc_last_device_status.argtypes = [vp]
         L.mc_profile_enable.argtypes = [vp, i32]
+        L.mc_profile_select.argtypes = [vp, u64]
         L.mc_profile_reset.argtypes = [vp]
         L.mc_profile_kernels.argtypes = []
         L.mc_profile_kernels.restype = i32
@@ -83,8 +84,15 @@ def _check(status: int, what: str) -> None:
         raise McError(status, what)
 
 
-def _ptr_array(tensors: Sequence) -> C.Array:
+def ptr_array(tensors: Sequence) -> C.Array:
+    """Host array of device addresses, one per tensor.  Callers in a hot loop build it once and pass it
+    in place of the tensor list (the tensors must stay alive and in place)."""
+    if isinstance(tensors, C.Array):
+        return tensors
     return (C.c_void_p * max(len(tensors), 1))(*[t.data_ptr() if t is not None else None for t in tensors])
+
+
+_ptr_array = ptr_array
 
 
 def _stream_handle(stream) -> Optional[int]:
@@ -155,7 +163,8 @@ class Context:
                                  _stream_handle(stream)), "mc_compress")
 
     def mc_decompress_sum(self, group: int, payloads: Sequence, alpha: float, outs: Sequence, stream=None) -> None:
-        _check(lib().mc_decompress_sum(self._h, group, _ptr_array(payloads), len(payloads), alpha, _ptr_array(outs),
+        W = len(payloads)
+        _check(lib().mc_decompress_sum(self._h, group, _ptr_array(payloads), W, alpha, _ptr_array(outs),
                                        _stream_handle(stream)), "mc_decompress_sum")
 
     # state helpers --------------------------------------------------------------
@@ -171,8 +180,21 @@ class Context:
         return int(lib().mc_last_device_status(self._h))
 
     # profiling ------------------------------------------------------------------
-    def profile_enable(self, on: bool) -> None:
+    def profile_enable(self, on: bool, all_kernels: bool = False) -> None:
+        if all_kernels:
+            _check(lib().mc_profile_select(self._h, (1 << 64) - 1), "mc_profile_select")
         _check(lib().mc_profile_enable(self._h, 1 if on else 0), "mc_profile_enable")
+
+    def profile_enable_only(self, kernel_name: str) -> None:
+        """Time only the named kernel slot (keeps event overhead out of a timed region)."""
+        for i in range(lib().mc_profile_kernels()):
+            name = C.c_char_p()
+            _check(lib().mc_profile_read(self._h, i, C.byref(name), None, None), "mc_profile_read")
+            if name.value.decode() == kernel_name:
+                _check(lib().mc_profile_select(self._h, 1 << i), "mc_profile_select")
+                self.profile_enable(True)
+                return
+        raise KeyError(kernel_name)
 
     def profile_reset(self) -> None:
         _check(lib().mc_profile_reset(self._h), "mc_profile_reset")

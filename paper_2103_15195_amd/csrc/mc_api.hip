@@ -36,6 +36,7 @@ struct ProfEvent { int id; hipEvent_t a, b; };
 
 struct Profiler {
     bool on = false;
+    uint64_t mask = ~0ull;            // kernel slots that are timed while `on`
     std::vector<ProfEvent> pending;
     std::vector<hipEvent_t> pool;
     int64_t launches[K_COUNT] = {};
@@ -63,8 +64,7 @@ namespace mc {
 void prof_begin(const LaunchCtx &lc, int id)
 {
     Profiler *p = static_cast<Profiler *>(lc.prof);
-    if (!p || !p->on) return;
-    (void)id;
+    if (!p || !p->on || !((p->mask >> id) & 1ull)) return;
     hipEvent_t a = nullptr;
     if (!p->pool.empty()) { a = p->pool.back(); p->pool.pop_back(); }
     else if (hipEventCreate(&a) != hipSuccess) { p->current = nullptr; return; }
@@ -450,6 +450,13 @@ int mc_profile_enable(mc_ctx *ctx, int32_t on)
 {
     if (!ctx) return MC_ERR_INVALID_ARG;
     ctx->prof.on = on != 0;
+    return MC_OK;
+}
+
+int mc_profile_select(mc_ctx *ctx, uint64_t kernel_mask)
+{
+    if (!ctx) return MC_ERR_INVALID_ARG;
+    ctx->prof.mask = kernel_mask;
     return MC_OK;
 }
 
