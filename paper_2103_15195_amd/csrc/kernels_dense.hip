@@ -105,9 +105,16 @@ __global__ __launch_bounds__(kBlock) void scalar_finalize_k(const double *partia
     __shared__ double red[kBlock];
     double acc = 0.0;
     if (mode >= 0) {
-        for (uint32_t i = threadIdx.x; i < nblocks; i += kBlock) {
-            double v = partial[i];
-            acc = mode == RED_MAX_ABS ? fmax(acc, v) : acc + v;
+        // eight independent loads in flight per round; the order of additions depends on nblocks only
+        for (uint32_t base = 0; base < nblocks; base += 8 * kBlock) {
+            double v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                uint32_t i = base + u * kBlock + threadIdx.x;
+                v[u] = i < nblocks ? partial[i] : 0.0;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc = mode == RED_MAX_ABS ? fmax(acc, v[u]) : acc + v[u];
         }
     }
     red[threadIdx.x] = acc;
@@ -381,61 +388,100 @@ __device__ __forceinline__ void check_header(const PayloadHeader *h, uint32_t al
     if (h->magic != kMagic || h->algo != algo || h->n != (uint64_t)n) *status = 1;
 }
 
+// Workers are taken in batches: all loads of a batch (header scalars and codes)
+// are issued before the first is used, so a wavefront pays the HBM latency once
+// per batch instead of once per worker.
 template <int ALGO>
 __global__ __launch_bounds__(kBlock) void dense_decompress_k(GroupView out, PayloadPtrs pl, int W, float alpha,
                                                              uint32_t levels, int *status)
 {
+    constexpr int kBatch = (ALGO == MC_ALGO_EFSIGN || ALGO == MC_ALGO_TERNGRAD) ? 8 : 4;
     const Chunk c = my_chunk(out.n);
     if (blockIdx.x == 0 && (int)threadIdx.x < W)
         check_header(reinterpret_cast<const PayloadHeader *>(pl.p[threadIdx.x]), ALGO, out.n, status);
     if (c.base >= out.n) return;
     const uint32_t nwords = (out.n + 31u) >> 5;
+    const uint32_t wi = (c.base >> 5) + (c.lane & 31u);      // bit planes: lanes 0..31 hold the chunk's 32 words
+    const uint32_t sh = c.lane & 31u;
+    const bool upper = c.lane >= 32;
     float acc[kSteps];
 #pragma unroll
     for (int j = 0; j < kSteps; ++j) acc[j] = 0.0f;
-    for (int w = 0; w < W; ++w) {
-        const uint8_t *pay = pl.p[w];
-        const float scale = reinterpret_cast<const PayloadHeader *>(pay)->scale;
-        const uint8_t *body = pay + kHeaderBytes;
-        if (ALGO == MC_ALGO_EFSIGN) {
-            // lanes 0..31 fetch the chunk's 32 words once; step j uses words 2j and 2j+1
-            const uint32_t *words = reinterpret_cast<const uint32_t *>(body);
-            uint32_t wi = (c.base >> 5) + (c.lane & 31u);
-            uint32_t mine = wi < nwords ? ld_stream(words + wi) : 0u;
+    for (int w0 = 0; w0 < W; w0 += kBatch) {
+        float scale[kBatch];
 #pragma unroll
-            for (int j = 0; j < kSteps; ++j) {
-                uint32_t lo = __builtin_amdgcn_readlane(mine, 2 * j), hi = __builtin_amdgcn_readlane(mine, 2 * j + 1);
-                uint32_t word = c.lane < 32 ? lo : hi;
-                float d = ((word >> (c.lane & 31u)) & 1u) ? scale : -scale;
-                acc[j] = acc[j] + d;
+        for (int b = 0; b < kBatch; ++b)
+            scale[b] = w0 + b < W ? reinterpret_cast<const PayloadHeader *>(pl.p[w0 + b])->scale : 0.0f;
+        if (ALGO == MC_ALGO_EFSIGN) {
+            uint32_t mine[kBatch];
+#pragma unroll
+            for (int b = 0; b < kBatch; ++b) {
+                mine[b] = 0u;
+                if (w0 + b < W && wi < nwords)
+                    mine[b] = ld_stream(reinterpret_cast<const uint32_t *>(pl.p[w0 + b] + kHeaderBytes) + wi);
+            }
+#pragma unroll
+            for (int b = 0; b < kBatch; ++b) {
+                if (w0 + b < W) {
+#pragma unroll
+                    for (int j = 0; j < kSteps; ++j) {
+                        uint32_t lo = __builtin_amdgcn_readlane(mine[b], 2 * j), hi = __builtin_amdgcn_readlane(mine[b], 2 * j + 1);
+                        float d = (((upper ? hi : lo) >> sh) & 1u) ? scale[b] : -scale[b];
+                        acc[j] = acc[j] + d;
+                    }
+                }
             }
         } else if (ALGO == MC_ALGO_TERNGRAD) {
-            const uint32_t *nzp = reinterpret_cast<const uint32_t *>(body), *ngp = nzp + nwords;
-            uint32_t wi = (c.base >> 5) + (c.lane & 31u);
-            uint32_t mnz = wi < nwords ? ld_stream(nzp + wi) : 0u;
-            uint32_t mng = wi < nwords ? ld_stream(ngp + wi) : 0u;
+            uint32_t mnz[kBatch], mng[kBatch];
 #pragma unroll
-            for (int j = 0; j < kSteps; ++j) {
-                uint32_t nzl = __builtin_amdgcn_readlane(mnz, 2 * j), nzh = __builtin_amdgcn_readlane(mnz, 2 * j + 1);
-                uint32_t ngl = __builtin_amdgcn_readlane(mng, 2 * j), ngh = __builtin_amdgcn_readlane(mng, 2 * j + 1);
-                uint32_t nz = ((c.lane < 32 ? nzl : nzh) >> (c.lane & 31u)) & 1u;
-                uint32_t ng = ((c.lane < 32 ? ngl : ngh) >> (c.lane & 31u)) & 1u;
-                float d = nz ? (ng ? -scale : scale) : 0.0f;
-                acc[j] = acc[j] + d;
+            for (int b = 0; b < kBatch; ++b) {
+                mnz[b] = 0u; mng[b] = 0u;
+                if (w0 + b < W && wi < nwords) {
+                    const uint32_t *nzp = reinterpret_cast<const uint32_t *>(pl.p[w0 + b] + kHeaderBytes);
+                    mnz[b] = ld_stream(nzp + wi);
+                    mng[b] = ld_stream(nzp + nwords + wi);
+                }
+            }
+#pragma unroll
+            for (int b = 0; b < kBatch; ++b) {
+                if (w0 + b < W) {
+#pragma unroll
+                    for (int j = 0; j < kSteps; ++j) {
+                        uint32_t nzl = __builtin_amdgcn_readlane(mnz[b], 2 * j), nzh = __builtin_amdgcn_readlane(mnz[b], 2 * j + 1);
+                        uint32_t ngl = __builtin_amdgcn_readlane(mng[b], 2 * j), ngh = __builtin_amdgcn_readlane(mng[b], 2 * j + 1);
+                        uint32_t nz = ((upper ? nzh : nzl) >> sh) & 1u, ng = ((upper ? ngh : ngl) >> sh) & 1u;
+                        float d = nz ? (ng ? -scale[b] : scale[b]) : 0.0f;
+                        acc[j] = acc[j] + d;
+                    }
+                }
             }
         } else if (ALGO == MC_ALGO_QSGD) {
-            const int8_t *codes = reinterpret_cast<const int8_t *>(body);
-            const float q = (float)((double)scale / (double)(float)levels);
-            int8_t cd[kSteps];
-            load_flat<int8_t>(codes, c, out.n, cd, (int8_t)0);
+            int8_t cd[kBatch][kSteps];
 #pragma unroll
-            for (int j = 0; j < kSteps; ++j) acc[j] = acc[j] + (float)cd[j] * q;
+            for (int b = 0; b < kBatch; ++b) {
+                if (w0 + b < W) load_flat<int8_t>(reinterpret_cast<const int8_t *>(pl.p[w0 + b] + kHeaderBytes), c, out.n, cd[b], (int8_t)0);
+            }
+#pragma unroll
+            for (int b = 0; b < kBatch; ++b) {
+                if (w0 + b < W) {
+                    const float q = (float)((double)scale[b] / (double)(float)levels);
+#pragma unroll
+                    for (int j = 0; j < kSteps; ++j) acc[j] = acc[j] + (float)cd[b][j] * q;
+                }
+            }
         } else {   // FP16
-            const _Float16 *h = reinterpret_cast<const _Float16 *>(body);
-            _Float16 hv[kSteps];
-            load_flat<_Float16>(h, c, out.n, hv, (_Float16)0.0f);
+            _Float16 hv[kBatch][kSteps];
 #pragma unroll
-            for (int j = 0; j < kSteps; ++j) acc[j] = acc[j] + (float)hv[j];
+            for (int b = 0; b < kBatch; ++b) {
+                if (w0 + b < W) load_flat<_Float16>(reinterpret_cast<const _Float16 *>(pl.p[w0 + b] + kHeaderBytes), c, out.n, hv[b], (_Float16)0.0f);
+            }
+#pragma unroll
+            for (int b = 0; b < kBatch; ++b) {
+                if (w0 + b < W) {
+#pragma unroll
+                    for (int j = 0; j < kSteps; ++j) acc[j] = acc[j] + (float)hv[b][j];
+                }
+            }
         }
     }
 #pragma unroll

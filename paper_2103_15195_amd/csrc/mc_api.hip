@@ -23,6 +23,7 @@ struct Group {
     uint64_t goff = 0;
     uint64_t k = 0;
     uint32_t *d_seg_off = nullptr;       // live.size() + 1 flat offsets
+    uint32_t *d_chunk_seg = nullptr;     // per 1024-element chunk: tensor holding its first element
 };
 
 struct PtrSlot {
@@ -54,6 +55,7 @@ struct mc_ctx {
     size_t max_live = 0;
     double *d_partial = nullptr;
     SparseScratch sparse{};
+    uint32_t *d_hints = nullptr;        // one candidate-filter hint per group
     int *d_status = nullptr;
     std::vector<PtrSlot> slots;
     uint64_t clock = 0;
@@ -86,8 +88,8 @@ void prof_end(const LaunchCtx &lc, int id)
 
 static const char *kKernelNames[K_COUNT] = {
     "upload_ptrs", "efsign_compress", "scalar_finalize", "accum_reduce", "qsgd_encode", "tern_encode",
-    "fp16_compress", "dense_decompress", "sparse_accum", "select_bin", "sparse_hist", "sparse_count",
-    "sparse_scan", "sparse_emit", "sparse_decompress", "state_convert"};
+    "fp16_compress", "dense_decompress", "sparse_accum", "sparse_refill", "cand_hist", "cand_count",
+    "cand_emit", "sparse_index", "sparse_decompress", "state_convert"};
 
 static void prof_drain(Profiler &p)
 {
@@ -175,13 +177,16 @@ int mc_ctx_destroy(mc_ctx *ctx)
     (void)hipDeviceSynchronize();
     prof_drain(ctx->prof);
     for (hipEvent_t e : ctx->prof.pool) (void)hipEventDestroy(e);
-    for (Group &g : ctx->groups) if (g.d_seg_off) (void)hipFree(g.d_seg_off);
+    for (Group &g : ctx->groups) {
+        if (g.d_seg_off) (void)hipFree(g.d_seg_off);
+        if (g.d_chunk_seg) (void)hipFree(g.d_chunk_seg);
+    }
     for (PtrSlot &s : ctx->slots) if (s.dev) (void)hipFree(s.dev);
     if (ctx->d_partial) (void)hipFree(ctx->d_partial);
-    if (ctx->sparse.hist) (void)hipFree(ctx->sparse.hist);
-    if (ctx->sparse.sel) (void)hipFree(ctx->sparse.sel);
-    if (ctx->sparse.tile_gt) (void)hipFree(ctx->sparse.tile_gt);
-    if (ctx->sparse.tile_eq) (void)hipFree(ctx->sparse.tile_eq);
+    void *sparse_bufs[] = {ctx->sparse.hist, ctx->sparse.sel, ctx->d_hints, ctx->sparse.total, ctx->sparse.cand_bits,
+                           ctx->sparse.cand_loc, ctx->sparse.run, ctx->sparse.blk_gt, ctx->sparse.blk_eq,
+                           ctx->sparse.wave_gt, ctx->sparse.wave_eq, ctx->sparse.tile_off};
+    for (void *b : sparse_bufs) if (b) (void)hipFree(b);
     if (ctx->d_status) (void)hipFree(ctx->d_status);
     if (switched) (void)hipSetDevice(prev);
     delete ctx;
@@ -237,6 +242,13 @@ int mc_ctx_create(mc_ctx **out, const mc_config *cfg, const int64_t *numel, int3
             goff += n;
             if (hipMalloc(&g.d_seg_off, off.size() * sizeof(uint32_t)) != hipSuccess) { rc = MC_ERR_ALLOC; break; }
             if (hipMemcpy(g.d_seg_off, off.data(), off.size() * sizeof(uint32_t), hipMemcpyHostToDevice) != hipSuccess) { rc = MC_ERR_DEVICE; break; }
+            std::vector<uint32_t> cseg((size_t)((n + kChunk - 1) / kChunk) + 1, 0u);
+            for (size_t c = 0, sidx = 0; c * kChunk < n; ++c) {
+                while (off[sidx + 1] <= c * kChunk) ++sidx;
+                cseg[c] = (uint32_t)sidx;
+            }
+            if (hipMalloc(&g.d_chunk_seg, cseg.size() * sizeof(uint32_t)) != hipSuccess) { rc = MC_ERR_ALLOC; break; }
+            if (hipMemcpy(g.d_chunk_seg, cseg.data(), cseg.size() * sizeof(uint32_t), hipMemcpyHostToDevice) != hipSuccess) { rc = MC_ERR_DEVICE; break; }
             ctx->max_tiles = std::max<uint32_t>(ctx->max_tiles, (uint32_t)((n + kTile - 1) / kTile));
             ctx->max_live = std::max(ctx->max_live, g.live.size());
         }
@@ -245,13 +257,26 @@ int mc_ctx_create(mc_ctx **out, const mc_config *cfg, const int64_t *numel, int3
         if (rc == MC_OK && hipMalloc(&ctx->d_status, sizeof(int)) != hipSuccess) rc = MC_ERR_ALLOC;
         if (rc == MC_OK && hipMemset(ctx->d_status, 0, sizeof(int)) != hipSuccess) rc = MC_ERR_DEVICE;
         if (rc == MC_OK && is_sparse(cfg->algo)) {
+            SparseScratch &sp = ctx->sparse;
             const size_t hist_bytes = (2048 + 1024 + 1024) * sizeof(uint32_t);
-            if (hipMalloc(&ctx->sparse.hist, hist_bytes) != hipSuccess ||
-                hipMalloc(&ctx->sparse.sel, sizeof(SelectState)) != hipSuccess ||
-                hipMalloc(&ctx->sparse.tile_gt, tiles * sizeof(uint32_t)) != hipSuccess ||
-                hipMalloc(&ctx->sparse.tile_eq, tiles * sizeof(uint32_t)) != hipSuccess) rc = MC_ERR_ALLOC;
-            else if (hipMemset(ctx->sparse.hist, 0, hist_bytes) != hipSuccess ||
-                     hipMemset(ctx->sparse.sel, 0, sizeof(SelectState)) != hipSuccess) rc = MC_ERR_DEVICE;
+            const size_t chunks = tiles * kWavesPerBlock, slots = chunks * kChunk;
+            const size_t off_words = (size_t)kMaxWorkers * (tiles + 1);
+            if (hipMalloc(&sp.hist, hist_bytes) != hipSuccess || hipMalloc(&sp.sel, 4 * sizeof(SelectState)) != hipSuccess ||
+                hipMalloc(&ctx->d_hints, y * sizeof(uint32_t)) != hipSuccess ||
+                hipMalloc(&sp.total, sizeof(unsigned long long)) != hipSuccess ||
+                hipMalloc(&sp.cand_bits, slots * sizeof(uint32_t)) != hipSuccess ||
+                hipMalloc(&sp.cand_loc, slots * sizeof(uint16_t)) != hipSuccess ||
+                hipMalloc(&sp.run, chunks * sizeof(uint32_t)) != hipSuccess ||
+                hipMalloc(&sp.blk_gt, kMaxCandBlocks * sizeof(uint32_t)) != hipSuccess ||
+                hipMalloc(&sp.blk_eq, kMaxCandBlocks * sizeof(uint32_t)) != hipSuccess ||
+                hipMalloc(&sp.wave_gt, kMaxCandBlocks * kWavesPerBlock * sizeof(uint32_t)) != hipSuccess ||
+                hipMalloc(&sp.wave_eq, kMaxCandBlocks * kWavesPerBlock * sizeof(uint32_t)) != hipSuccess ||
+                hipMalloc(&sp.tile_off, off_words * sizeof(uint32_t)) != hipSuccess) rc = MC_ERR_ALLOC;
+            else if (hipMemset(sp.hist, 0, hist_bytes) != hipSuccess || hipMemset(sp.sel, 0, 4 * sizeof(SelectState)) != hipSuccess ||
+                     hipMemset(ctx->d_hints, 0, y * sizeof(uint32_t)) != hipSuccess ||
+                     hipMemset(sp.total, 0, sizeof(unsigned long long)) != hipSuccess ||
+                     hipMemset(sp.run, 0, chunks * sizeof(uint32_t)) != hipSuccess ||
+                     hipMemset(sp.tile_off, 0, off_words * sizeof(uint32_t)) != hipSuccess) rc = MC_ERR_DEVICE;
         }
         if (rc == MC_OK) {
             ctx->slots.resize(kPtrSlots);
@@ -354,7 +379,7 @@ int mc_compress(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter, cons
         launch_scalar_finalize(lc, ctx->d_partial, 0, -1, 0, hdr, (uint32_t)cfg.algo, 0, levels, nullptr);
         return check_launch();
     }
-    GroupView gv{G.d_seg_off, device_ptrs(ctx, lc, group, G, reinterpret_cast<const void *const *>(grad_ptrs)),
+    GroupView gv{G.d_seg_off, G.d_chunk_seg, device_ptrs(ctx, lc, group, G, reinterpret_cast<const void *const *>(grad_ptrs)),
                  (uint32_t)G.live.size(), n, G.goff};
     switch (cfg.algo) {
     case MC_ALGO_EFSIGN:
@@ -377,7 +402,11 @@ int mc_compress(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter, cons
         break;
     case MC_ALGO_TOPK:
     case MC_ALGO_DGC:
-        launch_sparse_compress(lc, cfg.algo, gv, ef, sf, cfg.dgc_momentum, G.k, hdr, ctx->sparse);
+    {
+        SparseScratch sp = ctx->sparse;
+        sp.hint = ctx->d_hints + group;
+        launch_sparse_compress(lc, cfg.algo, gv, ef, sf, cfg.dgc_momentum, G.k, hdr, sp);
+    }
         break;
     default: return MC_ERR_INVALID_ARG;
     }
@@ -401,10 +430,10 @@ int mc_decompress_sum(mc_ctx *ctx, int32_t group, const void *const *payloads, i
     if (G.n == 0) return MC_OK;
     LaunchCtx lc{static_cast<hipStream_t>(stream), &ctx->prof};
     (void)hipGetLastError();
-    GroupView gv{G.d_seg_off, device_ptrs(ctx, lc, group, G, reinterpret_cast<const void *const *>(out_ptrs)),
+    GroupView gv{G.d_seg_off, G.d_chunk_seg, device_ptrs(ctx, lc, group, G, reinterpret_cast<const void *const *>(out_ptrs)),
                  (uint32_t)G.live.size(), G.n, G.goff};
     const mc_config &cfg = ctx->cfg;
-    if (is_sparse(cfg.algo)) launch_sparse_decompress(lc, cfg.algo, gv, pl, W, alpha, G.k, ctx->d_status);
+    if (is_sparse(cfg.algo)) launch_sparse_decompress(lc, cfg.algo, gv, pl, W, alpha, G.k, ctx->sparse.tile_off, ctx->d_status);
     else {
         const uint32_t levels = cfg.algo == MC_ALGO_QSGD ? (1u << (cfg.qsgd_bits - 1)) - 1u : 0u;
         launch_dense_decompress(lc, cfg.algo, gv, pl, W, alpha, levels, ctx->d_status);

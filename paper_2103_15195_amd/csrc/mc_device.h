@@ -26,6 +26,7 @@ constexpr int kWavesPerBlock = kBlock / kWave;
 // of tensor s (strictly increasing, seg_off[nseg] = n); ptrs[s] its address.
 struct GroupView {
     const uint32_t *seg_off;
+    const uint32_t *chunk_seg;   // tensor that holds the first element of each 1024-element chunk
     const uintptr_t *ptrs;
     uint32_t nseg;
     uint32_t n;
@@ -53,15 +54,10 @@ __device__ __forceinline__ T ld_stream(const T *p) { return __builtin_nontempora
 template <typename T>
 __device__ __forceinline__ void st_stream(T *p, T v) { __builtin_nontemporal_store(v, p); }
 
-// largest s with seg_off[s] <= i, for i < n
-__device__ __forceinline__ uint32_t seg_find(const uint32_t *off, uint32_t nseg, uint32_t i)
+// tensor that holds the first element of the chunk (chunks start at multiples of 1024)
+__device__ __forceinline__ uint32_t seg_of_chunk(const GroupView &g, const Chunk &c)
 {
-    uint32_t lo = 0, hi = nseg;
-    while (hi - lo > 1) {
-        uint32_t mid = (lo + hi) >> 1;
-        if (off[mid] <= i) lo = mid; else hi = mid;
-    }
-    return lo;
+    return __builtin_amdgcn_readfirstlane(g.chunk_seg[c.base >> 10]);
 }
 
 // ---- flat (contiguous) buffers -------------------------------------------
@@ -97,7 +93,7 @@ __device__ __forceinline__ void store_flat(T *buf, const Chunk &c, uint32_t n, c
 // only grow with j, so the cursor never moves back).
 __device__ __forceinline__ void load_seg(const GroupView &g, const Chunk &c, float (&v)[kSteps])
 {
-    uint32_t s = seg_find(g.seg_off, g.nseg, c.base);
+    uint32_t s = seg_of_chunk(g, c);
     uint32_t beg = g.seg_off[s], end = g.seg_off[s + 1];
     if (c.full && end - c.base >= (uint32_t)kChunk) {
         const float *p = reinterpret_cast<const float *>(g.ptrs[s]) + (c.base - beg) + c.lane;
@@ -120,7 +116,7 @@ __device__ __forceinline__ void load_seg(const GroupView &g, const Chunk &c, flo
 
 __device__ __forceinline__ void store_seg(const GroupView &g, const Chunk &c, const float (&v)[kSteps])
 {
-    uint32_t s = seg_find(g.seg_off, g.nseg, c.base);
+    uint32_t s = seg_of_chunk(g, c);
     uint32_t beg = g.seg_off[s], end = g.seg_off[s + 1];
     if (c.full && end - c.base >= (uint32_t)kChunk) {
         float *p = reinterpret_cast<float *>(g.ptrs[s]) + (c.base - beg) + c.lane;
@@ -154,10 +150,6 @@ __device__ __forceinline__ void store_plane(uint32_t *plane, uint32_t nwords, co
     }
     __builtin_amdgcn_wave_barrier();
 }
-
-// word holding the bit of flat element i, for the chunk mapping: lanes 0..31 of
-// step j read word 2j, lanes 32..63 word 2j+1 of the chunk
-__device__ __forceinline__ uint32_t plane_word(const uint32_t *plane, uint32_t i) { return plane[i >> 5]; }
 
 // ---- reductions ----------------------------------------------------------------
 __device__ __forceinline__ double wave_sum(double x)

@@ -40,8 +40,8 @@ struct SelectState {
 // profiling slots
 enum KernelId {
     K_UPLOAD = 0, K_EFSIGN_COMPRESS, K_SCALAR_FINALIZE, K_ACCUM_REDUCE, K_QSGD_ENCODE, K_TERN_ENCODE,
-    K_FP16_COMPRESS, K_DENSE_DECOMPRESS, K_SPARSE_ACCUM, K_SELECT_BIN, K_SPARSE_HIST, K_SPARSE_COUNT,
-    K_SPARSE_SCAN, K_SPARSE_EMIT, K_SPARSE_DECOMPRESS, K_STATE_CONVERT, K_COUNT
+    K_FP16_COMPRESS, K_DENSE_DECOMPRESS, K_SPARSE_ACCUM, K_SPARSE_REFILL, K_CAND_HIST, K_CAND_COUNT,
+    K_CAND_EMIT, K_SPARSE_INDEX, K_SPARSE_DECOMPRESS, K_STATE_CONVERT, K_COUNT
 };
 
 // reduction kinds of the two-pass quantizers
@@ -72,15 +72,23 @@ void launch_dense_decompress(const LaunchCtx &lc, int algo, const GroupView &out
 void launch_state_convert(const LaunchCtx &lc, int algo, bool to_residual, uint32_t nfloats, const void *src, void *dst);
 
 // ---- sparse kernels (kernels_sparse.hip) ----------------------------------------
+constexpr uint32_t kMaxCandBlocks = 1024;   // grid of the kernels that walk the candidate slots
+
 struct SparseScratch {
-    uint32_t *hist;        // 2048 + 1024 + 1024 bins, zero between calls
-    SelectState *sel;
-    uint32_t *tile_gt;     // per tile: entries above the threshold (then exclusive prefix)
-    uint32_t *tile_eq;     // per tile: entries equal to the threshold (then exclusive prefix)
+    uint32_t *hist;        // 2048 + 1024 + 1024 bins; each level is cleared by a later kernel of the same call
+    SelectState *sel;      // [1..3]: prefix / need after each radix level
+    uint32_t *hint;        // this group's candidate filter: keys >= hint are candidates (0 = everything)
+    unsigned long long *total;   // candidates found by the accumulate kernel
+    uint32_t *cand_bits;   // candidate values (fp32 bit patterns), 1024 slots per chunk, filled from the front
+    uint16_t *cand_loc;    // candidate positions inside their chunk
+    uint32_t *run;         // candidates per chunk
+    uint32_t *blk_gt, *blk_eq;     // per block of the candidate kernels: kept above / equal to the threshold
+    uint32_t *wave_gt, *wave_eq;   // same per wavefront
+    uint32_t *tile_off;    // decompress: per worker, first payload entry of every 4096-element tile
 };
 void launch_sparse_compress(const LaunchCtx &lc, int algo, const GroupView &g, bool ef, float *state_f, float momentum,
                             uint64_t k, PayloadHeader *hdr, const SparseScratch &sc);
 void launch_sparse_decompress(const LaunchCtx &lc, int algo, const GroupView &out, const PayloadPtrs &pl, int W,
-                              float alpha, uint64_t k, int *status);
+                              float alpha, uint64_t k, uint32_t *tile_off, int *status);
 
 }  // namespace mc

@@ -126,6 +126,25 @@ def test_without_error_feedback(algo):
     H.run_parity(numel, algo, 2, 3, 2, normal_grads(sum(numel), seed=8), use_ef=0, ratio_ppm=20000, seed=11)
 
 
+@pytest.mark.parametrize("algo", ["topk", "dgc"])
+@pytest.mark.parametrize("use_ef", [1, 0])
+def test_sparsifier_when_the_candidate_filter_misses(algo, use_ef):
+    """The candidate filter is seeded by the previous call's threshold.  Gradients that shrink by orders of
+    magnitude between calls (over iterations, and between the workers that share a context) leave fewer than k
+    candidates and force the refill path; growing ones make nearly everything a candidate.  Results stay exact."""
+    if algo == "dgc" and not use_ef:
+        pytest.skip("DGC always carries state")
+    numel = [30000, 17, 5000, 12000]
+    total = sum(numel)
+
+    def grads(w, it):
+        rng = np.random.default_rng([23, w, it])
+        scale = [1.0, 1e-3, 10.0, 1e-6, 1e-6, 1.0][it] * (1.0 if w % 2 == 0 else 1e-2)
+        return rng.standard_normal(total, dtype=np.float32) * np.float32(scale)
+    H.run_parity(numel, algo, 2, 3, 6, grads, ratio_ppm=10000, use_ef=use_ef, dgc_momentum=0.5)
+    H.run_parity(numel, algo, 1, 2, 6, grads, ratio_ppm=300000, use_ef=use_ef, dgc_momentum=0.5)
+
+
 @pytest.mark.parametrize("bits", [2, 4, 7])
 def test_qsgd_code_widths(bits):
     H.run_parity([9000, 100], "qsgd", 1, 2, 2, normal_grads(9100, seed=bits), qsgd_bits=bits, seed=21)
