@@ -12,7 +12,7 @@ import os
 from typing import List, Optional, Sequence
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libmergecomp.so")
+LIB_PATH = os.environ.get("MERGECOMP_LIB", os.path.join(_HERE, "libmergecomp.so"))   # override: a build to compare against
 
 MC_ALGO_EFSIGN, MC_ALGO_TOPK, MC_ALGO_DGC, MC_ALGO_QSGD, MC_ALGO_TERNGRAD, MC_ALGO_FP16 = 1, 2, 3, 4, 5, 6
 ALGO_IDS = {"efsign": 1, "topk": 2, "dgc": 3, "qsgd": 4, "terngrad": 5, "fp16": 6}

@@ -33,6 +33,30 @@ void launch_upload_ptrs(const LaunchCtx &lc, const uintptr_t *host, uintptr_t *d
     }
 }
 
+// Per-chunk address table of a freshly uploaded tensor address list: the address of
+// the chunk's first element when all 1024 elements lie in one tensor, else 0.
+__global__ __launch_bounds__(kBlock) void expand_ptrs_k(GroupView g, uintptr_t *chunk_addr)
+{
+    const uint32_t nchunks = (g.n + (uint32_t)kChunk - 1u) / (uint32_t)kChunk;
+    const uint32_t c = blockIdx.x * kBlock + threadIdx.x;
+    if (c >= nchunks) return;
+    const uint32_t base = c * (uint32_t)kChunk;
+    const uint32_t s = g.chunk_seg[c];
+    const uint32_t beg = g.seg_off[s], end = g.seg_off[s + 1];
+    uintptr_t a = 0;
+    if (g.n - base >= (uint32_t)kChunk && end - base >= (uint32_t)kChunk) a = g.ptrs[s] + (uintptr_t)(base - beg) * sizeof(float);
+    chunk_addr[c] = a;
+}
+
+void launch_expand_ptrs(const LaunchCtx &lc, const GroupView &g, uintptr_t *chunk_addr)
+{
+    if (g.n == 0) return;
+    const uint32_t nchunks = (uint32_t)(((uint64_t)g.n + kChunk - 1) / kChunk);
+    prof_begin(lc, K_UPLOAD);
+    hipLaunchKernelGGL(expand_ptrs_k, dim3((nchunks + kBlock - 1) / kBlock), dim3(kBlock), 0, lc.stream, g, chunk_addr);
+    prof_end(lc, K_UPLOAD);
+}
+
 static inline uint32_t tiles_of(uint32_t n) { return (uint32_t)(((uint64_t)n + kTile - 1) / kTile); }
 
 // ---------------------------------------------------------------------------
@@ -489,6 +513,104 @@ __global__ __launch_bounds__(kBlock) void dense_decompress_k(GroupView out, Payl
     store_seg(out, c, acc);
 }
 
+// ---------------------------------------------------------------------------
+// EF-Sign decompress-and-sum.  With W sign planes the per-element work of the
+// generic kernel (extract bit, select +-scale, add; W times) exceeds what the
+// vector ALUs can do at HBM speed, so this kernel works on whole words:
+//   * the sum of the first (up to) 8 workers takes one of 2^8 values per group;
+//     every block tabulates them in LDS with the very same sequence of fp32
+//     additions  ((0 + d_0) + d_1) + ... , so a lookup returns the exact result;
+//   * a lane owns 32 consecutive elements, i.e. one word of every worker's plane;
+//     four 8x8 bit-matrix transposes turn its 8 words into 32 table indices;
+//   * further workers (W > 8) are added one by one in order;
+//   * results go through a skewed LDS stage so that the global stores are the
+//     usual 256 contiguous bytes per wave instruction.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint64_t transpose8x8(uint64_t x)
+{
+    // bit (8 r + c) <-> bit (8 c + r): three rounds of masked swaps
+    uint64_t t;
+    t = 0x0f0f0f0f00000000ull & (x ^ (x << 28)); x ^= t ^ (t >> 28);
+    t = 0x3333000033330000ull & (x ^ (x << 14)); x ^= t ^ (t >> 14);
+    t = 0x5500550055005500ull & (x ^ (x << 7));  x ^= t ^ (t >> 7);
+    return x;
+}
+
+constexpr int kSignWaveElems = 2048;                       // 64 lanes x 32 elements
+constexpr int kSignTile = kSignWaveElems * kWavesPerBlock; // 8192 elements per block
+
+__global__ __launch_bounds__(kBlock) void efsign_decompress_k(GroupView out, PayloadPtrs pl, int W, float alpha, int *status)
+{
+    __shared__ float table[256];
+    __shared__ float stage[kWavesPerBlock][kSignWaveElems + 64];
+    const uint32_t t = threadIdx.x;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(t >> 6), lane = t & 63u;
+    if (blockIdx.x == 0 && (int)t < W)
+        check_header(reinterpret_cast<const PayloadHeader *>(pl.p[t]), MC_ALGO_EFSIGN, out.n, status);
+    const int Wt = W < 8 ? W : 8;
+    {
+        float sc[8];
+#pragma unroll
+        for (int b = 0; b < 8; ++b) sc[b] = b < Wt ? reinterpret_cast<const PayloadHeader *>(pl.p[b])->scale : 0.0f;
+        float acc = 0.0f;
+#pragma unroll
+        for (int b = 0; b < 8; ++b) if (b < Wt) acc = acc + (((t >> b) & 1u) ? sc[b] : -sc[b]);
+        table[t] = W <= 8 ? alpha * acc : acc;
+    }
+    __syncthreads();
+    const uint32_t wbase = blockIdx.x * (uint32_t)kSignTile + wave * (uint32_t)kSignWaveElems;
+    if (wbase >= out.n) return;
+    const uint32_t nwords = (out.n + 31u) >> 5;
+    const uint32_t wi = (wbase >> 5) + lane;
+    uint32_t wd[8];
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+        wd[b] = 0u;
+        if (b < Wt && wi < nwords) wd[b] = ld_stream(reinterpret_cast<const uint32_t *>(pl.p[b] + kHeaderBytes) + wi);
+    }
+    float acc[32];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        // byte q of the 8 words -> rows of an 8x8 bit matrix (row = worker, column = element 8q + c)
+        uint32_t lo = ((wd[0] >> (8 * q)) & 0xFFu) | (((wd[1] >> (8 * q)) & 0xFFu) << 8) |
+                      (((wd[2] >> (8 * q)) & 0xFFu) << 16) | (((wd[3] >> (8 * q)) & 0xFFu) << 24);
+        uint32_t hi = ((wd[4] >> (8 * q)) & 0xFFu) | (((wd[5] >> (8 * q)) & 0xFFu) << 8) |
+                      (((wd[6] >> (8 * q)) & 0xFFu) << 16) | (((wd[7] >> (8 * q)) & 0xFFu) << 24);
+        uint64_t x = transpose8x8((uint64_t)lo | ((uint64_t)hi << 32));
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[8 * q + e] = table[(uint32_t)(x >> (8 * e)) & 0xFFu];
+    }
+    if (W > 8) {
+        for (int w = 8; w < W; ++w) {
+            const float sc = reinterpret_cast<const PayloadHeader *>(pl.p[w])->scale;
+            uint32_t word = wi < nwords ? ld_stream(reinterpret_cast<const uint32_t *>(pl.p[w] + kHeaderBytes) + wi) : 0u;
+#pragma unroll
+            for (int e = 0; e < 32; ++e) acc[e] = acc[e] + (((word >> e) & 1u) ? sc : -sc);
+        }
+#pragma unroll
+        for (int e = 0; e < 32; ++e) acc[e] = alpha * acc[e];
+    }
+    float *mine = stage[wave];
+#pragma unroll
+    for (int e = 0; e < 32; ++e) mine[33 * lane + e] = acc[e];          // element 32 lane + e, skewed by lane
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        Chunk c;
+        c.base = wbase + half * (uint32_t)kChunk;
+        c.lane = lane;
+        c.full = c.base < out.n && out.n - c.base >= (uint32_t)kChunk;
+        if (c.base >= out.n) break;
+        float v[kSteps];
+#pragma unroll
+        for (int j = 0; j < kSteps; ++j) {
+            uint32_t i = half * kChunk + 64 * j + lane;              // element of the wave's 2048
+            v[j] = mine[i + (i >> 5)];
+        }
+        store_seg(out, c, v);
+    }
+}
+
 void launch_dense_decompress(const LaunchCtx &lc, int algo, const GroupView &out, const PayloadPtrs &pl, int W,
                              float alpha, uint32_t levels, int *status)
 {
@@ -496,7 +618,10 @@ void launch_dense_decompress(const LaunchCtx &lc, int algo, const GroupView &out
     dim3 grid(tiles_of(out.n)), block(kBlock);
     prof_begin(lc, K_DENSE_DECOMPRESS);
     switch (algo) {
-    case MC_ALGO_EFSIGN: hipLaunchKernelGGL(dense_decompress_k<MC_ALGO_EFSIGN>, grid, block, 0, lc.stream, out, pl, W, alpha, levels, status); break;
+    case MC_ALGO_EFSIGN:
+        hipLaunchKernelGGL(efsign_decompress_k, dim3((uint32_t)(((uint64_t)out.n + kSignTile - 1) / kSignTile)), block, 0,
+                           lc.stream, out, pl, W, alpha, status);
+        break;
     case MC_ALGO_TERNGRAD: hipLaunchKernelGGL(dense_decompress_k<MC_ALGO_TERNGRAD>, grid, block, 0, lc.stream, out, pl, W, alpha, levels, status); break;
     case MC_ALGO_QSGD: hipLaunchKernelGGL(dense_decompress_k<MC_ALGO_QSGD>, grid, block, 0, lc.stream, out, pl, W, alpha, levels, status); break;
     default: hipLaunchKernelGGL(dense_decompress_k<MC_ALGO_FP16>, grid, block, 0, lc.stream, out, pl, W, alpha, levels, status); break;

@@ -11,10 +11,13 @@
 //                whose key reaches a *hint* (a little below the last threshold of this
 //                group) is copied, in index order, into the candidate slots of its
 //                1024-element chunk, and counted in the level-1 histogram
-//   refill       runs only if fewer than k candidates were found (first call, or the
-//                distribution moved): makes every element a candidate
-//   hist 2, 3    each block first resolves the previous level from its histogram,
-//                then histograms the candidates that match the prefix
+//   plan         one block: lists the non-empty chunks, cuts the candidate sequence into
+//                equal shares (one per wavefront of the later kernels; a few tensors hold
+//                most candidates), resolves radix level 1.  If fewer than k candidates
+//                were found (first call, or the distribution moved) all blocks instead
+//                make every element a candidate (refill)
+//   hist 2, 3    histogram the candidates that match the prefix resolved so far; the
+//                previous level is resolved by every wavefront for itself
 //   count        resolves level 3 (threshold key T, number of keys == T to take),
 //                counts kept candidates per block / wavefront, publishes the next hint
 //   emit         ordered compaction of the kept candidates into (idx, val); kept
@@ -32,6 +35,12 @@ static inline uint32_t tiles_of(uint32_t n) { return (uint32_t)(((uint64_t)n + k
 static inline uint32_t chunks_of(uint32_t n) { return (uint32_t)(((uint64_t)n + kChunk - 1) / kChunk); }
 
 constexpr int kBins1 = 2048, kBins2 = 1024, kBins3 = 1024;
+// Histogram scratch: the three radix levels one after the other.  Global atomics on
+// one address serialise (tens of nanoseconds each on this part), so only the bins
+// themselves are updated -- no shared summary counters -- and a level is resolved
+// by a wavefront that reads all its bins.
+constexpr int kHist1 = 0, kHist2 = kHist1 + kBins1, kHist3 = kHist2 + kBins2;
+static_assert(kHist3 + kBins3 == kHistWords, "histogram scratch layout");
 constexpr uint32_t kHintMargin = 3u << 19;   // 3/16 of an octave below the last threshold
 
 __device__ __forceinline__ uint32_t key_of(float x) { return __float_as_uint(x) & 0x7FFFFFFFu; }
@@ -46,11 +55,12 @@ __device__ __forceinline__ Chunk chunk_at(uint32_t tile, uint32_t n)
     return c;
 }
 
-__device__ __forceinline__ void flush_hist(const uint32_t *lds, uint32_t *global, int bins)
+// add a block's LDS histogram to the global one (fine bins only)
+__device__ __forceinline__ void flush_fine(const uint32_t *lds, uint32_t *fine, int bins)
 {
-    for (int b = threadIdx.x; b < bins; b += kBlock) {
+    for (int b = threadIdx.x; b < bins; b += blockDim.x) {
         uint32_t h = lds[b];
-        if (h) atomicAdd(&global[b], h);
+        if (h) atomicAdd(&fine[b], h);
     }
 }
 
@@ -88,13 +98,13 @@ __global__ __launch_bounds__(kBlock) void sparse_accum_k(GroupView g, float *st,
     uint32_t run = 0;
     if (c.base < g.n) {
         float p[kSteps];
-        load_seg(g, c, p);
         if (ALGO == MC_ALGO_DGC) {
             // momentum correction: u = m u + g ; v = v + u ; the vector compressed is v
             float *vbuf = st, *ubuf = st + g.n;
             float u[kSteps], v[kSteps];
             load_flat(ubuf, c, g.n, u, 0.0f);
             load_flat(vbuf, c, g.n, v, 0.0f);
+            load_seg(g, c, p);
 #pragma unroll
             for (int j = 0; j < kSteps; ++j) {
                 float mu = momentum * u[j];
@@ -107,9 +117,12 @@ __global__ __launch_bounds__(kBlock) void sparse_accum_k(GroupView g, float *st,
         } else if (EF) {
             float e[kSteps];
             load_flat(st, c, g.n, e, 0.0f);
+            load_seg(g, c, p);
 #pragma unroll
             for (int j = 0; j < kSteps; ++j) p[j] = p[j] + e[j];
             store_flat(st, c, g.n, p);
+        } else {
+            load_seg(g, c, p);
         }
         uint64_t flag[kSteps];
 #pragma unroll
@@ -118,84 +131,34 @@ __global__ __launch_bounds__(kBlock) void sparse_accum_k(GroupView g, float *st,
             flag[j] = __builtin_amdgcn_ballot_w64(valid && key_of(p[j]) >= hint);
         }
         run = put_candidates(c, p, flag, sc.cand_bits, sc.cand_loc, hist);
-        if (c.lane == 0) sc.run[c.base >> 10] = run;
     }
     if (c.lane == 0) wcnt[threadIdx.x >> 6] = run;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t t = wcnt[0] + wcnt[1] + wcnt[2] + wcnt[3];
-        if (t) atomicAdd(sc.total, (unsigned long long)t);
-    }
-    flush_hist(hist, sc.hist, kBins1);
-}
-
-// the vector the selection works on: v / p kept in the state, or the gradient itself
-template <bool FROM_STATE>
-__device__ __forceinline__ void load_sel(const GroupView &g, const float *st, const Chunk &c, float (&p)[kSteps])
-{
-    if (FROM_STATE) load_flat(st, c, g.n, p, 0.0f);
-    else load_seg(g, c, p);
+    if (threadIdx.x == 0)       // candidates of the tile's four chunks, 16 bits each (a chunk holds at most 1024)
+        sc.tile_runs[blockIdx.x] = (uint64_t)wcnt[0] | ((uint64_t)wcnt[1] << 16) | ((uint64_t)wcnt[2] << 32) | ((uint64_t)wcnt[3] << 48);
+    flush_fine(hist, sc.hist + kHist1, kBins1);
 }
 
 // ---------------------------------------------------------------------------
-// refill: only if the hint left fewer than k candidates.  Every element becomes a
-// candidate; the elements below the hint (not counted yet) join the histogram.
+// Resolve one radix level by a whole block from the fine bins: find the bin b with
+//   count(bins > b) < need <= count(bins >= b)        and  rest = need - count(bins > b).
+// Result through LDS: out[0] = bin, out[1..2] = rest (lo, hi).  THREADS = blockDim.x.
 // ---------------------------------------------------------------------------
-template <bool FROM_STATE>
-__global__ __launch_bounds__(kBlock) void sparse_refill_k(GroupView g, const float *st, uint64_t k, SparseScratch sc)
-{
-    __shared__ uint32_t hist[kBins1];
-    if (*sc.total >= k) return;
-    for (int b = threadIdx.x; b < kBins1; b += kBlock) hist[b] = 0u;
-    __syncthreads();
-    const uint32_t hint = *sc.hint;
-    const uint32_t ntiles = (g.n + (uint32_t)kTile - 1u) / (uint32_t)kTile;
-    for (uint32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const Chunk c = chunk_at(tile, g.n);
-        if (c.base >= g.n) continue;
-        float p[kSteps];
-        load_sel<FROM_STATE>(g, st, c, p);
-        uint32_t cnt = 0;
-#pragma unroll
-        for (int j = 0; j < kSteps; ++j) {
-            uint32_t i = c.base + 64 * j + c.lane;
-            if (c.full || i < g.n) {
-                sc.cand_bits[i] = __float_as_uint(p[j]);
-                sc.cand_loc[i] = (uint16_t)(64 * j + c.lane);
-                if (key_of(p[j]) < hint) atomicAdd(&hist[key_of(p[j]) >> 20], 1u);
-                cnt = 64 * j + c.lane + 1;
-            }
-        }
-        // elements of the chunk = largest valid local index + 1, held by the last valid lane
-        uint32_t m = cnt;
-#pragma unroll
-        for (int s = 32; s >= 1; s >>= 1) { uint32_t o = __shfl_xor(m, s, 64); m = o > m ? o : m; }
-        if (c.lane == 0) sc.run[c.base >> 10] = m;
-    }
-    __syncthreads();
-    flush_hist(hist, sc.hist, kBins1);
-}
-
-// ---------------------------------------------------------------------------
-// Resolve one radix level, by every thread block for itself: find the bin b with
-//   count(bins > b) < need <= count(bins >= b)
-// Returns through LDS: out[0] = bin, out[1..2] = need - count(bins > b) (lo, hi).
-// ---------------------------------------------------------------------------
-template <int BINS>
-__device__ __forceinline__ void resolve_level(const uint32_t *ghist, uint64_t need, uint64_t *above /* kBlock */,
+template <int BINS, int THREADS>
+__device__ __forceinline__ void resolve_block(const uint32_t *fine, uint64_t need, uint64_t *above /* THREADS */,
                                               uint32_t *out /* 3 */)
 {
-    constexpr int kPer = BINS / kBlock;
+    constexpr int kPer = BINS / THREADS;
     const int t = threadIdx.x;
     uint32_t h[kPer];
     uint64_t own = 0;
 #pragma unroll
-    for (int i = 0; i < kPer; ++i) { h[i] = ghist[t * kPer + i]; own += h[i]; }
+    for (int i = 0; i < kPer; ++i) { h[i] = fine[t * kPer + i]; own += h[i]; }
     if (t == 0) { out[0] = 0u; out[1] = 0u; out[2] = 0u; }    // defined result even for an inconsistent histogram
     above[t] = own;
     __syncthreads();
-    for (int d = 1; d < kBlock; d <<= 1) {               // inclusive suffix sum over threads
-        uint64_t add = t + d < kBlock ? above[t + d] : 0;
+    for (int d = 1; d < THREADS; d <<= 1) {              // inclusive suffix sum over threads
+        uint64_t add = t + d < THREADS ? above[t + d] : 0;
         __syncthreads();
         above[t] += add;
         __syncthreads();
@@ -216,100 +179,346 @@ __device__ __forceinline__ void resolve_level(const uint32_t *ghist, uint64_t ne
     __syncthreads();
 }
 
-// chunks [first, last) owned by a block of the candidate kernels, and by each of its wavefronts
-struct ChunkRange { uint32_t first, last; };
-__device__ __forceinline__ ChunkRange wave_range(uint32_t nchunks, uint32_t per_wave)
+// ---------------------------------------------------------------------------
+// Resolve one radix level inside a wavefront: every lane reads BINS / 64 adjacent
+// bins (one vector load), a suffix scan over the lanes finds the lane where the
+// running count crosses `need`, and that lane walks its own bins.  One memory
+// latency, no block barrier.
+// ---------------------------------------------------------------------------
+template <int BINS>
+__device__ __forceinline__ void resolve_wave(const uint32_t *fine, uint64_t need, uint32_t &bin, uint64_t &rest)
 {
-    uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    uint64_t first = ((uint64_t)blockIdx.x * kWavesPerBlock + wave) * per_wave;
-    ChunkRange r;
-    r.first = first < nchunks ? (uint32_t)first : nchunks;
-    r.last = first + per_wave < nchunks ? (uint32_t)(first + per_wave) : nchunks;
-    return r;
+    constexpr int kPer = BINS / 64;
+    const uint32_t lane = threadIdx.x & 63u;
+    uint32_t h[kPer];
+    uint64_t own = 0;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) { h[i] = fine[lane * kPer + i]; own += h[i]; }
+    uint64_t incl = own;                                    // inclusive suffix sum over lanes
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        uint64_t o = __shfl_down(incl, d, 64);
+        if (lane + d < 64) incl += o;
+    }
+    uint64_t run = incl - own;                              // keys in the bins of higher lanes
+    const bool mine = run < need && need <= incl;
+    uint32_t b = 0;
+    uint64_t r = 0;
+    if (mine) {
+#pragma unroll
+        for (int i = kPer - 1; i >= 0; --i) {
+            if (run < need && need <= run + h[i]) { b = lane * kPer + i; r = need - run; }
+            run += h[i];
+        }
+    }
+    const uint64_t hit = __builtin_amdgcn_ballot_w64(mine);
+    const uint32_t src = hit ? (uint32_t)__builtin_ctzll(hit) : 0u;     // an inconsistent histogram still gives a defined bin
+    bin = __shfl(b, src, 64);
+    rest = __shfl(r, src, 64);
+}
+
+// the vector the selection works on: v / p kept in the state, or the gradient itself
+template <bool FROM_STATE>
+__device__ __forceinline__ void load_sel(const GroupView &g, const float *st, const Chunk &c, float (&p)[kSteps])
+{
+    if (FROM_STATE) load_flat(st, c, g.n, p, 0.0f);
+    else load_seg(g, c, p);
+}
+
+// ---------------------------------------------------------------------------
+// plan (one block works) or refill (all blocks work), 1024 threads per block.
+//
+// plan: the candidates sit in per-chunk slots, very unevenly (a few tensors hold
+// most of them).  One block scans the per-tile counts and lists the non-empty
+// tiles with their running candidate numbers, cuts the candidate sequence into
+// equal shares, one per wavefront of the later kernels, and resolves radix level 1.
+//
+// refill: runs instead if the hint left fewer than k candidates.  Every element
+// becomes a candidate (chunk c holds candidates 1024 c ...), the elements below the
+// hint join the level-1 histogram, and level 1 is resolved by the next kernel.
+// ---------------------------------------------------------------------------
+constexpr int kPlanThreads = 1024;
+constexpr int kPlanPer = 16;          // tile counts a thread keeps in registers (covers 2^26 elements per group)
+
+__device__ __forceinline__ uint32_t runs_total(uint64_t runs)
+{
+    return (uint32_t)(runs & 0xFFFFu) + (uint32_t)((runs >> 16) & 0xFFFFu) + (uint32_t)((runs >> 32) & 0xFFFFu) + (uint32_t)(runs >> 48);
+}
+
+template <bool FROM_STATE>
+__global__ __launch_bounds__(kPlanThreads) void sparse_plan_k(GroupView g, const float *st, uint64_t k, uint32_t nwaves,
+                                                              SparseScratch sc)
+{
+    __shared__ uint32_t hist[kBins1];
+    __shared__ uint32_t wsum[kPlanThreads / 64];
+    __shared__ uint32_t wsum_ne[kPlanThreads / 64];
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    const uint32_t nch = (g.n + (uint32_t)kChunk - 1u) / (uint32_t)kChunk;
+    const uint32_t ntiles = (g.n + (uint32_t)kTile - 1u) / (uint32_t)kTile;
+    // ---- every block: candidates and non-empty tiles before each thread's run of tiles
+    const uint32_t per = (ntiles + kPlanThreads - 1) / kPlanThreads;
+    const uint32_t lo = t * per < ntiles ? t * per : ntiles;
+    const uint32_t hi = lo + per < ntiles ? lo + per : ntiles;
+    const bool in_regs = per <= (uint32_t)kPlanPer;
+    uint64_t r[kPlanPer];
+    uint32_t own = 0, own_ne = 0;               // candidate numbers fit 32 bits: a group has fewer than 2^32 elements
+    if (in_regs) {
+#pragma unroll
+        for (int i = 0; i < kPlanPer; ++i) r[i] = lo + i < hi ? sc.tile_runs[lo + i] : 0ull;   // all loads in flight at once
+#pragma unroll
+        for (int i = 0; i < kPlanPer; ++i) { own += runs_total(r[i]); own_ne += r[i] != 0ull; }
+    } else {
+        for (uint32_t c = lo; c < hi; ++c) { uint64_t x = sc.tile_runs[c]; own += runs_total(x); own_ne += x != 0ull; }
+    }
+    uint32_t incl = own, incl_ne = own_ne;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        uint32_t a = __shfl_up(incl, d, 64), b = __shfl_up(incl_ne, d, 64);
+        if (lane >= (uint32_t)d) { incl += a; incl_ne += b; }
+    }
+    if (lane == 63) { wsum[wave] = incl; wsum_ne[wave] = incl_ne; }
+    __syncthreads();
+    uint32_t p = incl - own, total = 0, q = incl_ne - own_ne, nonempty = 0;
+#pragma unroll
+    for (int w = 0; w < kPlanThreads / 64; ++w) {
+        if ((uint32_t)w < wave) { p += wsum[w]; q += wsum_ne[w]; }
+        total += wsum[w]; nonempty += wsum_ne[w];
+    }
+    if ((uint64_t)total >= k) {
+        if (blockIdx.x != 0) return;
+        // ---- plan
+        const uint32_t share = total ? (total + nwaves - 1) / nwaves : 1u;
+        auto place = [&](uint32_t tile, uint64_t runs) {
+            if (runs) {
+                const uint32_t cnt = runs_total(runs);
+                sc.ne_tile[q] = tile;
+                sc.ne_prefix[q] = p;
+                sc.ne_runs[q] = runs;
+                // wavefront j starts at candidate j * share: inside this tile if p <= j * share < p + cnt
+                for (uint64_t j = (p + share - 1) / share; j * share < (uint64_t)p + cnt; ++j) sc.wave_start[j] = q;
+                ++q;
+                p += cnt;
+            }
+        };
+        if (in_regs) {
+#pragma unroll
+            for (int i = 0; i < kPlanPer; ++i) place(lo + i, r[i]);
+        } else {
+            for (uint32_t c = lo; c < hi; ++c) place(c, sc.tile_runs[c]);
+        }
+        if (t == 0) sc.ne_prefix[nonempty] = total;
+        for (uint32_t j = t; j <= nwaves; j += kPlanThreads)
+            if ((uint64_t)j * share >= total) sc.wave_start[j] = nonempty;
+        // ---- radix level 1 (need = k) from the bins the accumulate kernel filled
+        if (wave == 0) {
+            uint32_t bin;
+            uint64_t rest;
+            resolve_wave<kBins1>(sc.hist + kHist1, k, bin, rest);
+            if (lane == 0) {
+                PlanState pl;
+                pl.total = total; pl.nonempty = nonempty; pl.share = share; pl.uniform = 0;
+                *sc.plan = pl;
+                SelectState s;
+                s.prefix = bin << 20; s.pad0 = 0; s.need = rest;
+                sc.sel[1] = s;
+            }
+        }
+        return;
+    }
+    // ---- refill
+    for (int b = t; b < kBins1; b += kPlanThreads) hist[b] = 0u;
+    __syncthreads();
+    const uint32_t hint = *sc.hint;
+    const uint32_t uwave = __builtin_amdgcn_readfirstlane(wave), waves = kPlanThreads / 64;
+    for (uint32_t ch = blockIdx.x * waves + uwave; ch < nch; ch += gridDim.x * waves) {
+        Chunk c;
+        c.base = ch * (uint32_t)kChunk;
+        c.lane = lane;
+        c.full = g.n - c.base >= (uint32_t)kChunk;
+        float v[kSteps];
+        load_sel<FROM_STATE>(g, st, c, v);
+#pragma unroll
+        for (int j = 0; j < kSteps; ++j) {
+            uint32_t i = c.base + 64 * j + c.lane;
+            if (c.full || i < g.n) {
+                sc.cand_bits[i] = __float_as_uint(v[j]);
+                sc.cand_loc[i] = (uint16_t)(64 * j + c.lane);
+                if (key_of(v[j]) < hint) atomicAdd(&hist[key_of(v[j]) >> 20], 1u);
+            }
+        }
+    }
+    __syncthreads();
+    flush_fine(hist, sc.hist + kHist1, kBins1);
+    if (blockIdx.x == 0 && t == 0) {
+        PlanState pl;
+        pl.total = g.n; pl.nonempty = ntiles; pl.share = (g.n + nwaves - 1) / nwaves; pl.uniform = 1;
+        *sc.plan = pl;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Walk one wavefront's share of the candidates, in index order.  The share is a
+// range of candidate numbers; the plan says in which non-empty tile it starts.
+// A window of 63 non-empty tiles (ids, first candidate numbers, per-chunk counts) is held
+// in LDS; every lane finds its candidate's chunk by binary search there; four
+// rounds of 64 candidates are fetched together, so the wavefront pays the memory
+// latency once per 256 candidates.
+// `body(valid, chunk, bits, loc)` is called by all 64 lanes (it may use ballots).
+// ---------------------------------------------------------------------------
+struct CandWindow { uint32_t first[64]; uint32_t tile[64]; uint64_t runs[64]; };
+
+template <bool WITH_LOC, typename Body>
+__device__ __forceinline__ void for_each_candidate(const SparseScratch &sc, uint32_t n, CandWindow *win /* LDS, per wavefront */,
+                                                   Body body)
+{
+    constexpr int kRounds = 4;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t w = blockIdx.x * kWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint64_t total = sc.plan->total;
+    const uint32_t share = sc.plan->share, uniform = sc.plan->uniform, nonempty = sc.plan->nonempty;
+    const uint64_t f_lo = (uint64_t)w * share;
+    if (f_lo >= total) return;
+    const uint64_t f_hi = f_lo + share < total ? f_lo + share : total;
+    uint32_t q0 = uniform ? (uint32_t)(f_lo >> 12) : sc.wave_start[w];
+    for (;;) {
+        const uint32_t q = q0 + lane < nonempty ? q0 + lane : nonempty;
+        uint32_t first, tile;
+        uint64_t runs = 0;
+        if (uniform) { first = q < nonempty ? q * (uint32_t)kTile : n; tile = q; }
+        else {
+            first = sc.ne_prefix[q];
+            tile = q < nonempty ? sc.ne_tile[q] : 0u;
+            runs = q < nonempty ? sc.ne_runs[q] : 0ull;
+        }
+        __builtin_amdgcn_wave_barrier();
+        win->first[lane] = first;
+        win->tile[lane] = tile;
+        win->runs[lane] = runs;
+        __builtin_amdgcn_wave_barrier();
+        const uint64_t win_lo = __builtin_amdgcn_readlane(first, 0), win_hi = __builtin_amdgcn_readlane(first, 63);
+        const uint64_t a = f_lo > win_lo ? f_lo : win_lo, b = f_hi < win_hi ? f_hi : win_hi;
+        for (uint64_t f0 = a; f0 < b; f0 += 64 * kRounds) {
+            uint32_t ch[kRounds], bits[kRounds], loc[kRounds];
+            size_t slot[kRounds];
+            bool valid[kRounds];
+#pragma unroll
+            for (int u = 0; u < kRounds; ++u) {
+                const uint64_t f = f0 + 64 * u + lane;
+                valid[u] = f < b;
+                const uint32_t f32 = (uint32_t)f;
+                uint32_t ci = 0;
+#pragma unroll
+                for (int step = 32; step >= 1; step >>= 1)
+                    if (valid[u] && win->first[ci + step] <= f32) ci += step;   // ci + step <= 63; f < first[63] keeps ci <= 62
+                uint32_t off = valid[u] ? f32 - win->first[ci] : 0u;            // candidate number inside the tile
+                uint32_t sub;                                                    // chunk of the tile, then slot inside it
+                if (uniform) { sub = off >> 10; off &= 1023u; }
+                else {
+                    const uint64_t rr = win->runs[ci];
+                    const uint32_t r0 = (uint32_t)(rr & 0xFFFFu), r1 = r0 + (uint32_t)((rr >> 16) & 0xFFFFu),
+                                   r2 = r1 + (uint32_t)((rr >> 32) & 0xFFFFu);
+                    sub = (off >= r0) + (off >= r1) + (off >= r2);
+                    off -= sub == 0 ? 0u : sub == 1 ? r0 : sub == 2 ? r1 : r2;
+                }
+                ch[u] = win->tile[ci] * kWavesPerBlock + sub;
+                slot[u] = valid[u] ? (size_t)ch[u] * kChunk + off : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < kRounds; ++u) {
+                bits[u] = sc.cand_bits[slot[u]];
+                loc[u] = WITH_LOC ? sc.cand_loc[slot[u]] : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < kRounds; ++u)
+                if (f0 + 64 * u < b) body(valid[u], ch[u], bits[u], loc[u]);
+        }
+        if (win_hi >= f_hi || q0 + 63 >= nonempty) break;
+        q0 += 63;
+    }
 }
 
 // ---------------------------------------------------------------------------
 // level 2 / level 3 histogram over the candidates
-//   LEVEL 2: resolves level 1 (2048 bins, need = k), histograms bits 19..10 of matching keys
-//   LEVEL 3: resolves level 2 (1024 bins), histograms bits 9..0
+//   LEVEL 2: level 1 comes resolved from the plan (after a refill: resolved here, by the block),
+//            histograms bits 19..10 of the matching keys
+//   LEVEL 3: resolves level 2 (1024 bins, per wavefront), histograms bits 9..0
 // Block 0 records the resolved prefix for the next kernel and clears the histogram
 // that the previous kernel has finished reading.
 // ---------------------------------------------------------------------------
 template <int LEVEL>
-__global__ __launch_bounds__(kBlock) void cand_hist_k(uint32_t nchunks, uint32_t per_wave, uint64_t k, SparseScratch sc)
+__global__ __launch_bounds__(kBlock) void cand_hist_k(uint32_t n, uint64_t k, SparseScratch sc)
 {
     __shared__ uint32_t hist[1024];
+    __shared__ CandWindow win[kWavesPerBlock];
     __shared__ uint64_t above[kBlock];
     __shared__ uint32_t res[3];
     for (int b = threadIdx.x; b < 1024; b += kBlock) hist[b] = 0u;
-    uint32_t *h1 = sc.hist, *h2 = sc.hist + kBins1, *h3 = h2 + kBins2;
     uint32_t prefix;
     if (LEVEL == 2) {
-        resolve_level<kBins1>(h1, k, above, res);
-        prefix = res[0] << 20;
+        if (sc.plan->uniform) {                       // after a refill nobody has resolved level 1 yet
+            resolve_block<kBins1, kBlock>(sc.hist + kHist1, k, above, res);
+            prefix = res[0] << 20;
+            if (blockIdx.x == 0 && threadIdx.x == 0) {
+                SelectState s;
+                s.prefix = prefix; s.pad0 = 0; s.need = (uint64_t)res[1] | ((uint64_t)res[2] << 32);
+                sc.sel[1] = s;
+            }
+        } else prefix = sc.sel[1].prefix;
     } else {
         const SelectState s1 = sc.sel[1];
-        resolve_level<kBins2>(h2, s1.need, above, res);
-        prefix = s1.prefix | (res[0] << 10);
-    }
-    if (blockIdx.x == 0) {
-        if (threadIdx.x == 0) {
-            SelectState s;
-            s.prefix = prefix; s.pad0 = 0; s.need = (uint64_t)res[1] | ((uint64_t)res[2] << 32);
-            sc.sel[LEVEL == 2 ? 1 : 2] = s;
-        }
-        if (LEVEL == 3) for (int b = threadIdx.x; b < kBins1; b += kBlock) h1[b] = 0u;   // level 2 is done with it
-    }
-    constexpr int kMatchShift = LEVEL == 2 ? 20 : 10;
-    const uint32_t want = prefix >> kMatchShift;
-    const ChunkRange r = wave_range(nchunks, per_wave);
-    const uint32_t lane = threadIdx.x & 63u;
-    for (uint32_t ch = r.first; ch < r.last; ++ch) {
-        const uint32_t cnt = sc.run[ch];
-        const uint32_t *bits = sc.cand_bits + (size_t)ch * kChunk;
-        for (uint32_t e = lane; e < cnt; e += 64) {
-            uint32_t key = bits[e] & 0x7FFFFFFFu;
-            if ((key >> kMatchShift) == want) atomicAdd(&hist[(key >> (kMatchShift - 10)) & 1023u], 1u);
+        uint32_t bin;
+        uint64_t rest;
+        resolve_wave<kBins2>(sc.hist + kHist2, s1.need, bin, rest);
+        prefix = s1.prefix | (bin << 10);
+        if (blockIdx.x == 0) {
+            if (threadIdx.x == 0) {
+                SelectState s;
+                s.prefix = prefix; s.pad0 = 0; s.need = rest;
+                sc.sel[2] = s;
+            }
+            for (int b = threadIdx.x; b < kHist2 - kHist1; b += kBlock) sc.hist[kHist1 + b] = 0u;   // level 2 is done with level 1
         }
     }
     __syncthreads();
-    flush_hist(hist, LEVEL == 2 ? h2 : h3, 1024);
+    constexpr int kMatchShift = LEVEL == 2 ? 20 : 10;
+    const uint32_t want = prefix >> kMatchShift;
+    for_each_candidate<false>(sc, n, &win[threadIdx.x >> 6], [&](bool valid, uint32_t, uint32_t bits, uint32_t) {
+        uint32_t key = bits & 0x7FFFFFFFu;
+        if (valid && (key >> kMatchShift) == want) atomicAdd(&hist[(key >> (kMatchShift - 10)) & 1023u], 1u);
+    });
+    __syncthreads();
+    flush_fine(hist, sc.hist + (LEVEL == 2 ? kHist2 : kHist3), 1024);
 }
 
 // ---------------------------------------------------------------------------
 // count: resolve level 3 -> threshold key T and `need` (keys == T to take, in
 // index order); kept candidates per wavefront and per block.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void cand_count_k(uint32_t nchunks, uint32_t per_wave, SparseScratch sc)
+__global__ __launch_bounds__(kBlock) void cand_count_k(uint32_t n, SparseScratch sc)
 {
-    __shared__ uint64_t above[kBlock];
-    __shared__ uint32_t res[3];
     __shared__ uint32_t wgt[kWavesPerBlock], weq[kWavesPerBlock];
+    __shared__ CandWindow win[kWavesPerBlock];
     const SelectState s2 = sc.sel[2];
-    resolve_level<kBins3>(sc.hist + kBins1 + kBins2, s2.need, above, res);
-    const uint32_t T = s2.prefix | res[0];
+    uint32_t bin;
+    uint64_t rest;
+    resolve_wave<kBins3>(sc.hist + kHist3, s2.need, bin, rest);
+    const uint32_t T = s2.prefix | bin;
     if (blockIdx.x == 0) {
         if (threadIdx.x == 0) {
             SelectState s;
-            s.prefix = T; s.pad0 = 0; s.need = (uint64_t)res[1] | ((uint64_t)res[2] << 32);
+            s.prefix = T; s.pad0 = 0; s.need = rest;
             sc.sel[3] = s;
             *sc.hint = T > kHintMargin ? T - kHintMargin : 0u;      // where the next call starts filtering
         }
-        for (int b = threadIdx.x; b < kBins2; b += kBlock) sc.hist[kBins1 + b] = 0u;      // level 3 is done with it
+        for (int b = threadIdx.x; b < kHist3 - kHist2; b += kBlock) sc.hist[kHist2 + b] = 0u;   // level 3 is done with level 2
     }
-    const ChunkRange r = wave_range(nchunks, per_wave);
     const uint32_t lane = threadIdx.x & 63u;
     uint32_t ngt = 0, neq = 0;
-    for (uint32_t ch = r.first; ch < r.last; ++ch) {
-        const uint32_t cnt = sc.run[ch];
-        const uint32_t *bits = sc.cand_bits + (size_t)ch * kChunk;
-        for (uint32_t e0 = 0; e0 < cnt; e0 += 64) {
-            uint32_t e = e0 + lane;
-            uint32_t key = e < cnt ? bits[e] & 0x7FFFFFFFu : 0u;
-            ngt += __popcll(__builtin_amdgcn_ballot_w64(e < cnt && key > T));
-            neq += __popcll(__builtin_amdgcn_ballot_w64(e < cnt && key == T));
-        }
-    }
+    for_each_candidate<false>(sc, n, &win[threadIdx.x >> 6], [&](bool valid, uint32_t, uint32_t bits, uint32_t) {
+        uint32_t key = bits & 0x7FFFFFFFu;
+        ngt += __popcll(__builtin_amdgcn_ballot_w64(valid && key > T));
+        neq += __popcll(__builtin_amdgcn_ballot_w64(valid && key == T));
+    });
     const uint32_t wave = threadIdx.x >> 6;
     if (lane == 0) {
         wgt[wave] = ngt; weq[wave] = neq;
@@ -330,79 +539,80 @@ __global__ __launch_bounds__(kBlock) void cand_count_k(uint32_t nchunks, uint32_
 // Every block adds up the counts of the blocks before it; nothing waits.
 // ---------------------------------------------------------------------------
 template <int ALGO, bool EF>
-__global__ __launch_bounds__(kBlock) void cand_emit_k(uint32_t n, uint32_t nchunks, uint32_t per_wave, float *st,
-                                                      PayloadHeader *hdr, uint64_t k, SparseScratch sc)
+__global__ __launch_bounds__(kBlock) void cand_emit_k(uint32_t n, float *st, PayloadHeader *hdr, uint64_t k, SparseScratch sc)
 {
-    __shared__ uint64_t sgt[kBlock], seq[kBlock];
+    __shared__ uint64_t sgt[kWavesPerBlock], seq[kWavesPerBlock];
+    __shared__ CandWindow win[kWavesPerBlock];
     const SelectState s3 = sc.sel[3];
     const uint32_t T = s3.prefix;
     const uint64_t need = s3.need;
     uint32_t *idx = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(hdr) + kHeaderBytes);
     float *val = reinterpret_cast<float *>(idx + k);
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t lane = threadIdx.x & 63u;
+    // kept-before of this block: sum over the blocks before it (at most 1024), four loads per thread
+    uint64_t ag = 0, ae = 0;
+    {
+        uint32_t vg[4], ve[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            uint32_t b = u * kBlock + threadIdx.x;
+            vg[u] = b < blockIdx.x ? sc.blk_gt[b] : 0u;
+            ve[u] = b < blockIdx.x ? sc.blk_eq[b] : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { ag += vg[u]; ae += ve[u]; }
+    }
+    // kept-before of this wavefront inside the block
+    uint64_t wg = 0, we = 0;
+    if (lane < wave) {
+        wg = sc.wave_gt[blockIdx.x * kWavesPerBlock + lane];
+        we = sc.wave_eq[blockIdx.x * kWavesPerBlock + lane];
+    }
     if (blockIdx.x == 0) {
         if (threadIdx.x == 0) {
             PayloadHeader h;
             h.magic = kMagic; h.algo = ALGO; h.n = n; h.k = k; h.scale = 0.0f; h.levels = 0;
             for (int i = 0; i < 8; ++i) h.pad[i] = 0;
             *hdr = h;
-            *sc.total = 0ull;
         }
-        for (int b = threadIdx.x; b < kBins3; b += kBlock) sc.hist[kBins1 + kBins2 + b] = 0u;   // count is done with it
+        for (int b = threadIdx.x; b < kHistWords - kHist3; b += kBlock) sc.hist[kHist3 + b] = 0u;   // count is done with level 3
     }
-    // kept-before of this block: sum over the blocks before it
-    uint64_t ag = 0, ae = 0;
-    for (uint32_t b = threadIdx.x; b < blockIdx.x; b += kBlock) { ag += sc.blk_gt[b]; ae += sc.blk_eq[b]; }
-    sgt[threadIdx.x] = ag; seq[threadIdx.x] = ae;
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+        ag += __shfl_xor(ag, m, 64); ae += __shfl_xor(ae, m, 64);
+        wg += __shfl_xor(wg, m, 64); we += __shfl_xor(we, m, 64);
+    }
+    if (lane == 0) { sgt[wave] = ag; seq[wave] = ae; }
     __syncthreads();
-    for (int s = kBlock / 2; s >= 1; s >>= 1) {
-        if ((int)threadIdx.x < s) { sgt[threadIdx.x] += sgt[threadIdx.x + s]; seq[threadIdx.x] += seq[threadIdx.x + s]; }
-        __syncthreads();
-    }
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    uint64_t gt_before = sgt[0], eq_before = seq[0];
-    for (uint32_t w = 0; w < wave; ++w) {
-        gt_before += sc.wave_gt[blockIdx.x * kWavesPerBlock + w];
-        eq_before += sc.wave_eq[blockIdx.x * kWavesPerBlock + w];
-    }
-    const ChunkRange r = wave_range(nchunks, per_wave);
-    const uint32_t lane = threadIdx.x & 63u;
-    for (uint32_t ch = r.first; ch < r.last; ++ch) {
-        const uint32_t cnt = sc.run[ch];
-        const uint32_t *bits = sc.cand_bits + (size_t)ch * kChunk;
-        const uint16_t *loc = sc.cand_loc + (size_t)ch * kChunk;
-        for (uint32_t e0 = 0; e0 < cnt; e0 += 64) {
-            uint32_t e = e0 + lane;
-            uint32_t b = e < cnt ? bits[e] : 0u;
-            uint32_t key = b & 0x7FFFFFFFu;
-            bool is_gt = e < cnt && key > T, is_eq = e < cnt && key == T;
-            uint64_t bgt = __builtin_amdgcn_ballot_w64(is_gt), beq = __builtin_amdgcn_ballot_w64(is_eq);
-            uint64_t gtb = gt_before + lanes_below(bgt), eqb = eq_before + lanes_below(beq);
-            if (is_gt || (is_eq && eqb < need)) {
-                uint64_t pos = gtb + (eqb < need ? eqb : need);
-                uint32_t i = ch * (uint32_t)kChunk + loc[e];
-                if (pos < k && i < n) {                  // always true for consistent scratch; guards the buffers
-                    idx[pos] = i;
-                    val[pos] = __uint_as_float(b);
-                    if (ALGO == MC_ALGO_DGC) { st[i] = 0.0f; st[(size_t)n + i] = 0.0f; }   // momentum factor masking
-                    else if (EF) st[i] = 0.0f;
-                }
+    uint64_t gt_before = (sgt[0] + sgt[1]) + (sgt[2] + sgt[3]) + wg;
+    uint64_t eq_before = (seq[0] + seq[1]) + (seq[2] + seq[3]) + we;
+    for_each_candidate<true>(sc, n, &win[wave], [&](bool valid, uint32_t chunk, uint32_t b, uint32_t loc) {
+        const uint32_t key = b & 0x7FFFFFFFu;
+        const bool is_gt = valid && key > T, is_eq = valid && key == T;
+        const uint64_t bgt = __builtin_amdgcn_ballot_w64(is_gt), beq = __builtin_amdgcn_ballot_w64(is_eq);
+        const uint64_t gtb = gt_before + lanes_below(bgt), eqb = eq_before + lanes_below(beq);
+        if (is_gt || (is_eq && eqb < need)) {
+            const uint64_t pos = gtb + (eqb < need ? eqb : need);
+            const uint32_t i = chunk * (uint32_t)kChunk + loc;
+            if (pos < k && i < n) {                  // always true for consistent scratch; guards the buffers
+                idx[pos] = i;
+                val[pos] = __uint_as_float(b);
+                if (ALGO == MC_ALGO_DGC) { st[i] = 0.0f; st[(size_t)n + i] = 0.0f; }   // momentum factor masking
+                else if (EF) st[i] = 0.0f;
             }
-            gt_before += __popcll(bgt);
-            eq_before += __popcll(beq);
         }
-    }
+        gt_before += __popcll(bgt);
+        eq_before += __popcll(beq);
+    });
 }
 
-// geometry of the candidate kernels: at most 1024 blocks, each wavefront a contiguous run of chunks
-static inline void cand_geometry(uint32_t nchunks, uint32_t *blocks, uint32_t *per_wave)
+// grid of the kernels that walk the candidates: one wavefront per share, at most kMaxCandBlocks blocks
+static inline uint32_t cand_blocks(uint32_t nchunks)
 {
-    const uint32_t max_waves = kMaxCandBlocks * kWavesPerBlock;
-    uint32_t pw = (nchunks + max_waves - 1) / max_waves;
-    if (pw < 1) pw = 1;
-    uint32_t waves = (nchunks + pw - 1) / pw;
-    *per_wave = pw;
-    *blocks = (waves + kWavesPerBlock - 1) / kWavesPerBlock;
-    if (*blocks < 1) *blocks = 1;
+    uint32_t b = (nchunks + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (b < 1) b = 1;
+    return b < kMaxCandBlocks ? b : kMaxCandBlocks;
 }
 
 template <int ALGO, bool EF>
@@ -411,26 +621,26 @@ static void sparse_compress_t(const LaunchCtx &lc, const GroupView &g, float *st
 {
     constexpr bool FS = (ALGO == MC_ALGO_DGC) || EF;
     const uint32_t nt = tiles_of(g.n), nch = chunks_of(g.n);
-    uint32_t cblocks, per_wave;
-    cand_geometry(nch, &cblocks, &per_wave);
-    dim3 grid(nt), block(kBlock), cgrid(cblocks), rgrid(nt < 1024 ? nt : 1024);
+    const uint32_t cblocks = cand_blocks(nch), nwaves = cblocks * kWavesPerBlock;
+    const uint32_t pblocks = (nch + 15) / 16 < 256 ? (nch + 15) / 16 : 256;
+    dim3 grid(nt), block(kBlock), cgrid(cblocks);
     prof_begin(lc, K_SPARSE_ACCUM);
     hipLaunchKernelGGL((sparse_accum_k<ALGO, EF>), grid, block, 0, lc.stream, g, st, momentum, sc);
     prof_end(lc, K_SPARSE_ACCUM);
-    prof_begin(lc, K_SPARSE_REFILL);
-    hipLaunchKernelGGL(sparse_refill_k<FS>, rgrid, block, 0, lc.stream, g, st, k, sc);
-    prof_end(lc, K_SPARSE_REFILL);
+    prof_begin(lc, K_SPARSE_PLAN);
+    hipLaunchKernelGGL(sparse_plan_k<FS>, dim3(pblocks), dim3(kPlanThreads), 0, lc.stream, g, st, k, nwaves, sc);
+    prof_end(lc, K_SPARSE_PLAN);
     prof_begin(lc, K_CAND_HIST);
-    hipLaunchKernelGGL(cand_hist_k<2>, cgrid, block, 0, lc.stream, nch, per_wave, k, sc);
+    hipLaunchKernelGGL(cand_hist_k<2>, cgrid, block, 0, lc.stream, g.n, k, sc);
     prof_end(lc, K_CAND_HIST);
     prof_begin(lc, K_CAND_HIST);
-    hipLaunchKernelGGL(cand_hist_k<3>, cgrid, block, 0, lc.stream, nch, per_wave, k, sc);
+    hipLaunchKernelGGL(cand_hist_k<3>, cgrid, block, 0, lc.stream, g.n, k, sc);
     prof_end(lc, K_CAND_HIST);
     prof_begin(lc, K_CAND_COUNT);
-    hipLaunchKernelGGL(cand_count_k, cgrid, block, 0, lc.stream, nch, per_wave, sc);
+    hipLaunchKernelGGL(cand_count_k, cgrid, block, 0, lc.stream, g.n, sc);
     prof_end(lc, K_CAND_COUNT);
     prof_begin(lc, K_CAND_EMIT);
-    hipLaunchKernelGGL((cand_emit_k<ALGO, EF>), cgrid, block, 0, lc.stream, g.n, nch, per_wave, st, hdr, k, sc);
+    hipLaunchKernelGGL((cand_emit_k<ALGO, EF>), cgrid, block, 0, lc.stream, g.n, st, hdr, k, sc);
     prof_end(lc, K_CAND_EMIT);
 }
 
@@ -445,15 +655,17 @@ void launch_sparse_compress(const LaunchCtx &lc, int algo, const GroupView &g, b
 
 // ---------------------------------------------------------------------------
 // Sparse decompress-and-sum.  Every worker's indices ascend, so a 4096-element
-// output tile owns one contiguous run of each list.  A first kernel writes, per
-// worker, where each tile's run starts (one thread per payload entry, no search);
+// output tile owns one contiguous run of each list.  A first kernel records, per
+// worker and tile, where that run starts and ends (one thread per payload entry, no
+// search; entries are stamped with a per-call epoch instead of clearing the table);
 // the second accumulates each tile in LDS, one worker after the other in ascending
 // worker order -- the same order of fp32 additions as a dense sum, since adding
 // the +0 of an absent entry changes nothing -- and writes it once.  No atomics, no
 // pre-zeroed output, bit-reproducible.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void sparse_index_k(int algo, uint32_t n, PayloadPtrs pl, int W, uint64_t k64,
-                                                         uint32_t ntiles, uint32_t *tile_off, int *status)
+                                                         uint32_t ntiles, uint32_t epoch, uint64_t *tile_first,
+                                                         uint64_t *tile_last, int *status)
 {
     const uint32_t k = (uint32_t)k64;
     const uint32_t w = blockIdx.y;
@@ -462,21 +674,22 @@ __global__ __launch_bounds__(kBlock) void sparse_index_k(int algo, uint32_t n, P
         if (h->magic != kMagic || h->algo != (uint32_t)algo || h->n != (uint64_t)n || h->k != k64) *status = 1;
     }
     const uint32_t *idx = reinterpret_cast<const uint32_t *>(pl.p[w] + kHeaderBytes);
-    uint32_t *off = tile_off + (size_t)w * (ntiles + 1);
     const uint32_t e = blockIdx.x * kBlock + threadIdx.x;
-    if (e > k) return;
-    // entry e starts the runs of all tiles after the tile of entry e-1, up to and including its own;
-    // the virtual entry k (one past the end) closes the tiles behind the last entry
-    int64_t t_prev = e == 0 ? -1 : (int64_t)(idx[e - 1] >> 12);
-    int64_t t_cur = e == k ? (int64_t)ntiles : (int64_t)(idx[e] >> 12);
-    if (t_cur > (int64_t)ntiles) t_cur = ntiles;
-    for (int64_t t = t_prev + 1; t <= t_cur; ++t) off[t] = e;
+    if (e >= k) return;
+    // the first entry of a tile's run records where the run starts, the last one where it ends;
+    // both are stamped with this call's epoch, so tiles without entries need no clearing
+    const uint32_t tile = idx[e] >> 12;
+    if (tile >= ntiles) return;
+    const uint64_t stamp = (uint64_t)epoch << 32;
+    if (e == 0 || (idx[e - 1] >> 12) != tile) tile_first[(size_t)w * ntiles + tile] = stamp | e;
+    if (e == k - 1 || (idx[e + 1] >> 12) != tile) tile_last[(size_t)w * ntiles + tile] = stamp | (e + 1);
 }
 
 constexpr int kSparseBatch = 8;
 
 __global__ __launch_bounds__(kBlock) void sparse_decompress_k(GroupView out, PayloadPtrs pl, int W, float alpha,
-                                                              uint64_t k64, uint32_t ntiles, const uint32_t *tile_off)
+                                                              uint64_t k64, uint32_t ntiles, uint32_t epoch,
+                                                              const uint64_t *tile_first, const uint64_t *tile_last)
 {
     __shared__ float acc[kTile];
     const uint32_t k = (uint32_t)k64;
@@ -492,11 +705,14 @@ __global__ __launch_bounds__(kBlock) void sparse_decompress_k(GroupView out, Pay
         for (int b = 0; b < kSparseBatch; ++b) {
             lo[b] = hi[b] = 0;
             if (w0 + b < W) {
-                const uint32_t *off = tile_off + (size_t)(w0 + b) * (ntiles + 1) + blockIdx.x;
-                lo[b] = off[0]; hi[b] = off[1];
-                lo[b] = lo[b] < k ? lo[b] : k;
-                hi[b] = hi[b] < k ? hi[b] : k;
-                if (hi[b] - lo[b] > (uint32_t)kTile) hi[b] = lo[b];      // inconsistent payload: a tile holds at most 4096
+                const uint64_t f = tile_first[(size_t)(w0 + b) * ntiles + blockIdx.x];
+                const uint64_t l = tile_last[(size_t)(w0 + b) * ntiles + blockIdx.x];
+                if ((uint32_t)(f >> 32) == epoch && (uint32_t)(l >> 32) == epoch) {      // else: no entry in this tile
+                    lo[b] = (uint32_t)f < k ? (uint32_t)f : k;
+                    hi[b] = (uint32_t)l < k ? (uint32_t)l : k;
+                    // inconsistent payload (indices not ascending): a tile holds at most 4096 entries
+                    if (hi[b] < lo[b] || hi[b] - lo[b] > (uint32_t)kTile) hi[b] = lo[b];
+                }
             }
         }
         uint32_t ix[kSparseBatch];
@@ -536,16 +752,17 @@ __global__ __launch_bounds__(kBlock) void sparse_decompress_k(GroupView out, Pay
 }
 
 void launch_sparse_decompress(const LaunchCtx &lc, int algo, const GroupView &out, const PayloadPtrs &pl, int W,
-                              float alpha, uint64_t k, uint32_t *tile_off, int *status)
+                              float alpha, uint64_t k, uint32_t epoch, uint64_t *tile_first, uint64_t *tile_last, int *status)
 {
     if (out.n == 0) return;
     const uint32_t nt = tiles_of(out.n);
     prof_begin(lc, K_SPARSE_INDEX);
-    hipLaunchKernelGGL(sparse_index_k, dim3((uint32_t)((k + 1 + kBlock - 1) / kBlock), W), dim3(kBlock), 0, lc.stream, algo,
-                       out.n, pl, W, k, nt, tile_off, status);
+    hipLaunchKernelGGL(sparse_index_k, dim3((uint32_t)((k + kBlock - 1) / kBlock), W), dim3(kBlock), 0, lc.stream, algo,
+                       out.n, pl, W, k, nt, epoch, tile_first, tile_last, status);
     prof_end(lc, K_SPARSE_INDEX);
     prof_begin(lc, K_SPARSE_DECOMPRESS);
-    hipLaunchKernelGGL(sparse_decompress_k, dim3(nt), dim3(kBlock), 0, lc.stream, out, pl, W, alpha, k, nt, tile_off);
+    hipLaunchKernelGGL(sparse_decompress_k, dim3(nt), dim3(kBlock), 0, lc.stream, out, pl, W, alpha, k, nt, epoch, tile_first,
+                       tile_last);
     prof_end(lc, K_SPARSE_DECOMPRESS);
 }
 

@@ -30,7 +30,8 @@ struct PtrSlot {
     int32_t group = -1;
     uint64_t stamp = 0;
     std::vector<uintptr_t> host;
-    uintptr_t *dev = nullptr;
+    uintptr_t *dev = nullptr;            // tensor addresses
+    uintptr_t *dev_chunk = nullptr;      // per-chunk direct addresses derived from them
 };
 
 struct ProfEvent { int id; hipEvent_t a, b; };
@@ -59,6 +60,7 @@ struct mc_ctx {
     int *d_status = nullptr;
     std::vector<PtrSlot> slots;
     uint64_t clock = 0;
+    uint32_t epoch = 0;                 // stamps the sparse decompress tile table; 0 is never used
     Profiler prof;
 };
 
@@ -88,7 +90,7 @@ void prof_end(const LaunchCtx &lc, int id)
 
 static const char *kKernelNames[K_COUNT] = {
     "upload_ptrs", "efsign_compress", "scalar_finalize", "accum_reduce", "qsgd_encode", "tern_encode",
-    "fp16_compress", "dense_decompress", "sparse_accum", "sparse_refill", "cand_hist", "cand_count",
+    "fp16_compress", "dense_decompress", "sparse_accum", "sparse_plan", "cand_hist", "cand_count",
     "cand_emit", "sparse_index", "sparse_decompress", "state_convert"};
 
 static void prof_drain(Profiler &p)
@@ -181,11 +183,14 @@ int mc_ctx_destroy(mc_ctx *ctx)
         if (g.d_seg_off) (void)hipFree(g.d_seg_off);
         if (g.d_chunk_seg) (void)hipFree(g.d_chunk_seg);
     }
-    for (PtrSlot &s : ctx->slots) if (s.dev) (void)hipFree(s.dev);
+    for (PtrSlot &s : ctx->slots) {
+        if (s.dev) (void)hipFree(s.dev);
+        if (s.dev_chunk) (void)hipFree(s.dev_chunk);
+    }
     if (ctx->d_partial) (void)hipFree(ctx->d_partial);
-    void *sparse_bufs[] = {ctx->sparse.hist, ctx->sparse.sel, ctx->d_hints, ctx->sparse.total, ctx->sparse.cand_bits,
-                           ctx->sparse.cand_loc, ctx->sparse.run, ctx->sparse.blk_gt, ctx->sparse.blk_eq,
-                           ctx->sparse.wave_gt, ctx->sparse.wave_eq, ctx->sparse.tile_off};
+    void *sparse_bufs[] = {ctx->sparse.hist, ctx->sparse.sel, ctx->d_hints, ctx->sparse.plan, ctx->sparse.ne_tile, ctx->sparse.ne_prefix, ctx->sparse.ne_runs, ctx->sparse.wave_start, ctx->sparse.cand_bits,
+                           ctx->sparse.cand_loc, ctx->sparse.tile_runs, ctx->sparse.blk_gt, ctx->sparse.blk_eq,
+                           ctx->sparse.wave_gt, ctx->sparse.wave_eq, ctx->sparse.tile_first, ctx->sparse.tile_last};
     for (void *b : sparse_bufs) if (b) (void)hipFree(b);
     if (ctx->d_status) (void)hipFree(ctx->d_status);
     if (switched) (void)hipSetDevice(prev);
@@ -258,30 +263,39 @@ int mc_ctx_create(mc_ctx **out, const mc_config *cfg, const int64_t *numel, int3
         if (rc == MC_OK && hipMemset(ctx->d_status, 0, sizeof(int)) != hipSuccess) rc = MC_ERR_DEVICE;
         if (rc == MC_OK && is_sparse(cfg->algo)) {
             SparseScratch &sp = ctx->sparse;
-            const size_t hist_bytes = (2048 + 1024 + 1024) * sizeof(uint32_t);
+            const size_t hist_bytes = kHistWords * sizeof(uint32_t);
             const size_t chunks = tiles * kWavesPerBlock, slots = chunks * kChunk;
-            const size_t off_words = (size_t)kMaxWorkers * (tiles + 1);
+            const size_t off_words = (size_t)kMaxWorkers * tiles;
             if (hipMalloc(&sp.hist, hist_bytes) != hipSuccess || hipMalloc(&sp.sel, 4 * sizeof(SelectState)) != hipSuccess ||
                 hipMalloc(&ctx->d_hints, y * sizeof(uint32_t)) != hipSuccess ||
-                hipMalloc(&sp.total, sizeof(unsigned long long)) != hipSuccess ||
+                hipMalloc(&sp.plan, sizeof(PlanState)) != hipSuccess ||
+                hipMalloc(&sp.ne_tile, tiles * sizeof(uint32_t)) != hipSuccess ||
+                hipMalloc(&sp.ne_prefix, (tiles + 1) * sizeof(uint32_t)) != hipSuccess ||
+                hipMalloc(&sp.ne_runs, tiles * sizeof(uint64_t)) != hipSuccess ||
+                hipMalloc(&sp.wave_start, (kMaxCandBlocks * kWavesPerBlock + 1) * sizeof(uint32_t)) != hipSuccess ||
                 hipMalloc(&sp.cand_bits, slots * sizeof(uint32_t)) != hipSuccess ||
                 hipMalloc(&sp.cand_loc, slots * sizeof(uint16_t)) != hipSuccess ||
-                hipMalloc(&sp.run, chunks * sizeof(uint32_t)) != hipSuccess ||
+                hipMalloc(&sp.tile_runs, tiles * sizeof(uint64_t)) != hipSuccess ||
                 hipMalloc(&sp.blk_gt, kMaxCandBlocks * sizeof(uint32_t)) != hipSuccess ||
                 hipMalloc(&sp.blk_eq, kMaxCandBlocks * sizeof(uint32_t)) != hipSuccess ||
                 hipMalloc(&sp.wave_gt, kMaxCandBlocks * kWavesPerBlock * sizeof(uint32_t)) != hipSuccess ||
                 hipMalloc(&sp.wave_eq, kMaxCandBlocks * kWavesPerBlock * sizeof(uint32_t)) != hipSuccess ||
-                hipMalloc(&sp.tile_off, off_words * sizeof(uint32_t)) != hipSuccess) rc = MC_ERR_ALLOC;
+                hipMalloc(&sp.tile_first, off_words * sizeof(uint64_t)) != hipSuccess ||
+                hipMalloc(&sp.tile_last, off_words * sizeof(uint64_t)) != hipSuccess) rc = MC_ERR_ALLOC;
             else if (hipMemset(sp.hist, 0, hist_bytes) != hipSuccess || hipMemset(sp.sel, 0, 4 * sizeof(SelectState)) != hipSuccess ||
                      hipMemset(ctx->d_hints, 0, y * sizeof(uint32_t)) != hipSuccess ||
-                     hipMemset(sp.total, 0, sizeof(unsigned long long)) != hipSuccess ||
-                     hipMemset(sp.run, 0, chunks * sizeof(uint32_t)) != hipSuccess ||
-                     hipMemset(sp.tile_off, 0, off_words * sizeof(uint32_t)) != hipSuccess) rc = MC_ERR_DEVICE;
+                     hipMemset(sp.plan, 0, sizeof(PlanState)) != hipSuccess ||
+                     hipMemset(sp.tile_runs, 0, tiles * sizeof(uint64_t)) != hipSuccess ||
+                     hipMemset(sp.tile_first, 0, off_words * sizeof(uint64_t)) != hipSuccess ||
+                     hipMemset(sp.tile_last, 0, off_words * sizeof(uint64_t)) != hipSuccess) rc = MC_ERR_DEVICE;
         }
         if (rc == MC_OK) {
-            ctx->slots.resize(kPtrSlots);
+            // the per-chunk address tables of all slots together stay below 256 MiB
+            const size_t per_slot = tiles * kWavesPerBlock * sizeof(uintptr_t);
+            ctx->slots.resize(std::min<size_t>(kPtrSlots, std::max<size_t>(4, (size_t(256) << 20) / per_slot)));
             for (PtrSlot &s : ctx->slots) {
-                if (hipMalloc(&s.dev, std::max<size_t>(ctx->max_live, 1) * sizeof(uintptr_t)) != hipSuccess) { rc = MC_ERR_ALLOC; break; }
+                if (hipMalloc(&s.dev, std::max<size_t>(ctx->max_live, 1) * sizeof(uintptr_t)) != hipSuccess ||
+                    hipMalloc(&s.dev_chunk, tiles * kWavesPerBlock * sizeof(uintptr_t)) != hipSuccess) { rc = MC_ERR_ALLOC; break; }
                 s.host.reserve(ctx->max_live);
             }
         }
@@ -325,29 +339,38 @@ size_t mc_state_bytes(const mc_ctx *ctx, int32_t group)
     return kHeaderBytes + sizeof(float) * (size_t)g->n * (ctx->cfg.algo == MC_ALGO_DGC ? 2 : 1);
 }
 
-// Device copy of a per-call tensor address list (only tensors that hold elements).
-// Lists seen before are served from the cache; a new list replaces the least
-// recently used slot and is uploaded through a kernel's argument buffer, in
-// stream order with the kernels that will read it.
-static const uintptr_t *device_ptrs(mc_ctx *ctx, const LaunchCtx &lc, int32_t group, const Group &g, const void *const *ptrs)
+// Device view of a group over a per-call tensor address list (only tensors that hold
+// elements).  Lists seen before are served from the cache; a new list replaces the
+// least recently used slot: it is uploaded through a kernel's argument buffer and
+// expanded into the per-chunk address table, in stream order with the kernels that
+// will read it.
+static GroupView group_view(mc_ctx *ctx, const LaunchCtx &lc, int32_t group, const Group &g, const void *const *ptrs)
 {
     static thread_local std::vector<uintptr_t> want;
     want.clear();
     for (int32_t rel : g.live) want.push_back(reinterpret_cast<uintptr_t>(ptrs[rel]));
+    GroupView gv{g.d_seg_off, g.d_chunk_seg, nullptr, nullptr, (uint32_t)g.live.size(), g.n, g.goff};
     PtrSlot *victim = &ctx->slots[0];
     for (PtrSlot &s : ctx->slots) {
         if (s.group == group && s.host.size() == want.size() &&
             std::memcmp(s.host.data(), want.data(), want.size() * sizeof(uintptr_t)) == 0) {
             s.stamp = ++ctx->clock;
-            return s.dev;
+            gv.ptrs = s.dev;
+            gv.chunk_addr = s.dev_chunk;
+            return gv;
         }
         if (s.stamp < victim->stamp) victim = &s;
     }
     victim->group = group;
     victim->stamp = ++ctx->clock;
     victim->host = want;
-    if (!want.empty()) launch_upload_ptrs(lc, want.data(), victim->dev, (uint32_t)want.size());
-    return victim->dev;
+    gv.ptrs = victim->dev;
+    gv.chunk_addr = victim->dev_chunk;
+    if (!want.empty()) {
+        launch_upload_ptrs(lc, want.data(), victim->dev, (uint32_t)want.size());
+        launch_expand_ptrs(lc, gv, victim->dev_chunk);
+    }
+    return gv;
 }
 
 static int check_launch() { return hipGetLastError() == hipSuccess ? MC_OK : MC_ERR_DEVICE; }
@@ -379,8 +402,7 @@ int mc_compress(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter, cons
         launch_scalar_finalize(lc, ctx->d_partial, 0, -1, 0, hdr, (uint32_t)cfg.algo, 0, levels, nullptr);
         return check_launch();
     }
-    GroupView gv{G.d_seg_off, G.d_chunk_seg, device_ptrs(ctx, lc, group, G, reinterpret_cast<const void *const *>(grad_ptrs)),
-                 (uint32_t)G.live.size(), n, G.goff};
+    GroupView gv = group_view(ctx, lc, group, G, reinterpret_cast<const void *const *>(grad_ptrs));
     switch (cfg.algo) {
     case MC_ALGO_EFSIGN:
         launch_efsign_compress(lc, gv, ef, sf, ef ? &sh->scale : nullptr, reinterpret_cast<uint32_t *>(body), nwords, ctx->d_partial);
@@ -430,10 +452,11 @@ int mc_decompress_sum(mc_ctx *ctx, int32_t group, const void *const *payloads, i
     if (G.n == 0) return MC_OK;
     LaunchCtx lc{static_cast<hipStream_t>(stream), &ctx->prof};
     (void)hipGetLastError();
-    GroupView gv{G.d_seg_off, G.d_chunk_seg, device_ptrs(ctx, lc, group, G, reinterpret_cast<const void *const *>(out_ptrs)),
-                 (uint32_t)G.live.size(), G.n, G.goff};
+    GroupView gv = group_view(ctx, lc, group, G, reinterpret_cast<const void *const *>(out_ptrs));
     const mc_config &cfg = ctx->cfg;
-    if (is_sparse(cfg.algo)) launch_sparse_decompress(lc, cfg.algo, gv, pl, W, alpha, G.k, ctx->sparse.tile_off, ctx->d_status);
+    if (is_sparse(cfg.algo) && ++ctx->epoch == 0) ctx->epoch = 1;
+    if (is_sparse(cfg.algo)) launch_sparse_decompress(lc, cfg.algo, gv, pl, W, alpha, G.k, ctx->epoch, ctx->sparse.tile_first,
+                                                    ctx->sparse.tile_last, ctx->d_status);
     else {
         const uint32_t levels = cfg.algo == MC_ALGO_QSGD ? (1u << (cfg.qsgd_bits - 1)) - 1u : 0u;
         launch_dense_decompress(lc, cfg.algo, gv, pl, W, alpha, levels, ctx->d_status);

@@ -28,6 +28,7 @@ struct GroupView {
     const uint32_t *seg_off;
     const uint32_t *chunk_seg;   // tensor that holds the first element of each 1024-element chunk
     const uintptr_t *ptrs;
+    const uintptr_t *chunk_addr; // address of each chunk's first element if the whole chunk lies in one tensor, else 0
     uint32_t nseg;
     uint32_t n;
     uint64_t goff;   // model-global flat index of element 0 (random streams only)
@@ -88,18 +89,20 @@ __device__ __forceinline__ void store_flat(T *buf, const Chunk &c, uint32_t n, c
 }
 
 // ---- segmented (per-tensor) buffers ------------------------------------------
-// Fast path: the chunk lies inside one tensor.  Otherwise every lane walks the
-// segment table forward from the chunk's first tensor (flat indices of a lane
-// only grow with j, so the cursor never moves back).
+// Fast path: the chunk lies inside one tensor and its address was tabulated when
+// the tensor address list was uploaded (one scalar load, then the data).
+// Otherwise every lane walks the segment table forward from the chunk's first
+// tensor (flat indices of a lane only grow with j, so the cursor never moves back).
 __device__ __forceinline__ void load_seg(const GroupView &g, const Chunk &c, float (&v)[kSteps])
 {
-    uint32_t s = seg_of_chunk(g, c);
-    uint32_t beg = g.seg_off[s], end = g.seg_off[s + 1];
-    if (c.full && end - c.base >= (uint32_t)kChunk) {
-        const float *p = reinterpret_cast<const float *>(g.ptrs[s]) + (c.base - beg) + c.lane;
+    const uintptr_t direct = g.chunk_addr[c.base >> 10];
+    if (direct) {
+        const float *p = reinterpret_cast<const float *>(direct) + c.lane;
 #pragma unroll
         for (int j = 0; j < kSteps; ++j) v[j] = ld_stream(p + 64 * j);
     } else {
+        uint32_t s = seg_of_chunk(g, c);
+        uint32_t beg = g.seg_off[s], end = g.seg_off[s + 1];
         const float *p = reinterpret_cast<const float *>(g.ptrs[s]);
 #pragma unroll
         for (int j = 0; j < kSteps; ++j) {
@@ -116,13 +119,14 @@ __device__ __forceinline__ void load_seg(const GroupView &g, const Chunk &c, flo
 
 __device__ __forceinline__ void store_seg(const GroupView &g, const Chunk &c, const float (&v)[kSteps])
 {
-    uint32_t s = seg_of_chunk(g, c);
-    uint32_t beg = g.seg_off[s], end = g.seg_off[s + 1];
-    if (c.full && end - c.base >= (uint32_t)kChunk) {
-        float *p = reinterpret_cast<float *>(g.ptrs[s]) + (c.base - beg) + c.lane;
+    const uintptr_t direct = g.chunk_addr[c.base >> 10];
+    if (direct) {
+        float *p = reinterpret_cast<float *>(direct) + c.lane;
 #pragma unroll
         for (int j = 0; j < kSteps; ++j) st_stream(p + 64 * j, v[j]);
     } else {
+        uint32_t s = seg_of_chunk(g, c);
+        uint32_t beg = g.seg_off[s], end = g.seg_off[s + 1];
         float *p = reinterpret_cast<float *>(g.ptrs[s]);
 #pragma unroll
         for (int j = 0; j < kSteps; ++j) {

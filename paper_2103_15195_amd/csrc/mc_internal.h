@@ -40,7 +40,7 @@ struct SelectState {
 // profiling slots
 enum KernelId {
     K_UPLOAD = 0, K_EFSIGN_COMPRESS, K_SCALAR_FINALIZE, K_ACCUM_REDUCE, K_QSGD_ENCODE, K_TERN_ENCODE,
-    K_FP16_COMPRESS, K_DENSE_DECOMPRESS, K_SPARSE_ACCUM, K_SPARSE_REFILL, K_CAND_HIST, K_CAND_COUNT,
+    K_FP16_COMPRESS, K_DENSE_DECOMPRESS, K_SPARSE_ACCUM, K_SPARSE_PLAN, K_CAND_HIST, K_CAND_COUNT,
     K_CAND_EMIT, K_SPARSE_INDEX, K_SPARSE_DECOMPRESS, K_STATE_CONVERT, K_COUNT
 };
 
@@ -56,6 +56,7 @@ void prof_end(const LaunchCtx &lc, int id);
 
 // ---- dense kernels (kernels_dense.hip) -----------------------------------------
 void launch_upload_ptrs(const LaunchCtx &lc, const uintptr_t *host, uintptr_t *dev, uint32_t count);
+void launch_expand_ptrs(const LaunchCtx &lc, const GroupView &g, uintptr_t *chunk_addr);
 void launch_efsign_compress(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, const float *scale_prev,
                             uint32_t *words, uint32_t nwords, double *partial);
 void launch_scalar_finalize(const LaunchCtx &lc, const double *partial, uint32_t nblocks, int mode, uint32_t n,
@@ -73,22 +74,36 @@ void launch_state_convert(const LaunchCtx &lc, int algo, bool to_residual, uint3
 
 // ---- sparse kernels (kernels_sparse.hip) ----------------------------------------
 constexpr uint32_t kMaxCandBlocks = 1024;   // grid of the kernels that walk the candidate slots
+constexpr int kHistWords = 2048 + 1024 + 1024;   // bins of the three radix levels
+
+// what the plan kernel tells the kernels that walk the candidates
+struct PlanState {
+    unsigned long long total;   // candidates to walk: what the accumulate kernel kept, or n after a refill
+    uint32_t nonempty;          // tiles that hold candidates
+    uint32_t share;             // candidates per wavefront
+    uint32_t uniform;           // 1 after a refill: chunk c holds candidates 1024 c, 1024 c + 1, ...
+};
 
 struct SparseScratch {
-    uint32_t *hist;        // 2048 + 1024 + 1024 bins; each level is cleared by a later kernel of the same call
+    uint32_t *hist;        // kHistWords counters; each level is cleared by a later kernel of the same call
     SelectState *sel;      // [1..3]: prefix / need after each radix level
     uint32_t *hint;        // this group's candidate filter: keys >= hint are candidates (0 = everything)
-    unsigned long long *total;   // candidates found by the accumulate kernel
+    PlanState *plan;
+    uint32_t *ne_tile;     // ids of the tiles that hold candidates, ascending
+    uint32_t *ne_prefix;   // candidates before each of them (one extra entry: the total)
+    uint64_t *ne_runs;     // their per-chunk counts
+    uint32_t *wave_start;  // per wavefront of the later kernels: where in that list its share starts
     uint32_t *cand_bits;   // candidate values (fp32 bit patterns), 1024 slots per chunk, filled from the front
     uint16_t *cand_loc;    // candidate positions inside their chunk
-    uint32_t *run;         // candidates per chunk
+    uint64_t *tile_runs;   // candidates of the four chunks of every tile, 16 bits each
     uint32_t *blk_gt, *blk_eq;     // per block of the candidate kernels: kept above / equal to the threshold
     uint32_t *wave_gt, *wave_eq;   // same per wavefront
-    uint32_t *tile_off;    // decompress: per worker, first payload entry of every 4096-element tile
+    uint64_t *tile_first, *tile_last;   // decompress: per worker and 4096-element tile, (epoch << 32 | entry) of its run
 };
 void launch_sparse_compress(const LaunchCtx &lc, int algo, const GroupView &g, bool ef, float *state_f, float momentum,
                             uint64_t k, PayloadHeader *hdr, const SparseScratch &sc);
 void launch_sparse_decompress(const LaunchCtx &lc, int algo, const GroupView &out, const PayloadPtrs &pl, int W,
-                              float alpha, uint64_t k, uint32_t *tile_off, int *status);
+                              float alpha, uint64_t k, uint32_t epoch, uint64_t *tile_first, uint64_t *tile_last,
+                              int *status);
 
 }  // namespace mc

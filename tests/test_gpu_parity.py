@@ -254,7 +254,7 @@ def test_profile_hooks_count_launches():
     prof = ctx.profile_read()
     assert prof["efsign_compress"]["launches"] == 3 and prof["scalar_finalize"]["launches"] == 3
     assert prof["efsign_compress"]["total_ms"] > 0
-    assert prof["upload_ptrs"]["launches"] == 1                # the tensor address list is cached after the first call
+    assert prof["upload_ptrs"]["launches"] == 2                # address list uploaded + expanded once, then cached
     ctx.profile_reset()
     ctx.profile_enable(False)
     ctx.mc_compress(0, 0, 3, [g], st, pay)
