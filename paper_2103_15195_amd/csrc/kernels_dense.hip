@@ -542,7 +542,7 @@ constexpr int kSignTile = kSignWaveElems * kWavesPerBlock; // 8192 elements per 
 __global__ __launch_bounds__(kBlock) void efsign_decompress_k(GroupView out, PayloadPtrs pl, int W, float alpha, int *status)
 {
     __shared__ float table[256];
-    __shared__ float stage[kWavesPerBlock][kSignWaveElems + 64];
+    __shared__ float stage[kWavesPerBlock][kChunk + 32];
     const uint32_t t = threadIdx.x;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(t >> 6), lane = t & 63u;
     if (blockIdx.x == 0 && (int)t < W)
@@ -590,24 +590,29 @@ __global__ __launch_bounds__(kBlock) void efsign_decompress_k(GroupView out, Pay
 #pragma unroll
         for (int e = 0; e < 32; ++e) acc[e] = alpha * acc[e];
     }
+    // two halves of 1024 elements through one stage: lanes 32 h .. 32 h + 31 own the elements of half h
     float *mine = stage[wave];
 #pragma unroll
-    for (int e = 0; e < 32; ++e) mine[33 * lane + e] = acc[e];          // element 32 lane + e, skewed by lane
-    __builtin_amdgcn_wave_barrier();
-#pragma unroll
     for (int half = 0; half < 2; ++half) {
+        __builtin_amdgcn_wave_barrier();
+        if ((lane >> 5) == (uint32_t)half) {
+#pragma unroll
+            for (int e = 0; e < 32; ++e) mine[33 * (lane & 31u) + e] = acc[e];     // element 32 (lane % 32) + e, skewed
+        }
+        __builtin_amdgcn_wave_barrier();
         Chunk c;
         c.base = wbase + half * (uint32_t)kChunk;
         c.lane = lane;
         c.full = c.base < out.n && out.n - c.base >= (uint32_t)kChunk;
-        if (c.base >= out.n) break;
-        float v[kSteps];
+        if (c.base < out.n) {
+            float v[kSteps];
 #pragma unroll
-        for (int j = 0; j < kSteps; ++j) {
-            uint32_t i = half * kChunk + 64 * j + lane;              // element of the wave's 2048
-            v[j] = mine[i + (i >> 5)];
+            for (int j = 0; j < kSteps; ++j) {
+                uint32_t i = 64 * j + lane;                              // element of this half
+                v[j] = mine[i + (i >> 5)];
+            }
+            store_seg(out, c, v);
         }
-        store_seg(out, c, v);
     }
 }
 

@@ -255,6 +255,18 @@ __global__ __launch_bounds__(kPlanThreads) void sparse_plan_k(GroupView g, const
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const uint32_t nch = (g.n + (uint32_t)kChunk - 1u) / (uint32_t)kChunk;
     const uint32_t ntiles = (g.n + (uint32_t)kTile - 1u) / (uint32_t)kTile;
+    // ---- radix level 1 (need = k) from the bins the accumulate kernel filled: the last wavefront of block 0
+    // does it while the others wait for their loads (after a refill the next kernel resolves again)
+    if (blockIdx.x == 0 && wave == kPlanThreads / 64 - 1) {
+        uint32_t bin;
+        uint64_t rest;
+        resolve_wave<kBins1>(sc.hist + kHist1, k, bin, rest);
+        if (lane == 0) {
+            SelectState s;
+            s.prefix = bin << 20; s.pad0 = 0; s.need = rest;
+            sc.sel[1] = s;
+        }
+    }
     // ---- every block: candidates and non-empty tiles before each thread's run of tiles
     const uint32_t per = (ntiles + kPlanThreads - 1) / kPlanThreads;
     const uint32_t lo = t * per < ntiles ? t * per : ntiles;
@@ -309,19 +321,10 @@ __global__ __launch_bounds__(kPlanThreads) void sparse_plan_k(GroupView g, const
         if (t == 0) sc.ne_prefix[nonempty] = total;
         for (uint32_t j = t; j <= nwaves; j += kPlanThreads)
             if ((uint64_t)j * share >= total) sc.wave_start[j] = nonempty;
-        // ---- radix level 1 (need = k) from the bins the accumulate kernel filled
-        if (wave == 0) {
-            uint32_t bin;
-            uint64_t rest;
-            resolve_wave<kBins1>(sc.hist + kHist1, k, bin, rest);
-            if (lane == 0) {
-                PlanState pl;
-                pl.total = total; pl.nonempty = nonempty; pl.share = share; pl.uniform = 0;
-                *sc.plan = pl;
-                SelectState s;
-                s.prefix = bin << 20; s.pad0 = 0; s.need = rest;
-                sc.sel[1] = s;
-            }
+        if (t == 0) {
+            PlanState pl;
+            pl.total = total; pl.nonempty = nonempty; pl.share = share; pl.uniform = 0;
+            *sc.plan = pl;
         }
         return;
     }
@@ -367,36 +370,66 @@ __global__ __launch_bounds__(kPlanThreads) void sparse_plan_k(GroupView g, const
 // ---------------------------------------------------------------------------
 struct CandWindow { uint32_t first[64]; uint32_t tile[64]; uint64_t runs[64]; };
 
+// A wavefront's share and the first window of its walk, fetched early so that the
+// latency overlaps with whatever the kernel does before it walks.
+struct CandCursor {
+    uint64_t f_lo, f_hi;
+    uint32_t uniform, nonempty, q0;
+    uint32_t first, tile;      // this lane's entry of the first window
+    uint64_t runs;
+    bool active;
+};
+
+__device__ __forceinline__ void window_entry(const SparseScratch &sc, uint32_t n, const CandCursor &cur, uint32_t q0,
+                                             uint32_t &first, uint32_t &tile, uint64_t &runs)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t q = q0 + lane < cur.nonempty ? q0 + lane : cur.nonempty;
+    runs = 0;
+    if (cur.uniform) { first = q < cur.nonempty ? q * (uint32_t)kTile : n; tile = q; }
+    else {
+        first = sc.ne_prefix[q];
+        tile = q < cur.nonempty ? sc.ne_tile[q] : 0u;
+        runs = q < cur.nonempty ? sc.ne_runs[q] : 0ull;
+    }
+}
+
+__device__ __forceinline__ CandCursor cand_begin(const SparseScratch &sc, uint32_t n)
+{
+    CandCursor cur;
+    const uint32_t w = blockIdx.x * kWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t start = sc.wave_start[w];           // meaningless after a refill, then unused
+    const uint64_t total = sc.plan->total;
+    const uint32_t share = sc.plan->share;
+    cur.uniform = sc.plan->uniform;
+    cur.nonempty = sc.plan->nonempty;
+    cur.f_lo = (uint64_t)w * share;
+    cur.f_hi = cur.f_lo + share < total ? cur.f_lo + share : total;
+    cur.active = cur.f_lo < total;
+    cur.q0 = cur.uniform ? (uint32_t)(cur.f_lo >> 12) : start;
+    cur.first = 0; cur.tile = 0; cur.runs = 0;
+    if (cur.active) window_entry(sc, n, cur, cur.q0, cur.first, cur.tile, cur.runs);
+    return cur;
+}
+
 template <bool WITH_LOC, typename Body>
-__device__ __forceinline__ void for_each_candidate(const SparseScratch &sc, uint32_t n, CandWindow *win /* LDS, per wavefront */,
-                                                   Body body)
+__device__ __forceinline__ void cand_run(const CandCursor &cur, const SparseScratch &sc, uint32_t n,
+                                         CandWindow *win /* LDS, per wavefront */, Body body)
 {
     constexpr int kRounds = 4;
+    if (!cur.active) return;
     const uint32_t lane = threadIdx.x & 63u;
-    const uint32_t w = blockIdx.x * kWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint64_t total = sc.plan->total;
-    const uint32_t share = sc.plan->share, uniform = sc.plan->uniform, nonempty = sc.plan->nonempty;
-    const uint64_t f_lo = (uint64_t)w * share;
-    if (f_lo >= total) return;
-    const uint64_t f_hi = f_lo + share < total ? f_lo + share : total;
-    uint32_t q0 = uniform ? (uint32_t)(f_lo >> 12) : sc.wave_start[w];
+    const uint32_t uniform = cur.uniform;
+    uint32_t q0 = cur.q0, first = cur.first, tile = cur.tile;
+    uint64_t runs = cur.runs;
     for (;;) {
-        const uint32_t q = q0 + lane < nonempty ? q0 + lane : nonempty;
-        uint32_t first, tile;
-        uint64_t runs = 0;
-        if (uniform) { first = q < nonempty ? q * (uint32_t)kTile : n; tile = q; }
-        else {
-            first = sc.ne_prefix[q];
-            tile = q < nonempty ? sc.ne_tile[q] : 0u;
-            runs = q < nonempty ? sc.ne_runs[q] : 0ull;
-        }
         __builtin_amdgcn_wave_barrier();
         win->first[lane] = first;
         win->tile[lane] = tile;
         win->runs[lane] = runs;
         __builtin_amdgcn_wave_barrier();
         const uint64_t win_lo = __builtin_amdgcn_readlane(first, 0), win_hi = __builtin_amdgcn_readlane(first, 63);
-        const uint64_t a = f_lo > win_lo ? f_lo : win_lo, b = f_hi < win_hi ? f_hi : win_hi;
+        const uint64_t a = cur.f_lo > win_lo ? cur.f_lo : win_lo, b = cur.f_hi < win_hi ? cur.f_hi : win_hi;
         for (uint64_t f0 = a; f0 < b; f0 += 64 * kRounds) {
             uint32_t ch[kRounds], bits[kRounds], loc[kRounds];
             size_t slot[kRounds];
@@ -432,8 +465,9 @@ __device__ __forceinline__ void for_each_candidate(const SparseScratch &sc, uint
             for (int u = 0; u < kRounds; ++u)
                 if (f0 + 64 * u < b) body(valid[u], ch[u], bits[u], loc[u]);
         }
-        if (win_hi >= f_hi || q0 + 63 >= nonempty) break;
+        if (win_hi >= cur.f_hi || q0 + 63 >= cur.nonempty) break;
         q0 += 63;
+        window_entry(sc, n, cur, q0, first, tile, runs);
     }
 }
 
@@ -453,6 +487,7 @@ __global__ __launch_bounds__(kBlock) void cand_hist_k(uint32_t n, uint64_t k, Sp
     __shared__ uint64_t above[kBlock];
     __shared__ uint32_t res[3];
     for (int b = threadIdx.x; b < 1024; b += kBlock) hist[b] = 0u;
+    const CandCursor cur = cand_begin(sc, n);
     uint32_t prefix;
     if (LEVEL == 2) {
         if (sc.plan->uniform) {                       // after a refill nobody has resolved level 1 yet
@@ -482,7 +517,7 @@ __global__ __launch_bounds__(kBlock) void cand_hist_k(uint32_t n, uint64_t k, Sp
     __syncthreads();
     constexpr int kMatchShift = LEVEL == 2 ? 20 : 10;
     const uint32_t want = prefix >> kMatchShift;
-    for_each_candidate<false>(sc, n, &win[threadIdx.x >> 6], [&](bool valid, uint32_t, uint32_t bits, uint32_t) {
+    cand_run<false>(cur, sc, n, &win[threadIdx.x >> 6], [&](bool valid, uint32_t, uint32_t bits, uint32_t) {
         uint32_t key = bits & 0x7FFFFFFFu;
         if (valid && (key >> kMatchShift) == want) atomicAdd(&hist[(key >> (kMatchShift - 10)) & 1023u], 1u);
     });
@@ -498,6 +533,7 @@ __global__ __launch_bounds__(kBlock) void cand_count_k(uint32_t n, SparseScratch
 {
     __shared__ uint32_t wgt[kWavesPerBlock], weq[kWavesPerBlock];
     __shared__ CandWindow win[kWavesPerBlock];
+    const CandCursor cur = cand_begin(sc, n);
     const SelectState s2 = sc.sel[2];
     uint32_t bin;
     uint64_t rest;
@@ -514,7 +550,7 @@ __global__ __launch_bounds__(kBlock) void cand_count_k(uint32_t n, SparseScratch
     }
     const uint32_t lane = threadIdx.x & 63u;
     uint32_t ngt = 0, neq = 0;
-    for_each_candidate<false>(sc, n, &win[threadIdx.x >> 6], [&](bool valid, uint32_t, uint32_t bits, uint32_t) {
+    cand_run<false>(cur, sc, n, &win[threadIdx.x >> 6], [&](bool valid, uint32_t, uint32_t bits, uint32_t) {
         uint32_t key = bits & 0x7FFFFFFFu;
         ngt += __popcll(__builtin_amdgcn_ballot_w64(valid && key > T));
         neq += __popcll(__builtin_amdgcn_ballot_w64(valid && key == T));
@@ -551,18 +587,17 @@ __global__ __launch_bounds__(kBlock) void cand_emit_k(uint32_t n, float *st, Pay
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t lane = threadIdx.x & 63u;
     // kept-before of this block: sum over the blocks before it (at most 1024), four loads per thread
-    uint64_t ag = 0, ae = 0;
-    {
-        uint32_t vg[4], ve[4];
+    uint32_t vg[4], ve[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            uint32_t b = u * kBlock + threadIdx.x;
-            vg[u] = b < blockIdx.x ? sc.blk_gt[b] : 0u;
-            ve[u] = b < blockIdx.x ? sc.blk_eq[b] : 0u;
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) { ag += vg[u]; ae += ve[u]; }
+    for (int u = 0; u < 4; ++u) {
+        uint32_t b = u * kBlock + threadIdx.x;
+        vg[u] = b < blockIdx.x ? sc.blk_gt[b] : 0u;
+        ve[u] = b < blockIdx.x ? sc.blk_eq[b] : 0u;
     }
+    const CandCursor cur = cand_begin(sc, n);       // its loads fly while the sums below are formed
+    uint64_t ag = 0, ae = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) { ag += vg[u]; ae += ve[u]; }
     // kept-before of this wavefront inside the block
     uint64_t wg = 0, we = 0;
     if (lane < wave) {
@@ -587,7 +622,7 @@ __global__ __launch_bounds__(kBlock) void cand_emit_k(uint32_t n, float *st, Pay
     __syncthreads();
     uint64_t gt_before = (sgt[0] + sgt[1]) + (sgt[2] + sgt[3]) + wg;
     uint64_t eq_before = (seq[0] + seq[1]) + (seq[2] + seq[3]) + we;
-    for_each_candidate<true>(sc, n, &win[wave], [&](bool valid, uint32_t chunk, uint32_t b, uint32_t loc) {
+    cand_run<true>(cur, sc, n, &win[wave], [&](bool valid, uint32_t chunk, uint32_t b, uint32_t loc) {
         const uint32_t key = b & 0x7FFFFFFFu;
         const bool is_gt = valid && key > T, is_eq = valid && key == T;
         const uint64_t bgt = __builtin_amdgcn_ballot_w64(is_gt), beq = __builtin_amdgcn_ballot_w64(is_eq);
@@ -685,7 +720,8 @@ __global__ __launch_bounds__(kBlock) void sparse_index_k(int algo, uint32_t n, P
     if (e == k - 1 || (idx[e + 1] >> 12) != tile) tile_last[(size_t)w * ntiles + tile] = stamp | (e + 1);
 }
 
-constexpr int kSparseBatch = 8;
+constexpr int kSparseBatch = 8;    // workers whose entries are in flight together
+constexpr int kSparseRounds = 4;   // rounds of 256 entries per worker fetched up front
 
 __global__ __launch_bounds__(kBlock) void sparse_decompress_k(GroupView out, PayloadPtrs pl, int W, float alpha,
                                                               uint64_t k64, uint32_t ntiles, uint32_t epoch,
@@ -715,27 +751,48 @@ __global__ __launch_bounds__(kBlock) void sparse_decompress_k(GroupView out, Pay
                 }
             }
         }
-        uint32_t ix[kSparseBatch];
-        float vv[kSparseBatch];
+        if (W <= kSparseBatch) {          // most tiles hold no kept entry at all: they are just zero-filled
+            bool any = false;
+#pragma unroll
+            for (int b = 0; b < kSparseBatch; ++b) any = any || hi[b] > lo[b];
+            if (!any) {
+                const Chunk c = my_chunk(out.n);
+                if (c.base >= out.n) return;
+                float z[kSteps];
+#pragma unroll
+                for (int j = 0; j < kSteps; ++j) z[j] = alpha * 0.0f;
+                store_seg(out, c, z);
+                return;
+            }
+        }
+        // the kept entries cluster in a few tensors: a tile there holds hundreds of entries per worker.
+        // Four rounds of 256 entries of every worker of the batch are requested at once.
+        uint32_t ix[kSparseBatch][kSparseRounds];
+        float vv[kSparseBatch][kSparseRounds];
 #pragma unroll
         for (int b = 0; b < kSparseBatch; ++b) {
-            ix[b] = 0xFFFFFFFFu; vv[b] = 0.0f;
-            if (w0 + b < W && lo[b] + t < hi[b]) {
-                const uint32_t *idx = reinterpret_cast<const uint32_t *>(pl.p[w0 + b] + kHeaderBytes);
-                ix[b] = ld_stream(idx + lo[b] + t);
-                vv[b] = ld_stream(reinterpret_cast<const float *>(idx + k) + lo[b] + t);
+            const uint32_t *idx = reinterpret_cast<const uint32_t *>(pl.p[w0 + b < W ? w0 + b : 0] + kHeaderBytes);
+            const float *val = reinterpret_cast<const float *>(idx + k);
+#pragma unroll
+            for (int r = 0; r < kSparseRounds; ++r) {
+                const uint32_t e = lo[b] + r * kBlock + t;
+                ix[b][r] = 0xFFFFFFFFu; vv[b][r] = 0.0f;
+                if (w0 + b < W && e < hi[b]) { ix[b][r] = ld_stream(idx + e); vv[b][r] = ld_stream(val + e); }
             }
         }
 #pragma unroll
         for (int b = 0; b < kSparseBatch; ++b) {
             if (w0 + b < W) {
-                uint32_t local = ix[b] - tb;
-                if (ix[b] != 0xFFFFFFFFu && local < (uint32_t)kTile) acc[local] = acc[local] + vv[b];
-                // the rare tile with more than 256 entries of one worker
+#pragma unroll
+                for (int r = 0; r < kSparseRounds; ++r) {
+                    const uint32_t local = ix[b][r] - tb;
+                    if (ix[b][r] != 0xFFFFFFFFu && local < (uint32_t)kTile) acc[local] = acc[local] + vv[b][r];
+                }
+                // more than 1024 entries of one worker in the tile
                 const uint32_t *idx = reinterpret_cast<const uint32_t *>(pl.p[w0 + b] + kHeaderBytes);
                 const float *val = reinterpret_cast<const float *>(idx + k);
-                for (uint32_t e = lo[b] + kBlock + t; e < hi[b]; e += kBlock) {
-                    uint32_t l2 = idx[e] - tb;
+                for (uint32_t e = lo[b] + kSparseRounds * kBlock + t; e < hi[b]; e += kBlock) {
+                    const uint32_t l2 = idx[e] - tb;
                     if (l2 < (uint32_t)kTile) acc[l2] = acc[l2] + val[e];
                 }
                 __syncthreads();
