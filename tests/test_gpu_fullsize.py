@@ -1,0 +1,137 @@
+"""Full-size GPU-vs-oracle parity (BASELINE configs[2..4]) through the C ABI, in the launch
+configuration bench.py times: ResNet-50-, ResNet-101- and Mask R-CNN-shaped gradient sets, every
+tensor its own device allocation, y and W as the configurations list them.
+
+The oracle's exact top-k sorts the whole group (seconds per worker at these sizes), so:
+  * every worker is compressed on the GPU, the payload and residual of a sample of workers
+    (first and last) are compared with the oracle byte for byte, for every listed y;
+  * dense-code algorithms are also decompressed-and-summed from the oracle's payloads of all W
+    workers and compared element by element;
+  * the sparse decompress-and-sum is compared element by element on W seeded synthetic payloads
+    (valid ascending index lists with the clustering real gradients show: a few tensors hold
+    most entries), which the oracle decodes one by one.
+Two iterations are run where stated, so that the error-feedback state and the candidate filter of
+the sparsifiers (seeded by the previous threshold) are exercised at full size.
+"""
+import gc
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as O
+from paper_2103_15195_amd import binding as B
+from paper_2103_15195_amd import workloads as WL
+
+import harness as H
+
+pytestmark = pytest.mark.gpu
+
+_flats = {}
+
+
+def grads_of(cfg):
+    """Seeded gradients of a configuration, generated once per module run (other configurations are dropped)."""
+    for other in [c for c in _flats if c != cfg]:
+        del _flats[other]
+    gc.collect()
+    wl = WL.workload(cfg)
+    cache = _flats.setdefault(cfg, {})
+
+    def fn(w, it):
+        if (w, it) not in cache:
+            cache[(w, it)] = WL.gradients_flat(wl, w, it)
+        return cache[(w, it)]
+    return wl, fn
+
+
+def synthetic_sparse_payloads(algo_id, flats, lo, n, k, seed):
+    """W valid sparse payloads of one group: the k largest magnitudes of each worker's slice (library partition),
+    ascending indices, values copied.  Any valid payload serves: the oracle decodes what the GPU decodes."""
+    pays = []
+    for w, flat in enumerate(flats):
+        x = flat[lo:lo + n]
+        idx = np.sort(np.argpartition(np.abs(x), n - k)[n - k:]).astype(np.uint32)
+        pay = np.zeros(64 + 8 * k, np.uint8)
+        pay[0:4] = np.frombuffer(np.uint32(0x3150434D).tobytes(), np.uint8)
+        pay[4:8] = np.frombuffer(np.uint32(algo_id).tobytes(), np.uint8)
+        pay[8:16] = np.frombuffer(np.uint64(n).tobytes(), np.uint8)
+        pay[16:24] = np.frombuffer(np.uint64(k).tobytes(), np.uint8)
+        pay[64:64 + 4 * k] = idx.view(np.uint8)
+        pay[64 + 4 * k:] = (x[idx] * np.float32(1 + 0.25 * w)).astype(np.float32).view(np.uint8)
+        pays.append(pay)
+    return pays
+
+
+def sparse_decompress_fullsize(wl, algo, y, W, grads, ppm):
+    numel = wl.numel.tolist()
+    bounds = B.mc_partition(numel, y)
+    ctx = B.Context(algo, numel, bounds, ratio_ppm=ppm)
+    offs = np.concatenate([[0], np.cumsum(numel)]).astype(np.int64)
+    flats = [grads(w, 0) for w in range(W)]
+    outs = [torch.full((int(m),), float("nan"), dtype=torch.float32, device=H.DEV) for m in numel]
+    for j in range(y):
+        lo, n = int(offs[bounds[j]]), int(offs[bounds[j + 1]] - offs[bounds[j]])
+        k = ctx.group_k(j)
+        pays = synthetic_sparse_payloads(H.ALGOS[algo], flats, lo, n, k, seed=j)
+        for rep in range(2):             # twice: the tile table of the second call carries a new epoch
+            ctx.mc_decompress_sum(j, [torch.from_numpy(p).to(H.DEV) for p in pays], 0.125, outs[bounds[j]:bounds[j + 1]])
+        assert ctx.mc_last_device_status() == B.MC_OK
+        got = H.gather_flat(outs[bounds[j]:bounds[j + 1]])
+        want = O.decompress_sum(pays, n, 0.125)
+        assert H.same_bits(got, want), f"{algo} y={y} group {j}: {np.count_nonzero(H.u32(got) != H.u32(want))} elements differ"
+    ctx.close()
+
+
+def compress_fullsize(cfg, algo, y, W, *, iters, oracle_workers, ppm=10000, **kw):
+    wl, grads = grads_of(cfg)
+    st = H.run_parity(wl.numel, algo, y, W, iters, grads, oracle_workers=oracle_workers, ratio_ppm=ppm, seed=2021, **kw)
+    print(f"[config{cfg} {algo} y={y}] checks={st.compress_checks}+{st.decompress_checks} conditional={st.conditional}", flush=True)
+    return st
+
+
+# ---- configs[2]: ResNet-50 shapes, y in {1,2,3,4}, W = 8; EF-Sign, Top-k 1 %, DGC 0.1 %, QSGD-8, TernGrad ----------
+@pytest.mark.parametrize("y", [1, 2, 3, 4])
+@pytest.mark.parametrize("algo", ["efsign", "qsgd", "terngrad"])
+def test_config2_resnet50_dense(algo, y):
+    everyone = y in (1, 4)
+    st = compress_fullsize(2, algo, y, 8, iters=2 if y == 1 else 1, oracle_workers=None if everyone else [0, 7])
+    assert st.decompress_checks == (y if everyone else 0)
+
+
+@pytest.mark.parametrize("y", [1, 2, 3, 4])
+@pytest.mark.parametrize("algo,ppm", [("topk", 10000), ("dgc", 1000)])
+def test_config2_resnet50_sparse(algo, ppm, y):
+    compress_fullsize(2, algo, y, 8, iters=2 if y == 1 else 1, oracle_workers=[0, 7] if y == 1 else [3], ppm=ppm)
+    wl, grads = grads_of(2)
+    sparse_decompress_fullsize(wl, algo, y, 8, grads, ppm)
+
+
+# ---- configs[3]: ResNet-101 shapes, y in {1,2,4}, W = 16; Top-k 0.1 % and EF-Sign ------------------------------------
+@pytest.mark.parametrize("y", [1, 2, 4])
+def test_config3_resnet101_efsign(y):
+    st = compress_fullsize(3, "efsign", y, 16, iters=2 if y == 1 else 1, oracle_workers=None if y == 1 else [0, 15])
+    assert st.decompress_checks == (1 if y == 1 else 0)
+
+
+@pytest.mark.parametrize("y", [1, 2, 4])
+def test_config3_resnet101_topk(y):
+    compress_fullsize(3, "topk", y, 16, iters=2 if y == 1 else 1, oracle_workers=[0] if y == 1 else [15], ppm=1000)
+    wl, grads = grads_of(3)
+    sparse_decompress_fullsize(wl, "topk", y, 16, grads, 1000)
+
+
+# ---- configs[4]: Mask R-CNN shapes (odd tensor sizes, Student-t values), y in {1,2,4}, W = 8; all six algorithms ----
+@pytest.mark.parametrize("y", [1, 2, 4])
+@pytest.mark.parametrize("algo", ["efsign", "qsgd", "terngrad", "fp16"])
+def test_config4_maskrcnn_dense(algo, y):
+    st = compress_fullsize(4, algo, y, 8, iters=2 if y == 1 else 1, oracle_workers=None if y == 4 else [0, 7])
+    assert st.decompress_checks == (4 if y == 4 else 0)
+
+
+@pytest.mark.parametrize("y", [1, 2, 4])
+@pytest.mark.parametrize("algo", ["topk", "dgc"])
+def test_config4_maskrcnn_sparse(algo, y):
+    compress_fullsize(4, algo, y, 8, iters=2 if y == 1 else 1, oracle_workers=[0] if y == 1 else [7])
+    wl, grads = grads_of(4)
+    sparse_decompress_fullsize(wl, algo, y, 8, grads, 10000)
