@@ -43,7 +43,9 @@ ALGO_BYTES = {
 CALL_BYTES = {"efsign": (12.125, lambda W: W / 8.0 + 4.0), "topk": (12.08, lambda W: 4.0 + 0.08 * W)}
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None = not measured
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {        # profiles/bench_resnet50_efsign_topk.txt, read + write, scaled by the copy calibration
+    "efsign_compress": 316.21e6, "sparse_accum": 317.93e6, "dense_decompress": 133.32e6, "sparse_decompress": 135.31e6,
+}
 
 
 def parse():
@@ -55,6 +57,9 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-curve", action="store_true", help="skip the compress-time-vs-y curve")
     ap.add_argument("--algos", default="efsign,topk")
+    ap.add_argument("--grad-layout", default="separate", choices=["separate", "views"],
+                    help="separate: every gradient tensor its own allocation (a model's .grad tensors); views: the "
+                         "tensors of a worker are views into one buffer (a bucketed gradient store)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run 10 plain device copies of 256 MiB (a kernel of known traffic, used to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -129,7 +134,11 @@ def main():
 
     flats = [WL.gradients_flat(wl, w, 0) for w in range(W)]
     offs = np.concatenate([[0], np.cumsum(numel)])
-    grads = [[torch.from_numpy(f[offs[t]:offs[t + 1]]).to("cuda:0") for t in range(len(numel))] for f in flats]
+    if args.grad_layout == "views":
+        bufs = [torch.from_numpy(f).to("cuda:0") for f in flats]
+        grads = [[b[offs[t]:offs[t + 1]] for t in range(len(numel))] for b in bufs]
+    else:
+        grads = [[torch.from_numpy(f[offs[t]:offs[t + 1]]).to("cuda:0") for t in range(len(numel))] for f in flats]
 
     if args.calibrate_copy:
         src = torch.ones(1 << 26, dtype=torch.float32, device="cuda:0")      # 256 MiB in, 256 MiB out per copy
@@ -234,7 +243,7 @@ def main():
         "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "resnet50-shaped gradients, 161 tensors, 25557032 fp32, per-tensor std log-uniform [1e-4,1e-1]",
-                   "y": args.y, "workers": W, "algorithms": algos, "topk_ratio_ppm": 10000,
+                   "y": args.y, "workers": W, "grad_layout": args.grad_layout, "algorithms": algos, "topk_ratio_ppm": 10000,
                    "step": "per algorithm: one worker's mc_compress + one mc_decompress_sum over W payloads"},
         "roofline": {"bound": "hbm", "kernel": f"{dom_algo}:{dom_kernel}", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(dom_kernel),

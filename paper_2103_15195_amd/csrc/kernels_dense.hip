@@ -122,36 +122,38 @@ void launch_efsign_compress(const LaunchCtx &lc, const GroupView &g, bool ef, fl
 //   RED_MEAN_ABS: scale = (float)(sum / n)      RED_L2: norm = (float)sqrt(sum)
 //   RED_MAX_ABS : max of the partials (exact)   mode < 0: header only
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void scalar_finalize_k(const double *partial, uint32_t nblocks, int mode, uint32_t n,
-                                                            PayloadHeader *hdr, uint32_t algo, uint64_t k, uint32_t levels,
-                                                            float *state_scale)
+constexpr int kFinalThreads = 1024;
+
+__global__ __launch_bounds__(kFinalThreads) void scalar_finalize_k(const double *partial, uint32_t nblocks, int mode, uint32_t n,
+                                                                   PayloadHeader *hdr, uint32_t algo, uint64_t k, uint32_t levels,
+                                                                   float *state_scale)
 {
-    __shared__ double red[kBlock];
+    __shared__ double red[kFinalThreads / 64];
     double acc = 0.0;
     if (mode >= 0) {
-        // eight independent loads in flight per round; the order of additions depends on nblocks only
-        for (uint32_t base = 0; base < nblocks; base += 8 * kBlock) {
+        // eight independent loads in flight per thread and round (one round up to 8192 partials);
+        // the order of additions depends on nblocks only
+        for (uint32_t base = 0; base < nblocks; base += 8 * kFinalThreads) {
             double v[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                uint32_t i = base + u * kBlock + threadIdx.x;
+                uint32_t i = base + u * kFinalThreads + threadIdx.x;
                 v[u] = i < nblocks ? partial[i] : 0.0;
             }
 #pragma unroll
             for (int u = 0; u < 8; ++u) acc = mode == RED_MAX_ABS ? fmax(acc, v[u]) : acc + v[u];
         }
     }
-    red[threadIdx.x] = acc;
-    __syncthreads();
-    for (int s = kBlock / 2; s >= 1; s >>= 1) {
-        if ((int)threadIdx.x < s) {
-            double a = red[threadIdx.x], b = red[threadIdx.x + s];
-            red[threadIdx.x] = mode == RED_MAX_ABS ? fmax(a, b) : a + b;
-        }
-        __syncthreads();
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+        double o = __shfl_xor(acc, m, 64);
+        acc = mode == RED_MAX_ABS ? fmax(acc, o) : acc + o;
     }
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
     if (threadIdx.x == 0) {
         double S = red[0];
+        for (int w = 1; w < kFinalThreads / 64; ++w) S = mode == RED_MAX_ABS ? fmax(S, red[w]) : S + red[w];
         float scale = 0.0f;
         if (n > 0) {
             if (mode == RED_MEAN_ABS) scale = (float)(S / (double)n);
@@ -170,7 +172,7 @@ void launch_scalar_finalize(const LaunchCtx &lc, const double *partial, uint32_t
                             PayloadHeader *hdr, uint32_t algo, uint64_t k, uint32_t levels, float *state_scale)
 {
     prof_begin(lc, K_SCALAR_FINALIZE);
-    hipLaunchKernelGGL(scalar_finalize_k, dim3(1), dim3(kBlock), 0, lc.stream, partial, nblocks, mode, n, hdr, algo, k,
+    hipLaunchKernelGGL(scalar_finalize_k, dim3(1), dim3(kFinalThreads), 0, lc.stream, partial, nblocks, mode, n, hdr, algo, k,
                        levels, state_scale);
     prof_end(lc, K_SCALAR_FINALIZE);
 }

@@ -73,7 +73,10 @@ void launch_dense_decompress(const LaunchCtx &lc, int algo, const GroupView &out
 void launch_state_convert(const LaunchCtx &lc, int algo, bool to_residual, uint32_t nfloats, const void *src, void *dst);
 
 // ---- sparse kernels (kernels_sparse.hip) ----------------------------------------
-constexpr uint32_t kMaxCandBlocks = 512;   // grid of the kernels that walk the candidate slots
+#ifndef MC_CAND_BLOCKS
+#define MC_CAND_BLOCKS 512
+#endif
+constexpr uint32_t kMaxCandBlocks = MC_CAND_BLOCKS;   // grid of the kernels that walk the candidate slots
 constexpr int kHistWords = 2048 + 1024 + 1024;   // bins of the three radix levels
 
 // what the plan kernel tells the kernels that walk the candidates
