@@ -28,7 +28,7 @@ void launch_upload_ptrs(const LaunchCtx &lc, const uintptr_t *host, uintptr_t *d
         uint32_t m = count - done < 256 ? count - done : 256;
         for (uint32_t i = 0; i < 256; ++i) ch.p[i] = i < m ? host[done + i] : 0;
         prof_begin(lc, K_UPLOAD);
-        hipLaunchKernelGGL(upload_ptrs_k, dim3(1), dim3(256), 0, lc.stream, ch, dev + done, m);
+        MC_LAUNCH(upload_ptrs_k, dim3(1), dim3(256), lc, ch, dev + done, m);
         prof_end(lc, K_UPLOAD);
     }
 }
@@ -53,7 +53,7 @@ void launch_expand_ptrs(const LaunchCtx &lc, const GroupView &g, uintptr_t *chun
     if (g.n == 0) return;
     const uint32_t nchunks = (uint32_t)(((uint64_t)g.n + kChunk - 1) / kChunk);
     prof_begin(lc, K_UPLOAD);
-    hipLaunchKernelGGL(expand_ptrs_k, dim3((nchunks + kBlock - 1) / kBlock), dim3(kBlock), 0, lc.stream, g, chunk_addr);
+    MC_LAUNCH(expand_ptrs_k, dim3((nchunks + kBlock - 1) / kBlock), dim3(kBlock), lc, g, chunk_addr);
     prof_end(lc, K_UPLOAD);
 }
 
@@ -110,8 +110,8 @@ void launch_efsign_compress(const LaunchCtx &lc, const GroupView &g, bool ef, fl
     if (g.n == 0) return;
     dim3 grid(tiles_of(g.n)), block(kBlock);
     prof_begin(lc, K_EFSIGN_COMPRESS);
-    if (ef) hipLaunchKernelGGL(efsign_compress_k<true>, grid, block, 0, lc.stream, g, state_f, scale_prev, words, nwords, partial);
-    else hipLaunchKernelGGL(efsign_compress_k<false>, grid, block, 0, lc.stream, g, state_f, scale_prev, words, nwords, partial);
+    if (ef) MC_LAUNCH(efsign_compress_k<true>, grid, block, lc, g, state_f, scale_prev, words, nwords, partial);
+    else MC_LAUNCH(efsign_compress_k<false>, grid, block, lc, g, state_f, scale_prev, words, nwords, partial);
     prof_end(lc, K_EFSIGN_COMPRESS);
 }
 
@@ -172,7 +172,7 @@ void launch_scalar_finalize(const LaunchCtx &lc, const double *partial, uint32_t
                             PayloadHeader *hdr, uint32_t algo, uint64_t k, uint32_t levels, float *state_scale)
 {
     prof_begin(lc, K_SCALAR_FINALIZE);
-    hipLaunchKernelGGL(scalar_finalize_k, dim3(1), dim3(kFinalThreads), 0, lc.stream, partial, nblocks, mode, n, hdr, algo, k,
+    MC_LAUNCH(scalar_finalize_k, dim3(1), dim3(kFinalThreads), lc, partial, nblocks, mode, n, hdr, algo, k,
                        levels, state_scale);
     prof_end(lc, K_SCALAR_FINALIZE);
 }
@@ -220,11 +220,11 @@ void launch_accum_reduce(const LaunchCtx &lc, const GroupView &g, bool ef, float
     dim3 grid(tiles_of(g.n)), block(kBlock);
     prof_begin(lc, K_ACCUM_REDUCE);
     if (mode == RED_L2) {
-        if (ef) hipLaunchKernelGGL((accum_reduce_k<true, RED_L2>), grid, block, 0, lc.stream, g, state_f, partial);
-        else hipLaunchKernelGGL((accum_reduce_k<false, RED_L2>), grid, block, 0, lc.stream, g, state_f, partial);
+        if (ef) MC_LAUNCH((accum_reduce_k<true, RED_L2>), grid, block, lc, g, state_f, partial);
+        else MC_LAUNCH((accum_reduce_k<false, RED_L2>), grid, block, lc, g, state_f, partial);
     } else {
-        if (ef) hipLaunchKernelGGL((accum_reduce_k<true, RED_MAX_ABS>), grid, block, 0, lc.stream, g, state_f, partial);
-        else hipLaunchKernelGGL((accum_reduce_k<false, RED_MAX_ABS>), grid, block, 0, lc.stream, g, state_f, partial);
+        if (ef) MC_LAUNCH((accum_reduce_k<true, RED_MAX_ABS>), grid, block, lc, g, state_f, partial);
+        else MC_LAUNCH((accum_reduce_k<false, RED_MAX_ABS>), grid, block, lc, g, state_f, partial);
     }
     prof_end(lc, K_ACCUM_REDUCE);
 }
@@ -313,8 +313,8 @@ void launch_qsgd_encode(const LaunchCtx &lc, const GroupView &g, bool ef, float 
     if (g.n == 0) return;
     dim3 grid(tiles_of(g.n)), block(kBlock);
     prof_begin(lc, K_QSGD_ENCODE);
-    if (ef) hipLaunchKernelGGL(qsgd_encode_k<true>, grid, block, 0, lc.stream, g, state_f, hdr, codes, levels, seed, worker, iter_lo);
-    else hipLaunchKernelGGL(qsgd_encode_k<false>, grid, block, 0, lc.stream, g, state_f, hdr, codes, levels, seed, worker, iter_lo);
+    if (ef) MC_LAUNCH(qsgd_encode_k<true>, grid, block, lc, g, state_f, hdr, codes, levels, seed, worker, iter_lo);
+    else MC_LAUNCH(qsgd_encode_k<false>, grid, block, lc, g, state_f, hdr, codes, levels, seed, worker, iter_lo);
     prof_end(lc, K_QSGD_ENCODE);
 }
 
@@ -357,8 +357,8 @@ void launch_tern_encode(const LaunchCtx &lc, const GroupView &g, bool ef, float 
     if (g.n == 0) return;
     dim3 grid(tiles_of(g.n)), block(kBlock);
     prof_begin(lc, K_TERN_ENCODE);
-    if (ef) hipLaunchKernelGGL(tern_encode_k<true>, grid, block, 0, lc.stream, g, state_f, hdr, planes, nwords, seed, worker, iter_lo);
-    else hipLaunchKernelGGL(tern_encode_k<false>, grid, block, 0, lc.stream, g, state_f, hdr, planes, nwords, seed, worker, iter_lo);
+    if (ef) MC_LAUNCH(tern_encode_k<true>, grid, block, lc, g, state_f, hdr, planes, nwords, seed, worker, iter_lo);
+    else MC_LAUNCH(tern_encode_k<false>, grid, block, lc, g, state_f, hdr, planes, nwords, seed, worker, iter_lo);
     prof_end(lc, K_TERN_ENCODE);
 }
 
@@ -398,8 +398,8 @@ void launch_fp16_compress(const LaunchCtx &lc, const GroupView &g, bool ef, floa
     if (g.n == 0) return;
     dim3 grid(tiles_of(g.n)), block(kBlock);
     prof_begin(lc, K_FP16_COMPRESS);
-    if (ef) hipLaunchKernelGGL(fp16_compress_k<true>, grid, block, 0, lc.stream, g, state_f, halves);
-    else hipLaunchKernelGGL(fp16_compress_k<false>, grid, block, 0, lc.stream, g, state_f, halves);
+    if (ef) MC_LAUNCH(fp16_compress_k<true>, grid, block, lc, g, state_f, halves);
+    else MC_LAUNCH(fp16_compress_k<false>, grid, block, lc, g, state_f, halves);
     prof_end(lc, K_FP16_COMPRESS);
 }
 
@@ -626,12 +626,11 @@ void launch_dense_decompress(const LaunchCtx &lc, int algo, const GroupView &out
     prof_begin(lc, K_DENSE_DECOMPRESS);
     switch (algo) {
     case MC_ALGO_EFSIGN:
-        hipLaunchKernelGGL(efsign_decompress_k, dim3((uint32_t)(((uint64_t)out.n + kSignTile - 1) / kSignTile)), block, 0,
-                           lc.stream, out, pl, W, alpha, status);
+        MC_LAUNCH(efsign_decompress_k, dim3((uint32_t)(((uint64_t)out.n + kSignTile - 1) / kSignTile)), block, lc, out, pl, W, alpha, status);
         break;
-    case MC_ALGO_TERNGRAD: hipLaunchKernelGGL(dense_decompress_k<MC_ALGO_TERNGRAD>, grid, block, 0, lc.stream, out, pl, W, alpha, levels, status); break;
-    case MC_ALGO_QSGD: hipLaunchKernelGGL(dense_decompress_k<MC_ALGO_QSGD>, grid, block, 0, lc.stream, out, pl, W, alpha, levels, status); break;
-    default: hipLaunchKernelGGL(dense_decompress_k<MC_ALGO_FP16>, grid, block, 0, lc.stream, out, pl, W, alpha, levels, status); break;
+    case MC_ALGO_TERNGRAD: MC_LAUNCH(dense_decompress_k<MC_ALGO_TERNGRAD>, grid, block, lc, out, pl, W, alpha, levels, status); break;
+    case MC_ALGO_QSGD: MC_LAUNCH(dense_decompress_k<MC_ALGO_QSGD>, grid, block, lc, out, pl, W, alpha, levels, status); break;
+    default: MC_LAUNCH(dense_decompress_k<MC_ALGO_FP16>, grid, block, lc, out, pl, W, alpha, levels, status); break;
     }
     prof_end(lc, K_DENSE_DECOMPRESS);
 }
@@ -664,7 +663,7 @@ void launch_state_convert(const LaunchCtx &lc, int algo, bool to_residual, uint3
 {
     uint32_t work = nfloats > 16 ? nfloats : 16;
     prof_begin(lc, K_STATE_CONVERT);
-    hipLaunchKernelGGL(state_convert_k, dim3((work + kBlock - 1) / kBlock), dim3(kBlock), 0, lc.stream, algo,
+    MC_LAUNCH(state_convert_k, dim3((work + kBlock - 1) / kBlock), dim3(kBlock), lc, algo,
                        to_residual ? 1 : 0, nfloats, (const uint8_t *)src, (uint8_t *)dst);
     prof_end(lc, K_STATE_CONVERT);
 }

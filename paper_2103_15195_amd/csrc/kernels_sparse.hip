@@ -660,22 +660,22 @@ static void sparse_compress_t(const LaunchCtx &lc, const GroupView &g, float *st
     const uint32_t pblocks = (nch + 15) / 16 < 256 ? (nch + 15) / 16 : 256;
     dim3 grid(nt), block(kBlock), cgrid(cblocks);
     prof_begin(lc, K_SPARSE_ACCUM);
-    hipLaunchKernelGGL((sparse_accum_k<ALGO, EF>), grid, block, 0, lc.stream, g, st, momentum, sc);
+    MC_LAUNCH((sparse_accum_k<ALGO, EF>), grid, block, lc, g, st, momentum, sc);
     prof_end(lc, K_SPARSE_ACCUM);
     prof_begin(lc, K_SPARSE_PLAN);
-    hipLaunchKernelGGL(sparse_plan_k<FS>, dim3(pblocks), dim3(kPlanThreads), 0, lc.stream, g, st, k, nwaves, sc);
+    MC_LAUNCH(sparse_plan_k<FS>, dim3(pblocks), dim3(kPlanThreads), lc, g, st, k, nwaves, sc);
     prof_end(lc, K_SPARSE_PLAN);
     prof_begin(lc, K_CAND_HIST);
-    hipLaunchKernelGGL(cand_hist_k<2>, cgrid, block, 0, lc.stream, g.n, k, sc);
+    MC_LAUNCH(cand_hist_k<2>, cgrid, block, lc, g.n, k, sc);
     prof_end(lc, K_CAND_HIST);
     prof_begin(lc, K_CAND_HIST);
-    hipLaunchKernelGGL(cand_hist_k<3>, cgrid, block, 0, lc.stream, g.n, k, sc);
+    MC_LAUNCH(cand_hist_k<3>, cgrid, block, lc, g.n, k, sc);
     prof_end(lc, K_CAND_HIST);
     prof_begin(lc, K_CAND_COUNT);
-    hipLaunchKernelGGL(cand_count_k, cgrid, block, 0, lc.stream, g.n, sc);
+    MC_LAUNCH(cand_count_k, cgrid, block, lc, g.n, sc);
     prof_end(lc, K_CAND_COUNT);
     prof_begin(lc, K_CAND_EMIT);
-    hipLaunchKernelGGL((cand_emit_k<ALGO, EF>), cgrid, block, 0, lc.stream, g.n, st, hdr, k, sc);
+    MC_LAUNCH((cand_emit_k<ALGO, EF>), cgrid, block, lc, g.n, st, hdr, k, sc);
     prof_end(lc, K_CAND_EMIT);
 }
 
@@ -814,11 +814,11 @@ void launch_sparse_decompress(const LaunchCtx &lc, int algo, const GroupView &ou
     if (out.n == 0) return;
     const uint32_t nt = tiles_of(out.n);
     prof_begin(lc, K_SPARSE_INDEX);
-    hipLaunchKernelGGL(sparse_index_k, dim3((uint32_t)((k + kBlock - 1) / kBlock), W), dim3(kBlock), 0, lc.stream, algo,
+    MC_LAUNCH(sparse_index_k, dim3((uint32_t)((k + kBlock - 1) / kBlock), W), dim3(kBlock), lc, algo,
                        out.n, pl, W, k, nt, epoch, tile_first, tile_last, status);
     prof_end(lc, K_SPARSE_INDEX);
     prof_begin(lc, K_SPARSE_DECOMPRESS);
-    hipLaunchKernelGGL(sparse_decompress_k, dim3(nt), dim3(kBlock), 0, lc.stream, out, pl, W, alpha, k, nt, epoch, tile_first,
+    MC_LAUNCH(sparse_decompress_k, dim3(nt), dim3(kBlock), lc, out, pl, W, alpha, k, nt, epoch, tile_first,
                        tile_last);
     prof_end(lc, K_SPARSE_DECOMPRESS);
 }

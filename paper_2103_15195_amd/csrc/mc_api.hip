@@ -43,7 +43,6 @@ struct Profiler {
     std::vector<hipEvent_t> pool;
     int64_t launches[K_COUNT] = {};
     double ms[K_COUNT] = {};
-    hipEvent_t current = nullptr;
 };
 
 }  // namespace
@@ -65,26 +64,33 @@ struct mc_ctx {
 };
 
 namespace mc {
+static hipEvent_t prof_event(Profiler *p)
+{
+    hipEvent_t e = nullptr;
+    if (!p->pool.empty()) { e = p->pool.back(); p->pool.pop_back(); }
+    else if (hipEventCreate(&e) != hipSuccess) e = nullptr;
+    return e;
+}
 void prof_begin(const LaunchCtx &lc, int id)
 {
     Profiler *p = static_cast<Profiler *>(lc.prof);
+    lc.ev_a = lc.ev_b = nullptr;
     if (!p || !p->on || !((p->mask >> id) & 1ull)) return;
-    hipEvent_t a = nullptr;
-    if (!p->pool.empty()) { a = p->pool.back(); p->pool.pop_back(); }
-    else if (hipEventCreate(&a) != hipSuccess) { p->current = nullptr; return; }
-    (void)hipEventRecord(a, lc.stream);
-    p->current = a;
+    hipEvent_t a = prof_event(p), b = prof_event(p);
+    if (!a || !b) {
+        if (a) p->pool.push_back(a);
+        if (b) p->pool.push_back(b);
+        return;
+    }
+    lc.ev_a = a;
+    lc.ev_b = b;
 }
 void prof_end(const LaunchCtx &lc, int id)
 {
     Profiler *p = static_cast<Profiler *>(lc.prof);
-    if (!p || !p->on || !p->current) return;
-    hipEvent_t b = nullptr;
-    if (!p->pool.empty()) { b = p->pool.back(); p->pool.pop_back(); }
-    else if (hipEventCreate(&b) != hipSuccess) { p->pool.push_back(p->current); p->current = nullptr; return; }
-    (void)hipEventRecord(b, lc.stream);
-    p->pending.push_back({id, p->current, b});
-    p->current = nullptr;
+    if (!p || !lc.ev_a) return;
+    p->pending.push_back({id, lc.ev_a, lc.ev_b});
+    lc.ev_a = lc.ev_b = nullptr;
 }
 }  // namespace mc
 
@@ -388,7 +394,7 @@ int mc_compress(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter, cons
     for (int32_t rel : G.live) if (!grad_ptrs[rel] || (reinterpret_cast<uintptr_t>(grad_ptrs[rel]) & 3u)) return MC_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(payload_out) & 15u) || (reinterpret_cast<uintptr_t>(state) & 15u)) return MC_ERR_INVALID_ARG;
 
-    LaunchCtx lc{static_cast<hipStream_t>(stream), &ctx->prof};
+    LaunchCtx lc{static_cast<hipStream_t>(stream), &ctx->prof, nullptr, nullptr};
     (void)hipGetLastError();
     PayloadHeader *hdr = static_cast<PayloadHeader *>(payload_out);
     uint8_t *body = static_cast<uint8_t *>(payload_out) + kHeaderBytes;
@@ -450,7 +456,7 @@ int mc_decompress_sum(mc_ctx *ctx, int32_t group, const void *const *payloads, i
         pl.p[w] = static_cast<const uint8_t *>(payloads[w]);
     }
     if (G.n == 0) return MC_OK;
-    LaunchCtx lc{static_cast<hipStream_t>(stream), &ctx->prof};
+    LaunchCtx lc{static_cast<hipStream_t>(stream), &ctx->prof, nullptr, nullptr};
     (void)hipGetLastError();
     GroupView gv = group_view(ctx, lc, group, G, reinterpret_cast<const void *const *>(out_ptrs));
     const mc_config &cfg = ctx->cfg;
@@ -472,7 +478,7 @@ static int state_convert(mc_ctx *ctx, int32_t group, const void *src, void *dst,
     // an empty group has no residual: the plain side may be null, the opaque side never
     if (!(to_residual ? src : dst) || (nf > 0 && !(to_residual ? dst : src))) return MC_ERR_INVALID_ARG;
     if (nf == 0 && to_residual) return MC_OK;
-    LaunchCtx lc{static_cast<hipStream_t>(stream), &ctx->prof};
+    LaunchCtx lc{static_cast<hipStream_t>(stream), &ctx->prof, nullptr, nullptr};
     (void)hipGetLastError();
     launch_state_convert(lc, ctx->cfg.algo, to_residual, nf, src, dst);
     return check_launch();

@@ -1,6 +1,7 @@
 // Host <-> kernel-launcher interface of the library (not part of the C ABI).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "../../include/mergecomp.h"
@@ -50,9 +51,17 @@ enum ReduceMode { RED_MEAN_ABS = 0, RED_L2 = 1, RED_MAX_ABS = 2 };
 struct LaunchCtx {               // what a launcher needs besides its arguments
     hipStream_t stream;
     void *prof;                  // opaque: profiling recorder or null
+    mutable hipEvent_t ev_a = nullptr, ev_b = nullptr;   // set by prof_begin when the next launch is to be timed
 };
+// prof_begin arms the next MC_LAUNCH with a start / stop event pair (if that kernel slot is being timed);
+// the events are attached to the dispatch itself, so they bracket the kernel's execution only.
 void prof_begin(const LaunchCtx &lc, int id);
 void prof_end(const LaunchCtx &lc, int id);
+#define MC_LAUNCH(kernel, grid, block, lc, ...)                                                                       \
+    do {                                                                                                              \
+        if ((lc).ev_a) hipExtLaunchKernelGGL(kernel, grid, block, 0, (lc).stream, (lc).ev_a, (lc).ev_b, 0, __VA_ARGS__); \
+        else hipLaunchKernelGGL(kernel, grid, block, 0, (lc).stream, __VA_ARGS__);                                    \
+    } while (0)
 
 // ---- dense kernels (kernels_dense.hip) -----------------------------------------
 void launch_upload_ptrs(const LaunchCtx &lc, const uintptr_t *host, uintptr_t *dev, uint32_t count);
