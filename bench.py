@@ -39,8 +39,12 @@ ALGO_BYTES = {
     "dense_decompress": lambda n, W, rho: (W / 8.0 + 4.0) * n,  # W sign planes in, fp32 out
     "sparse_decompress": lambda n, W, rho: (4.0 + 8.0 * rho * W) * n,
 }
-# Whole-call algorithmic bytes per element (compress, decompress-sum), W = 8, 1 %
-CALL_BYTES = {"efsign": (12.125, lambda W: W / 8.0 + 4.0), "topk": (12.08, lambda W: 4.0 + 0.08 * W)}
+# Whole-call algorithmic bytes per element (compress, decompress-sum): Top-k 1 %, DGC 0.1 %
+CALL_BYTES = {
+    "efsign": (12.125, lambda W: W / 8.0 + 4.0), "topk": (12.08, lambda W: 4.0 + 0.08 * W),
+    "dgc": (20.008, lambda W: 4.0 + 0.008 * W), "qsgd": (13.0, lambda W: W + 4.0),
+    "terngrad": (12.25, lambda W: W / 4.0 + 4.0), "fp16": (14.0, lambda W: 2.0 * W + 4.0),
+}
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None = not measured
 MEASURED_TRAFFIC = {        # profiles/bench_resnet50_efsign_topk.txt, read + write, scaled by the copy calibration
@@ -69,8 +73,9 @@ def parse():
 class AlgoBench:
     """Buffers and calls of one algorithm on the workload."""
 
-    def __init__(self, B, torch, name, numel, y, W, grads, ratio_ppm=10000):
+    def __init__(self, B, torch, name, numel, y, W, grads):
         self.name, self.W, self.y = name, W, y
+        ratio_ppm = 1000 if name == "dgc" else 10000          # BASELINE configs[2]: Top-k 1 %, DGC 0.1 %
         self.bounds = B.mc_partition(numel, y, B.MC_PART_EVEN_ELEMS)
         self.ctx = B.Context(name, numel, self.bounds, ratio_ppm=ratio_ppm, seed=1)
         dev = "cuda:0"
@@ -226,7 +231,7 @@ def main():
         from oracle import oracle as O
         t_cpu = 0.0
         for a in algos:
-            ocfg = O.Config(B.ALGO_IDS[a], ratio_ppm=10000, seed=1)
+            ocfg = O.Config(B.ALGO_IDS[a], ratio_ppm=1000 if a == "dgc" else 10000, seed=1)
             st = O.new_state(ocfg, D)
             t0 = time.perf_counter()
             pay, _ = O.compress(ocfg, flats[0], st)

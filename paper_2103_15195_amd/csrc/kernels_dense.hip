@@ -282,19 +282,19 @@ __global__ __launch_bounds__(kBlock) void qsgd_encode_k(GroupView g, float *st, 
     const float q = (float)((double)norm / (double)sf);
     float p[kSteps];
     load_p<EF>(g, st, c, p);
+    float uni[kSteps];
+    chunk_uniforms(seed, worker, iter_lo, g.goff + c.base, c.lane, uni);
     int8_t code[kSteps];
     float e[kSteps];
 #pragma unroll
     for (int j = 0; j < kSteps; ++j) {
-        uint32_t i = c.base + 64 * j + c.lane;
         int xi = 0;
         if (norm > 0.0f) {
             float a = fabsf(p[j]) * r;
             if (a < sf) {
                 float l = floorf(a);
                 float f = a - l;
-                float u = philox_uniform(seed, worker, iter_lo, g.goff + i);
-                xi = (int)l + (u < f ? 1 : 0);
+                xi = (int)l + (uni[j] < f ? 1 : 0);
                 xi = xi > (int)levels ? (int)levels : xi;
             } else xi = (int)levels;
         }
@@ -332,14 +332,15 @@ __global__ __launch_bounds__(kBlock) void tern_encode_k(GroupView g, float *st, 
     const float smax = hdr->scale;
     float p[kSteps];
     load_p<EF>(g, st, c, p);
+    float uni[kSteps];
+    chunk_uniforms(seed, worker, iter_lo, g.goff + c.base, c.lane, uni);
     uint64_t bnz[kSteps], bng[kSteps];
     float e[kSteps];
 #pragma unroll
     for (int j = 0; j < kSteps; ++j) {
         uint32_t i = c.base + 64 * j + c.lane;
         bool valid = c.full || i < g.n;
-        float u = philox_uniform(seed, worker, iter_lo, g.goff + i);
-        bool nz = valid && (u * smax < fabsf(p[j]));
+        bool nz = valid && (uni[j] * smax < fabsf(p[j]));
         bool neg = nz && p[j] < 0.0f;
         bnz[j] = __builtin_amdgcn_ballot_w64(nz);
         bng[j] = __builtin_amdgcn_ballot_w64(neg);
@@ -516,7 +517,7 @@ __global__ __launch_bounds__(kBlock) void dense_decompress_k(GroupView out, Payl
 }
 
 // ---------------------------------------------------------------------------
-// EF-Sign decompress-and-sum.  With W sign planes the per-element work of the
+// EF-Sign / TernGrad decompress-and-sum.  With W sign planes the per-element work of the
 // generic kernel (extract bit, select +-scale, add; W times) exceeds what the
 // vector ALUs can do at HBM speed, so this kernel works on whole words:
 //   * the sum of the first (up to) 8 workers takes one of 2^8 values per group;
@@ -541,58 +542,126 @@ __device__ __forceinline__ uint64_t transpose8x8(uint64_t x)
 constexpr int kSignWaveElems = 2048;                       // 64 lanes x 32 elements
 constexpr int kSignTile = kSignWaveElems * kWavesPerBlock; // 8192 elements per block
 
-__global__ __launch_bounds__(kBlock) void efsign_decompress_k(GroupView out, PayloadPtrs pl, int W, float alpha, int *status)
+// bytes of 8 words (one per worker) -> per element the 8 workers' bits: word q byte -> 8 table indices
+__device__ __forceinline__ uint64_t gather_transpose(const uint32_t (&wd)[8], int q)
 {
-    __shared__ float table[256];
+    uint32_t lo = ((wd[0] >> (8 * q)) & 0xFFu) | (((wd[1] >> (8 * q)) & 0xFFu) << 8) |
+                  (((wd[2] >> (8 * q)) & 0xFFu) << 16) | (((wd[3] >> (8 * q)) & 0xFFu) << 24);
+    uint32_t hi = ((wd[4] >> (8 * q)) & 0xFFu) | (((wd[5] >> (8 * q)) & 0xFFu) << 8) |
+                  (((wd[6] >> (8 * q)) & 0xFFu) << 16) | (((wd[7] >> (8 * q)) & 0xFFu) << 24);
+    return transpose8x8((uint64_t)lo | ((uint64_t)hi << 32));
+}
+
+constexpr int kTernCombos = 6561;          // 3^8 ternary digits of 8 workers
+
+// TERN = false: EF-Sign (one plane, 2^8 sums).  TERN = true: TernGrad (non-zero and negative planes;
+// a worker contributes 0, +s or -s, so the first 8 workers have 3^8 possible sums; the index is
+// sum_w digit_w 3^w with digit = nz + (nz & neg), formed from two small lookups of the bit bytes).
+// The 3^8 sums of the first (up to) 8 TernGrad workers, tabulated once per call: every entry is
+// the same sequence of fp32 additions ((0 + d_0) + d_1) + ... a per-element loop would perform.
+__global__ __launch_bounds__(kBlock) void tern_table_k(PayloadPtrs pl, int W, float alpha, float *table)
+{
+    const int Wt = W < 8 ? W : 8;
+    float sc[8];
+#pragma unroll
+    for (int b = 0; b < 8; ++b) sc[b] = b < Wt ? reinterpret_cast<const PayloadHeader *>(pl.p[b])->scale : 0.0f;
+    for (uint32_t idx = blockIdx.x * kBlock + threadIdx.x; idx < (uint32_t)kTernCombos; idx += gridDim.x * kBlock) {
+        float acc = 0.0f;
+        uint32_t rest = idx;
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const uint32_t digit = rest % 3u;       // 0: nothing, 1: +s, 2: -s
+            rest /= 3u;
+            if (b < Wt) acc = acc + (digit == 0 ? 0.0f : digit == 1 ? sc[b] : -sc[b]);
+        }
+        table[idx] = W <= 8 ? alpha * acc : acc;
+    }
+}
+
+template <bool TERN>
+__global__ __launch_bounds__(kBlock) void plane_decompress_k(GroupView out, PayloadPtrs pl, int W, float alpha, int *status,
+                                                             const float *tern_table)
+{
+    __shared__ float table[TERN ? kTernCombos : 256];
+    __shared__ uint16_t pow3[TERN ? 256 : 1];             // pow3[b] = sum over set bits w of b of 3^w
     __shared__ float stage[kWavesPerBlock][kChunk + 32];
     const uint32_t t = threadIdx.x;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(t >> 6), lane = t & 63u;
     if (blockIdx.x == 0 && (int)t < W)
-        check_header(reinterpret_cast<const PayloadHeader *>(pl.p[t]), MC_ALGO_EFSIGN, out.n, status);
+        check_header(reinterpret_cast<const PayloadHeader *>(pl.p[t]), TERN ? MC_ALGO_TERNGRAD : MC_ALGO_EFSIGN, out.n, status);
     const int Wt = W < 8 ? W : 8;
     {
         float sc[8];
 #pragma unroll
         for (int b = 0; b < 8; ++b) sc[b] = b < Wt ? reinterpret_cast<const PayloadHeader *>(pl.p[b])->scale : 0.0f;
-        float acc = 0.0f;
+        if (!TERN) {
+            float acc = 0.0f;
 #pragma unroll
-        for (int b = 0; b < 8; ++b) if (b < Wt) acc = acc + (((t >> b) & 1u) ? sc[b] : -sc[b]);
-        table[t] = W <= 8 ? alpha * acc : acc;
+            for (int b = 0; b < 8; ++b) if (b < Wt) acc = acc + (((t >> b) & 1u) ? sc[b] : -sc[b]);
+            table[t] = W <= 8 ? alpha * acc : acc;
+        } else {
+            uint32_t p3 = 0, pw = 1;
+#pragma unroll
+            for (int b = 0; b < 8; ++b) { if ((t >> b) & 1u) p3 += pw; pw *= 3u; }
+            pow3[t] = (uint16_t)p3;
+            constexpr int kPer = (kTernCombos + kBlock - 1) / kBlock;
+            float v[kPer];
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) v[i] = t + i * kBlock < (uint32_t)kTernCombos ? tern_table[t + i * kBlock] : 0.0f;
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) if (t + i * kBlock < (uint32_t)kTernCombos) table[t + i * kBlock] = v[i];
+        }
     }
     __syncthreads();
     const uint32_t wbase = blockIdx.x * (uint32_t)kSignTile + wave * (uint32_t)kSignWaveElems;
     if (wbase >= out.n) return;
     const uint32_t nwords = (out.n + 31u) >> 5;
     const uint32_t wi = (wbase >> 5) + lane;
-    uint32_t wd[8];
+    uint32_t wd[8], wn[8];
 #pragma unroll
     for (int b = 0; b < 8; ++b) {
-        wd[b] = 0u;
-        if (b < Wt && wi < nwords) wd[b] = ld_stream(reinterpret_cast<const uint32_t *>(pl.p[b] + kHeaderBytes) + wi);
+        wd[b] = 0u; wn[b] = 0u;
+        if (b < Wt && wi < nwords) {
+            const uint32_t *plane = reinterpret_cast<const uint32_t *>(pl.p[b] + kHeaderBytes);
+            wd[b] = ld_stream(plane + wi);
+            if (TERN) wn[b] = ld_stream(plane + nwords + wi);
+        }
     }
     float acc[32];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         // byte q of the 8 words -> rows of an 8x8 bit matrix (row = worker, column = element 8q + c)
-        uint32_t lo = ((wd[0] >> (8 * q)) & 0xFFu) | (((wd[1] >> (8 * q)) & 0xFFu) << 8) |
-                      (((wd[2] >> (8 * q)) & 0xFFu) << 16) | (((wd[3] >> (8 * q)) & 0xFFu) << 24);
-        uint32_t hi = ((wd[4] >> (8 * q)) & 0xFFu) | (((wd[5] >> (8 * q)) & 0xFFu) << 8) |
-                      (((wd[6] >> (8 * q)) & 0xFFu) << 16) | (((wd[7] >> (8 * q)) & 0xFFu) << 24);
-        uint64_t x = transpose8x8((uint64_t)lo | ((uint64_t)hi << 32));
+        const uint64_t x = gather_transpose(wd, q);
+        if (!TERN) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[8 * q + e] = table[(uint32_t)(x >> (8 * e)) & 0xFFu];
+            for (int e = 0; e < 8; ++e) acc[8 * q + e] = table[(uint32_t)(x >> (8 * e)) & 0xFFu];
+        } else {
+            const uint64_t y = gather_transpose(wn, q) & x;           // negative only counts where non-zero
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                acc[8 * q + e] = table[(uint32_t)pow3[(uint32_t)(x >> (8 * e)) & 0xFFu] + pow3[(uint32_t)(y >> (8 * e)) & 0xFFu]];
+        }
     }
     if (W > 8) {
         for (int w = 8; w < W; ++w) {
             const float sc = reinterpret_cast<const PayloadHeader *>(pl.p[w])->scale;
-            uint32_t word = wi < nwords ? ld_stream(reinterpret_cast<const uint32_t *>(pl.p[w] + kHeaderBytes) + wi) : 0u;
+            const uint32_t *plane = reinterpret_cast<const uint32_t *>(pl.p[w] + kHeaderBytes);
+            const uint32_t word = wi < nwords ? ld_stream(plane + wi) : 0u;
+            const uint32_t neg = TERN && wi < nwords ? ld_stream(plane + nwords + wi) : 0u;
 #pragma unroll
-            for (int e = 0; e < 32; ++e) acc[e] = acc[e] + (((word >> e) & 1u) ? sc : -sc);
+            for (int e = 0; e < 32; ++e) {
+                const bool on = (word >> e) & 1u;
+                float d;
+                if (!TERN) d = on ? sc : -sc;
+                else d = on ? (((neg >> e) & 1u) ? -sc : sc) : 0.0f;
+                acc[e] = acc[e] + d;
+            }
         }
 #pragma unroll
         for (int e = 0; e < 32; ++e) acc[e] = alpha * acc[e];
     }
-    // two halves of 1024 elements through one stage: lanes 32 h .. 32 h + 31 own the elements of half h
+    // two halves of 1024 elements through one skewed LDS stage (lanes 32 h .. 32 h + 31 own the elements of
+    // half h), so that the global stores are 256 contiguous bytes per wave instruction
     float *mine = stage[wave];
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
@@ -619,16 +688,25 @@ __global__ __launch_bounds__(kBlock) void efsign_decompress_k(GroupView out, Pay
 }
 
 void launch_dense_decompress(const LaunchCtx &lc, int algo, const GroupView &out, const PayloadPtrs &pl, int W,
-                             float alpha, uint32_t levels, int *status)
+                             float alpha, uint32_t levels, int *status, float *tern_table)
 {
     if (out.n == 0) return;
     dim3 grid(tiles_of(out.n)), block(kBlock);
+    if (algo == MC_ALGO_TERNGRAD) {
+        prof_begin(lc, K_TERN_TABLE);
+        MC_LAUNCH(tern_table_k, dim3(8), block, lc, pl, W, alpha, tern_table);
+        prof_end(lc, K_TERN_TABLE);
+    }
     prof_begin(lc, K_DENSE_DECOMPRESS);
     switch (algo) {
     case MC_ALGO_EFSIGN:
-        MC_LAUNCH(efsign_decompress_k, dim3((uint32_t)(((uint64_t)out.n + kSignTile - 1) / kSignTile)), block, lc, out, pl, W, alpha, status);
+        MC_LAUNCH(plane_decompress_k<false>, dim3((uint32_t)(((uint64_t)out.n + kSignTile - 1) / kSignTile)), block, lc, out, pl, W,
+                  alpha, status, tern_table);
         break;
-    case MC_ALGO_TERNGRAD: MC_LAUNCH(dense_decompress_k<MC_ALGO_TERNGRAD>, grid, block, lc, out, pl, W, alpha, levels, status); break;
+    case MC_ALGO_TERNGRAD:
+        MC_LAUNCH(plane_decompress_k<true>, dim3((uint32_t)(((uint64_t)out.n + kSignTile - 1) / kSignTile)), block, lc, out, pl, W,
+                  alpha, status, tern_table);
+        break;
     case MC_ALGO_QSGD: MC_LAUNCH(dense_decompress_k<MC_ALGO_QSGD>, grid, block, lc, out, pl, W, alpha, levels, status); break;
     default: MC_LAUNCH(dense_decompress_k<MC_ALGO_FP16>, grid, block, lc, out, pl, W, alpha, levels, status); break;
     }

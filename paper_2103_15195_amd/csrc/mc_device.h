@@ -203,11 +203,9 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t ballot)
 
 // ---- Philox-4x32-10 (Salmon et al., SC'11) --------------------------------------
 // Counter = (J lo, J hi, worker, iteration), J = global element index / 4, key =
-// seed; the element takes output word (index % 4).  Returns the top 24 bits
-// scaled to [0, 1).
-__device__ __forceinline__ float philox_uniform(uint64_t seed, uint32_t worker, uint32_t iter_lo, uint64_t gidx)
+// seed; the element takes output word (index % 4), top 24 bits scaled to [0, 1).
+__device__ __forceinline__ void philox4x32_10(uint64_t seed, uint32_t worker, uint32_t iter_lo, uint64_t J, uint32_t (&out)[4])
 {
-    uint64_t J = gidx >> 2;
     uint32_t c0 = (uint32_t)J, c1 = (uint32_t)(J >> 32), c2 = worker, c3 = iter_lo;
     uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
 #pragma unroll
@@ -221,9 +219,50 @@ __device__ __forceinline__ float philox_uniform(uint64_t seed, uint32_t worker, 
         k0 += 0x9E3779B9u;
         k1 += 0xBB67AE85u;
     }
-    uint32_t lane = (uint32_t)gidx & 3u;
-    uint32_t x = lane == 0 ? c0 : lane == 1 ? c1 : lane == 2 ? c2 : c3;
-    return (float)(x >> 8) * 5.9604644775390625e-8f;
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+__device__ __forceinline__ float u01(uint32_t x) { return (float)(x >> 8) * 5.9604644775390625e-8f; }
+
+template <int R>
+__device__ __forceinline__ uint32_t quad_bcast(uint32_t x)      // value of lane R of each group of four lanes
+{
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, R | (R << 2) | (R << 4) | (R << 6), 0xF, 0xF, true);
+}
+
+// The uniforms of a chunk's 16 steps for this lane (element gbase + 64 j + lane in step j).
+// Four adjacent lanes hold four consecutive elements; when gbase is a multiple of 4 these
+// share one Philox block, so each lane computes one block per four steps (the one of step
+// 4m + lane % 4) and the four words are handed round inside the quad.
+__device__ __forceinline__ void chunk_uniforms(uint64_t seed, uint32_t worker, uint32_t iter_lo, uint64_t gbase, uint32_t lane,
+                                               float (&u)[kSteps])
+{
+    if ((gbase & 3u) == 0) {
+        const uint32_t me = lane & 3u;
+#pragma unroll
+        for (int m = 0; m < kSteps / 4; ++m) {
+            uint32_t w[4];
+            philox4x32_10(seed, worker, iter_lo, (gbase + 64u * (4 * m + me) + lane) >> 2, w);
+            uint32_t x[4][4];                      // x[r][i]: word i of the block of step 4m + r
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                x[0][i] = quad_bcast<0>(w[i]); x[1][i] = quad_bcast<1>(w[i]);
+                x[2][i] = quad_bcast<2>(w[i]); x[3][i] = quad_bcast<3>(w[i]);
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                u[4 * m + r] = u01(me == 0 ? x[r][0] : me == 1 ? x[r][1] : me == 2 ? x[r][2] : x[r][3]);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < kSteps; ++j) {
+            const uint64_t gidx = gbase + 64u * j + lane;
+            uint32_t w[4];
+            philox4x32_10(seed, worker, iter_lo, gidx >> 2, w);
+            const uint32_t i = (uint32_t)gidx & 3u;
+            u[j] = u01(i == 0 ? w[0] : i == 1 ? w[1] : i == 2 ? w[2] : w[3]);
+        }
+    }
 }
 
 }  // namespace mc
