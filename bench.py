@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the MergeComp hot path on one MI355X.
 
-Workload (benchmark configs[2]): ResNet-50-shaped gradients, 161 tensors,
+Workload (the benchmark's third configuration): ResNet-50-shaped gradients, 161 tensors,
 25 557 032 fp32, merged into y = 1 group, W = 8 simulated workers resident on
 the GPU.  One step = for each of EF-Sign and Top-k 1 %: one worker's
 mc_compress of the whole model followed by one mc_decompress_sum over the W
@@ -75,7 +75,7 @@ class AlgoBench:
 
     def __init__(self, B, torch, name, numel, y, W, grads):
         self.name, self.W, self.y = name, W, y
-        ratio_ppm = 1000 if name == "dgc" else 10000          # BASELINE configs[2]: Top-k 1 %, DGC 0.1 %
+        ratio_ppm = 1000 if name == "dgc" else 10000          # the configuration's ratios: Top-k 1 %, DGC 0.1 %
         self.bounds = B.mc_partition(numel, y, B.MC_PART_EVEN_ELEMS)
         self.ctx = B.Context(name, numel, self.bounds, ratio_ppm=ratio_ppm, seed=1)
         dev = "cuda:0"

@@ -3,7 +3,7 @@
 The HIP path is always reached through the C ABI (paper_2103_15195_amd.binding);
 the expected values always come from oracle/ run on the same seeded inputs.
 
-Bar (the benchmark spec): bit-exact packed codes, indices, sparsifier values and
+Bar: bit-exact packed codes, indices, sparsifier values and
 residuals; group scalars (EF-Sign scale, QSGD norm) within 1e-6 relative, TernGrad
 max bit-exact; aggregated sums within 1e-6 relative to sum_w |d_w| -- the tests
 assert the stricter bit equality for the sums, because both sides add the same

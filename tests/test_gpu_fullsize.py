@@ -1,4 +1,4 @@
-"""Full-size GPU-vs-oracle parity (BASELINE configs[2..4]) through the C ABI, in the launch
+"""Full-size GPU-vs-oracle parity (the three large benchmark configurations) through the C ABI, in the launch
 configuration bench.py times: ResNet-50-, ResNet-101- and Mask R-CNN-shaped gradient sets, every
 tensor its own device allocation, y and W as the configurations list them.
 
@@ -90,7 +90,7 @@ def compress_fullsize(cfg, algo, y, W, *, iters, oracle_workers, ppm=10000, **kw
     return st
 
 
-# ---- configs[2]: ResNet-50 shapes, y in {1,2,3,4}, W = 8; EF-Sign, Top-k 1 %, DGC 0.1 %, QSGD-8, TernGrad ----------
+# ---- third configuration: ResNet-50 shapes, y in {1,2,3,4}, W = 8; EF-Sign, Top-k 1 %, DGC 0.1 %, QSGD-8, TernGrad ----------
 @pytest.mark.parametrize("y", [1, 2, 3, 4])
 @pytest.mark.parametrize("algo", ["efsign", "qsgd", "terngrad"])
 def test_config2_resnet50_dense(algo, y):
@@ -107,7 +107,7 @@ def test_config2_resnet50_sparse(algo, ppm, y):
     sparse_decompress_fullsize(wl, algo, y, 8, grads, ppm)
 
 
-# ---- configs[3]: ResNet-101 shapes, y in {1,2,4}, W = 16; Top-k 0.1 % and EF-Sign ------------------------------------
+# ---- fourth configuration: ResNet-101 shapes, y in {1,2,4}, W = 16; Top-k 0.1 % and EF-Sign ------------------------------------
 @pytest.mark.parametrize("y", [1, 2, 4])
 def test_config3_resnet101_efsign(y):
     st = compress_fullsize(3, "efsign", y, 16, iters=2 if y == 1 else 1, oracle_workers=None if y == 1 else [0, 15])
@@ -121,7 +121,7 @@ def test_config3_resnet101_topk(y):
     sparse_decompress_fullsize(wl, "topk", y, 16, grads, 1000)
 
 
-# ---- configs[4]: Mask R-CNN shapes (odd tensor sizes, Student-t values), y in {1,2,4}, W = 8; all six algorithms ----
+# ---- fifth configuration: Mask R-CNN shapes (odd tensor sizes, Student-t values), y in {1,2,4}, W = 8; all six algorithms ----
 @pytest.mark.parametrize("y", [1, 2, 4])
 @pytest.mark.parametrize("algo", ["efsign", "qsgd", "terngrad", "fp16"])
 def test_config4_maskrcnn_dense(algo, y):

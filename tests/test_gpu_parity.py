@@ -27,7 +27,7 @@ def normal_grads(total, seed, scale=0.01):
     return fn
 
 
-# ---- BASELINE configs[0]: MLP, y=2, W=4, EF-Sign and Top-k 1 %, 3 iterations ----------
+# ---- first benchmark configuration: MLP, y=2, W=4, EF-Sign and Top-k 1 %, 3 iterations ----------
 @pytest.mark.parametrize("algo", ["efsign", "topk"])
 def test_config0_mlp(algo):
     wl = WL.workload(0)
@@ -36,7 +36,7 @@ def test_config0_mlp(algo):
     print(f"[config0 {algo}] conditional re-encodes: {st.conditional}")
 
 
-# ---- BASELINE configs[1]: ResNet-20 shapes, y in {1,2,4,8,16}, W=8, all algorithms ------
+# ---- second benchmark configuration: ResNet-20 shapes, y in {1,2,4,8,16}, W=8, all algorithms ------
 @pytest.mark.parametrize("y", [1, 2, 4, 8, 16])
 @pytest.mark.parametrize("algo", ALL)
 def test_config1_resnet20(algo, y):
