@@ -164,6 +164,19 @@ int mc_state_import_residual(mc_ctx *ctx, int32_t group, const float *e_in, void
  * mc_decompress_sum since the last call saw a mismatching header; clears the flag. */
 int mc_last_device_status(mc_ctx *ctx);
 
+/* Diagnostic for the sparsifiers (Top-k, DGC; Section 5.1 names their selection as the
+ * costly step).  Synchronises the context's device and reports which route the exact
+ * selection of the most recent mc_compress took:
+ *   MC_SELECT_FAST    the threshold fell inside the histogram window kept around the
+ *                     last threshold of this (group, worker): one more radix level
+ *   MC_SELECT_ABOVE   it rose above that window (also the first call): three levels
+ *   MC_SELECT_REFILL  fewer than k elements passed the candidate filter: the group was
+ *                     streamed a second time
+ * The result of mc_compress is identical on all routes; only its cost differs.
+ * Returns the route, or a negative mc_status (MC_ERR_INVALID_ARG for a dense algorithm). */
+enum { MC_SELECT_ABOVE = 0, MC_SELECT_FAST = 1, MC_SELECT_REFILL = 2 };
+int mc_last_select_route(mc_ctx *ctx);
+
 /*
  * Per-kernel timing with HIP events recorded on the caller's stream around each
  * launch (off by default).  mc_profile_read synchronises the recorded events.

@@ -17,12 +17,13 @@ LIB_PATH = os.environ.get("MERGECOMP_LIB", os.path.join(_HERE, "libmergecomp.so"
 MC_ALGO_EFSIGN, MC_ALGO_TOPK, MC_ALGO_DGC, MC_ALGO_QSGD, MC_ALGO_TERNGRAD, MC_ALGO_FP16 = 1, 2, 3, 4, 5, 6
 ALGO_IDS = {"efsign": 1, "topk": 2, "dgc": 3, "qsgd": 4, "terngrad": 5, "fp16": 6}
 MC_PART_EVEN_COUNT, MC_PART_EVEN_ELEMS, MC_PART_USER = 0, 1, 2
+MC_SELECT_ABOVE, MC_SELECT_FAST, MC_SELECT_REFILL = 0, 1, 2
 MC_OK, MC_ERR_INVALID_ARG, MC_ERR_RANGE, MC_ERR_ALLOC, MC_ERR_DEVICE, MC_ERR_PAYLOAD = 0, -1, -2, -3, -4, -5
 
 EXPORTS = [
     "mc_partition", "mc_ctx_create", "mc_ctx_destroy", "mc_group_numel", "mc_group_k", "mc_group_tensors",
     "mc_payload_bytes", "mc_state_bytes", "mc_compress", "mc_decompress_sum", "mc_state_export_residual",
-    "mc_state_import_residual", "mc_last_device_status", "mc_profile_enable", "mc_profile_select", "mc_profile_reset",
+    "mc_state_import_residual", "mc_last_device_status", "mc_last_select_route", "mc_profile_enable", "mc_profile_select", "mc_profile_reset",
     "mc_profile_kernels", "mc_profile_read", "mc_strerror", "mc_version",
 ]
 
@@ -66,6 +67,7 @@ def lib():
         L.mc_state_export_residual.argtypes = [vp, i32, vp, vp, vp]
         L.mc_state_import_residual.argtypes = [vp, i32, vp, vp, vp]
         L.mc_last_device_status.argtypes = [vp]
+        L.mc_last_select_route.argtypes = [vp]
         L.mc_profile_enable.argtypes = [vp, i32]
         L.mc_profile_select.argtypes = [vp, u64]
         L.mc_profile_reset.argtypes = [vp]
@@ -178,6 +180,12 @@ class Context:
 
     def mc_last_device_status(self) -> int:
         return int(lib().mc_last_device_status(self._h))
+
+    def mc_last_select_route(self) -> int:
+        r = int(lib().mc_last_select_route(self._h))
+        if r < 0:
+            raise McError(r, "mc_last_select_route")
+        return r
 
     # profiling ------------------------------------------------------------------
     def profile_enable(self, on: bool, all_kernels: bool = False) -> None:

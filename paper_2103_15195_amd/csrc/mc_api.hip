@@ -55,7 +55,7 @@ struct mc_ctx {
     size_t max_live = 0;
     double *d_partial = nullptr;
     SparseScratch sparse{};
-    uint32_t *d_hints = nullptr;        // one candidate-filter hint per group
+    uint32_t *d_hints = nullptr;        // candidate-filter hints: kHintWorkers per group (worker id modulo that)
     int *d_status = nullptr;
     float *d_tern_table = nullptr;      // TernGrad: the 3^8 sums of the first 8 workers of the current decompress call
     std::vector<PtrSlot> slots;
@@ -97,7 +97,7 @@ void prof_end(const LaunchCtx &lc, int id)
 
 static const char *kKernelNames[K_COUNT] = {
     "upload_ptrs", "efsign_compress", "scalar_finalize", "accum_reduce", "qsgd_encode", "tern_encode",
-    "fp16_compress", "dense_decompress", "sparse_accum", "sparse_plan", "cand_hist", "cand_count",
+    "fp16_compress", "dense_decompress", "sparse_accum", "sparse_seed", "cand_hist2", "cand_hist3", "cand_count",
     "cand_emit", "sparse_index", "sparse_decompress", "state_convert", "tern_table"};
 
 static void prof_drain(Profiler &p)
@@ -195,9 +195,9 @@ int mc_ctx_destroy(mc_ctx *ctx)
         if (s.dev_chunk) (void)hipFree(s.dev_chunk);
     }
     if (ctx->d_partial) (void)hipFree(ctx->d_partial);
-    void *sparse_bufs[] = {ctx->sparse.hist, ctx->sparse.sel, ctx->d_hints, ctx->sparse.plan, ctx->sparse.ne_tile, ctx->sparse.ne_prefix, ctx->sparse.ne_runs, ctx->sparse.wave_start, ctx->sparse.cand_bits,
-                           ctx->sparse.cand_loc, ctx->sparse.tile_runs, ctx->sparse.blk_gt, ctx->sparse.blk_eq,
-                           ctx->sparse.wave_gt, ctx->sparse.wave_eq, ctx->sparse.tile_first, ctx->sparse.tile_last};
+    void *sparse_bufs[] = {ctx->sparse.hist, ctx->sparse.sel, ctx->d_hints, ctx->sparse.cand_bits, ctx->sparse.cand_loc,
+                           ctx->sparse.tile_runs, ctx->sparse.tile_cnt, ctx->sparse.blk_cnt, ctx->sparse.tile_first,
+                           ctx->sparse.tile_last};
     for (void *b : sparse_bufs) if (b) (void)hipFree(b);
     if (ctx->d_status) (void)hipFree(ctx->d_status);
     if (ctx->d_tern_table) (void)hipFree(ctx->d_tern_table);
@@ -276,24 +276,16 @@ int mc_ctx_create(mc_ctx **out, const mc_config *cfg, const int64_t *numel, int3
             const size_t chunks = tiles * kWavesPerBlock, slots = chunks * kChunk;
             const size_t off_words = (size_t)kMaxWorkers * tiles;
             if (hipMalloc(&sp.hist, hist_bytes) != hipSuccess || hipMalloc(&sp.sel, 4 * sizeof(SelectState)) != hipSuccess ||
-                hipMalloc(&ctx->d_hints, y * sizeof(uint32_t)) != hipSuccess ||
-                hipMalloc(&sp.plan, sizeof(PlanState)) != hipSuccess ||
-                hipMalloc(&sp.ne_tile, tiles * sizeof(uint32_t)) != hipSuccess ||
-                hipMalloc(&sp.ne_prefix, (tiles + 1) * sizeof(uint32_t)) != hipSuccess ||
-                hipMalloc(&sp.ne_runs, tiles * sizeof(uint64_t)) != hipSuccess ||
-                hipMalloc(&sp.wave_start, (kMaxCandBlocks * kWavesPerBlock + 1) * sizeof(uint32_t)) != hipSuccess ||
+                hipMalloc(&ctx->d_hints, (size_t)y * kHintWorkers * sizeof(uint32_t)) != hipSuccess ||
                 hipMalloc(&sp.cand_bits, slots * sizeof(uint32_t)) != hipSuccess ||
                 hipMalloc(&sp.cand_loc, slots * sizeof(uint16_t)) != hipSuccess ||
                 hipMalloc(&sp.tile_runs, tiles * sizeof(uint64_t)) != hipSuccess ||
-                hipMalloc(&sp.blk_gt, kMaxCandBlocks * sizeof(uint32_t)) != hipSuccess ||
-                hipMalloc(&sp.blk_eq, kMaxCandBlocks * sizeof(uint32_t)) != hipSuccess ||
-                hipMalloc(&sp.wave_gt, kMaxCandBlocks * kWavesPerBlock * sizeof(uint32_t)) != hipSuccess ||
-                hipMalloc(&sp.wave_eq, kMaxCandBlocks * kWavesPerBlock * sizeof(uint32_t)) != hipSuccess ||
+                hipMalloc(&sp.tile_cnt, tiles * sizeof(uint32_t)) != hipSuccess ||
+                hipMalloc(&sp.blk_cnt, (tiles + kWavesPerBlock - 1) / kWavesPerBlock * sizeof(uint32_t)) != hipSuccess ||
                 hipMalloc(&sp.tile_first, off_words * sizeof(uint64_t)) != hipSuccess ||
                 hipMalloc(&sp.tile_last, off_words * sizeof(uint64_t)) != hipSuccess) rc = MC_ERR_ALLOC;
             else if (hipMemset(sp.hist, 0, hist_bytes) != hipSuccess || hipMemset(sp.sel, 0, 4 * sizeof(SelectState)) != hipSuccess ||
-                     hipMemset(ctx->d_hints, 0, y * sizeof(uint32_t)) != hipSuccess ||
-                     hipMemset(sp.plan, 0, sizeof(PlanState)) != hipSuccess ||
+                     hipMemset(ctx->d_hints, 0, (size_t)y * kHintWorkers * sizeof(uint32_t)) != hipSuccess ||
                      hipMemset(sp.tile_runs, 0, tiles * sizeof(uint64_t)) != hipSuccess ||
                      hipMemset(sp.tile_first, 0, off_words * sizeof(uint64_t)) != hipSuccess ||
                      hipMemset(sp.tile_last, 0, off_words * sizeof(uint64_t)) != hipSuccess) rc = MC_ERR_DEVICE;
@@ -435,7 +427,8 @@ int mc_compress(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter, cons
     case MC_ALGO_DGC:
     {
         SparseScratch sp = ctx->sparse;
-        sp.hint = ctx->d_hints + group;
+        // a context may compress for several simulated workers whose thresholds differ: each keeps its own hint
+        sp.hint = ctx->d_hints + (size_t)group * kHintWorkers + worker % kHintWorkers;
         launch_sparse_compress(lc, cfg.algo, gv, ef, sf, cfg.dgc_momentum, G.k, hdr, sp);
     }
         break;
@@ -505,6 +498,15 @@ int mc_last_device_status(mc_ctx *ctx)
     if (hipMemcpy(&flag, ctx->d_status, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess) return MC_ERR_DEVICE;
     if (flag && hipMemset(ctx->d_status, 0, sizeof(int)) != hipSuccess) return MC_ERR_DEVICE;
     return flag ? MC_ERR_PAYLOAD : MC_OK;
+}
+
+int mc_last_select_route(mc_ctx *ctx)
+{
+    if (!ctx || !is_sparse(ctx->cfg.algo) || !ctx->sparse.sel) return MC_ERR_INVALID_ARG;
+    SelectState s;
+    if (hipDeviceSynchronize() != hipSuccess) return MC_ERR_DEVICE;
+    if (hipMemcpy(&s, ctx->sparse.sel, sizeof(s), hipMemcpyDeviceToHost) != hipSuccess) return MC_ERR_DEVICE;
+    return (s.mode & 1u) ? MC_SELECT_FAST : (s.mode & 2u) ? MC_SELECT_REFILL : MC_SELECT_ABOVE;
 }
 
 int mc_profile_enable(mc_ctx *ctx, int32_t on)

@@ -33,15 +33,15 @@ struct PtrChunk { uintptr_t p[256]; };
 
 // radix-select state carried between the passes of the exact top-k
 struct SelectState {
-    uint32_t prefix;     // bits of the threshold key decided so far
-    uint32_t pad0;
-    uint64_t need;       // entries still to take among keys that match the prefix
+    uint32_t lo;         // the threshold key lies in [lo, lo + range of the levels still to resolve)
+    uint32_t mode;       // what the seed kernel found (fast / refill flags)
+    uint64_t need;       // entries still to take among the keys of that range
 };
 
 // profiling slots
 enum KernelId {
     K_UPLOAD = 0, K_EFSIGN_COMPRESS, K_SCALAR_FINALIZE, K_ACCUM_REDUCE, K_QSGD_ENCODE, K_TERN_ENCODE,
-    K_FP16_COMPRESS, K_DENSE_DECOMPRESS, K_SPARSE_ACCUM, K_SPARSE_PLAN, K_CAND_HIST, K_CAND_COUNT,
+    K_FP16_COMPRESS, K_DENSE_DECOMPRESS, K_SPARSE_ACCUM, K_SPARSE_SEED, K_CAND_HIST2, K_CAND_HIST3, K_CAND_COUNT,
     K_CAND_EMIT, K_SPARSE_INDEX, K_SPARSE_DECOMPRESS, K_STATE_CONVERT, K_TERN_TABLE, K_COUNT
 };
 
@@ -82,34 +82,18 @@ void launch_dense_decompress(const LaunchCtx &lc, int algo, const GroupView &out
 void launch_state_convert(const LaunchCtx &lc, int algo, bool to_residual, uint32_t nfloats, const void *src, void *dst);
 
 // ---- sparse kernels (kernels_sparse.hip) ----------------------------------------
-#ifndef MC_CAND_BLOCKS
-#define MC_CAND_BLOCKS 512
-#endif
-constexpr uint32_t kMaxCandBlocks = MC_CAND_BLOCKS;   // grid of the kernels that walk the candidate slots
-constexpr int kHistWords = 2048 + 1024 + 1024;   // bins of the three radix levels
-
-// what the plan kernel tells the kernels that walk the candidates
-struct PlanState {
-    unsigned long long total;   // candidates to walk: what the accumulate kernel kept, or n after a refill
-    uint32_t nonempty;          // tiles that hold candidates
-    uint32_t share;             // candidates per wavefront
-    uint32_t uniform;           // 1 after a refill: chunk c holds candidates 1024 c, 1024 c + 1, ...
-};
+constexpr int kHintWorkers = 64;                         // hints kept per group, one per worker id modulo this
+constexpr int kHistWords = 2048 + 2048 + 1024 + 1024;   // bins of the window and of the three radix levels
 
 struct SparseScratch {
     uint32_t *hist;        // kHistWords counters; each level is cleared by a later kernel of the same call
-    SelectState *sel;      // [1..3]: prefix / need after each radix level
+    SelectState *sel;      // [0]: after the seed, [1..3]: after each radix level
     uint32_t *hint;        // this group's candidate filter: keys >= hint are candidates (0 = everything)
-    PlanState *plan;
-    uint32_t *ne_tile;     // ids of the tiles that hold candidates, ascending
-    uint32_t *ne_prefix;   // candidates before each of them (one extra entry: the total)
-    uint64_t *ne_runs;     // their per-chunk counts
-    uint32_t *wave_start;  // per wavefront of the later kernels: where in that list its share starts
     uint32_t *cand_bits;   // candidate values (fp32 bit patterns), 1024 slots per chunk, filled from the front
     uint16_t *cand_loc;    // candidate positions inside their chunk
     uint64_t *tile_runs;   // candidates of the four chunks of every tile, 16 bits each
-    uint32_t *blk_gt, *blk_eq;     // per block of the candidate kernels: kept above / equal to the threshold
-    uint32_t *wave_gt, *wave_eq;   // same per wavefront
+    uint32_t *tile_cnt;    // per tile: candidates above (low 16 bits) / equal to (high 16 bits) the threshold
+    uint32_t *blk_cnt;     // the same per block of four tiles
     uint64_t *tile_first, *tile_last;   // decompress: per worker and 4096-element tile, (epoch << 32 | entry) of its run
 };
 void launch_sparse_compress(const LaunchCtx &lc, int algo, const GroupView &g, bool ef, float *state_f, float momentum,

@@ -260,3 +260,43 @@ def test_profile_hooks_count_launches():
     ctx.mc_compress(0, 0, 3, [g], st, pay)
     assert ctx.profile_read() == {}
     ctx.close()
+
+
+@pytest.mark.parametrize("algo", ["topk", "dgc"])
+def test_selection_routes_are_all_taken_and_exact(algo):
+    """The exact selection has three routes: the threshold key T falls inside the histogram window that the
+    library keeps from (last T - 3/16 octave) upward over 2047 bins of 1024 keys; above it; or below its start
+    (too few candidates -> second streaming pass).  Drive one (group, worker) through all three by scaling the
+    gradients; the route expected follows from the oracle's thresholds; every payload and residual is compared."""
+    n, tensors = 300000, [120000, 7, 179993]
+    ctx = B.Context(algo, tensors, [0, 3], ratio_ppm=10000, dgc_momentum=0.0, seed=3)
+    ocfg = O.Config(H.ALGOS[algo], ratio_ppm=10000, dgc_momentum=0.0, seed=3)
+    st = torch.zeros(ctx.state_bytes(0), dtype=torch.uint8, device=H.DEV)
+    pay = torch.zeros(ctx.payload_bytes(0), dtype=torch.uint8, device=H.DEV)
+    ost = O.new_state(ocfg, n)
+    k = ctx.group_k(0)
+    rng = np.random.default_rng(77)
+    hint, seen = 0, []
+    for it, scale in enumerate([1.0, 0.3, 0.3, 64.0, 20.0, 20.0, None, 1e-3]):
+        if scale is None:                 # forget the accumulated residual: the next, tiny, gradient stands alone
+            st.zero_()
+            ost[:] = 0
+            continue
+        g = (rng.standard_normal(n, dtype=np.float32) * np.float32(scale)).astype(np.float32)
+        ctx.mc_compress(0, 5, it, H.device_tensors(g, tensors), st, pay)
+        got = ctx.mc_last_select_route()
+        op, _ = O.compress(ocfg, g, ost, group_off=0, worker=5, it=it)
+        T = int((op[64 + 4 * k:].view(np.uint32) & 0x7FFFFFFF).min())          # k-th largest key
+        want = B.MC_SELECT_REFILL if T < hint else B.MC_SELECT_FAST if T - hint < 2047 * 1024 else B.MC_SELECT_ABOVE
+        assert got == want, f"call {it}: route {got}, expected {want} (T {T:#x}, hint {hint:#x})"
+        hint = T - (3 << 19) if T > (3 << 19) else 0
+        seen.append(got)
+        assert np.array_equal(pay.cpu().numpy(), op), f"call {it} (route {got}): payload differs"
+        e = torch.empty(O.state_floats(ocfg, n), dtype=torch.float32, device=H.DEV)
+        ctx.mc_state_export_residual(0, st, e)
+        assert H.same_bits(e.cpu().numpy(), ost), f"call {it}: residual differs"
+    assert set(seen) == {B.MC_SELECT_ABOVE, B.MC_SELECT_FAST, B.MC_SELECT_REFILL}, seen
+    # another worker id of the same context has no hint of its own yet
+    ctx.mc_compress(0, 6, 9, H.device_tensors(g, tensors), torch.zeros_like(st), pay)
+    assert ctx.mc_last_select_route() == B.MC_SELECT_ABOVE
+    ctx.close()
