@@ -22,15 +22,22 @@
  * gradient + old residual; exact-k; EF-Sign decode == scale*sign and the closed
  * form of the residual energy; unbiasedness of QSGD / TernGrad by averaging;
  * fp16 cast against a library cast; W=1 aggregate == decode; partition counts
- * against C(N-1, y-1) enumeration.  Parity of absolute values with the paper is
- * unpinned: the paper prints no compressor input/output pair.
+ * against C(N-1, y-1) enumeration.  The four further schemes of Table 1: sign
+ * planes against a library bit packer and scale invariance, the vote against a
+ * library sign-of-sum, SigNUM with beta = 0 == SignSGD and the closed form of a
+ * constant gradient, OneBit's two means against library means and the
+ * least-squares property, Rand-k against a library stable argsort of the
+ * pinned Philox draws, exact-k, value independence and uniformity.  Parity of
+ * absolute values with the paper is unpinned: the paper prints no compressor
+ * input/output pair.
  */
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
 
-enum { ALG_EFSIGN = 1, ALG_TOPK = 2, ALG_DGC = 3, ALG_QSGD = 4, ALG_TERNGRAD = 5, ALG_FP16 = 6 };
+enum { ALG_EFSIGN = 1, ALG_TOPK = 2, ALG_DGC = 3, ALG_QSGD = 4, ALG_TERNGRAD = 5, ALG_FP16 = 6,
+       ALG_SIGNSGD = 7, ALG_SIGNUM = 8, ALG_ONEBIT = 9, ALG_RANDK = 10 };
 enum { PART_EVEN_COUNT = 0, PART_EVEN_ELEMS = 1, PART_USER = 2 };
 
 #define HDR_BYTES 64u
@@ -41,7 +48,7 @@ typedef struct {
     int32_t use_ef;        /* 1: p = g + e and e is updated; 0: p = g, state untouched */
     uint32_t ratio_ppm;    /* kept fraction of sparsifiers, parts per million */
     int32_t qsgd_bits;     /* code width incl. sign; levels s = 2^(bits-1) - 1 */
-    float dgc_momentum;    /* m of the momentum correction */
+    float dgc_momentum;    /* m of DGC's momentum correction; beta of SigNUM */
     uint64_t seed;         /* Philox key */
 } orc_config;
 
@@ -135,19 +142,24 @@ static int64_t pad4(int64_t b) { return (b + 3) / 4 * 4; }
 int64_t orc_payload_bytes(const orc_config *c, int64_t n)
 {
     switch (c->algo) {
-    case ALG_EFSIGN:   return HDR_BYTES + 4 * words32(n);
+    case ALG_EFSIGN:
+    case ALG_SIGNSGD:
+    case ALG_SIGNUM:
+    case ALG_ONEBIT:   return HDR_BYTES + 4 * words32(n);
     case ALG_TERNGRAD: return HDR_BYTES + 8 * words32(n);
     case ALG_QSGD:     return HDR_BYTES + pad4(n);
     case ALG_FP16:     return HDR_BYTES + pad4(2 * n);
     case ALG_TOPK:
-    case ALG_DGC:      return HDR_BYTES + 8 * orc_topk_count(n, c->ratio_ppm);
+    case ALG_DGC:
+    case ALG_RANDK:    return HDR_BYTES + 8 * orc_topk_count(n, c->ratio_ppm);
     }
     return -1;
 }
 
-/* floats of error-feedback memory per group: residual e (DGC: v then u) */
+/* floats of per-group memory: residual e (DGC: v then u; SigNUM: the momentum; SignSGD: none) */
 int64_t orc_state_floats(const orc_config *c, int64_t n)
 {
+    if (c->algo == ALG_SIGNSGD) return 0;
     return c->algo == ALG_DGC ? 2 * n : n;
 }
 
@@ -223,16 +235,30 @@ static int cmp_key_desc_idx_asc(const void *a, const void *b)
     return 0;
 }
 
+/* The 31-bit selection key of Rand-k: the element's Philox word (same counter layout as
+ * orc_uniform) without its lowest bit.  Taking the k largest keys picks k distinct
+ * positions uniformly at random, whatever the values are. */
+uint32_t orc_randk_key(uint64_t seed, uint32_t worker, uint64_t iter, uint64_t global_index)
+{
+    uint64_t J = global_index >> 2;
+    uint32_t ctr[4] = { (uint32_t)J, (uint32_t)(J >> 32), worker, (uint32_t)iter };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t r[4];
+    orc_philox4x32_10(ctr, key, r);
+    return r[global_index & 3u] >> 1;
+}
+
 /* selected[i] = 1 for the k elements that come first when all elements are
- * ordered by (|p| descending, index ascending).  |p| is compared on the bit
- * pattern with the sign cleared, which orders finite fp32 magnitudes. */
-static int select_topk(const float *p, int64_t n, int64_t k, uint8_t *selected)
+ * ordered by (key descending, index ascending).  Top-k / DGC: key = |p| compared on
+ * the bit pattern with the sign cleared, which orders finite fp32 magnitudes
+ * (rk = NULL).  Rand-k: key = rk[i]. */
+static int select_topk(const float *p, const uint32_t *rk, int64_t n, int64_t k, uint8_t *selected)
 {
     keyidx *a = (keyidx *)malloc((size_t)(n > 0 ? n : 1) * sizeof(keyidx));
     if (!a) return -3;
     for (int64_t i = 0; i < n; ++i) {
         uint32_t b; memcpy(&b, &p[i], 4);
-        a[i].key = b & 0x7FFFFFFFu; a[i].idx = (uint32_t)i;
+        a[i].key = rk ? rk[i] : (b & 0x7FFFFFFFu); a[i].idx = (uint32_t)i;
     }
     qsort(a, (size_t)n, sizeof(keyidx), cmp_key_desc_idx_asc);
     memset(selected, 0, (size_t)n);
@@ -247,16 +273,19 @@ static int select_topk(const float *p, int64_t n, int64_t k, uint8_t *selected)
 /*   state       error-feedback memory: e[n]  (DGC: v[n] then u[n])           */
 /*   payload     out, orc_payload_bytes() bytes                               */
 /*   group_off   model-global flat index of the group's element 0 (RNG only)   */
-/*   scale_in    NULL, or the group scalar to encode with instead of the one   */
-/*               computed here (EF-Sign scale, QSGD norm, TernGrad max); used  */
-/*               by parity tests once the scalars themselves have been checked */
-/*   scale_out   NULL, or receives the scalar computed here                    */
+/*   scale_in    NULL, or the group scalar(s) to encode with instead of the    */
+/*               ones computed here (EF-Sign scale, QSGD norm, TernGrad max;   */
+/*               OneBit: two floats, the means); used by parity tests once the */
+/*               scalars themselves have been checked                          */
+/*   scale_out   NULL, or receives the scalar(s) computed here (OneBit: two)   */
 /* ------------------------------------------------------------------------ */
 int orc_compress(const orc_config *c, int64_t n, uint64_t group_off, uint32_t worker, uint64_t iter,
                  const float *g, float *state, uint8_t *payload, const float *scale_in, float *scale_out)
 {
     if (!c || !payload || n < 0 || (n > 0 && !g)) return -1;
     if (n >= ((int64_t)1 << 32)) return -2;
+    if (c->algo == ALG_SIGNSGD && c->use_ef) return -1;             /* plain signs: nothing is remembered */
+    if ((c->algo == ALG_SIGNUM || c->algo == ALG_RANDK) && !c->use_ef) return -1;   /* these always carry state */
     const int ef = c->use_ef != 0;
     if (ef && n > 0 && !state) return -1;
     memset(payload, 0, (size_t)orc_payload_bytes(c, n));
@@ -274,6 +303,14 @@ int orc_compress(const orc_config *c, int64_t n, uint64_t group_off, uint32_t wo
             u[i] = mu + g[i];
             v[i] = v[i] + u[i];
             p[i] = v[i];
+        }
+    } else if (c->algo == ALG_SIGNUM) {
+        /* the vector whose signs are sent is the momentum m = beta*m + (1 - beta)*g */
+        const float beta = c->dgc_momentum, omb = 1.0f - beta;
+        for (int64_t i = 0; i < n; ++i) {
+            float bm = beta * state[i], og = omb * g[i];
+            state[i] = bm + og;
+            p[i] = state[i];
         }
     } else {
         for (int64_t i = 0; i < n; ++i) p[i] = ef ? g[i] + state[i] : g[i];
@@ -298,12 +335,51 @@ int orc_compress(const orc_config *c, int64_t n, uint64_t group_off, uint32_t wo
         }
         break;
     }
+    case ALG_SIGNSGD:
+    case ALG_SIGNUM: {
+        /* delta = sign(p), sign(0) = +1: one bit per element, decoded as +-1; no residual
+         * (SignSGD: p = g; SigNUM: p = momentum, updated above) */
+        put_header(payload, c->algo, n, 0, 1.0f, 0);
+        uint32_t *w = (uint32_t *)(payload + HDR_BYTES);
+        for (int64_t i = 0; i < n; ++i) if (p[i] >= 0.0f) w[i / 32] |= 1u << (i % 32);
+        break;
+    }
+    case ALG_ONEBIT: {
+        /* one bit per element, reconstructed as the mean of its class: mu+ over the
+         * elements with p >= 0, mu- over those with p < 0 ; e = p - delta */
+        double Sp = 0.0, Sn = 0.0; int64_t np = 0;
+        for (int64_t i = 0; i < n; ++i) { if (p[i] >= 0.0f) { Sp += (double)p[i]; ++np; } else Sn += (double)p[i]; }
+        float mu[2];
+        mu[0] = np > 0 ? (float)(Sp / (double)np) : 0.0f;
+        mu[1] = n - np > 0 ? (float)(Sn / (double)(n - np)) : 0.0f;
+        if (scale_out) { scale_out[0] = mu[0]; scale_out[1] = mu[1]; }
+        if (scale_in) { mu[0] = scale_in[0]; mu[1] = scale_in[1]; }
+        put_header(payload, c->algo, n, 0, mu[0], 0);
+        memcpy(payload + 32, &mu[1], 4);                 /* second scalar right after the common fields */
+        uint32_t *w = (uint32_t *)(payload + HDR_BYTES);
+        for (int64_t i = 0; i < n; ++i) {
+            int bit = p[i] >= 0.0f;
+            if (bit) w[i / 32] |= 1u << (i % 32);
+            float d = bit ? mu[0] : mu[1];
+            if (ef) state[i] = p[i] - d;
+        }
+        break;
+    }
     case ALG_TOPK:
-    case ALG_DGC: {
+    case ALG_DGC:
+    case ALG_RANDK: {
         int64_t k = orc_topk_count(n, c->ratio_ppm);
         uint8_t *sel = (uint8_t *)malloc((size_t)(n > 0 ? n : 1));
         if (!sel) { rc = -3; break; }
-        rc = select_topk(p, n, k, sel);
+        uint32_t *rk = NULL;
+        if (c->algo == ALG_RANDK) {
+            /* k positions chosen uniformly at random (independent of the values): the k largest Philox keys */
+            rk = (uint32_t *)malloc((size_t)(n > 0 ? n : 1) * sizeof(uint32_t));
+            if (!rk) { free(sel); rc = -3; break; }
+            for (int64_t i = 0; i < n; ++i) rk[i] = orc_randk_key(c->seed, worker, iter, group_off + (uint64_t)i);
+        }
+        rc = select_topk(p, rk, n, k, sel);
+        free(rk);
         if (rc) { free(sel); break; }
         put_header(payload, c->algo, n, k, 0.0f, 0);
         uint32_t *idx = (uint32_t *)(payload + HDR_BYTES);
@@ -409,8 +485,21 @@ int orc_decode(const uint8_t *payload, int64_t n, float *d)
         for (int64_t i = 0; i < n; ++i) d[i] = ((w[i / 32] >> (i % 32)) & 1u) ? scale : -scale;
         break;
     }
+    case ALG_SIGNSGD:
+    case ALG_SIGNUM: {
+        const uint32_t *w = (const uint32_t *)body;
+        for (int64_t i = 0; i < n; ++i) d[i] = ((w[i / 32] >> (i % 32)) & 1u) ? 1.0f : -1.0f;
+        break;
+    }
+    case ALG_ONEBIT: {
+        float lo; memcpy(&lo, payload + 32, 4);
+        const uint32_t *w = (const uint32_t *)body;
+        for (int64_t i = 0; i < n; ++i) d[i] = ((w[i / 32] >> (i % 32)) & 1u) ? scale : lo;
+        break;
+    }
     case ALG_TOPK:
-    case ALG_DGC: {
+    case ALG_DGC:
+    case ALG_RANDK: {
         const uint32_t *idx = (const uint32_t *)body;
         const float *val = (const float *)(body + 4 * k);
         for (int64_t i = 0; i < n; ++i) d[i] = 0.0f;
@@ -443,7 +532,9 @@ int orc_decode(const uint8_t *payload, int64_t n, float *d)
 
 /* ------------------------------------------------------------------------ */
 /* aggregate: out = alpha * (((0 + d_0) + d_1) + ... + d_{W-1}), fp32, workers */
-/* in ascending order (Algorithm 1: g~ = aggregate(C^-1(Delta)))               */
+/* in ascending order (Algorithm 1: g~ = aggregate(C^-1(Delta))).              */
+/* SignSGD / SigNUM aggregate by majority vote: the sum of the +-1 becomes its */
+/* sign (-1, 0 on a tie, +1) before alpha is applied.                          */
 /* ------------------------------------------------------------------------ */
 int orc_decompress_sum(int64_t n, const uint8_t *const *payloads, int32_t W, float alpha, float *out)
 {
@@ -456,6 +547,9 @@ int orc_decompress_sum(int64_t n, const uint8_t *const *payloads, int32_t W, flo
         if (rc) { free(d); return rc; }
         for (int64_t i = 0; i < n; ++i) out[i] = out[i] + d[i];
     }
+    uint32_t algo; memcpy(&algo, payloads[0] + 4, 4);
+    if (algo == ALG_SIGNSGD || algo == ALG_SIGNUM)
+        for (int64_t i = 0; i < n; ++i) out[i] = out[i] > 0.0f ? 1.0f : (out[i] < 0.0f ? -1.0f : 0.0f);
     for (int64_t i = 0; i < n; ++i) out[i] = alpha * out[i];
     free(d);
     return 0;

@@ -20,8 +20,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "mc_oracle.c")
 _LIB = os.path.join(_HERE, "libmc_oracle.so")
 
-EFSIGN, TOPK, DGC, QSGD, TERNGRAD, FP16 = 1, 2, 3, 4, 5, 6
-ALGO_NAMES = {EFSIGN: "efsign", TOPK: "topk", DGC: "dgc", QSGD: "qsgd", TERNGRAD: "terngrad", FP16: "fp16"}
+EFSIGN, TOPK, DGC, QSGD, TERNGRAD, FP16, SIGNSGD, SIGNUM, ONEBIT, RANDK = 1, 2, 3, 4, 5, 6, 7, 8, 9, 10
+ALGO_NAMES = {EFSIGN: "efsign", TOPK: "topk", DGC: "dgc", QSGD: "qsgd", TERNGRAD: "terngrad", FP16: "fp16",
+              SIGNSGD: "signsgd", SIGNUM: "signum", ONEBIT: "onebit", RANDK: "randk"}
 PART_EVEN_COUNT, PART_EVEN_ELEMS, PART_USER = 0, 1, 2
 HDR = 64
 
@@ -64,6 +65,8 @@ def lib():
         L.orc_philox4x32_10.restype = None
         L.orc_uniform.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint64]
         L.orc_uniform.restype = C.c_float
+        L.orc_randk_key.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint64]
+        L.orc_randk_key.restype = C.c_uint32
         L.orc_partition.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.orc_partition.restype = C.c_int
         L.orc_topk_count.argtypes = [C.c_int64, C.c_uint32]
@@ -101,6 +104,10 @@ def uniform(seed: int, worker: int, it: int, global_index: int) -> float:
     return float(lib().orc_uniform(seed, worker, it, global_index))
 
 
+def randk_key(seed: int, worker: int, it: int, global_index: int) -> int:
+    return int(lib().orc_randk_key(seed, worker, it, global_index))
+
+
 def partition(numel: Sequence[int], y: int, policy: int = PART_EVEN_ELEMS,
               user_bounds: Optional[Sequence[int]] = None) -> np.ndarray:
     nm = np.ascontiguousarray(numel, dtype=np.int64)
@@ -131,16 +138,19 @@ def new_state(cfg: Config, n: int) -> np.ndarray:
 
 
 def compress(cfg: Config, g: np.ndarray, state: Optional[np.ndarray], *, group_off: int = 0, worker: int = 0,
-             it: int = 0, scale_in: Optional[float] = None) -> Tuple[np.ndarray, float]:
-    """Returns (payload bytes, group scalar computed by the oracle); state is updated in place."""
+             it: int = 0, scale_in=None) -> Tuple[np.ndarray, float]:
+    """Returns (payload bytes, group scalar computed by the oracle); state is updated in place.
+    OneBit has two group scalars: scale_in is then a pair, and the second one computed is header()["scale2"]."""
     g = np.ascontiguousarray(g, dtype=np.float32)
     n = g.size
     if state is not None:
         assert state.dtype == np.float32 and state.flags.c_contiguous and state.size == state_floats(cfg, n)
     payload = np.zeros(payload_bytes(cfg, n), dtype=np.uint8)
     c = cfg.c()
-    sin = None if scale_in is None else np.array([scale_in], dtype=np.float32)
-    sout = np.zeros(1, dtype=np.float32)
+    sin = None if scale_in is None else np.atleast_1d(np.asarray(scale_in, dtype=np.float32)).copy()
+    if sin is not None:
+        assert sin.size == (2 if cfg.algo == ONEBIT else 1)
+    sout = np.zeros(2, dtype=np.float32)
     rc = lib().orc_compress(C.byref(c), n, group_off, worker, it, _ptr(g), _ptr(state), _ptr(payload),
                             _ptr(sin), _ptr(sout))
     if rc:
@@ -189,6 +199,7 @@ def header(payload: np.ndarray) -> dict:
         "k": int(np.frombuffer(b, np.uint64, 1, 16)[0]),
         "scale": float(np.frombuffer(b, np.float32, 1, 24)[0]),
         "levels": int(np.frombuffer(b, np.uint32, 1, 28)[0]),
+        "scale2": float(np.frombuffer(b, np.float32, 1, 32)[0]),       # OneBit: mean of the negative class
     }
 
 
