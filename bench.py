@@ -44,6 +44,9 @@ CALL_BYTES = {
     "efsign": (12.125, lambda W: W / 8.0 + 4.0), "topk": (12.08, lambda W: 4.0 + 0.08 * W),
     "dgc": (20.008, lambda W: 4.0 + 0.008 * W), "qsgd": (13.0, lambda W: W + 4.0),
     "terngrad": (12.25, lambda W: W / 4.0 + 4.0), "fp16": (14.0, lambda W: 2.0 * W + 4.0),
+    # the four further schemes of the paper's Table 1 (Rand-k 1 %)
+    "signsgd": (4.125, lambda W: W / 8.0 + 4.0), "signum": (12.125, lambda W: W / 8.0 + 4.0),
+    "onebit": (12.125, lambda W: W / 8.0 + 4.0), "randk": (12.08, lambda W: 4.0 + 0.08 * W),
 }
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None = not measured
@@ -60,6 +63,8 @@ def parse():
     ap.add_argument("--y", type=int, default=1, help="number of merged groups for the headline run")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-curve", action="store_true", help="skip the compress-time-vs-y curve")
+    ap.add_argument("--no-layerwise", action="store_true",
+                    help="skip the layer-wise comparison (y = number of tensors: one compress / decompress per tensor)")
     ap.add_argument("--algos", default="efsign,topk")
     ap.add_argument("--grad-layout", default="separate", choices=["separate", "views"],
                     help="separate: every gradient tensor its own allocation (a model's .grad tensors); views: the "
@@ -225,13 +230,29 @@ def main():
             curve[a] = {"y": [int(v) for v in ys], "compress_us": [float(v) for v in ts], "B_h_us": float(bh),
                         "gamma_h_D_us": float(c0), "inv_gamma_h_GBps": float(4.0 * D / c0 * 1e-3) if c0 > 0 else None}
 
+    # ---- layer-wise compression (Section 3: one encode and one decode per tensor) against merged ---------
+    layerwise = None
+    if not args.no_layerwise:
+        layerwise = {}
+        N = len(numel)
+        for a in algos:
+            lb = AlgoBench(B, torch, a, numel, N, W, grads)
+            tc = timed(torch, lambda i: (setattr(lb, "it", lb.it + 1), lb.compress(i % W)), 10)
+            td = timed(torch, lambda i: lb.decompress(), 10)
+            lb.close()
+            del lb
+            torch.cuda.empty_cache()
+            merged = per_algo[a]["compress_us"] + per_algo[a]["decompress_sum_us"]
+            layerwise[a] = {"groups": N, "compress_us": tc * 1e6, "decompress_sum_us": td * 1e6,
+                            "merged_over_layerwise_speedup": (tc + td) * 1e6 / merged}
+
     # ---- the oracle on this host's cores -----------------------------------------------------------
     cpu = None
     if not args.no_cpu:
         from oracle import oracle as O
         t_cpu = 0.0
         for a in algos:
-            ocfg = O.Config(B.ALGO_IDS[a], ratio_ppm=1000 if a == "dgc" else 10000, seed=1)
+            ocfg = O.Config(B.ALGO_IDS[a], ratio_ppm=1000 if a == "dgc" else 10000, seed=1, use_ef=0 if a == "signsgd" else 1)
             st = O.new_state(ocfg, D)
             t0 = time.perf_counter()
             pay, _ = O.compress(ocfg, flats[0], st)
@@ -258,6 +279,7 @@ def main():
         "per_algo": per_algo,
         "kernels_us_per_step": {k: round(v["us_per_step"], 2) for k, v in sorted(kernels.items())},
         "compress_time_vs_y": curve,
+        "layerwise_vs_merged": layerwise,
     }
     for b in benches.values():
         b.close()

@@ -33,15 +33,19 @@
  *   byte  4  uint32  algorithm id (mc_algo)
  *   byte  8  uint64  n, elements of the group
  *   byte 16  uint64  k, kept entries (sparsifiers; 0 otherwise)
- *   byte 24  float   group scalar: EF-Sign scale, QSGD norm, TernGrad max (0 otherwise)
+ *   byte 24  float   group scalar: EF-Sign scale, QSGD norm, TernGrad max, OneBit mean of the
+ *                    non-negative class, SignSGD / SigNUM 1.0 (0 otherwise)
  *   byte 28  uint32  QSGD levels s (0 otherwise)
- *   byte 32..63      zero
+ *   byte 32  float   OneBit mean of the negative class (0 otherwise)
+ *   byte 36..63      zero
  *   byte 64  body:
- *     EF-Sign   ceil(n/32) uint32; element i <-> bit (i%32) of word i/32, 1 = non-negative; pad bits 0
+ *     EF-Sign, OneBit, SignSGD, SigNUM
+ *               ceil(n/32) uint32; element i <-> bit (i%32) of word i/32, 1 = non-negative; pad bits 0
  *     TernGrad  non-zero plane ceil(n/32) uint32, then negative plane, same bit order
  *     QSGD      n int8 codes in [-s, s], zero-padded to a multiple of 4 bytes
  *     FP16      n binary16, zero-padded to a multiple of 4 bytes
- *     Top-k/DGC idx[k] uint32 ascending group-relative indices, then val[k] float
+ *     Top-k, DGC, Rand-k
+ *               idx[k] uint32 ascending group-relative indices, then val[k] float
  *   Payload buffers must be 16-byte aligned.
  */
 #ifndef MERGECOMP_H
@@ -64,7 +68,12 @@ typedef enum {
     MC_ALGO_DGC = 3,      /* momentum correction + exact top-k + momentum factor masking      */
     MC_ALGO_QSGD = 4,     /* stochastic rounding to s levels of |p|/||p||_2 (Section 5: 8 bit) */
     MC_ALGO_TERNGRAD = 5, /* ternary {-s,0,+s}, s = max|p|, Bernoulli(|p|/s)                   */
-    MC_ALGO_FP16 = 6      /* binary16 cast, round to nearest even                              */
+    MC_ALGO_FP16 = 6,     /* binary16 cast, round to nearest even                              */
+    /* the other four schemes of Table 1 */
+    MC_ALGO_SIGNSGD = 7,  /* sign(g), no memory; aggregated by majority vote: sign of the sum   */
+    MC_ALGO_SIGNUM = 8,   /* sign of the momentum m = beta m + (1-beta) g; majority vote         */
+    MC_ALGO_ONEBIT = 9,   /* 1 bit, decoded as the mean of its class (p>=0 / p<0); error feedback */
+    MC_ALGO_RANDK = 10    /* k positions drawn uniformly (largest Philox keys); error feedback   */
 } mc_algo;
 
 /* Partition policies for mc_partition. */
@@ -85,12 +94,13 @@ typedef enum {
 
 typedef struct {
     int32_t algo;        /* mc_algo                                                             */
-    int32_t use_ef;      /* 1: p = g + e and the residual e is updated; 0: p = g, state unused   */
+    int32_t use_ef;      /* 1: p = g + e and the residual e is updated; 0: p = g, state unused.
+                            Must be 1 for DGC, SigNUM, Rand-k (they always carry state), 0 for SignSGD */
     uint32_t ratio_ppm;  /* sparsifiers: kept fraction in parts per million (Section 5: 10000)   */
     int32_t qsgd_bits;   /* QSGD code width incl. sign, 2..8; levels s = 2^(bits-1) - 1          */
-    float dgc_momentum;  /* DGC momentum m                                                       */
+    float dgc_momentum;  /* DGC momentum m; SigNUM beta                                          */
     uint32_t reserved;   /* must be 0                                                            */
-    uint64_t seed;       /* Philox key of the stochastic quantizers                              */
+    uint64_t seed;       /* Philox key of the stochastic quantizers and of Rand-k                */
 } mc_config;
 
 /*

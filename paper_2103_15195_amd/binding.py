@@ -15,7 +15,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("MERGECOMP_LIB", os.path.join(_HERE, "libmergecomp.so"))   # override: a build to compare against
 
 MC_ALGO_EFSIGN, MC_ALGO_TOPK, MC_ALGO_DGC, MC_ALGO_QSGD, MC_ALGO_TERNGRAD, MC_ALGO_FP16 = 1, 2, 3, 4, 5, 6
-ALGO_IDS = {"efsign": 1, "topk": 2, "dgc": 3, "qsgd": 4, "terngrad": 5, "fp16": 6}
+MC_ALGO_SIGNSGD, MC_ALGO_SIGNUM, MC_ALGO_ONEBIT, MC_ALGO_RANDK = 7, 8, 9, 10
+ALGO_IDS = {"efsign": 1, "topk": 2, "dgc": 3, "qsgd": 4, "terngrad": 5, "fp16": 6,
+            "signsgd": 7, "signum": 8, "onebit": 9, "randk": 10}
 MC_PART_EVEN_COUNT, MC_PART_EVEN_ELEMS, MC_PART_USER = 0, 1, 2
 MC_SELECT_ABOVE, MC_SELECT_FAST, MC_SELECT_REFILL = 0, 1, 2
 MC_OK, MC_ERR_INVALID_ARG, MC_ERR_RANGE, MC_ERR_ALLOC, MC_ERR_DEVICE, MC_ERR_PAYLOAD = 0, -1, -2, -3, -4, -5
@@ -118,9 +120,11 @@ def mc_partition(numel: Sequence[int], y: int, policy: int = MC_PART_EVEN_ELEMS,
 class Context:
     """One (config, tensor list, partition) on the current device: wraps mc_ctx."""
 
-    def __init__(self, algo, numel: Sequence[int], bounds: Sequence[int], *, use_ef: int = 1, ratio_ppm: int = 10000,
-                 qsgd_bits: int = 8, dgc_momentum: float = 0.9, seed: int = 0):
+    def __init__(self, algo, numel: Sequence[int], bounds: Sequence[int], *, use_ef: Optional[int] = None,
+                 ratio_ppm: int = 10000, qsgd_bits: int = 8, dgc_momentum: float = 0.9, seed: int = 0):
         algo = ALGO_IDS.get(algo, algo)
+        if use_ef is None:                       # SignSGD remembers nothing; everything else defaults to error feedback
+            use_ef = 0 if algo == MC_ALGO_SIGNSGD else 1
         self.algo = int(algo)
         self.numel = [int(x) for x in numel]
         self.bounds = [int(b) for b in bounds]

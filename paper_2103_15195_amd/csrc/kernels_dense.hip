@@ -60,32 +60,48 @@ void launch_expand_ptrs(const LaunchCtx &lc, const GroupView &g, uintptr_t *chun
 static inline uint32_t tiles_of(uint32_t n) { return (uint32_t)(((uint64_t)n + kTile - 1) / kTile); }
 
 // ---------------------------------------------------------------------------
-// EF-Sign, single pass.  delta = (||p||_1 / n) sign(p), p = g + e, e <- p - delta.
-// The sign bits do not depend on the scale, so the residual is not written:
-// the state keeps p and the scale of the call that produced it, and the
-// residual of the previous call is re-derived on the fly as
-//     e = p_prev - (p_prev >= 0 ? s_prev : -s_prev)
+// The one-bit schemes, single pass: one sign bit per element of a vector p.
+//   SIGN_EF       EF-Sign: delta = (||p||_1 / n) sign(p), p = g + e, e <- p - delta
+//   SIGN_MEANS    OneBit: delta = mean of the class (p >= 0 / p < 0) of the element, same residual rule
+//   SIGN_PLAIN    SignSGD: p = g, nothing is remembered
+//   SIGN_MOMENTUM SigNUM: p = m <- beta m + (1 - beta) g, the momentum is the state
+// The bits of the first two do not depend on their group scalars, so the residual is
+// not written: the state keeps p and the scalars of the call that produced it, and
+// the residual of the previous call is re-derived on the fly as
+//     e = p_prev - (p_prev >= 0 ? hi_prev : lo_prev)          (EF-Sign: hi = s, lo = -s)
 // with the same fp32 operations an explicit update would have used.
 // Traffic per element: read g, read p_prev, write p, 1/8 byte of sign bits.
+// Per-block partials: EF-Sign sum |p|; OneBit sum of the upper class, sum of the lower
+// class, size of the upper class (three arrays of gridDim.x doubles).
 // ---------------------------------------------------------------------------
-template <bool EF>
-__global__ __launch_bounds__(kBlock) void efsign_compress_k(GroupView g, float *st, const float *scale_prev,
-                                                            uint32_t *words, uint32_t nwords, double *partial)
+template <int MODE, bool EF>
+__global__ __launch_bounds__(kBlock) void sign_compress_k(GroupView g, float *st, const StateHeader *prev, float beta,
+                                                          uint32_t *words, uint32_t nwords, double *partial)
 {
     __shared__ uint64_t stage[kWavesPerBlock][kSteps];
     __shared__ double red[kWavesPerBlock];
     const Chunk c = my_chunk(g.n);
-    double acc = 0.0;
+    double acc = 0.0, acc_lo = 0.0, cnt_hi = 0.0;
     if (c.base < g.n) {
         float p[kSteps];
         load_seg(g, c, p);
-        if (EF) {
-            const float sp = *scale_prev;
+        if (MODE == SIGN_MOMENTUM) {
+            const float omb = 1.0f - beta;
             float q[kSteps];
             load_flat(st, c, g.n, q, 0.0f);
 #pragma unroll
             for (int j = 0; j < kSteps; ++j) {
-                float d = q[j] >= 0.0f ? sp : -sp;
+                const float bm = beta * q[j], og = omb * p[j];
+                p[j] = bm + og;
+            }
+            store_flat(st, c, g.n, p);
+        } else if (EF && MODE != SIGN_PLAIN) {
+            const float hi = prev->scale, lo = MODE == SIGN_MEANS ? prev->scale_lo : -hi;
+            float q[kSteps];
+            load_flat(st, c, g.n, q, 0.0f);
+#pragma unroll
+            for (int j = 0; j < kSteps; ++j) {
+                float d = q[j] >= 0.0f ? hi : lo;
                 float e = q[j] - d;
                 p[j] = p[j] + e;
             }
@@ -95,23 +111,54 @@ __global__ __launch_bounds__(kBlock) void efsign_compress_k(GroupView g, float *
 #pragma unroll
         for (int j = 0; j < kSteps; ++j) {
             bool valid = c.full || (c.base + 64 * j + c.lane < g.n);
-            b[j] = __builtin_amdgcn_ballot_w64(valid && p[j] >= 0.0f);
-            acc += valid ? fabs((double)p[j]) : 0.0;
+            const bool up = valid && p[j] >= 0.0f;
+            b[j] = __builtin_amdgcn_ballot_w64(up);
+            if (MODE == SIGN_EF) acc += valid ? fabs((double)p[j]) : 0.0;
+            if (MODE == SIGN_MEANS) {
+                acc += up ? (double)p[j] : 0.0;
+                acc_lo += valid && !up ? (double)p[j] : 0.0;
+            }
+        }
+        if (MODE == SIGN_MEANS) {
+#pragma unroll
+            for (int j = 0; j < kSteps; ++j) if (c.lane == 0) cnt_hi += (double)__popcll(b[j]);
         }
         store_plane(words, nwords, c, b, stage[threadIdx.x >> 6]);
     }
-    double t = block_sum(acc, red);
-    if (threadIdx.x == 0) partial[blockIdx.x] = t;
+    if (MODE == SIGN_EF || MODE == SIGN_MEANS) {
+        double t = block_sum(acc, red);
+        if (threadIdx.x == 0) partial[blockIdx.x] = t;
+    }
+    if (MODE == SIGN_MEANS) {
+        double t = block_sum(acc_lo, red);
+        if (threadIdx.x == 0) partial[gridDim.x + blockIdx.x] = t;
+        t = block_sum(cnt_hi, red);
+        if (threadIdx.x == 0) partial[2 * gridDim.x + blockIdx.x] = t;
+    }
 }
 
-void launch_efsign_compress(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, const float *scale_prev,
-                            uint32_t *words, uint32_t nwords, double *partial)
+void launch_sign_compress(const LaunchCtx &lc, int mode, const GroupView &g, bool ef, float *state_f, const StateHeader *prev,
+                          float beta, uint32_t *words, uint32_t nwords, double *partial)
 {
     if (g.n == 0) return;
     dim3 grid(tiles_of(g.n)), block(kBlock);
     prof_begin(lc, K_EFSIGN_COMPRESS);
-    if (ef) MC_LAUNCH(efsign_compress_k<true>, grid, block, lc, g, state_f, scale_prev, words, nwords, partial);
-    else MC_LAUNCH(efsign_compress_k<false>, grid, block, lc, g, state_f, scale_prev, words, nwords, partial);
+    switch (mode) {
+    case SIGN_EF:
+        if (ef) MC_LAUNCH((sign_compress_k<SIGN_EF, true>), grid, block, lc, g, state_f, prev, beta, words, nwords, partial);
+        else MC_LAUNCH((sign_compress_k<SIGN_EF, false>), grid, block, lc, g, state_f, prev, beta, words, nwords, partial);
+        break;
+    case SIGN_MEANS:
+        if (ef) MC_LAUNCH((sign_compress_k<SIGN_MEANS, true>), grid, block, lc, g, state_f, prev, beta, words, nwords, partial);
+        else MC_LAUNCH((sign_compress_k<SIGN_MEANS, false>), grid, block, lc, g, state_f, prev, beta, words, nwords, partial);
+        break;
+    case SIGN_PLAIN:
+        MC_LAUNCH((sign_compress_k<SIGN_PLAIN, false>), grid, block, lc, g, state_f, prev, beta, words, nwords, partial);
+        break;
+    default:
+        MC_LAUNCH((sign_compress_k<SIGN_MOMENTUM, true>), grid, block, lc, g, state_f, prev, beta, words, nwords, partial);
+        break;
+    }
     prof_end(lc, K_EFSIGN_COMPRESS);
 }
 
@@ -121,6 +168,9 @@ void launch_efsign_compress(const LaunchCtx &lc, const GroupView &g, bool ef, fl
 // write the payload header (and, for EF-Sign, the scale kept in the state).
 //   RED_MEAN_ABS: scale = (float)(sum / n)      RED_L2: norm = (float)sqrt(sum)
 //   RED_MAX_ABS : max of the partials (exact)   mode < 0: header only
+//   RED_ONE     : scale = 1 (SignSGD, SigNUM: the decoded values are +-1)
+//   RED_MEANS   : three partial arrays (sum of the upper class, of the lower class, size of the
+//                 upper class) -> scale = mean of the upper class, second scalar = mean of the lower
 // ---------------------------------------------------------------------------
 constexpr int kFinalThreads = 1024;
 
@@ -129,8 +179,44 @@ __global__ __launch_bounds__(kFinalThreads) void scalar_finalize_k(const double 
                                                                    float *state_scale)
 {
     __shared__ double red[kFinalThreads / 64];
+    if (mode == RED_MEANS) {
+        // the three sums one after the other, each in the fixed order of the single-sum case
+        double S[3];
+        for (int a = 0; a < 3; ++a) {
+            double acc = 0.0;
+            for (uint32_t base = 0; base < nblocks; base += 8 * kFinalThreads) {
+                double v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    uint32_t i = base + u * kFinalThreads + threadIdx.x;
+                    v[u] = i < nblocks ? partial[(size_t)a * nblocks + i] : 0.0;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) acc += v[u];
+            }
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
+            __syncthreads();
+            if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+            __syncthreads();
+            double T = red[0];
+            for (int w = 1; w < kFinalThreads / 64; ++w) T += red[w];
+            S[a] = T;
+        }
+        if (threadIdx.x == 0) {
+            const double n_hi = S[2], n_lo = (double)n - S[2];
+            const float hi = n_hi > 0.0 ? (float)(S[0] / n_hi) : 0.0f, lo = n_lo > 0.0 ? (float)(S[1] / n_lo) : 0.0f;
+            PayloadHeader h;
+            h.magic = kMagic; h.algo = algo; h.n = n; h.k = k; h.scale = hi; h.levels = levels;
+            for (int i = 0; i < 8; ++i) h.pad[i] = 0;
+            h.pad[0] = __float_as_uint(lo);
+            *hdr = h;
+            if (state_scale) { state_scale[0] = hi; state_scale[1] = lo; }
+        }
+        return;
+    }
     double acc = 0.0;
-    if (mode >= 0) {
+    if (mode >= 0 && mode != RED_ONE) {
         // eight independent loads in flight per thread and round (one round up to 8192 partials);
         // the order of additions depends on nblocks only
         for (uint32_t base = 0; base < nblocks; base += 8 * kFinalThreads) {
@@ -160,6 +246,7 @@ __global__ __launch_bounds__(kFinalThreads) void scalar_finalize_k(const double 
             else if (mode == RED_L2) scale = (float)sqrt(S);
             else if (mode == RED_MAX_ABS) scale = (float)S;
         }
+        if (mode == RED_ONE) scale = 1.0f;
         PayloadHeader h;
         h.magic = kMagic; h.algo = algo; h.n = n; h.k = k; h.scale = scale; h.levels = levels;
         for (int i = 0; i < 8; ++i) h.pad[i] = 0;
@@ -168,6 +255,7 @@ __global__ __launch_bounds__(kFinalThreads) void scalar_finalize_k(const double 
     }
 }
 
+// state_scale: where the state keeps the scalar(s) of this call (EF-Sign: one float, OneBit: two), or null
 void launch_scalar_finalize(const LaunchCtx &lc, const double *partial, uint32_t nblocks, int mode, uint32_t n,
                             PayloadHeader *hdr, uint32_t algo, uint64_t k, uint32_t levels, float *state_scale)
 {
@@ -578,9 +666,20 @@ __global__ __launch_bounds__(kBlock) void tern_table_k(PayloadPtrs pl, int W, fl
     }
 }
 
+// what a set / clear bit of worker w decodes to (one-plane schemes)
+__device__ __forceinline__ void plane_levels(const PayloadHeader *h, int kind, float &hi, float &lo)
+{
+    hi = kind == PLANE_VOTE ? 1.0f : h->scale;
+    lo = kind == PLANE_MEANS ? __uint_as_float(h->pad[0]) : -hi;
+}
+__device__ __forceinline__ float vote_of(float tally) { return tally > 0.0f ? 1.0f : (tally < 0.0f ? -1.0f : 0.0f); }
+
+// kind (one-plane schemes only): PLANE_SCALE  EF-Sign, a bit decodes to +-scale
+//                                PLANE_MEANS  OneBit, to the mean of its class
+//                                PLANE_VOTE   SignSGD / SigNUM, to +-1, and the sum becomes its sign (majority vote)
 template <bool TERN>
 __global__ __launch_bounds__(kBlock) void plane_decompress_k(GroupView out, PayloadPtrs pl, int W, float alpha, int *status,
-                                                             const float *tern_table)
+                                                             const float *tern_table, int algo, int kind)
 {
     __shared__ float table[TERN ? kTernCombos : 256];
     __shared__ uint16_t pow3[TERN ? 256 : 1];             // pow3[b] = sum over set bits w of b of 3^w
@@ -588,16 +687,20 @@ __global__ __launch_bounds__(kBlock) void plane_decompress_k(GroupView out, Payl
     const uint32_t t = threadIdx.x;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(t >> 6), lane = t & 63u;
     if (blockIdx.x == 0 && (int)t < W)
-        check_header(reinterpret_cast<const PayloadHeader *>(pl.p[t]), TERN ? MC_ALGO_TERNGRAD : MC_ALGO_EFSIGN, out.n, status);
+        check_header(reinterpret_cast<const PayloadHeader *>(pl.p[t]), algo, out.n, status);
     const int Wt = W < 8 ? W : 8;
     {
-        float sc[8];
-#pragma unroll
-        for (int b = 0; b < 8; ++b) sc[b] = b < Wt ? reinterpret_cast<const PayloadHeader *>(pl.p[b])->scale : 0.0f;
         if (!TERN) {
             float acc = 0.0f;
 #pragma unroll
-            for (int b = 0; b < 8; ++b) if (b < Wt) acc = acc + (((t >> b) & 1u) ? sc[b] : -sc[b]);
+            for (int b = 0; b < 8; ++b) {
+                if (b < Wt) {
+                    float hi, lo;
+                    plane_levels(reinterpret_cast<const PayloadHeader *>(pl.p[b]), kind, hi, lo);
+                    acc = acc + (((t >> b) & 1u) ? hi : lo);
+                }
+            }
+            if (W <= 8 && kind == PLANE_VOTE) acc = vote_of(acc);
             table[t] = W <= 8 ? alpha * acc : acc;
         } else {
             uint32_t p3 = 0, pw = 1;
@@ -644,7 +747,8 @@ __global__ __launch_bounds__(kBlock) void plane_decompress_k(GroupView out, Payl
     }
     if (W > 8) {
         for (int w = 8; w < W; ++w) {
-            const float sc = reinterpret_cast<const PayloadHeader *>(pl.p[w])->scale;
+            float sc = reinterpret_cast<const PayloadHeader *>(pl.p[w])->scale, sl = -sc;
+            if (!TERN) plane_levels(reinterpret_cast<const PayloadHeader *>(pl.p[w]), kind, sc, sl);
             const uint32_t *plane = reinterpret_cast<const uint32_t *>(pl.p[w] + kHeaderBytes);
             const uint32_t word = wi < nwords ? ld_stream(plane + wi) : 0u;
             const uint32_t neg = TERN && wi < nwords ? ld_stream(plane + nwords + wi) : 0u;
@@ -652,13 +756,13 @@ __global__ __launch_bounds__(kBlock) void plane_decompress_k(GroupView out, Payl
             for (int e = 0; e < 32; ++e) {
                 const bool on = (word >> e) & 1u;
                 float d;
-                if (!TERN) d = on ? sc : -sc;
+                if (!TERN) d = on ? sc : sl;
                 else d = on ? (((neg >> e) & 1u) ? -sc : sc) : 0.0f;
                 acc[e] = acc[e] + d;
             }
         }
 #pragma unroll
-        for (int e = 0; e < 32; ++e) acc[e] = alpha * acc[e];
+        for (int e = 0; e < 32; ++e) acc[e] = alpha * (!TERN && kind == PLANE_VOTE ? vote_of(acc[e]) : acc[e]);
     }
     // two halves of 1024 elements through one skewed LDS stage (lanes 32 h .. 32 h + 31 own the elements of
     // half h), so that the global stores are 256 contiguous bytes per wave instruction
@@ -700,12 +804,16 @@ void launch_dense_decompress(const LaunchCtx &lc, int algo, const GroupView &out
     prof_begin(lc, K_DENSE_DECOMPRESS);
     switch (algo) {
     case MC_ALGO_EFSIGN:
+    case MC_ALGO_ONEBIT:
+    case MC_ALGO_SIGNSGD:
+    case MC_ALGO_SIGNUM:
         MC_LAUNCH(plane_decompress_k<false>, dim3((uint32_t)(((uint64_t)out.n + kSignTile - 1) / kSignTile)), block, lc, out, pl, W,
-                  alpha, status, tern_table);
+                  alpha, status, tern_table, algo,
+                  algo == MC_ALGO_EFSIGN ? PLANE_SCALE : algo == MC_ALGO_ONEBIT ? PLANE_MEANS : PLANE_VOTE);
         break;
     case MC_ALGO_TERNGRAD:
         MC_LAUNCH(plane_decompress_k<true>, dim3((uint32_t)(((uint64_t)out.n + kSignTile - 1) / kSignTile)), block, lc, out, pl, W,
-                  alpha, status, tern_table);
+                  alpha, status, tern_table, algo, PLANE_SCALE);
         break;
     case MC_ALGO_QSGD: MC_LAUNCH(dense_decompress_k<MC_ALGO_QSGD>, grid, block, lc, out, pl, W, alpha, levels, status); break;
     default: MC_LAUNCH(dense_decompress_k<MC_ALGO_FP16>, grid, block, lc, out, pl, W, alpha, levels, status); break;
@@ -714,8 +822,9 @@ void launch_dense_decompress(const LaunchCtx &lc, int algo, const GroupView &out
 }
 
 // ---------------------------------------------------------------------------
-// State <-> plain residual.  Only EF-Sign keeps something other than the
-// residual itself (p and the last scale); the other algorithms copy.
+// State <-> plain residual.  Only EF-Sign and OneBit keep something other than
+// the residual itself (p and the scalars of the last call); the other algorithms
+// copy (SigNUM: the momentum).
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void state_convert_k(int algo, int to_residual, uint32_t nfloats, const uint8_t *src, uint8_t *dst)
 {
@@ -727,12 +836,13 @@ __global__ __launch_bounds__(kBlock) void state_convert_k(int algo, int to_resid
         if (i < nfloats) {
             float v = f[i];
             if (algo == MC_ALGO_EFSIGN) { float sp = h->scale; v = v - (v >= 0.0f ? sp : -sp); }
+            if (algo == MC_ALGO_ONEBIT) v = v - (v >= 0.0f ? h->scale : h->scale_lo);
             e[i] = v;
         }
     } else {
         const float *e = reinterpret_cast<const float *>(src);
         float *f = reinterpret_cast<float *>(dst + kHeaderBytes);
-        if (i < nfloats) f[i] = e[i];       // EF-Sign: p = e with scale 0 re-derives exactly e
+        if (i < nfloats) f[i] = e[i];       // EF-Sign, OneBit: p = e with scalars 0 re-derives exactly e
         if (i < kHeaderBytes / 4) reinterpret_cast<uint32_t *>(dst)[i] = 0u;
     }
 }

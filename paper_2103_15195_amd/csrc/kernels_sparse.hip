@@ -1,6 +1,8 @@
-// Sparsifiers (Top-k, DGC) for gfx950: exact top-k of |p| over a whole merged
+// Sparsifiers (Top-k, DGC, Rand-k) for gfx950: exact top-k of |p| over a whole merged
 // group, ties at the threshold taken in index order (lower index wins), payload
 // written in ascending index order, and the sparse decompress-and-sum.
+// Rand-k is the same selection on keys that do not depend on the values: the k
+// largest of the elements' Philox words (31 bits) are k positions drawn uniformly.
 //
 // The paper singles out the top-k() operation as the cost that merging alone
 // does not remove (Section 5.1).  Here the selection is a radix select on the
@@ -65,7 +67,9 @@ __device__ __forceinline__ void flush_fine(const uint32_t *lds, uint32_t *fine, 
 }
 
 // Copy the flagged elements of a chunk, in index order, into the chunk's candidate slots.
-__device__ __forceinline__ uint32_t put_candidates(const Chunk &c, const float (&p)[kSteps], const uint64_t (&flag)[kSteps],
+// bits: what the later kernels see of the element (its key is bits & 0x7FFFFFFF): the value itself, or
+// for Rand-k the random key.
+__device__ __forceinline__ uint32_t put_candidates(const Chunk &c, const uint32_t (&bits)[kSteps], const uint64_t (&flag)[kSteps],
                                                    uint32_t hint, uint32_t *cand_bits, uint16_t *cand_loc, uint32_t *hist /* LDS */)
 {
     uint32_t run = 0;
@@ -74,9 +78,9 @@ __device__ __forceinline__ uint32_t put_candidates(const Chunk &c, const float (
     for (int j = 0; j < kSteps; ++j) {
         if (flag[j] & me) {
             uint32_t slot = c.base + run + lanes_below(flag[j]);
-            cand_bits[slot] = __float_as_uint(p[j]);
+            cand_bits[slot] = bits[j];
             cand_loc[slot] = (uint16_t)(64 * j + c.lane);
-            const uint32_t bin = (key_of(p[j]) - hint) >> kWindowShift;
+            const uint32_t bin = ((bits[j] & 0x7FFFFFFFu) - hint) >> kWindowShift;
             atomicAdd(&hist[bin < (uint32_t)kBinsW - 1u ? bin : (uint32_t)kBinsW - 1u], 1u);
         }
         run += __popcll(flag[j]);
@@ -84,11 +88,14 @@ __device__ __forceinline__ uint32_t put_candidates(const Chunk &c, const float (
     return run;
 }
 
+// key of the stochastic choices: Philox key and the worker / iteration words of the counter
+struct RngKey { uint64_t seed; uint32_t worker, iter_lo; };
+
 // ---------------------------------------------------------------------------
 // accumulate + candidate filter + window histogram of the candidates
 // ---------------------------------------------------------------------------
 template <int ALGO, bool EF>
-__global__ __launch_bounds__(kBlock) void sparse_accum_k(GroupView g, float *st, float momentum, SparseScratch sc)
+__global__ __launch_bounds__(kBlock) void sparse_accum_k(GroupView g, float *st, float momentum, SparseScratch sc, RngKey rng)
 {
     __shared__ uint32_t hist[kBinsW];
     __shared__ uint32_t wcnt[kWavesPerBlock];
@@ -125,13 +132,22 @@ __global__ __launch_bounds__(kBlock) void sparse_accum_k(GroupView g, float *st,
         } else {
             load_seg(g, c, p);
         }
+        uint32_t bits[kSteps];
+        if (ALGO == MC_ALGO_RANDK) {
+            chunk_words(rng.seed, rng.worker, rng.iter_lo, g.goff + c.base, c.lane, bits);
+#pragma unroll
+            for (int j = 0; j < kSteps; ++j) bits[j] >>= 1;
+        } else {
+#pragma unroll
+            for (int j = 0; j < kSteps; ++j) bits[j] = __float_as_uint(p[j]);
+        }
         uint64_t flag[kSteps];
 #pragma unroll
         for (int j = 0; j < kSteps; ++j) {
             bool valid = c.full || c.base + 64 * j + c.lane < g.n;
-            flag[j] = __builtin_amdgcn_ballot_w64(valid && key_of(p[j]) >= hint);
+            flag[j] = __builtin_amdgcn_ballot_w64(valid && (bits[j] & 0x7FFFFFFFu) >= hint);
         }
-        run = put_candidates(c, p, flag, hint, sc.cand_bits, sc.cand_loc, hist);
+        run = put_candidates(c, bits, flag, hint, sc.cand_bits, sc.cand_loc, hist);
     }
     if (c.lane == 0) wcnt[threadIdx.x >> 6] = run;
     __syncthreads();
@@ -278,8 +294,8 @@ __device__ __forceinline__ TileJob my_tile(const SparseScratch &sc, uint32_t n, 
 // ---------------------------------------------------------------------------
 constexpr int kSeedThreads = 1024;
 
-template <bool FROM_STATE>
-__global__ __launch_bounds__(kSeedThreads) void sparse_seed_k(GroupView g, const float *st, uint64_t k, SparseScratch sc)
+template <bool FROM_STATE, bool RANDOM>
+__global__ __launch_bounds__(kSeedThreads) void sparse_seed_k(GroupView g, const float *st, uint64_t k, SparseScratch sc, RngKey rng)
 {
     __shared__ uint32_t hist[kBins1];
     __shared__ uint32_t verdict[4];              // found, bin, rest lo, rest hi
@@ -330,15 +346,24 @@ __global__ __launch_bounds__(kSeedThreads) void sparse_seed_k(GroupView g, const
         c.base = ch * (uint32_t)kChunk;
         c.lane = lane;
         c.full = g.n - c.base >= (uint32_t)kChunk;
-        float v[kSteps];
-        load_sel<FROM_STATE>(g, st, c, v);
+        uint32_t bits[kSteps];
+        if (RANDOM) {
+            chunk_words(rng.seed, rng.worker, rng.iter_lo, g.goff + c.base, c.lane, bits);
+#pragma unroll
+            for (int j = 0; j < kSteps; ++j) bits[j] >>= 1;
+        } else {
+            float v[kSteps];
+            load_sel<FROM_STATE>(g, st, c, v);
+#pragma unroll
+            for (int j = 0; j < kSteps; ++j) bits[j] = __float_as_uint(v[j]);
+        }
 #pragma unroll
         for (int j = 0; j < kSteps; ++j) {
             uint32_t i = c.base + 64 * j + c.lane;
             if (c.full || i < g.n) {
-                sc.cand_bits[i] = __float_as_uint(v[j]);
+                sc.cand_bits[i] = bits[j];
                 sc.cand_loc[i] = (uint16_t)(64 * j + c.lane);
-                atomicAdd(&hist[key_of(v[j]) >> 20], 1u);
+                atomicAdd(&hist[(bits[j] & 0x7FFFFFFFu) >> 20], 1u);
             }
         }
     }
@@ -518,7 +543,8 @@ __global__ __launch_bounds__(kBlock) void cand_emit_k(uint32_t n, uint32_t ntile
             const uint32_t i = chunk * (uint32_t)kChunk + loc;
             if (pos < k && i < n) {                  // always true for consistent scratch; guards the buffers
                 idx[pos] = i;
-                val[pos] = __uint_as_float(b);
+                if (ALGO == MC_ALGO_RANDK) val[pos] = st[i];      // the candidate slot holds the random key: the value is p
+                else val[pos] = __uint_as_float(b);
                 if (ALGO == MC_ALGO_DGC) { st[i] = 0.0f; st[(size_t)n + i] = 0.0f; }   // momentum factor masking
                 else if (EF) st[i] = 0.0f;
             }
@@ -530,17 +556,18 @@ __global__ __launch_bounds__(kBlock) void cand_emit_k(uint32_t n, uint32_t ntile
 
 template <int ALGO, bool EF>
 static void sparse_compress_t(const LaunchCtx &lc, const GroupView &g, float *st, float momentum, uint64_t k,
-                              PayloadHeader *hdr, const SparseScratch &sc)
+                              PayloadHeader *hdr, const SparseScratch &sc, const RngKey &rng)
 {
     constexpr bool FS = (ALGO == MC_ALGO_DGC) || EF;
+    constexpr bool RND = ALGO == MC_ALGO_RANDK;
     const uint32_t nt = tiles_of(g.n), nch = chunks_of(g.n);
     const uint32_t sblocks = (nch + 15) / 16 < 256 ? (nch + 15) / 16 : 256;      // enough to stream the group in a refill
     dim3 grid(nt), block(kBlock), cgrid((nt + kWavesPerBlock - 1) / kWavesPerBlock);
     prof_begin(lc, K_SPARSE_ACCUM);
-    MC_LAUNCH((sparse_accum_k<ALGO, EF>), grid, block, lc, g, st, momentum, sc);
+    MC_LAUNCH((sparse_accum_k<ALGO, EF>), grid, block, lc, g, st, momentum, sc, rng);
     prof_end(lc, K_SPARSE_ACCUM);
     prof_begin(lc, K_SPARSE_SEED);
-    MC_LAUNCH(sparse_seed_k<FS>, dim3(sblocks), dim3(kSeedThreads), lc, g, st, k, sc);
+    MC_LAUNCH((sparse_seed_k<FS, RND>), dim3(sblocks), dim3(kSeedThreads), lc, g, st, k, sc, rng);
     prof_end(lc, K_SPARSE_SEED);
     prof_begin(lc, K_CAND_HIST2);
     MC_LAUNCH(cand_hist_k<2>, cgrid, block, lc, g.n, nt, sc);
@@ -557,12 +584,14 @@ static void sparse_compress_t(const LaunchCtx &lc, const GroupView &g, float *st
 }
 
 void launch_sparse_compress(const LaunchCtx &lc, int algo, const GroupView &g, bool ef, float *state_f, float momentum,
-                            uint64_t k, PayloadHeader *hdr, const SparseScratch &sc)
+                            uint64_t k, PayloadHeader *hdr, const SparseScratch &sc, uint64_t seed, uint32_t worker, uint32_t iter_lo)
 {
     if (g.n == 0) return;
-    if (algo == MC_ALGO_DGC) sparse_compress_t<MC_ALGO_DGC, true>(lc, g, state_f, momentum, k, hdr, sc);
-    else if (ef) sparse_compress_t<MC_ALGO_TOPK, true>(lc, g, state_f, momentum, k, hdr, sc);
-    else sparse_compress_t<MC_ALGO_TOPK, false>(lc, g, state_f, momentum, k, hdr, sc);
+    const RngKey rng{seed, worker, iter_lo};
+    if (algo == MC_ALGO_DGC) sparse_compress_t<MC_ALGO_DGC, true>(lc, g, state_f, momentum, k, hdr, sc, rng);
+    else if (algo == MC_ALGO_RANDK) sparse_compress_t<MC_ALGO_RANDK, true>(lc, g, state_f, momentum, k, hdr, sc, rng);
+    else if (ef) sparse_compress_t<MC_ALGO_TOPK, true>(lc, g, state_f, momentum, k, hdr, sc, rng);
+    else sparse_compress_t<MC_ALGO_TOPK, false>(lc, g, state_f, momentum, k, hdr, sc, rng);
 }
 
 // ---------------------------------------------------------------------------

@@ -124,7 +124,10 @@ static uint64_t topk_count(uint64_t n, uint32_t ppm)
     return k;
 }
 
-static bool is_sparse(int algo) { return algo == MC_ALGO_TOPK || algo == MC_ALGO_DGC; }
+static bool is_sparse(int algo) { return algo == MC_ALGO_TOPK || algo == MC_ALGO_DGC || algo == MC_ALGO_RANDK; }
+// n-element vectors of a group's state: the residual (DGC: v and u; SigNUM: the momentum; SignSGD: nothing)
+static uint32_t state_vectors(int algo) { return algo == MC_ALGO_DGC ? 2u : algo == MC_ALGO_SIGNSGD ? 0u : 1u; }
+static bool always_state(int algo) { return algo == MC_ALGO_DGC || algo == MC_ALGO_SIGNUM || algo == MC_ALGO_RANDK; }
 
 extern "C" {
 
@@ -212,9 +215,10 @@ int mc_ctx_create(mc_ctx **out, const mc_config *cfg, const int64_t *numel, int3
     if (!out) return MC_ERR_INVALID_ARG;
     *out = nullptr;
     if (!cfg || !numel || !bounds || n_tensors < 1 || y < 1) return MC_ERR_INVALID_ARG;
-    if (cfg->algo < MC_ALGO_EFSIGN || cfg->algo > MC_ALGO_FP16 || cfg->reserved != 0) return MC_ERR_INVALID_ARG;
+    if (cfg->algo < MC_ALGO_EFSIGN || cfg->algo > MC_ALGO_RANDK || cfg->reserved != 0) return MC_ERR_INVALID_ARG;
     if (cfg->use_ef != 0 && cfg->use_ef != 1) return MC_ERR_INVALID_ARG;
-    if (cfg->algo == MC_ALGO_DGC && cfg->use_ef != 1) return MC_ERR_INVALID_ARG;
+    if (always_state(cfg->algo) && cfg->use_ef != 1) return MC_ERR_INVALID_ARG;
+    if (cfg->algo == MC_ALGO_SIGNSGD && cfg->use_ef != 0) return MC_ERR_INVALID_ARG;
     if (cfg->algo == MC_ALGO_QSGD && (cfg->qsgd_bits < 2 || cfg->qsgd_bits > 8)) return MC_ERR_INVALID_ARG;
     if (is_sparse(cfg->algo) && (cfg->ratio_ppm < 1 || cfg->ratio_ppm > 1000000u)) return MC_ERR_INVALID_ARG;
     if (y > n_tensors) return MC_ERR_RANGE;
@@ -266,7 +270,7 @@ int mc_ctx_create(mc_ctx **out, const mc_config *cfg, const int64_t *numel, int3
             ctx->max_live = std::max(ctx->max_live, g.live.size());
         }
         const size_t tiles = std::max<size_t>(ctx->max_tiles, 1);
-        if (rc == MC_OK && hipMalloc(&ctx->d_partial, tiles * sizeof(double)) != hipSuccess) rc = MC_ERR_ALLOC;
+        if (rc == MC_OK && hipMalloc(&ctx->d_partial, 3 * tiles * sizeof(double)) != hipSuccess) rc = MC_ERR_ALLOC;
         if (rc == MC_OK && hipMalloc(&ctx->d_status, sizeof(int)) != hipSuccess) rc = MC_ERR_ALLOC;
         if (rc == MC_OK && hipMemset(ctx->d_status, 0, sizeof(int)) != hipSuccess) rc = MC_ERR_DEVICE;
         if (rc == MC_OK && cfg->algo == MC_ALGO_TERNGRAD && hipMalloc(&ctx->d_tern_table, 6561 * sizeof(float)) != hipSuccess) rc = MC_ERR_ALLOC;
@@ -325,7 +329,10 @@ size_t mc_payload_bytes(const mc_ctx *ctx, int32_t group)
     if (!g) return 0;
     const uint64_t n = g->n, words = (n + 31) / 32;
     switch (ctx->cfg.algo) {
-    case MC_ALGO_EFSIGN: return kHeaderBytes + 4 * words;
+    case MC_ALGO_EFSIGN:
+    case MC_ALGO_ONEBIT:
+    case MC_ALGO_SIGNSGD:
+    case MC_ALGO_SIGNUM: return kHeaderBytes + 4 * words;
     case MC_ALGO_TERNGRAD: return kHeaderBytes + 8 * words;
     case MC_ALGO_QSGD: return kHeaderBytes + (n + 3) / 4 * 4;
     case MC_ALGO_FP16: return kHeaderBytes + (2 * n + 3) / 4 * 4;
@@ -337,7 +344,7 @@ size_t mc_state_bytes(const mc_ctx *ctx, int32_t group)
 {
     const Group *g = group_of(ctx, group);
     if (!g) return 0;
-    return kHeaderBytes + sizeof(float) * (size_t)g->n * (ctx->cfg.algo == MC_ALGO_DGC ? 2 : 1);
+    return kHeaderBytes + sizeof(float) * (size_t)g->n * state_vectors(ctx->cfg.algo);
 }
 
 // Device view of a group over a per-call tensor address list (only tensors that hold
@@ -400,14 +407,25 @@ int mc_compress(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter, cons
     const uint32_t levels = cfg.algo == MC_ALGO_QSGD ? (1u << (cfg.qsgd_bits - 1)) - 1u : 0u;
 
     if (n == 0) {   // nothing to encode: the payload is its header
-        launch_scalar_finalize(lc, ctx->d_partial, 0, -1, 0, hdr, (uint32_t)cfg.algo, 0, levels, nullptr);
+        const bool votes = cfg.algo == MC_ALGO_SIGNSGD || cfg.algo == MC_ALGO_SIGNUM;
+        launch_scalar_finalize(lc, ctx->d_partial, 0, votes ? RED_ONE : -1, 0, hdr, (uint32_t)cfg.algo, 0, levels, nullptr);
         return check_launch();
     }
     GroupView gv = group_view(ctx, lc, group, G, reinterpret_cast<const void *const *>(grad_ptrs));
     switch (cfg.algo) {
     case MC_ALGO_EFSIGN:
-        launch_efsign_compress(lc, gv, ef, sf, ef ? &sh->scale : nullptr, reinterpret_cast<uint32_t *>(body), nwords, ctx->d_partial);
+        launch_sign_compress(lc, SIGN_EF, gv, ef, sf, sh, 0.0f, reinterpret_cast<uint32_t *>(body), nwords, ctx->d_partial);
         launch_scalar_finalize(lc, ctx->d_partial, tiles, RED_MEAN_ABS, n, hdr, MC_ALGO_EFSIGN, 0, 0, ef ? &sh->scale : nullptr);
+        break;
+    case MC_ALGO_ONEBIT:
+        launch_sign_compress(lc, SIGN_MEANS, gv, ef, sf, sh, 0.0f, reinterpret_cast<uint32_t *>(body), nwords, ctx->d_partial);
+        launch_scalar_finalize(lc, ctx->d_partial, tiles, RED_MEANS, n, hdr, MC_ALGO_ONEBIT, 0, 0, ef ? &sh->scale : nullptr);
+        break;
+    case MC_ALGO_SIGNSGD:
+    case MC_ALGO_SIGNUM:
+        launch_sign_compress(lc, cfg.algo == MC_ALGO_SIGNSGD ? SIGN_PLAIN : SIGN_MOMENTUM, gv, ef, sf, sh, cfg.dgc_momentum,
+                             reinterpret_cast<uint32_t *>(body), nwords, ctx->d_partial);
+        launch_scalar_finalize(lc, ctx->d_partial, 0, RED_ONE, n, hdr, (uint32_t)cfg.algo, 0, 0, nullptr);
         break;
     case MC_ALGO_QSGD:
         launch_accum_reduce(lc, gv, ef, sf, RED_L2, ctx->d_partial);
@@ -425,11 +443,12 @@ int mc_compress(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter, cons
         break;
     case MC_ALGO_TOPK:
     case MC_ALGO_DGC:
+    case MC_ALGO_RANDK:
     {
         SparseScratch sp = ctx->sparse;
         // a context may compress for several simulated workers whose thresholds differ: each keeps its own hint
         sp.hint = ctx->d_hints + (size_t)group * kHintWorkers + worker % kHintWorkers;
-        launch_sparse_compress(lc, cfg.algo, gv, ef, sf, cfg.dgc_momentum, G.k, hdr, sp);
+        launch_sparse_compress(lc, cfg.algo, gv, ef, sf, cfg.dgc_momentum, G.k, hdr, sp, cfg.seed, worker, (uint32_t)iter);
     }
         break;
     default: return MC_ERR_INVALID_ARG;
@@ -470,7 +489,7 @@ static int state_convert(mc_ctx *ctx, int32_t group, const void *src, void *dst,
 {
     const Group *g = group_of(ctx, group);
     if (!g) return MC_ERR_INVALID_ARG;
-    const uint32_t nf = g->n * (ctx->cfg.algo == MC_ALGO_DGC ? 2u : 1u);
+    const uint32_t nf = g->n * state_vectors(ctx->cfg.algo);
     // an empty group has no residual: the plain side may be null, the opaque side never
     if (!(to_residual ? src : dst) || (nf > 0 && !(to_residual ? dst : src))) return MC_ERR_INVALID_ARG;
     if (nf == 0 && to_residual) return MC_OK;

@@ -242,12 +242,13 @@ __device__ __forceinline__ uint32_t quad_bcast(uint32_t x)      // value of lane
     return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, R | (R << 2) | (R << 4) | (R << 6), 0xF, 0xF, true);
 }
 
-// The uniforms of a chunk's 16 steps for this lane (element gbase + 64 j + lane in step j).
+// The Philox words of a chunk's 16 steps for this lane (element gbase + 64 j + lane in step j
+// takes word (index % 4) of block index / 4).
 // Four adjacent lanes hold four consecutive elements; when gbase is a multiple of 4 these
 // share one Philox block, so each lane computes one block per four steps (the one of step
 // 4m + lane % 4) and the four words are handed round inside the quad.
-__device__ __forceinline__ void chunk_uniforms(uint64_t seed, uint32_t worker, uint32_t iter_lo, uint64_t gbase, uint32_t lane,
-                                               float (&u)[kSteps])
+__device__ __forceinline__ void chunk_words(uint64_t seed, uint32_t worker, uint32_t iter_lo, uint64_t gbase, uint32_t lane,
+                                            uint32_t (&x)[kSteps])
 {
     if ((gbase & 3u) == 0) {
         const uint32_t me = lane & 3u;
@@ -255,15 +256,15 @@ __device__ __forceinline__ void chunk_uniforms(uint64_t seed, uint32_t worker, u
         for (int m = 0; m < kSteps / 4; ++m) {
             uint32_t w[4];
             philox4x32_10(seed, worker, iter_lo, (gbase + 64u * (4 * m + me) + lane) >> 2, w);
-            uint32_t x[4][4];                      // x[r][i]: word i of the block of step 4m + r
+            uint32_t y[4][4];                      // y[r][i]: word i of the block of step 4m + r
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                x[0][i] = quad_bcast<0>(w[i]); x[1][i] = quad_bcast<1>(w[i]);
-                x[2][i] = quad_bcast<2>(w[i]); x[3][i] = quad_bcast<3>(w[i]);
+                y[0][i] = quad_bcast<0>(w[i]); y[1][i] = quad_bcast<1>(w[i]);
+                y[2][i] = quad_bcast<2>(w[i]); y[3][i] = quad_bcast<3>(w[i]);
             }
 #pragma unroll
             for (int r = 0; r < 4; ++r)
-                u[4 * m + r] = u01(me == 0 ? x[r][0] : me == 1 ? x[r][1] : me == 2 ? x[r][2] : x[r][3]);
+                x[4 * m + r] = me == 0 ? y[r][0] : me == 1 ? y[r][1] : me == 2 ? y[r][2] : y[r][3];
         }
     } else {
 #pragma unroll
@@ -272,9 +273,19 @@ __device__ __forceinline__ void chunk_uniforms(uint64_t seed, uint32_t worker, u
             uint32_t w[4];
             philox4x32_10(seed, worker, iter_lo, gidx >> 2, w);
             const uint32_t i = (uint32_t)gidx & 3u;
-            u[j] = u01(i == 0 ? w[0] : i == 1 ? w[1] : i == 2 ? w[2] : w[3]);
+            x[j] = i == 0 ? w[0] : i == 1 ? w[1] : i == 2 ? w[2] : w[3];
         }
     }
+}
+
+// the same as uniforms in [0, 1)
+__device__ __forceinline__ void chunk_uniforms(uint64_t seed, uint32_t worker, uint32_t iter_lo, uint64_t gbase, uint32_t lane,
+                                               float (&u)[kSteps])
+{
+    uint32_t x[kSteps];
+    chunk_words(seed, worker, iter_lo, gbase, lane, x);
+#pragma unroll
+    for (int j = 0; j < kSteps; ++j) u[j] = u01(x[j]);
 }
 
 }  // namespace mc

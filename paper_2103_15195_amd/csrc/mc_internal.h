@@ -23,8 +23,9 @@ struct PayloadHeader {          // 64 bytes, see the layout in mergecomp.h
 static_assert(sizeof(PayloadHeader) == kHeaderBytes, "payload header is 64 bytes");
 
 struct StateHeader {            // 64 bytes in front of the error-feedback floats
-    float scale;                // EF-Sign: scale of the last call (0 after zero-fill / import)
-    uint32_t pad[15];
+    float scale;                // EF-Sign: scale of the last call; OneBit: mean of its upper class (0 after zero-fill / import)
+    float scale_lo;             // OneBit: mean of the lower class of the last call
+    uint32_t pad[14];
 };
 static_assert(sizeof(StateHeader) == kHeaderBytes, "state header is 64 bytes");
 
@@ -46,7 +47,10 @@ enum KernelId {
 };
 
 // reduction kinds of the two-pass quantizers
-enum ReduceMode { RED_MEAN_ABS = 0, RED_L2 = 1, RED_MAX_ABS = 2 };
+enum ReduceMode { RED_MEAN_ABS = 0, RED_L2 = 1, RED_MAX_ABS = 2, RED_ONE = 3, RED_MEANS = 4 };
+// the one-bit compressors (one kernel) and what their single plane decodes to
+enum SignMode { SIGN_EF = 0, SIGN_MEANS = 1, SIGN_PLAIN = 2, SIGN_MOMENTUM = 3 };
+enum PlaneKind { PLANE_SCALE = 0, PLANE_MEANS = 1, PLANE_VOTE = 2 };
 
 struct LaunchCtx {               // what a launcher needs besides its arguments
     hipStream_t stream;
@@ -66,8 +70,8 @@ void prof_end(const LaunchCtx &lc, int id);
 // ---- dense kernels (kernels_dense.hip) -----------------------------------------
 void launch_upload_ptrs(const LaunchCtx &lc, const uintptr_t *host, uintptr_t *dev, uint32_t count);
 void launch_expand_ptrs(const LaunchCtx &lc, const GroupView &g, uintptr_t *chunk_addr);
-void launch_efsign_compress(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, const float *scale_prev,
-                            uint32_t *words, uint32_t nwords, double *partial);
+void launch_sign_compress(const LaunchCtx &lc, int mode, const GroupView &g, bool ef, float *state_f, const StateHeader *prev,
+                          float beta, uint32_t *words, uint32_t nwords, double *partial);
 void launch_scalar_finalize(const LaunchCtx &lc, const double *partial, uint32_t nblocks, int mode, uint32_t n,
                             PayloadHeader *hdr, uint32_t algo, uint64_t k, uint32_t levels, float *state_scale);
 void launch_accum_reduce(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, int mode, double *partial);
@@ -97,7 +101,7 @@ struct SparseScratch {
     uint64_t *tile_first, *tile_last;   // decompress: per worker and 4096-element tile, (epoch << 32 | entry) of its run
 };
 void launch_sparse_compress(const LaunchCtx &lc, int algo, const GroupView &g, bool ef, float *state_f, float momentum,
-                            uint64_t k, PayloadHeader *hdr, const SparseScratch &sc);
+                            uint64_t k, PayloadHeader *hdr, const SparseScratch &sc, uint64_t seed, uint32_t worker, uint32_t iter_lo);
 void launch_sparse_decompress(const LaunchCtx &lc, int algo, const GroupView &out, const PayloadPtrs &pl, int W,
                               float alpha, uint64_t k, uint32_t epoch, uint64_t *tile_first, uint64_t *tile_last,
                               int *status);

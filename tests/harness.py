@@ -10,7 +10,7 @@ assert the stricter bit equality for the sums, because both sides add the same
 fp32 terms in the same worker order.
 
 Scalars and codes.  QSGD / TernGrad codes and every residual depend on the group
-scalar.  The oracle first runs on its own; if its scalar has the same bits as the
+scalar (OneBit: on its two class means).  The oracle first runs on its own; if its scalar has the same bits as the
 GPU's (the normal case: both accumulate in fp64) everything must match bit for
 bit.  If the scalars differ within the 1e-6 bar, the oracle's encode step is
 repeated with the GPU's scalar as input and must then match bit for bit; this is
@@ -28,7 +28,8 @@ from oracle import oracle as O
 from paper_2103_15195_amd import binding as B
 from paper_2103_15195_amd import workloads as WL
 
-ALGOS = {"efsign": 1, "topk": 2, "dgc": 3, "qsgd": 4, "terngrad": 5, "fp16": 6}
+ALGOS = {"efsign": 1, "topk": 2, "dgc": 3, "qsgd": 4, "terngrad": 5, "fp16": 6,
+         "signsgd": 7, "signum": 8, "onebit": 9, "randk": 10}
 DEV = "cuda:0"
 
 
@@ -77,8 +78,13 @@ def check_payload(algo: str, gpay: np.ndarray, opay: np.ndarray, what: str) -> b
     gh, oh = O.header(gpay), O.header(opay)
     for key in ("magic", "algo", "n", "k", "levels"):
         assert gh[key] == oh[key], f"{what}: header field {key}: gpu {gh[key]} oracle {oh[key]}"
-    assert not gpay[32:64].any(), f"{what}: header padding not zero"
+    assert not gpay[36 if algo == "onebit" else 32:64].any(), f"{what}: header padding not zero"
     gs, os_ = np.float32(gh["scale"]), np.float32(oh["scale"])
+    if algo == "onebit":                         # two scalars: the class means
+        g2, o2 = np.float32(gh["scale2"]), np.float32(oh["scale2"])
+        assert abs(float(g2) - float(o2)) <= 1e-6 * abs(float(o2)), f"{what}: lower mean gpu {g2!r} oracle {o2!r}"
+        assert abs(float(gs) - float(os_)) <= 1e-6 * abs(float(os_)), f"{what}: upper mean gpu {gs!r} oracle {os_!r}"
+        return gs.view(np.uint32) == os_.view(np.uint32) and g2.view(np.uint32) == o2.view(np.uint32)
     if algo == "terngrad":
         assert gs == os_, f"{what}: max|p| must be exact: gpu {gs!r} oracle {os_!r}"
     else:
@@ -98,6 +104,8 @@ def run_parity(numel: Sequence[int], algo: str, y: int, W: int, iters: int,
     aid = ALGOS[algo]
     bounds = B.mc_partition(numel, y, policy, user_bounds)
     assert bounds == list(O.partition(numel, y, policy, user_bounds)), "mc_partition differs from the oracle"
+    if algo == "signsgd":
+        cfgkw.setdefault("use_ef", 0)
     ctx = B.Context(aid, numel, bounds, **cfgkw)
     ocfg = O.Config(aid, **cfgkw)
     ef = ocfg.use_ef != 0
@@ -110,7 +118,7 @@ def run_parity(numel: Sequence[int], algo: str, y: int, W: int, iters: int,
         assert ctx.group_numel(j) == gn[j]
         assert ctx.payload_bytes(j) == O.payload_bytes(ocfg, gn[j])
         assert ctx.state_bytes(j) == 64 + 4 * O.state_floats(ocfg, gn[j])
-        assert ctx.group_k(j) == (O.topk_count(gn[j], ocfg.ratio_ppm) if algo in ("topk", "dgc") else 0)
+        assert ctx.group_k(j) == (O.topk_count(gn[j], ocfg.ratio_ppm) if algo in ("topk", "dgc", "randk") else 0)
 
     gstate = [[torch.zeros(ctx.state_bytes(j), dtype=torch.uint8, device=DEV) if ef else None for j in range(y)] for _ in workers]
     gpay = [[torch.full((ctx.payload_bytes(j),), 0xAB, dtype=torch.uint8, device=DEV) for j in range(y)] for _ in workers]
@@ -136,8 +144,9 @@ def run_parity(numel: Sequence[int], algo: str, y: int, W: int, iters: int,
                     stats.notes.append(f"{what}: scalar differs within 1e-6, oracle re-encoded with the GPU scalar")
                     if ef:
                         ostate[w][j][:] = before
+                    gh = O.header(gp)
                     op, _ = O.compress(ocfg, g, ostate[w][j], group_off=goff[j], worker=w, it=it,
-                                       scale_in=O.header(gp)["scale"])
+                                       scale_in=(gh["scale"], gh["scale2"]) if algo == "onebit" else gh["scale"])
                 assert gp.size == op.size
                 if not np.array_equal(gp, op):
                     bad = np.nonzero(gp != op)[0]

@@ -121,16 +121,17 @@ def test_config3_resnet101_topk(y):
     sparse_decompress_fullsize(wl, "topk", y, 16, grads, 1000)
 
 
-# ---- fifth configuration: Mask R-CNN shapes (odd tensor sizes, Student-t values), y in {1,2,4}, W = 8; all six algorithms ----
+# ---- fifth configuration: Mask R-CNN shapes (odd tensor sizes, Student-t values), y in {1,2,4}, W = 8; all algorithms,
+# the four further schemes of the paper's Table 1 included ----
 @pytest.mark.parametrize("y", [1, 2, 4])
-@pytest.mark.parametrize("algo", ["efsign", "qsgd", "terngrad", "fp16"])
+@pytest.mark.parametrize("algo", ["efsign", "qsgd", "terngrad", "fp16", "signsgd", "signum", "onebit"])
 def test_config4_maskrcnn_dense(algo, y):
     st = compress_fullsize(4, algo, y, 8, iters=2 if y == 1 else 1, oracle_workers=None if y == 4 else [0, 7])
     assert st.decompress_checks == (4 if y == 4 else 0)
 
 
 @pytest.mark.parametrize("y", [1, 2, 4])
-@pytest.mark.parametrize("algo", ["topk", "dgc"])
+@pytest.mark.parametrize("algo", ["topk", "dgc", "randk"])
 def test_config4_maskrcnn_sparse(algo, y):
     compress_fullsize(4, algo, y, 8, iters=2 if y == 1 else 1, oracle_workers=[0] if y == 1 else [7])
     wl, grads = grads_of(4)
