@@ -116,6 +116,44 @@ int mc_partition(const int64_t *numel, int32_t n_tensors, int32_t y, int32_t pol
                  const int32_t *user_bounds, int32_t *bounds_out);
 
 /*
+ * Iteration-time model of Section 4.3 and the partition search of Algorithm 2.  Host-only.
+ *
+ * F(X_y) = A + sum h(x_i) + sum g(x_i) - sum p(x_i) with the linear overheads of Assumption 1,
+ * h(x) = B_h + gamma_h x (compression) and g(x) = B_g + gamma_g x (communication), x in elements.
+ * The overlap p is not given in closed form by the paper; the schedule it describes (wait-free
+ * back-propagation, proof of Theorem 3) is evaluated directly: the GPU runs the forward pass
+ * (fwd_time), then back-propagation tensor by tensor in list order (bwd_time[t] seconds each) and
+ * compresses a group as soon as its last tensor is done; the network sends group i when it has been
+ * compressed and group i-1 has been sent.  F is the time at which the last group has been sent.
+ */
+typedef struct {
+    double fwd_time;  /* seconds of the iteration before back-propagation starts            */
+    double B_h;       /* compression: seconds per group (the B_h of Lemma 2)                */
+    double gamma_h;   /* compression: seconds per element                                   */
+    double B_g;       /* communication: seconds per group                                   */
+    double gamma_g;   /* communication: seconds per element                                 */
+} mc_time_model;
+
+/* F of the partition `bounds` (y+1 entries as returned by mc_partition).  All pointers host.
+ * Errors: MC_ERR_INVALID_ARG (null, N < 1, y < 1), MC_ERR_RANGE (y > N, bounds not increasing 0..N). */
+int mc_partition_cost(const int64_t *numel, const double *bwd_time, int32_t n_tensors, const mc_time_model *model,
+                      const int32_t *bounds, int32_t y, double *F_out);
+
+/*
+ * Algorithm 2: for y = 2 .. Y find X_y* = argmin F over all partitions into y contiguous groups
+ * and stop at y-1 if F_min(y-1) < F_min(y), at y if F_min(y-1) - F_min(y) < alpha F_min(y-1).
+ * The inner argmin is exact: F is monotone in the time the network becomes free, so a dynamic
+ * programme over (last tensor, groups used) finds it in O(N^2 y) instead of the O(N^(y-2) log N)
+ * enumeration of Theorem 3.
+ *   bounds_out  host, at least min(Y, N) + 1 entries; receives y_out + 1 boundaries
+ *   y_out       host, number of groups of the partition returned
+ *   F_out       host, its F (may be NULL)
+ * Errors: MC_ERR_INVALID_ARG (null, N < 1, Y < 1, alpha outside [0, 1), negative time), MC_ERR_ALLOC.
+ */
+int mc_partition_search(const int64_t *numel, const double *bwd_time, int32_t n_tensors, const mc_time_model *model,
+                        int32_t Y, double alpha, int32_t *bounds_out, int32_t *y_out, double *F_out);
+
+/*
  * Create a context for one (config, tensor list, partition) on the current HIP
  * device.  All arrays are host memory and are copied.  Allocates the device
  * segment tables and scratch for every group.

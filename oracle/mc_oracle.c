@@ -22,7 +22,9 @@
  * gradient + old residual; exact-k; EF-Sign decode == scale*sign and the closed
  * form of the residual energy; unbiasedness of QSGD / TernGrad by averaging;
  * fp16 cast against a library cast; W=1 aggregate == decode; partition counts
- * against C(N-1, y-1) enumeration.  The four further schemes of Table 1: sign
+ * against C(N-1, y-1) enumeration; the iteration-time model of the partition
+ * search against closed forms (one group, free network, saturated network)
+ * and a timeline worked by hand.  The four further schemes of Table 1: sign
  * planes against a library bit packer and scale invariance, the vote against a
  * library sign-of-sum, SigNUM with beta = 0 == SignSGD and the closed form of a
  * constant gradient, OneBit's two means against library means and the
@@ -120,6 +122,95 @@ int orc_partition(const int64_t *numel, int32_t N, int32_t y, int32_t policy,
         for (int j = 0; j < y; ++j) if (user_bounds[j + 1] <= user_bounds[j]) return -2;
         for (int j = 0; j <= y; ++j) bounds[j] = user_bounds[j];
     } else return -1;
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Iteration time of a partition (Section 4.3): F(X_y) = A + sum h(x_i) +      */
+/* sum g(x_i) - sum p(x_i) with linear h and g (Assumption 1).  The paper      */
+/* gives no formula for the overlap p; it describes the schedule (wait-free    */
+/* back-propagation, proof of Theorem 3), which is simulated here:             */
+/*   - the GPU runs forward, then back-propagation tensor by tensor in list    */
+/*     order (bwd[t] seconds each); when the last tensor of group i is done it  */
+/*     compresses the group, h(x_i) = B_h + gamma_h x_i, then goes on;          */
+/*   - the network sends group i for g(x_i) = B_g + gamma_g x_i seconds,        */
+/*     starting when its compression is done and group i-1 has been sent.       */
+/* F is the time at which the last group has been sent.                         */
+/* ------------------------------------------------------------------------ */
+typedef struct { double fwd, B_h, gamma_h, B_g, gamma_g; } orc_time_model;
+
+int orc_partition_cost(const int64_t *numel, const double *bwd, int32_t N, const orc_time_model *m,
+                       const int32_t *bounds, int32_t y, double *F)
+{
+    if (!numel || !bwd || !m || !bounds || !F || N < 1 || y < 1 || y > N) return -1;
+    if (bounds[0] != 0 || bounds[y] != N) return -2;
+    double gpu = m->fwd, net = 0.0;
+    for (int i = 0; i < y; ++i) {
+        if (bounds[i + 1] <= bounds[i]) return -2;
+        int64_t x = 0;
+        for (int t = bounds[i]; t < bounds[i + 1]; ++t) { gpu += bwd[t]; x += numel[t]; }
+        gpu += m->B_h + m->gamma_h * (double)x;                  /* compress the group */
+        double start = gpu > net ? gpu : net;                    /* the network may still be busy */
+        net = start + (m->B_g + m->gamma_g * (double)x);
+    }
+    *F = net;
+    return 0;
+}
+
+/* all partitions of N tensors into exactly y contiguous groups, the cheapest kept */
+static void enumerate_partitions(const int64_t *numel, const double *bwd, int32_t N, const orc_time_model *m, int32_t y,
+                                 int32_t *cur, int depth, double *bestF, int32_t *best)
+{
+    if (depth == y) {
+        cur[y] = N;
+        double F;
+        if (orc_partition_cost(numel, bwd, N, m, cur, y, &F) == 0 && F < *bestF) {
+            *bestF = F;
+            memcpy(best, cur, (size_t)(y + 1) * sizeof(int32_t));
+        }
+        return;
+    }
+    /* boundary `depth` lies after boundary depth-1 and leaves a tensor for each later group */
+    for (int32_t b = cur[depth - 1] + 1; b <= N - (y - depth); ++b) {
+        cur[depth] = b;
+        enumerate_partitions(numel, bwd, N, m, y, cur, depth + 1, bestF, best);
+    }
+}
+
+/* F_min(y) and one partition that attains it, by trying all C(N-1, y-1) (Lemma 1) */
+int orc_partition_best(const int64_t *numel, const double *bwd, int32_t N, const orc_time_model *m, int32_t y,
+                       int32_t *bounds, double *F)
+{
+    if (y < 1 || y > N || N > 24) return -2;
+    int32_t cur[26];
+    double bestF = INFINITY;
+    cur[0] = 0;
+    enumerate_partitions(numel, bwd, N, m, y, cur, 1, &bestF, bounds);
+    *F = bestF;
+    return 0;
+}
+
+/* The heuristic of Algorithm 2: grow y from 2; stop at y-1 as soon as the best y groups are slower
+ * than the best y-1, stop at y as soon as the gain drops below alpha * F_min(y-1), else end at Y. */
+int orc_partition_search(const int64_t *numel, const double *bwd, int32_t N, const orc_time_model *m, int32_t Y,
+                         double alpha, int32_t *bounds, int32_t *y_out, double *F_out)
+{
+    if (Y < 1 || N > 24) return -2;
+    if (Y > N) Y = N;
+    int32_t prev[26], now[26];
+    double Fprev, Fnow;
+    orc_partition_best(numel, bwd, N, m, 1, prev, &Fprev);
+    int32_t ybest = 1;
+    for (int32_t y = 2; y <= Y; ++y) {
+        orc_partition_best(numel, bwd, N, m, y, now, &Fnow);
+        if (Fprev < Fnow) break;                                   /* more groups made it worse: keep y-1 */
+        int stop = Fprev - Fnow < alpha * Fprev;                   /* marginal benefit too small: keep y, stop */
+        memcpy(prev, now, (size_t)(y + 1) * sizeof(int32_t));
+        Fprev = Fnow; ybest = y;
+        if (stop) break;
+    }
+    memcpy(bounds, prev, (size_t)(ybest + 1) * sizeof(int32_t));
+    *y_out = ybest; *F_out = Fprev;
     return 0;
 }
 

@@ -69,6 +69,12 @@ def lib():
         L.orc_randk_key.restype = C.c_uint32
         L.orc_partition.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.orc_partition.restype = C.c_int
+        L.orc_partition_cost.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(_TimeModel), C.c_void_p, C.c_int32,
+                                         C.POINTER(C.c_double)]
+        L.orc_partition_best.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(_TimeModel), C.c_int32, C.c_void_p,
+                                         C.POINTER(C.c_double)]
+        L.orc_partition_search.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(_TimeModel), C.c_int32, C.c_double,
+                                           C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_double)]
         L.orc_topk_count.argtypes = [C.c_int64, C.c_uint32]
         L.orc_topk_count.restype = C.c_int64
         L.orc_payload_bytes.argtypes = [C.POINTER(_Cfg), C.c_int64]
@@ -117,6 +123,64 @@ def partition(numel: Sequence[int], y: int, policy: int = PART_EVEN_ELEMS,
     if rc:
         raise ValueError(f"orc_partition failed: {rc}")
     return out
+
+
+class _TimeModel(C.Structure):
+    _fields_ = [("fwd", C.c_double), ("B_h", C.c_double), ("gamma_h", C.c_double), ("B_g", C.c_double),
+                ("gamma_g", C.c_double)]
+
+
+@dataclass
+class TimeModel:
+    """Seconds: forward time, then h(x) = B_h + gamma_h x (compress) and g(x) = B_g + gamma_g x (send), x in elements."""
+    fwd: float = 0.0
+    B_h: float = 0.0
+    gamma_h: float = 0.0
+    B_g: float = 0.0
+    gamma_g: float = 0.0
+
+    def c(self) -> _TimeModel:
+        return _TimeModel(self.fwd, self.B_h, self.gamma_h, self.B_g, self.gamma_g)
+
+
+def partition_cost(numel: Sequence[int], bwd: Sequence[float], model: TimeModel, bounds: Sequence[int]) -> float:
+    """F(X_y) of Section 4.3 for the partition given by its boundaries."""
+    nm = np.ascontiguousarray(numel, dtype=np.int64)
+    bw = np.ascontiguousarray(bwd, dtype=np.float64)
+    bd = np.ascontiguousarray(bounds, dtype=np.int32)
+    F = C.c_double()
+    m = model.c()
+    rc = lib().orc_partition_cost(_ptr(nm), _ptr(bw), len(nm), C.byref(m), _ptr(bd), len(bd) - 1, C.byref(F))
+    if rc:
+        raise ValueError(f"orc_partition_cost failed: {rc}")
+    return F.value
+
+
+def partition_best(numel: Sequence[int], bwd: Sequence[float], model: TimeModel, y: int) -> Tuple[np.ndarray, float]:
+    """Brute force over all partitions into y groups: (boundaries, F_min(y))."""
+    nm = np.ascontiguousarray(numel, dtype=np.int64)
+    bw = np.ascontiguousarray(bwd, dtype=np.float64)
+    out = np.zeros(y + 1, dtype=np.int32)
+    F = C.c_double()
+    m = model.c()
+    rc = lib().orc_partition_best(_ptr(nm), _ptr(bw), len(nm), C.byref(m), y, _ptr(out), C.byref(F))
+    if rc:
+        raise ValueError(f"orc_partition_best failed: {rc}")
+    return out, F.value
+
+
+def partition_search(numel: Sequence[int], bwd: Sequence[float], model: TimeModel, Y: int,
+                     alpha: float) -> Tuple[np.ndarray, float]:
+    """Algorithm 2 with a brute-force inner minimisation: (boundaries of the partition returned, its F)."""
+    nm = np.ascontiguousarray(numel, dtype=np.int64)
+    bw = np.ascontiguousarray(bwd, dtype=np.float64)
+    out = np.zeros(min(Y, len(nm)) + 1, dtype=np.int32)
+    F, y = C.c_double(), C.c_int32()
+    m = model.c()
+    rc = lib().orc_partition_search(_ptr(nm), _ptr(bw), len(nm), C.byref(m), Y, alpha, _ptr(out), C.byref(y), C.byref(F))
+    if rc:
+        raise ValueError(f"orc_partition_search failed: {rc}")
+    return out[:y.value + 1].copy(), F.value
 
 
 def topk_count(n: int, ppm: int) -> int:

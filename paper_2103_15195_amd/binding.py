@@ -23,7 +23,7 @@ MC_SELECT_ABOVE, MC_SELECT_FAST, MC_SELECT_REFILL = 0, 1, 2
 MC_OK, MC_ERR_INVALID_ARG, MC_ERR_RANGE, MC_ERR_ALLOC, MC_ERR_DEVICE, MC_ERR_PAYLOAD = 0, -1, -2, -3, -4, -5
 
 EXPORTS = [
-    "mc_partition", "mc_ctx_create", "mc_ctx_destroy", "mc_group_numel", "mc_group_k", "mc_group_tensors",
+    "mc_partition", "mc_partition_cost", "mc_partition_search", "mc_ctx_create", "mc_ctx_destroy", "mc_group_numel", "mc_group_k", "mc_group_tensors",
     "mc_payload_bytes", "mc_state_bytes", "mc_compress", "mc_decompress_sum", "mc_state_export_residual",
     "mc_state_import_residual", "mc_last_device_status", "mc_last_select_route", "mc_profile_enable", "mc_profile_select", "mc_profile_reset",
     "mc_profile_kernels", "mc_profile_read", "mc_strerror", "mc_version",
@@ -33,6 +33,11 @@ EXPORTS = [
 class McConfig(C.Structure):
     _fields_ = [("algo", C.c_int32), ("use_ef", C.c_int32), ("ratio_ppm", C.c_uint32), ("qsgd_bits", C.c_int32),
                 ("dgc_momentum", C.c_float), ("reserved", C.c_uint32), ("seed", C.c_uint64)]
+
+
+class McTimeModel(C.Structure):
+    _fields_ = [("fwd_time", C.c_double), ("B_h", C.c_double), ("gamma_h", C.c_double), ("B_g", C.c_double),
+                ("gamma_g", C.c_double)]
 
 
 class McError(RuntimeError):
@@ -54,6 +59,9 @@ def lib():
         L = C.CDLL(LIB_PATH)
         vp, i32, i64, u32, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_uint64
         L.mc_partition.argtypes = [vp, i32, i32, i32, vp, vp]
+        L.mc_partition_cost.argtypes = [vp, vp, i32, C.POINTER(McTimeModel), vp, i32, C.POINTER(C.c_double)]
+        L.mc_partition_search.argtypes = [vp, vp, i32, C.POINTER(McTimeModel), i32, C.c_double, vp, C.POINTER(i32),
+                                          C.POINTER(C.c_double)]
         L.mc_ctx_create.argtypes = [C.POINTER(vp), C.POINTER(McConfig), vp, i32, vp, i32]
         L.mc_ctx_destroy.argtypes = [vp]
         for f in (L.mc_group_numel, L.mc_group_k):
@@ -115,6 +123,28 @@ def mc_partition(numel: Sequence[int], y: int, policy: int = MC_PART_EVEN_ELEMS,
     out = (C.c_int32 * (max(y, 0) + 1))()
     _check(lib().mc_partition(nm, n, y, policy, ub, out), "mc_partition")
     return list(out)
+
+
+def mc_partition_cost(numel: Sequence[int], bwd_time: Sequence[float], model: McTimeModel, bounds: Sequence[int]) -> float:
+    """F(X_y) of the iteration-time model for a partition; host-only."""
+    n = len(numel)
+    nm = (C.c_int64 * max(n, 1))(*[int(x) for x in numel])
+    bw = (C.c_double * max(n, 1))(*[float(x) for x in bwd_time])
+    bd = (C.c_int32 * len(bounds))(*[int(b) for b in bounds])
+    F = C.c_double()
+    _check(lib().mc_partition_cost(nm, bw, n, C.byref(model), bd, len(bounds) - 1, C.byref(F)), "mc_partition_cost")
+    return F.value
+
+
+def mc_partition_search(numel: Sequence[int], bwd_time: Sequence[float], model: McTimeModel, Y: int, alpha: float):
+    """The paper's partition search: returns (boundaries of the partition chosen, its F); host-only."""
+    n = len(numel)
+    nm = (C.c_int64 * max(n, 1))(*[int(x) for x in numel])
+    bw = (C.c_double * max(n, 1))(*[float(x) for x in bwd_time])
+    out = (C.c_int32 * (max(min(Y, n), 1) + 1))()
+    y, F = C.c_int32(), C.c_double()
+    _check(lib().mc_partition_search(nm, bw, n, C.byref(model), Y, alpha, out, C.byref(y), C.byref(F)), "mc_partition_search")
+    return list(out)[:y.value + 1], F.value
 
 
 class Context:

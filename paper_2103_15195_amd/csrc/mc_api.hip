@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cstring>
 #include <new>
+#include <limits>
 #include <vector>
 
 #include "mc_internal.h"
@@ -177,6 +178,88 @@ int mc_partition(const int64_t *numel, int32_t n_tensors, int32_t y, int32_t pol
         while (t < N && prefix * (unsigned)y < D * (unsigned)j) prefix += (uint64_t)numel[t++];
         int32_t b = std::min(std::max(t, bounds_out[j - 1] + 1), N - (y - j));
         bounds_out[j] = b;
+    }
+    return MC_OK;
+}
+
+static bool valid_model(const mc_time_model *m)
+{
+    return m && m->fwd_time >= 0 && m->B_h >= 0 && m->gamma_h >= 0 && m->B_g >= 0 && m->gamma_g >= 0;
+}
+
+int mc_partition_cost(const int64_t *numel, const double *bwd_time, int32_t n_tensors, const mc_time_model *model,
+                      const int32_t *bounds, int32_t y, double *F_out)
+{
+    if (!numel || !bwd_time || !bounds || !F_out || !valid_model(model) || n_tensors < 1 || y < 1) return MC_ERR_INVALID_ARG;
+    if (y > n_tensors || bounds[0] != 0 || bounds[y] != n_tensors) return MC_ERR_RANGE;
+    for (int32_t j = 0; j < y; ++j) if (bounds[j + 1] <= bounds[j]) return MC_ERR_RANGE;
+    double gpu = model->fwd_time, net = 0.0;
+    for (int32_t j = 0; j < y; ++j) {
+        double x = 0.0;
+        for (int32_t t = bounds[j]; t < bounds[j + 1]; ++t) {
+            if (numel[t] < 0 || bwd_time[t] < 0) return MC_ERR_INVALID_ARG;
+            gpu += bwd_time[t];
+            x += (double)numel[t];
+        }
+        gpu += model->B_h + model->gamma_h * x;
+        net = std::max(gpu, net) + (model->B_g + model->gamma_g * x);
+    }
+    *F_out = net;
+    return MC_OK;
+}
+
+int mc_partition_search(const int64_t *numel, const double *bwd_time, int32_t n_tensors, const mc_time_model *model,
+                        int32_t Y, double alpha, int32_t *bounds_out, int32_t *y_out, double *F_out)
+{
+    if (!numel || !bwd_time || !bounds_out || !y_out || !valid_model(model) || n_tensors < 1 || Y < 1) return MC_ERR_INVALID_ARG;
+    if (!(alpha >= 0.0 && alpha < 1.0)) return MC_ERR_INVALID_ARG;
+    const int32_t N = n_tensors;
+    if (Y > N) Y = N;
+    try {
+        // prefix sums over tensors: elements and back-propagation time
+        std::vector<double> elems(N + 1, 0.0), bwd(N + 1, 0.0);
+        for (int32_t t = 0; t < N; ++t) {
+            if (numel[t] < 0 || bwd_time[t] < 0) return MC_ERR_INVALID_ARG;
+            elems[t + 1] = elems[t] + (double)numel[t];
+            bwd[t + 1] = bwd[t] + bwd_time[t];
+        }
+        // when the GPU has compressed the i-th group if that group ends before tensor e
+        auto gpu_done = [&](int32_t e, int32_t i) { return model->fwd_time + bwd[e] + i * model->B_h + model->gamma_h * elems[e]; };
+        auto send = [&](int32_t from, int32_t to) { return model->B_g + model->gamma_g * (elems[to] - elems[from]); };
+        // net[e]: earliest time the network is free after i groups that cover tensors [0, e); from[i][e]: where the
+        // last of them starts.  The time the network is free only ever delays what follows, so the earliest is best.
+        const double inf = std::numeric_limits<double>::infinity();
+        std::vector<double> net(N + 1, inf), next(N + 1, inf);
+        std::vector<std::vector<int32_t>> from(Y + 1, std::vector<int32_t>(N + 1, 0));
+        std::vector<int32_t> best_bounds, cur_bounds;
+        double F_prev = 0.0;
+        int32_t y_best = 1;
+        for (int32_t i = 1; i <= Y; ++i) {
+            std::fill(next.begin(), next.end(), inf);
+            for (int32_t e = i; e <= N - 0; ++e) {
+                if (i == 1) { next[e] = gpu_done(e, 1) + send(0, e); from[1][e] = 0; continue; }
+                for (int32_t s0 = i - 1; s0 < e; ++s0) {
+                    if (net[s0] == inf) continue;
+                    const double f = std::max(gpu_done(e, i), net[s0]) + send(s0, e);
+                    if (f < next[e]) { next[e] = f; from[i][e] = s0; }
+                }
+            }
+            net.swap(next);
+            const double F_now = net[N];
+            cur_bounds.assign(i + 1, 0);
+            cur_bounds[i] = N;
+            for (int32_t j = i, e = N; j >= 1; --j) { e = from[j][e]; cur_bounds[j - 1] = e; }
+            if (i == 1) { F_prev = F_now; best_bounds = cur_bounds; continue; }
+            if (F_prev < F_now) break;                               // more groups made it worse: keep y - 1
+            const bool stop = F_prev - F_now < alpha * F_prev;       // marginal benefit too small: keep y and stop
+            F_prev = F_now; best_bounds = cur_bounds; y_best = i;
+            if (stop) break;
+        }
+        for (int32_t j = 0; j <= y_best; ++j) bounds_out[j] = best_bounds[j];
+        *y_out = y_best;
+        if (F_out) *F_out = F_prev;
+    } catch (const std::bad_alloc &) {
+        return MC_ERR_ALLOC;
     }
     return MC_OK;
 }
