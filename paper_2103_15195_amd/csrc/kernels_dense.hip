@@ -74,13 +74,25 @@ static inline uint32_t tiles_of(uint32_t n) { return (uint32_t)(((uint64_t)n + k
 // Per-block partials: EF-Sign sum |p|; OneBit sum of the upper class, sum of the lower
 // class, size of the upper class (three arrays of gridDim.x doubles).
 // ---------------------------------------------------------------------------
+// header of a payload whose group scalar needs no reduction (written by one thread of the compress kernel itself)
+__device__ __forceinline__ void put_plain_header(PayloadHeader *hdr, uint32_t algo, uint32_t n, float scale)
+{
+    PayloadHeader h;
+    h.magic = kMagic; h.algo = algo; h.n = n; h.k = 0; h.scale = scale; h.levels = 0;
+    for (int i = 0; i < 8; ++i) h.pad[i] = 0;
+    *hdr = h;
+}
+
 template <int MODE, bool EF>
 __global__ __launch_bounds__(kBlock) void sign_compress_k(GroupView g, float *st, const StateHeader *prev, float beta,
-                                                          uint32_t *words, uint32_t nwords, double *partial)
+                                                          uint32_t *words, uint32_t nwords, double *partial,
+                                                          PayloadHeader *hdr, uint32_t algo)
 {
     __shared__ uint64_t stage[kWavesPerBlock][kSteps];
     __shared__ double red[kWavesPerBlock];
     const Chunk c = my_chunk(g.n);
+    // SignSGD, SigNUM: the decoded values are +-1, no finalize kernel follows
+    if ((MODE == SIGN_PLAIN || MODE == SIGN_MOMENTUM) && blockIdx.x == 0 && threadIdx.x == 0) put_plain_header(hdr, algo, g.n, 1.0f);
     double acc = 0.0, acc_lo = 0.0, cnt_hi = 0.0;
     if (c.base < g.n) {
         float p[kSteps];
@@ -138,25 +150,25 @@ __global__ __launch_bounds__(kBlock) void sign_compress_k(GroupView g, float *st
 }
 
 void launch_sign_compress(const LaunchCtx &lc, int mode, const GroupView &g, bool ef, float *state_f, const StateHeader *prev,
-                          float beta, uint32_t *words, uint32_t nwords, double *partial)
+                          float beta, uint32_t *words, uint32_t nwords, double *partial, PayloadHeader *hdr, uint32_t algo)
 {
     if (g.n == 0) return;
     dim3 grid(tiles_of(g.n)), block(kBlock);
     prof_begin(lc, K_EFSIGN_COMPRESS);
     switch (mode) {
     case SIGN_EF:
-        if (ef) MC_LAUNCH((sign_compress_k<SIGN_EF, true>), grid, block, lc, g, state_f, prev, beta, words, nwords, partial);
-        else MC_LAUNCH((sign_compress_k<SIGN_EF, false>), grid, block, lc, g, state_f, prev, beta, words, nwords, partial);
+        if (ef) MC_LAUNCH((sign_compress_k<SIGN_EF, true>), grid, block, lc, g, state_f, prev, beta, words, nwords, partial, hdr, algo);
+        else MC_LAUNCH((sign_compress_k<SIGN_EF, false>), grid, block, lc, g, state_f, prev, beta, words, nwords, partial, hdr, algo);
         break;
     case SIGN_MEANS:
-        if (ef) MC_LAUNCH((sign_compress_k<SIGN_MEANS, true>), grid, block, lc, g, state_f, prev, beta, words, nwords, partial);
-        else MC_LAUNCH((sign_compress_k<SIGN_MEANS, false>), grid, block, lc, g, state_f, prev, beta, words, nwords, partial);
+        if (ef) MC_LAUNCH((sign_compress_k<SIGN_MEANS, true>), grid, block, lc, g, state_f, prev, beta, words, nwords, partial, hdr, algo);
+        else MC_LAUNCH((sign_compress_k<SIGN_MEANS, false>), grid, block, lc, g, state_f, prev, beta, words, nwords, partial, hdr, algo);
         break;
     case SIGN_PLAIN:
-        MC_LAUNCH((sign_compress_k<SIGN_PLAIN, false>), grid, block, lc, g, state_f, prev, beta, words, nwords, partial);
+        MC_LAUNCH((sign_compress_k<SIGN_PLAIN, false>), grid, block, lc, g, state_f, prev, beta, words, nwords, partial, hdr, algo);
         break;
     default:
-        MC_LAUNCH((sign_compress_k<SIGN_MOMENTUM, true>), grid, block, lc, g, state_f, prev, beta, words, nwords, partial);
+        MC_LAUNCH((sign_compress_k<SIGN_MOMENTUM, true>), grid, block, lc, g, state_f, prev, beta, words, nwords, partial, hdr, algo);
         break;
     }
     prof_end(lc, K_EFSIGN_COMPRESS);
@@ -455,10 +467,11 @@ void launch_tern_encode(const LaunchCtx &lc, const GroupView &g, bool ef, float 
 // FP16, single pass: h = binary16(p) round-to-nearest-even, e <- p - (float)h.
 // ---------------------------------------------------------------------------
 template <bool EF>
-__global__ __launch_bounds__(kBlock) void fp16_compress_k(GroupView g, float *st, uint16_t *halves)
+__global__ __launch_bounds__(kBlock) void fp16_compress_k(GroupView g, float *st, uint16_t *halves, PayloadHeader *hdr)
 {
     __shared__ __attribute__((aligned(16))) uint16_t stage[kWavesPerBlock][kChunk];
     const Chunk c = my_chunk(g.n);
+    if (blockIdx.x == 0 && threadIdx.x == 0) put_plain_header(hdr, MC_ALGO_FP16, g.n, 0.0f);
     if (c.base >= g.n) return;
     float p[kSteps];
     load_seg(g, c, p);
@@ -483,12 +496,11 @@ __global__ __launch_bounds__(kBlock) void fp16_compress_k(GroupView g, float *st
 void launch_fp16_compress(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, PayloadHeader *hdr,
                           uint16_t *halves)
 {
-    (void)hdr;
     if (g.n == 0) return;
     dim3 grid(tiles_of(g.n)), block(kBlock);
     prof_begin(lc, K_FP16_COMPRESS);
-    if (ef) MC_LAUNCH(fp16_compress_k<true>, grid, block, lc, g, state_f, halves);
-    else MC_LAUNCH(fp16_compress_k<false>, grid, block, lc, g, state_f, halves);
+    if (ef) MC_LAUNCH(fp16_compress_k<true>, grid, block, lc, g, state_f, halves, hdr);
+    else MC_LAUNCH(fp16_compress_k<false>, grid, block, lc, g, state_f, halves, hdr);
     prof_end(lc, K_FP16_COMPRESS);
 }
 

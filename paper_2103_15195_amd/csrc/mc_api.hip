@@ -497,18 +497,17 @@ int mc_compress(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter, cons
     GroupView gv = group_view(ctx, lc, group, G, reinterpret_cast<const void *const *>(grad_ptrs));
     switch (cfg.algo) {
     case MC_ALGO_EFSIGN:
-        launch_sign_compress(lc, SIGN_EF, gv, ef, sf, sh, 0.0f, reinterpret_cast<uint32_t *>(body), nwords, ctx->d_partial);
+        launch_sign_compress(lc, SIGN_EF, gv, ef, sf, sh, 0.0f, reinterpret_cast<uint32_t *>(body), nwords, ctx->d_partial, hdr, MC_ALGO_EFSIGN);
         launch_scalar_finalize(lc, ctx->d_partial, tiles, RED_MEAN_ABS, n, hdr, MC_ALGO_EFSIGN, 0, 0, ef ? &sh->scale : nullptr);
         break;
     case MC_ALGO_ONEBIT:
-        launch_sign_compress(lc, SIGN_MEANS, gv, ef, sf, sh, 0.0f, reinterpret_cast<uint32_t *>(body), nwords, ctx->d_partial);
+        launch_sign_compress(lc, SIGN_MEANS, gv, ef, sf, sh, 0.0f, reinterpret_cast<uint32_t *>(body), nwords, ctx->d_partial, hdr, MC_ALGO_ONEBIT);
         launch_scalar_finalize(lc, ctx->d_partial, tiles, RED_MEANS, n, hdr, MC_ALGO_ONEBIT, 0, 0, ef ? &sh->scale : nullptr);
         break;
     case MC_ALGO_SIGNSGD:
     case MC_ALGO_SIGNUM:
         launch_sign_compress(lc, cfg.algo == MC_ALGO_SIGNSGD ? SIGN_PLAIN : SIGN_MOMENTUM, gv, ef, sf, sh, cfg.dgc_momentum,
-                             reinterpret_cast<uint32_t *>(body), nwords, ctx->d_partial);
-        launch_scalar_finalize(lc, ctx->d_partial, 0, RED_ONE, n, hdr, (uint32_t)cfg.algo, 0, 0, nullptr);
+                             reinterpret_cast<uint32_t *>(body), nwords, ctx->d_partial, hdr, (uint32_t)cfg.algo);
         break;
     case MC_ALGO_QSGD:
         launch_accum_reduce(lc, gv, ef, sf, RED_L2, ctx->d_partial);
@@ -521,7 +520,6 @@ int mc_compress(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter, cons
         launch_tern_encode(lc, gv, ef, sf, hdr, reinterpret_cast<uint32_t *>(body), nwords, cfg.seed, worker, (uint32_t)iter);
         break;
     case MC_ALGO_FP16:
-        launch_scalar_finalize(lc, ctx->d_partial, 0, -1, n, hdr, MC_ALGO_FP16, 0, 0, nullptr);
         launch_fp16_compress(lc, gv, ef, sf, hdr, reinterpret_cast<uint16_t *>(body));
         break;
     case MC_ALGO_TOPK:

@@ -71,7 +71,7 @@ void prof_end(const LaunchCtx &lc, int id);
 void launch_upload_ptrs(const LaunchCtx &lc, const uintptr_t *host, uintptr_t *dev, uint32_t count);
 void launch_expand_ptrs(const LaunchCtx &lc, const GroupView &g, uintptr_t *chunk_addr);
 void launch_sign_compress(const LaunchCtx &lc, int mode, const GroupView &g, bool ef, float *state_f, const StateHeader *prev,
-                          float beta, uint32_t *words, uint32_t nwords, double *partial);
+                          float beta, uint32_t *words, uint32_t nwords, double *partial, PayloadHeader *hdr, uint32_t algo);
 void launch_scalar_finalize(const LaunchCtx &lc, const double *partial, uint32_t nblocks, int mode, uint32_t n,
                             PayloadHeader *hdr, uint32_t algo, uint64_t k, uint32_t levels, float *state_scale);
 void launch_accum_reduce(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, int mode, double *partial);
