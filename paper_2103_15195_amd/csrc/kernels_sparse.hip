@@ -7,20 +7,20 @@
 // The paper singles out the top-k() operation as the cost that merging alone
 // does not remove (Section 5.1).  Here the selection is a radix select on the
 // 31-bit magnitude key that never sorts and, in the steady state, touches the
-// gradient once and resolves 21 of the 31 bits inside that one pass:
+// gradient once and resolves 20 of the 31 bits inside that one pass:
 //
 //   accumulate   p = g + e (DGC: u = m u + g, v = v + u) streamed once; every element
 //                whose key reaches a *hint* (a little below the last threshold of this
 //                group) is copied, in index order, into the candidate slots of its
 //                1024-element chunk, and counted in a *window* histogram: 2048 bins of
-//                1024 keys each, starting at the hint (the last bin also takes all above)
+//                2048 keys each, starting at the hint (the last bin also takes all above)
 //   seed         reads the window.  Usual case: the k-th largest key falls in one of its
-//                bins, which leaves 10 bits to resolve (fast mode).  Otherwise all blocks
+//                bins, which leaves 11 bits to resolve (fast mode).  Otherwise all blocks
 //                build a level-1 histogram (top 11 bits of key - lo) of the candidates
 //                above the window, or, if the hint left fewer than k candidates (first
 //                call, or the distribution moved down), of every element (refill)
 //   hist 2       only after a seed that was not fast: bits 19..10 of key - lo
-//   hist 3       the last 10 bits
+//   hist 3       the bits still open (11 after a fast seed, else 10)
 //   count        resolves level 3 (threshold key T, number of keys == T to take),
 //                counts kept candidates per tile, publishes the next hint
 //   emit         ordered compaction of the kept candidates into (idx, val); kept
@@ -40,8 +40,8 @@ namespace mc {
 static inline uint32_t tiles_of(uint32_t n) { return (uint32_t)(((uint64_t)n + kTile - 1) / kTile); }
 static inline uint32_t chunks_of(uint32_t n) { return (uint32_t)(((uint64_t)n + kChunk - 1) / kChunk); }
 
-constexpr int kBinsW = 2048, kBins1 = 2048, kBins2 = 1024, kBins3 = 1024;
-constexpr int kWindowShift = 10;                       // keys per window bin = 2^10: what hist 3 resolves
+constexpr int kWindowShift = 11;                       // keys per window bin = 2^11: what hist 3 resolves after a fast seed
+constexpr int kBinsW = 2048, kBins1 = 2048, kBins2 = 1024, kBins3 = 1 << kWindowShift;
 // Histogram scratch: the window and the three radix levels one after the other.  Global
 // atomics on one address serialise (tens of nanoseconds each on this part), so only
 // the bins themselves are updated -- no shared summary counters -- and a level is
@@ -49,7 +49,8 @@ constexpr int kWindowShift = 10;                       // keys per window bin = 
 constexpr int kHistW = 0, kHist1 = kHistW + kBinsW, kHist2 = kHist1 + kBins1, kHist3 = kHist2 + kBins2;
 static_assert(kHist3 + kBins3 == kHistWords, "histogram scratch layout");
 constexpr uint32_t kHintMargin = 3u << 19;   // 3/16 of an octave below the last threshold
-// the window spans 2^21 keys (a quarter octave), the last threshold sits 3/8 of the way up
+// The window spans 2^22 keys (half an octave) from the hint upward: it holds the new threshold if that
+// lies between 12 % below and 24 % above the last one (2^23 keys are one octave of magnitude).
 
 // seed result (SelectState::mode)
 constexpr uint32_t kModeFast = 1u;      // lo / need are those of level 3 already
@@ -388,7 +389,8 @@ __global__ __launch_bounds__(kSeedThreads) void sparse_seed_k(GroupView g, const
 template <int LEVEL>
 __global__ __launch_bounds__(kBlock) void cand_hist_k(uint32_t n, uint32_t ntiles, SparseScratch sc)
 {
-    __shared__ uint32_t hist[1024];
+    constexpr int kBins = LEVEL == 2 ? kBins2 : kBins3;
+    __shared__ uint32_t hist[kBins];
     const SelectState s0 = sc.sel[0];
     if (LEVEL == 2) {
         if (blockIdx.x == 0)                // the seed is done with the window
@@ -397,7 +399,7 @@ __global__ __launch_bounds__(kBlock) void cand_hist_k(uint32_t n, uint32_t ntile
     }
     const bool uniform = (s0.mode & kModeUniform) != 0u;
     TileJob job = my_tile(sc, n, ntiles);
-    for (int b = threadIdx.x; b < 1024; b += kBlock) hist[b] = 0u;
+    for (int b = threadIdx.x; b < kBins; b += kBlock) hist[b] = 0u;
     uint32_t lo;
     uint64_t need;
     if (LEVEL == 2) {
@@ -428,14 +430,15 @@ __global__ __launch_bounds__(kBlock) void cand_hist_k(uint32_t n, uint32_t ntile
     }
     __syncthreads();
     if (uniform) job.runs = job.tile < ntiles ? uniform_runs(job.tile, n) : 0ull;
-    constexpr uint32_t kRange = LEVEL == 2 ? 1u << 20 : 1u << 10;
+    // keys still undecided: level 2 leaves 2^10 to level 3; a fast seed leaves a whole window bin
+    const uint32_t kRange = LEVEL == 2 ? 1u << 20 : (s0.mode & kModeFast) ? 1u << kWindowShift : 1u << 10;
     constexpr int kShift = LEVEL == 2 ? 10 : 0;
     uint32_t any = 0;
     tile_walk<false>(sc, job.tile, job.runs, [&](bool valid, uint32_t, uint32_t bits, uint32_t) {
         const uint32_t d = (bits & 0x7FFFFFFFu) - lo;       // wraps to a large number for keys below lo
         if (valid && d < kRange) { atomicAdd(&hist[d >> kShift], 1u); any = 1u; }
     });
-    if (__syncthreads_or((int)any)) flush_fine(hist, sc.hist + (LEVEL == 2 ? kHist2 : kHist3), 1024);
+    if (__syncthreads_or((int)any)) flush_fine(hist, sc.hist + (LEVEL == 2 ? kHist2 : kHist3), kBins);
 }
 
 // ---------------------------------------------------------------------------
@@ -445,11 +448,20 @@ __global__ __launch_bounds__(kBlock) void cand_hist_k(uint32_t n, uint32_t ntile
 __global__ __launch_bounds__(kBlock) void cand_count_k(uint32_t n, uint32_t ntiles, SparseScratch sc)
 {
     __shared__ uint32_t wgt[kWavesPerBlock], weq[kWavesPerBlock];
+    __shared__ uint32_t res[3];
     TileJob job = my_tile(sc, n, ntiles);
     const SelectState s2 = sc.sel[2];
-    uint32_t bin;
-    uint64_t rest;
-    resolve_wave<kBins3>(sc.hist + kHist3, s2.need, bin, rest);
+    // one wavefront reads the bins for the block: every wavefront doing so would move the histogram
+    // once per tile of the group
+    if (threadIdx.x < 64) {
+        uint32_t b;
+        uint64_t r;
+        resolve_wave<kBins3>(sc.hist + kHist3, s2.need, b, r);
+        if (threadIdx.x == 0) { res[0] = b; res[1] = (uint32_t)r; res[2] = (uint32_t)(r >> 32); }
+    }
+    __syncthreads();
+    const uint32_t bin = res[0];
+    const uint64_t rest = (uint64_t)res[1] | ((uint64_t)res[2] << 32);
     const uint32_t T = s2.lo + bin;
     if (blockIdx.x == 0) {
         if (threadIdx.x == 0) {

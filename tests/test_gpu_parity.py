@@ -269,7 +269,7 @@ def test_profile_hooks_count_launches():
 @pytest.mark.parametrize("algo", ["topk", "dgc"])
 def test_selection_routes_are_all_taken_and_exact(algo):
     """The exact selection has three routes: the threshold key T falls inside the histogram window that the
-    library keeps from (last T - 3/16 octave) upward over 2047 bins of 1024 keys; above it; or below its start
+    library keeps from (last T - 3/16 octave) upward over 2047 bins of 2048 keys; above it; or below its start
     (too few candidates -> second streaming pass).  Drive one (group, worker) through all three by scaling the
     gradients; the route expected follows from the oracle's thresholds; every payload and residual is compared."""
     n, tensors = 300000, [120000, 7, 179993]
@@ -291,7 +291,7 @@ def test_selection_routes_are_all_taken_and_exact(algo):
         got = ctx.mc_last_select_route()
         op, _ = O.compress(ocfg, g, ost, group_off=0, worker=5, it=it)
         T = int((op[64 + 4 * k:].view(np.uint32) & 0x7FFFFFFF).min())          # k-th largest key
-        want = B.MC_SELECT_REFILL if T < hint else B.MC_SELECT_FAST if T - hint < 2047 * 1024 else B.MC_SELECT_ABOVE
+        want = B.MC_SELECT_REFILL if T < hint else B.MC_SELECT_FAST if T - hint < 2047 * 2048 else B.MC_SELECT_ABOVE
         assert got == want, f"call {it}: route {got}, expected {want} (T {T:#x}, hint {hint:#x})"
         hint = T - (3 << 19) if T > (3 << 19) else 0
         seen.append(got)
