@@ -51,6 +51,7 @@ typedef struct {
     uint32_t ratio_ppm;    /* kept fraction of sparsifiers, parts per million */
     int32_t qsgd_bits;     /* code width incl. sign; levels s = 2^(bits-1) - 1 */
     float dgc_momentum;    /* m of DGC's momentum correction; beta of SigNUM */
+    uint32_t sample_ppm;   /* DGC only: 0 = exact top-k; else the threshold is taken from a sample of this rate */
     uint64_t seed;         /* Philox key */
 } orc_config;
 
@@ -227,6 +228,15 @@ int64_t orc_topk_count(int64_t n, uint32_t ppm)
     return k;
 }
 
+/* entries a sparse payload has room for: k, or twice k (at most n) when DGC estimates its threshold
+ * from a sample and the number of kept entries varies from call to call */
+int64_t orc_sparse_capacity(const orc_config *c, int64_t n)
+{
+    int64_t k = orc_topk_count(n, c->ratio_ppm);
+    if (c->algo == ALG_DGC && c->sample_ppm) { k *= 2; if (k > n) k = n; }
+    return k;
+}
+
 static int64_t words32(int64_t n) { return (n + 31) / 32; }
 static int64_t pad4(int64_t b) { return (b + 3) / 4 * 4; }
 
@@ -242,7 +252,7 @@ int64_t orc_payload_bytes(const orc_config *c, int64_t n)
     case ALG_FP16:     return HDR_BYTES + pad4(2 * n);
     case ALG_TOPK:
     case ALG_DGC:
-    case ALG_RANDK:    return HDR_BYTES + 8 * orc_topk_count(n, c->ratio_ppm);
+    case ALG_RANDK:    return HDR_BYTES + 8 * orc_sparse_capacity(c, n);
     }
     return -1;
 }
@@ -459,6 +469,58 @@ int orc_compress(const orc_config *c, int64_t n, uint64_t group_off, uint32_t wo
     case ALG_TOPK:
     case ALG_DGC:
     case ALG_RANDK: {
+        if (c->algo == ALG_DGC && c->sample_ppm) {
+            /* DGC's cheaper selection: instead of the exact top-k of all n values, take the threshold
+             * that keeps the given ratio of a SAMPLE and send everything that reaches it.
+             *   sample      every stride-th element, stride = floor(1e6 / sample_ppm), starting at a
+             *               Philox-drawn offset (the word of the group's first element, see orc_uniform)
+             *   threshold   the ks-th largest key of the sample, ks = max(1, floor(m ratio)), m = sample size
+             *   kept        keys above the threshold, then keys equal to it, each in index order, until the
+             *               payload's capacity cap = min(n, 2k) is reached; the header's k is the count kept and
+             *               its levels field names the capacity (the values start after cap indices)
+             * unused payload entries stay zero; kept entries leave both accumulators. */
+            const int64_t cap = orc_sparse_capacity(c, n);
+            uint32_t stride = 1000000u / c->sample_ppm; if (stride < 1) stride = 1;
+            uint64_t J = group_off >> 2;
+            uint32_t ctr[4] = { (uint32_t)J, (uint32_t)(J >> 32), worker, (uint32_t)iter };
+            uint32_t key2[2] = { (uint32_t)c->seed, (uint32_t)(c->seed >> 32) }, r[4];
+            orc_philox4x32_10(ctr, key2, r);
+            const uint32_t first = r[group_off & 3u] % stride;
+            int64_t m = 0;
+            for (int64_t i = first; i < n; i += stride) ++m;
+            uint32_t thr = 0;                                   /* empty sample: everything reaches the threshold */
+            if (m > 0) {
+                keyidx *smp = (keyidx *)malloc((size_t)m * sizeof(keyidx));
+                if (!smp) { rc = -3; break; }
+                int64_t j = 0;
+                for (int64_t i = first; i < n; i += stride, ++j) {
+                    uint32_t bb; memcpy(&bb, &p[i], 4);
+                    smp[j].key = bb & 0x7FFFFFFFu; smp[j].idx = (uint32_t)i;
+                }
+                qsort(smp, (size_t)m, sizeof(keyidx), cmp_key_desc_idx_asc);
+                int64_t ks = (int64_t)(((__int128)m * c->ratio_ppm) / 1000000);
+                if (ks < 1) ks = 1;
+                thr = smp[ks - 1].key;
+                free(smp);
+            }
+            uint32_t *idx = (uint32_t *)(payload + HDR_BYTES);
+            float *val = (float *)(payload + HDR_BYTES + 4 * cap);
+            uint8_t *sel = (uint8_t *)calloc((size_t)(n > 0 ? n : 1), 1);
+            if (!sel) { rc = -3; break; }
+            int64_t kept = 0;
+            for (int pass = 0; pass < 2; ++pass)                /* above the threshold first, then equal to it */
+                for (int64_t i = 0; i < n && kept < cap; ++i) {
+                    uint32_t bb; memcpy(&bb, &p[i], 4); bb &= 0x7FFFFFFFu;
+                    if (pass == 0 ? bb > thr : bb == thr) { sel[i] = 1; ++kept; }
+                }
+            put_header(payload, c->algo, n, kept, 0.0f, (uint32_t)cap);   /* the capacity travels in the header */
+            int64_t j = 0;
+            float *v = state, *u = state + n;
+            for (int64_t i = 0; i < n; ++i)
+                if (sel[i]) { idx[j] = (uint32_t)i; val[j] = p[i]; ++j; v[i] = 0.0f; u[i] = 0.0f; }
+            free(sel);
+            break;
+        }
         int64_t k = orc_topk_count(n, c->ratio_ppm);
         uint8_t *sel = (uint8_t *)malloc((size_t)(n > 0 ? n : 1));
         if (!sel) { rc = -3; break; }
@@ -592,7 +654,8 @@ int orc_decode(const uint8_t *payload, int64_t n, float *d)
     case ALG_DGC:
     case ALG_RANDK: {
         const uint32_t *idx = (const uint32_t *)body;
-        const float *val = (const float *)(body + 4 * k);
+        /* values follow the index array, whose length is k, or the capacity named in the header (sampled DGC) */
+        const float *val = (const float *)(body + 4 * (levels ? (uint64_t)levels : k));
         for (int64_t i = 0; i < n; ++i) d[i] = 0.0f;
         for (uint64_t j = 0; j < k; ++j) { if (idx[j] >= (uint64_t)n) return -5; d[idx[j]] = val[j]; }
         break;

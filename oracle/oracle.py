@@ -38,7 +38,7 @@ def build(force: bool = False) -> str:
 
 class _Cfg(C.Structure):
     _fields_ = [("algo", C.c_int32), ("use_ef", C.c_int32), ("ratio_ppm", C.c_uint32),
-                ("qsgd_bits", C.c_int32), ("dgc_momentum", C.c_float), ("seed", C.c_uint64)]
+                ("qsgd_bits", C.c_int32), ("dgc_momentum", C.c_float), ("sample_ppm", C.c_uint32), ("seed", C.c_uint64)]
 
 
 @dataclass
@@ -49,9 +49,10 @@ class Config:
     qsgd_bits: int = 8
     dgc_momentum: float = 0.9
     seed: int = 0
+    dgc_sample_ppm: int = 0
 
     def c(self) -> _Cfg:
-        return _Cfg(self.algo, self.use_ef, self.ratio_ppm, self.qsgd_bits, self.dgc_momentum, self.seed)
+        return _Cfg(self.algo, self.use_ef, self.ratio_ppm, self.qsgd_bits, self.dgc_momentum, self.dgc_sample_ppm, self.seed)
 
 
 _lib = None
@@ -77,6 +78,8 @@ def lib():
                                            C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_double)]
         L.orc_topk_count.argtypes = [C.c_int64, C.c_uint32]
         L.orc_topk_count.restype = C.c_int64
+        L.orc_sparse_capacity.argtypes = [C.POINTER(_Cfg), C.c_int64]
+        L.orc_sparse_capacity.restype = C.c_int64
         L.orc_payload_bytes.argtypes = [C.POINTER(_Cfg), C.c_int64]
         L.orc_payload_bytes.restype = C.c_int64
         L.orc_state_floats.argtypes = [C.POINTER(_Cfg), C.c_int64]
@@ -187,6 +190,11 @@ def topk_count(n: int, ppm: int) -> int:
     return int(lib().orc_topk_count(n, ppm))
 
 
+def sparse_capacity(cfg: Config, n: int) -> int:
+    c = cfg.c()
+    return int(lib().orc_sparse_capacity(C.byref(c), n))
+
+
 def payload_bytes(cfg: Config, n: int) -> int:
     c = cfg.c()
     return int(lib().orc_payload_bytes(C.byref(c), n))
@@ -268,7 +276,9 @@ def header(payload: np.ndarray) -> dict:
 
 
 def sparse_view(payload: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
-    k = header(payload)["k"]
+    """(indices, values) of the kept entries; a payload with a capacity (sampled DGC) holds k <= capacity of them."""
+    h = header(payload)
+    k, cap = h["k"], h["levels"] or h["k"]
     idx = payload[HDR:HDR + 4 * k].view(np.uint32)
-    val = payload[HDR + 4 * k:HDR + 8 * k].view(np.float32)
+    val = payload[HDR + 4 * cap:HDR + 4 * cap + 4 * k].view(np.float32)
     return idx, val
