@@ -47,6 +47,8 @@ CALL_BYTES = {
     # the four further schemes of the paper's Table 1 (Rand-k 1 %)
     "signsgd": (4.125, lambda W: W / 8.0 + 4.0), "signum": (12.125, lambda W: W / 8.0 + 4.0),
     "onebit": (12.125, lambda W: W / 8.0 + 4.0), "randk": (12.08, lambda W: 4.0 + 0.08 * W),
+    # DGC 0.1 % with the threshold taken from a 1 % sample (about k entries kept, room for 2k)
+    "dgc-sampled": (20.008, lambda W: 4.0 + 0.008 * W),
 }
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None = not measured
@@ -82,9 +84,10 @@ class AlgoBench:
 
     def __init__(self, B, torch, name, numel, y, W, grads):
         self.name, self.W, self.y = name, W, y
-        ratio_ppm = 1000 if name == "dgc" else 10000          # the configuration's ratios: Top-k 1 %, DGC 0.1 %
+        ratio_ppm = 1000 if name.startswith("dgc") else 10000          # the configuration's ratios: Top-k 1 %, DGC 0.1 %
         self.bounds = B.mc_partition(numel, y, B.MC_PART_EVEN_ELEMS)
-        self.ctx = B.Context(name, numel, self.bounds, ratio_ppm=ratio_ppm, seed=1)
+        self.ctx = B.Context(name.split("-")[0], numel, self.bounds, ratio_ppm=ratio_ppm, seed=1,
+                             dgc_sample_ppm=10000 if name == "dgc-sampled" else 0)
         dev = "cuda:0"
         self.grads = grads
         self.state = [[torch.zeros(self.ctx.state_bytes(j), dtype=torch.uint8, device=dev) for j in range(y)] for _ in range(W)]
@@ -261,7 +264,8 @@ def main():
         from oracle import oracle as O
         t_cpu = 0.0
         for a in algos:
-            ocfg = O.Config(B.ALGO_IDS[a], ratio_ppm=1000 if a == "dgc" else 10000, seed=1, use_ef=0 if a == "signsgd" else 1)
+            ocfg = O.Config(B.ALGO_IDS[a.split("-")[0]], ratio_ppm=1000 if a.startswith("dgc") else 10000, seed=1,
+                            use_ef=0 if a == "signsgd" else 1, dgc_sample_ppm=10000 if a == "dgc-sampled" else 0)
             st = O.new_state(ocfg, D)
             t0 = time.perf_counter()
             pay, _ = O.compress(ocfg, flats[0], st)

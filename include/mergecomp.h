@@ -35,7 +35,7 @@
  *   byte 16  uint64  k, kept entries (sparsifiers; 0 otherwise)
  *   byte 24  float   group scalar: EF-Sign scale, QSGD norm, TernGrad max, OneBit mean of the
  *                    non-negative class, SignSGD / SigNUM 1.0 (0 otherwise)
- *   byte 28  uint32  QSGD levels s (0 otherwise)
+ *   byte 28  uint32  QSGD levels s; DGC with a sampled threshold: capacity c of the entry arrays (0 otherwise)
  *   byte 32  float   OneBit mean of the negative class (0 otherwise)
  *   byte 36..63      zero
  *   byte 64  body:
@@ -46,6 +46,7 @@
  *     FP16      n binary16, zero-padded to a multiple of 4 bytes
  *     Top-k, DGC, Rand-k
  *               idx[k] uint32 ascending group-relative indices, then val[k] float
+ *               (DGC with a sampled threshold: idx[c] then val[c], the first k of each in use, the rest zero)
  *   Payload buffers must be 16-byte aligned.
  */
 #ifndef MERGECOMP_H
@@ -99,7 +100,9 @@ typedef struct {
     uint32_t ratio_ppm;  /* sparsifiers: kept fraction in parts per million (Section 5: 10000)   */
     int32_t qsgd_bits;   /* QSGD code width incl. sign, 2..8; levels s = 2^(bits-1) - 1          */
     float dgc_momentum;  /* DGC momentum m; SigNUM beta                                          */
-    uint32_t reserved;   /* must be 0                                                            */
+    uint32_t dgc_sample_ppm; /* DGC only (else 0): 0 = exact top-k.  Otherwise the threshold is the one that keeps
+                            ratio_ppm of a SAMPLE of this rate (every floor(1e6/rate)-th element from a Philox-drawn
+                            start), everything reaching it is sent, and the payload has room for 2k entries   */
     uint64_t seed;       /* Philox key of the stochastic quantizers and of Rand-k                */
 } mc_config;
 

@@ -32,7 +32,7 @@ EXPORTS = [
 
 class McConfig(C.Structure):
     _fields_ = [("algo", C.c_int32), ("use_ef", C.c_int32), ("ratio_ppm", C.c_uint32), ("qsgd_bits", C.c_int32),
-                ("dgc_momentum", C.c_float), ("reserved", C.c_uint32), ("seed", C.c_uint64)]
+                ("dgc_momentum", C.c_float), ("dgc_sample_ppm", C.c_uint32), ("seed", C.c_uint64)]
 
 
 class McTimeModel(C.Structure):
@@ -151,7 +151,8 @@ class Context:
     """One (config, tensor list, partition) on the current device: wraps mc_ctx."""
 
     def __init__(self, algo, numel: Sequence[int], bounds: Sequence[int], *, use_ef: Optional[int] = None,
-                 ratio_ppm: int = 10000, qsgd_bits: int = 8, dgc_momentum: float = 0.9, seed: int = 0):
+                 ratio_ppm: int = 10000, qsgd_bits: int = 8, dgc_momentum: float = 0.9, seed: int = 0,
+                 dgc_sample_ppm: int = 0):
         algo = ALGO_IDS.get(algo, algo)
         if use_ef is None:                       # SignSGD remembers nothing; everything else defaults to error feedback
             use_ef = 0 if algo == MC_ALGO_SIGNSGD else 1
@@ -159,7 +160,7 @@ class Context:
         self.numel = [int(x) for x in numel]
         self.bounds = [int(b) for b in bounds]
         self.y = len(self.bounds) - 1
-        self.cfg = McConfig(self.algo, use_ef, ratio_ppm, qsgd_bits, dgc_momentum, 0, seed)
+        self.cfg = McConfig(self.algo, use_ef, ratio_ppm, qsgd_bits, dgc_momentum, dgc_sample_ppm, seed)
         nm = (C.c_int64 * max(len(self.numel), 1))(*self.numel)
         bd = (C.c_int32 * len(self.bounds))(*self.bounds)
         self._h = C.c_void_p()

@@ -67,11 +67,27 @@ __device__ __forceinline__ void flush_fine(const uint32_t *lds, uint32_t *fine, 
     }
 }
 
+// key of the stochastic choices: Philox key and the worker / iteration words of the counter
+struct RngKey { uint64_t seed; uint32_t worker, iter_lo; };
+
+// DGC with a sampled threshold: the histograms that find the threshold count only the sample, every
+// stride-th element of the group starting at `first` (drawn by the host with Philox).  stride = 0: off.
+struct SampleRule { uint32_t stride, first, inv /* floor(2^32 / stride) */; };
+
+__device__ __forceinline__ bool in_sample(const SampleRule &r, uint32_t i)
+{
+    if (r.stride <= 1u) return true;
+    uint32_t rem = i - __umulhi(i, r.inv) * r.stride;      // the quotient estimate is at most 1 too small
+    if (rem >= r.stride) rem -= r.stride;
+    return rem == r.first;
+}
+
 // Copy the flagged elements of a chunk, in index order, into the chunk's candidate slots.
 // bits: what the later kernels see of the element (its key is bits & 0x7FFFFFFF): the value itself, or
 // for Rand-k the random key.
 __device__ __forceinline__ uint32_t put_candidates(const Chunk &c, const uint32_t (&bits)[kSteps], const uint64_t (&flag)[kSteps],
-                                                   uint32_t hint, uint32_t *cand_bits, uint16_t *cand_loc, uint32_t *hist /* LDS */)
+                                                   uint32_t hint, uint32_t *cand_bits, uint16_t *cand_loc, uint32_t *hist /* LDS */,
+                                                   const SampleRule &smp)
 {
     uint32_t run = 0;
     const uint64_t me = 1ull << c.lane;
@@ -82,21 +98,20 @@ __device__ __forceinline__ uint32_t put_candidates(const Chunk &c, const uint32_
             cand_bits[slot] = bits[j];
             cand_loc[slot] = (uint16_t)(64 * j + c.lane);
             const uint32_t bin = ((bits[j] & 0x7FFFFFFFu) - hint) >> kWindowShift;
-            atomicAdd(&hist[bin < (uint32_t)kBinsW - 1u ? bin : (uint32_t)kBinsW - 1u], 1u);
+            if (in_sample(smp, c.base + 64 * j + c.lane))
+                atomicAdd(&hist[bin < (uint32_t)kBinsW - 1u ? bin : (uint32_t)kBinsW - 1u], 1u);
         }
         run += __popcll(flag[j]);
     }
     return run;
 }
 
-// key of the stochastic choices: Philox key and the worker / iteration words of the counter
-struct RngKey { uint64_t seed; uint32_t worker, iter_lo; };
-
 // ---------------------------------------------------------------------------
 // accumulate + candidate filter + window histogram of the candidates
 // ---------------------------------------------------------------------------
 template <int ALGO, bool EF>
-__global__ __launch_bounds__(kBlock) void sparse_accum_k(GroupView g, float *st, float momentum, SparseScratch sc, RngKey rng)
+__global__ __launch_bounds__(kBlock) void sparse_accum_k(GroupView g, float *st, float momentum, SparseScratch sc, RngKey rng,
+                                                         SampleRule smp)
 {
     __shared__ uint32_t hist[kBinsW];
     __shared__ uint32_t wcnt[kWavesPerBlock];
@@ -148,7 +163,7 @@ __global__ __launch_bounds__(kBlock) void sparse_accum_k(GroupView g, float *st,
             bool valid = c.full || c.base + 64 * j + c.lane < g.n;
             flag[j] = __builtin_amdgcn_ballot_w64(valid && (bits[j] & 0x7FFFFFFFu) >= hint);
         }
-        run = put_candidates(c, bits, flag, hint, sc.cand_bits, sc.cand_loc, hist);
+        run = put_candidates(c, bits, flag, hint, sc.cand_bits, sc.cand_loc, hist, smp);
     }
     if (c.lane == 0) wcnt[threadIdx.x >> 6] = run;
     __syncthreads();
@@ -296,7 +311,8 @@ __device__ __forceinline__ TileJob my_tile(const SparseScratch &sc, uint32_t n, 
 constexpr int kSeedThreads = 1024;
 
 template <bool FROM_STATE, bool RANDOM>
-__global__ __launch_bounds__(kSeedThreads) void sparse_seed_k(GroupView g, const float *st, uint64_t k, SparseScratch sc, RngKey rng)
+__global__ __launch_bounds__(kSeedThreads) void sparse_seed_k(GroupView g, const float *st, uint64_t k, SparseScratch sc, RngKey rng,
+                                                              SampleRule smp)
 {
     __shared__ uint32_t hist[kBins1];
     __shared__ uint32_t verdict[4];              // found, bin, rest lo, rest hi
@@ -326,9 +342,9 @@ __global__ __launch_bounds__(kSeedThreads) void sparse_seed_k(GroupView g, const
         // ---- above the window
         const uint32_t lo = hint + (((uint32_t)kBinsW - 1u) << kWindowShift);
         for (uint32_t tile = blockIdx.x * waves + uwave; tile < ntiles; tile += gridDim.x * waves) {
-            tile_walk<false>(sc, tile, sc.tile_runs[tile], [&](bool valid, uint32_t, uint32_t bits, uint32_t) {
+            tile_walk<true>(sc, tile, sc.tile_runs[tile], [&](bool valid, uint32_t chunk, uint32_t bits, uint32_t loc) {
                 const uint32_t key = bits & 0x7FFFFFFFu;
-                if (valid && key >= lo) atomicAdd(&hist[(key - lo) >> 20], 1u);
+                if (valid && key >= lo && in_sample(smp, chunk * (uint32_t)kChunk + loc)) atomicAdd(&hist[(key - lo) >> 20], 1u);
             });
         }
         __syncthreads();
@@ -364,7 +380,7 @@ __global__ __launch_bounds__(kSeedThreads) void sparse_seed_k(GroupView g, const
             if (c.full || i < g.n) {
                 sc.cand_bits[i] = bits[j];
                 sc.cand_loc[i] = (uint16_t)(64 * j + c.lane);
-                atomicAdd(&hist[(bits[j] & 0x7FFFFFFFu) >> 20], 1u);
+                if (in_sample(smp, i)) atomicAdd(&hist[(bits[j] & 0x7FFFFFFFu) >> 20], 1u);
             }
         }
     }
@@ -387,7 +403,7 @@ __global__ __launch_bounds__(kSeedThreads) void sparse_seed_k(GroupView g, const
 // that the previous kernel has finished reading.
 // ---------------------------------------------------------------------------
 template <int LEVEL>
-__global__ __launch_bounds__(kBlock) void cand_hist_k(uint32_t n, uint32_t ntiles, SparseScratch sc)
+__global__ __launch_bounds__(kBlock) void cand_hist_k(uint32_t n, uint32_t ntiles, SparseScratch sc, SampleRule smp)
 {
     constexpr int kBins = LEVEL == 2 ? kBins2 : kBins3;
     __shared__ uint32_t hist[kBins];
@@ -434,9 +450,9 @@ __global__ __launch_bounds__(kBlock) void cand_hist_k(uint32_t n, uint32_t ntile
     const uint32_t kRange = LEVEL == 2 ? 1u << 20 : (s0.mode & kModeFast) ? 1u << kWindowShift : 1u << 10;
     constexpr int kShift = LEVEL == 2 ? 10 : 0;
     uint32_t any = 0;
-    tile_walk<false>(sc, job.tile, job.runs, [&](bool valid, uint32_t, uint32_t bits, uint32_t) {
+    tile_walk<true>(sc, job.tile, job.runs, [&](bool valid, uint32_t chunk, uint32_t bits, uint32_t loc) {
         const uint32_t d = (bits & 0x7FFFFFFFu) - lo;       // wraps to a large number for keys below lo
-        if (valid && d < kRange) { atomicAdd(&hist[d >> kShift], 1u); any = 1u; }
+        if (valid && d < kRange && in_sample(smp, chunk * (uint32_t)kChunk + loc)) { atomicAdd(&hist[d >> kShift], 1u); any = 1u; }
     });
     if (__syncthreads_or((int)any)) flush_fine(hist, sc.hist + (LEVEL == 2 ? kHist2 : kHist3), kBins);
 }
@@ -495,15 +511,18 @@ __global__ __launch_bounds__(kBlock) void cand_count_k(uint32_t n, uint32_t ntil
 //   (#kept before it) = (#above before it) + min(#equal before it, need).
 // Every block adds up the counts of the blocks before it; nothing waits.
 // ---------------------------------------------------------------------------
-template <int ALGO, bool EF>
+// CAPPED (DGC with a sampled threshold): T comes from the sample, so the number of keys >= T varies.
+// k is then the payload's capacity: all keys above T are kept in index order while there is room, then
+// keys equal to T; the header records how many entries were kept and unused entries are zeroed.
+template <int ALGO, bool EF, bool CAPPED>
 __global__ __launch_bounds__(kBlock) void cand_emit_k(uint32_t n, uint32_t ntiles, float *st, PayloadHeader *hdr, uint64_t k,
                                                       SparseScratch sc)
 {
-    __shared__ uint64_t sgt[kWavesPerBlock], seq[kWavesPerBlock];
+    __shared__ uint64_t sgt[kWavesPerBlock], seq[kWavesPerBlock], stg[kWavesPerBlock], ste[kWavesPerBlock];
     TileJob job = my_tile(sc, n, ntiles);
     const SelectState s3 = sc.sel[3];
     const uint32_t T = s3.lo;
-    const uint64_t need = s3.need;
+    uint64_t need = s3.need;
     uint32_t *idx = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(hdr) + kHeaderBytes);
     float *val = reinterpret_cast<float *>(idx + k);
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -514,36 +533,54 @@ __global__ __launch_bounds__(kBlock) void cand_emit_k(uint32_t n, uint32_t ntile
         const uint32_t x = sc.tile_cnt[blockIdx.x * kWavesPerBlock + lane];
         wg = x & 0xFFFFu; we = x >> 16;
     }
-    // kept-before of this block: sum over the blocks before it, eight loads in flight per thread
-    uint64_t ag = 0, ae = 0;
-    for (uint32_t b0 = 0; b0 < blockIdx.x; b0 += 8 * kBlock) {
+    // kept-before of this block: sum over the blocks before it (CAPPED: and over all blocks), eight loads in
+    // flight per thread
+    uint64_t ag = 0, ae = 0, tg = 0, te = 0;
+    const uint32_t upto = CAPPED ? gridDim.x : blockIdx.x;
+    for (uint32_t b0 = 0; b0 < upto; b0 += 8 * kBlock) {
         uint32_t x[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const uint32_t b = b0 + u * kBlock + threadIdx.x;
-            x[u] = b < blockIdx.x ? sc.blk_cnt[b] : 0u;
+            x[u] = b < upto ? sc.blk_cnt[b] : 0u;
         }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) { ag += x[u] & 0xFFFFu; ae += x[u] >> 16; }
-    }
-    if (blockIdx.x == 0) {
-        if (threadIdx.x == 0) {
-            PayloadHeader h;
-            h.magic = kMagic; h.algo = ALGO; h.n = n; h.k = k; h.scale = 0.0f; h.levels = 0;
-            for (int i = 0; i < 8; ++i) h.pad[i] = 0;
-            *hdr = h;
+        for (int u = 0; u < 8; ++u) {
+            const uint32_t b = b0 + u * kBlock + threadIdx.x;
+            if (b < blockIdx.x) { ag += x[u] & 0xFFFFu; ae += x[u] >> 16; }
+            if (CAPPED) { tg += x[u] & 0xFFFFu; te += x[u] >> 16; }
         }
-        for (int b = threadIdx.x; b < kBins3; b += kBlock) sc.hist[kHist3 + b] = 0u;   // count is done with level 3
     }
+    if (blockIdx.x == 0)
+        for (int b = threadIdx.x; b < kBins3; b += kBlock) sc.hist[kHist3 + b] = 0u;   // count is done with level 3
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) {
         ag += __shfl_xor(ag, m, 64); ae += __shfl_xor(ae, m, 64);
         wg += __shfl_xor(wg, m, 64); we += __shfl_xor(we, m, 64);
+        if (CAPPED) { tg += __shfl_xor(tg, m, 64); te += __shfl_xor(te, m, 64); }
     }
-    if (lane == 0) { sgt[wave] = ag; seq[wave] = ae; }
+    if (lane == 0) { sgt[wave] = ag; seq[wave] = ae; stg[wave] = tg; ste[wave] = te; }
     __syncthreads();
     uint64_t gt_before = (sgt[0] + sgt[1]) + (sgt[2] + sgt[3]) + wg;
     uint64_t eq_before = (seq[0] + seq[1]) + (seq[2] + seq[3]) + we;
+    uint64_t kept = k;
+    if (CAPPED) {
+        const uint64_t all_gt = (stg[0] + stg[1]) + (stg[2] + stg[3]), all_eq = (ste[0] + ste[1]) + (ste[2] + ste[3]);
+        const uint64_t kept_gt = all_gt < k ? all_gt : k;
+        need = all_eq < k - kept_gt ? all_eq : k - kept_gt;
+        kept = kept_gt + need;
+        // entries of the payload that stay unused are zero
+        for (uint64_t pos = kept + (uint64_t)blockIdx.x * kBlock + threadIdx.x; pos < k; pos += (uint64_t)gridDim.x * kBlock) {
+            idx[pos] = 0u;
+            val[pos] = 0.0f;
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        PayloadHeader h;
+        h.magic = kMagic; h.algo = ALGO; h.n = n; h.k = kept; h.scale = 0.0f; h.levels = CAPPED ? (uint32_t)k : 0u;
+        for (int i = 0; i < 8; ++i) h.pad[i] = 0;
+        *hdr = h;
+    }
     if (s3.mode & kModeUniform) job.runs = job.tile < ntiles ? uniform_runs(job.tile, n) : 0ull;
     tile_walk<true>(sc, job.tile, job.runs, [&](bool valid, uint32_t chunk, uint32_t b, uint32_t loc) {
         const uint32_t key = b & 0x7FFFFFFFu;
@@ -553,7 +590,7 @@ __global__ __launch_bounds__(kBlock) void cand_emit_k(uint32_t n, uint32_t ntile
         if (is_gt || (is_eq && eqb < need)) {
             const uint64_t pos = gtb + (eqb < need ? eqb : need);
             const uint32_t i = chunk * (uint32_t)kChunk + loc;
-            if (pos < k && i < n) {                  // always true for consistent scratch; guards the buffers
+            if (pos < k && i < n) {                  // exact selection: always true for consistent scratch; CAPPED: room left
                 idx[pos] = i;
                 if (ALGO == MC_ALGO_RANDK) val[pos] = st[i];      // the candidate slot holds the random key: the value is p
                 else val[pos] = __uint_as_float(b);
@@ -566,9 +603,9 @@ __global__ __launch_bounds__(kBlock) void cand_emit_k(uint32_t n, uint32_t ntile
     });
 }
 
-template <int ALGO, bool EF>
-static void sparse_compress_t(const LaunchCtx &lc, const GroupView &g, float *st, float momentum, uint64_t k,
-                              PayloadHeader *hdr, const SparseScratch &sc, const RngKey &rng)
+template <int ALGO, bool EF, bool CAPPED>
+static void sparse_compress_t(const LaunchCtx &lc, const GroupView &g, float *st, float momentum, uint64_t k, uint64_t need,
+                              PayloadHeader *hdr, const SparseScratch &sc, const RngKey &rng, const SampleRule &smp)
 {
     constexpr bool FS = (ALGO == MC_ALGO_DGC) || EF;
     constexpr bool RND = ALGO == MC_ALGO_RANDK;
@@ -576,34 +613,43 @@ static void sparse_compress_t(const LaunchCtx &lc, const GroupView &g, float *st
     const uint32_t sblocks = (nch + 15) / 16 < 256 ? (nch + 15) / 16 : 256;      // enough to stream the group in a refill
     dim3 grid(nt), block(kBlock), cgrid((nt + kWavesPerBlock - 1) / kWavesPerBlock);
     prof_begin(lc, K_SPARSE_ACCUM);
-    MC_LAUNCH((sparse_accum_k<ALGO, EF>), grid, block, lc, g, st, momentum, sc, rng);
+    MC_LAUNCH((sparse_accum_k<ALGO, EF>), grid, block, lc, g, st, momentum, sc, rng, smp);
     prof_end(lc, K_SPARSE_ACCUM);
     prof_begin(lc, K_SPARSE_SEED);
-    MC_LAUNCH((sparse_seed_k<FS, RND>), dim3(sblocks), dim3(kSeedThreads), lc, g, st, k, sc, rng);
+    MC_LAUNCH((sparse_seed_k<FS, RND>), dim3(sblocks), dim3(kSeedThreads), lc, g, st, need, sc, rng, smp);
     prof_end(lc, K_SPARSE_SEED);
     prof_begin(lc, K_CAND_HIST2);
-    MC_LAUNCH(cand_hist_k<2>, cgrid, block, lc, g.n, nt, sc);
+    MC_LAUNCH(cand_hist_k<2>, cgrid, block, lc, g.n, nt, sc, smp);
     prof_end(lc, K_CAND_HIST2);
     prof_begin(lc, K_CAND_HIST3);
-    MC_LAUNCH(cand_hist_k<3>, cgrid, block, lc, g.n, nt, sc);
+    MC_LAUNCH(cand_hist_k<3>, cgrid, block, lc, g.n, nt, sc, smp);
     prof_end(lc, K_CAND_HIST3);
     prof_begin(lc, K_CAND_COUNT);
     MC_LAUNCH(cand_count_k, cgrid, block, lc, g.n, nt, sc);
     prof_end(lc, K_CAND_COUNT);
     prof_begin(lc, K_CAND_EMIT);
-    MC_LAUNCH((cand_emit_k<ALGO, EF>), cgrid, block, lc, g.n, nt, st, hdr, k, sc);
+    MC_LAUNCH((cand_emit_k<ALGO, EF, CAPPED>), cgrid, block, lc, g.n, nt, st, hdr, k, sc);
     prof_end(lc, K_CAND_EMIT);
 }
 
+// k: entries of the payload (the exact k, or the capacity when the threshold comes from a sample);
+// sample_stride > 0: DGC with a sampled threshold, the sample starts at sample_first and the threshold is its
+// sample_need-th largest key
 void launch_sparse_compress(const LaunchCtx &lc, int algo, const GroupView &g, bool ef, float *state_f, float momentum,
-                            uint64_t k, PayloadHeader *hdr, const SparseScratch &sc, uint64_t seed, uint32_t worker, uint32_t iter_lo)
+                            uint64_t k, PayloadHeader *hdr, const SparseScratch &sc, uint64_t seed, uint32_t worker, uint32_t iter_lo,
+                            uint32_t sample_stride, uint32_t sample_first, uint64_t sample_need)
 {
     if (g.n == 0) return;
     const RngKey rng{seed, worker, iter_lo};
-    if (algo == MC_ALGO_DGC) sparse_compress_t<MC_ALGO_DGC, true>(lc, g, state_f, momentum, k, hdr, sc, rng);
-    else if (algo == MC_ALGO_RANDK) sparse_compress_t<MC_ALGO_RANDK, true>(lc, g, state_f, momentum, k, hdr, sc, rng);
-    else if (ef) sparse_compress_t<MC_ALGO_TOPK, true>(lc, g, state_f, momentum, k, hdr, sc, rng);
-    else sparse_compress_t<MC_ALGO_TOPK, false>(lc, g, state_f, momentum, k, hdr, sc, rng);
+    SampleRule smp{0u, 0u, 0u};
+    if (algo == MC_ALGO_DGC && sample_stride) {
+        smp.stride = sample_stride; smp.first = sample_first;
+        smp.inv = sample_stride > 1 ? (uint32_t)((1ull << 32) / sample_stride) : 0u;
+        sparse_compress_t<MC_ALGO_DGC, true, true>(lc, g, state_f, momentum, k, sample_need, hdr, sc, rng, smp);
+    } else if (algo == MC_ALGO_DGC) sparse_compress_t<MC_ALGO_DGC, true, false>(lc, g, state_f, momentum, k, k, hdr, sc, rng, smp);
+    else if (algo == MC_ALGO_RANDK) sparse_compress_t<MC_ALGO_RANDK, true, false>(lc, g, state_f, momentum, k, k, hdr, sc, rng, smp);
+    else if (ef) sparse_compress_t<MC_ALGO_TOPK, true, false>(lc, g, state_f, momentum, k, k, hdr, sc, rng, smp);
+    else sparse_compress_t<MC_ALGO_TOPK, false, false>(lc, g, state_f, momentum, k, k, hdr, sc, rng, smp);
 }
 
 // ---------------------------------------------------------------------------
@@ -616,16 +662,19 @@ void launch_sparse_compress(const LaunchCtx &lc, int algo, const GroupView &g, b
 // the +0 of an absent entry changes nothing -- and writes it once.  No atomics, no
 // pre-zeroed output, bit-reproducible.
 // ---------------------------------------------------------------------------
+// capped: the payloads hold up to k64 entries (their capacity, repeated in the header), the header says how many
 __global__ __launch_bounds__(kBlock) void sparse_index_k(int algo, uint32_t n, PayloadPtrs pl, int W, uint64_t k64,
                                                          uint32_t ntiles, uint32_t epoch, uint64_t *tile_first,
-                                                         uint64_t *tile_last, int *status)
+                                                         uint64_t *tile_last, int *status, int capped)
 {
-    const uint32_t k = (uint32_t)k64;
     const uint32_t w = blockIdx.y;
+    const PayloadHeader *h = reinterpret_cast<const PayloadHeader *>(pl.p[w]);
+    const uint64_t held = h->k;
+    const bool fits = capped ? held <= k64 && h->levels == (uint32_t)k64 : held == k64;
     if (blockIdx.x == 0 && threadIdx.x == 0) {
-        const PayloadHeader *h = reinterpret_cast<const PayloadHeader *>(pl.p[w]);
-        if (h->magic != kMagic || h->algo != (uint32_t)algo || h->n != (uint64_t)n || h->k != k64) *status = 1;
+        if (h->magic != kMagic || h->algo != (uint32_t)algo || h->n != (uint64_t)n || !fits) *status = 1;
     }
+    const uint32_t k = fits ? (uint32_t)held : 0u;          // a payload that does not fit contributes nothing
     const uint32_t *idx = reinterpret_cast<const uint32_t *>(pl.p[w] + kHeaderBytes);
     const uint32_t e = blockIdx.x * kBlock + threadIdx.x;
     if (e >= k) return;
@@ -729,13 +778,14 @@ __global__ __launch_bounds__(kBlock) void sparse_decompress_k(GroupView out, Pay
 }
 
 void launch_sparse_decompress(const LaunchCtx &lc, int algo, const GroupView &out, const PayloadPtrs &pl, int W,
-                              float alpha, uint64_t k, uint32_t epoch, uint64_t *tile_first, uint64_t *tile_last, int *status)
+                              float alpha, uint64_t k, uint32_t epoch, uint64_t *tile_first, uint64_t *tile_last, int *status,
+                              bool capped)
 {
     if (out.n == 0) return;
     const uint32_t nt = tiles_of(out.n);
     prof_begin(lc, K_SPARSE_INDEX);
     MC_LAUNCH(sparse_index_k, dim3((uint32_t)((k + kBlock - 1) / kBlock), W), dim3(kBlock), lc, algo,
-                       out.n, pl, W, k, nt, epoch, tile_first, tile_last, status);
+                       out.n, pl, W, k, nt, epoch, tile_first, tile_last, status, capped ? 1 : 0);
     prof_end(lc, K_SPARSE_INDEX);
     prof_begin(lc, K_SPARSE_DECOMPRESS);
     MC_LAUNCH(sparse_decompress_k, dim3(nt), dim3(kBlock), lc, out, pl, W, alpha, k, nt, epoch, tile_first,

@@ -125,6 +125,22 @@ static uint64_t topk_count(uint64_t n, uint32_t ppm)
     return k;
 }
 
+// Philox-4x32-10 on the host: the sampled-threshold DGC draws where its sample starts from the word of the
+// group's first element (counter = (J lo, J hi, worker, iteration), J = model-global index / 4, key = seed).
+static uint32_t philox_word(uint64_t seed, uint32_t worker, uint32_t iter_lo, uint64_t global_index)
+{
+    const uint64_t J = global_index >> 2;
+    uint32_t c[4] = {(uint32_t)J, (uint32_t)(J >> 32), worker, iter_lo};
+    uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = 0xD2511F53ull * c[0], p1 = 0xCD9E8D57ull * c[2];
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c[1] ^ k0, n2 = (uint32_t)(p0 >> 32) ^ c[3] ^ k1;
+        c[1] = (uint32_t)p1; c[3] = (uint32_t)p0; c[0] = n0; c[2] = n2;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    return c[global_index & 3u];
+}
+
 static bool is_sparse(int algo) { return algo == MC_ALGO_TOPK || algo == MC_ALGO_DGC || algo == MC_ALGO_RANDK; }
 // n-element vectors of a group's state: the residual (DGC: v and u; SigNUM: the momentum; SignSGD: nothing)
 static uint32_t state_vectors(int algo) { return algo == MC_ALGO_DGC ? 2u : algo == MC_ALGO_SIGNSGD ? 0u : 1u; }
@@ -298,7 +314,8 @@ int mc_ctx_create(mc_ctx **out, const mc_config *cfg, const int64_t *numel, int3
     if (!out) return MC_ERR_INVALID_ARG;
     *out = nullptr;
     if (!cfg || !numel || !bounds || n_tensors < 1 || y < 1) return MC_ERR_INVALID_ARG;
-    if (cfg->algo < MC_ALGO_EFSIGN || cfg->algo > MC_ALGO_RANDK || cfg->reserved != 0) return MC_ERR_INVALID_ARG;
+    if (cfg->algo < MC_ALGO_EFSIGN || cfg->algo > MC_ALGO_RANDK) return MC_ERR_INVALID_ARG;
+    if (cfg->dgc_sample_ppm > 1000000u || (cfg->dgc_sample_ppm != 0 && cfg->algo != MC_ALGO_DGC)) return MC_ERR_INVALID_ARG;
     if (cfg->use_ef != 0 && cfg->use_ef != 1) return MC_ERR_INVALID_ARG;
     if (always_state(cfg->algo) && cfg->use_ef != 1) return MC_ERR_INVALID_ARG;
     if (cfg->algo == MC_ALGO_SIGNSGD && cfg->use_ef != 0) return MC_ERR_INVALID_ARG;
@@ -339,6 +356,7 @@ int mc_ctx_create(mc_ctx **out, const mc_config *cfg, const int64_t *numel, int3
             off.push_back((uint32_t)n);
             g.n = (uint32_t)n;
             g.k = is_sparse(cfg->algo) ? topk_count(n, cfg->ratio_ppm) : 0;
+            if (cfg->dgc_sample_ppm) g.k = std::min<uint64_t>(2 * g.k, n);     // sampled threshold: the payload's capacity
             goff += n;
             if (hipMalloc(&g.d_seg_off, off.size() * sizeof(uint32_t)) != hipSuccess) { rc = MC_ERR_ALLOC; break; }
             if (hipMemcpy(g.d_seg_off, off.data(), off.size() * sizeof(uint32_t), hipMemcpyHostToDevice) != hipSuccess) { rc = MC_ERR_DEVICE; break; }
@@ -529,7 +547,16 @@ int mc_compress(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter, cons
         SparseScratch sp = ctx->sparse;
         // a context may compress for several simulated workers whose thresholds differ: each keeps its own hint
         sp.hint = ctx->d_hints + (size_t)group * kHintWorkers + worker % kHintWorkers;
-        launch_sparse_compress(lc, cfg.algo, gv, ef, sf, cfg.dgc_momentum, G.k, hdr, sp, cfg.seed, worker, (uint32_t)iter);
+        uint32_t stride = 0, first = 0;
+        uint64_t need = 0;
+        if (cfg.dgc_sample_ppm) {       // sample: every stride-th element from `first`; threshold = its need-th largest key
+            stride = std::max<uint32_t>(1u, 1000000u / cfg.dgc_sample_ppm);
+            first = philox_word(cfg.seed, worker, (uint32_t)iter, G.goff) % stride;
+            const uint64_t m = n > first ? ((uint64_t)n - first + stride - 1) / stride : 0;
+            need = m ? std::max<uint64_t>(1, (uint64_t)(((unsigned __int128)m * cfg.ratio_ppm) / 1000000u)) : 0;
+        }
+        launch_sparse_compress(lc, cfg.algo, gv, ef, sf, cfg.dgc_momentum, G.k, hdr, sp, cfg.seed, worker, (uint32_t)iter,
+                               stride, first, need);
     }
         break;
     default: return MC_ERR_INVALID_ARG;
@@ -558,7 +585,7 @@ int mc_decompress_sum(mc_ctx *ctx, int32_t group, const void *const *payloads, i
     const mc_config &cfg = ctx->cfg;
     if (is_sparse(cfg.algo) && ++ctx->epoch == 0) ctx->epoch = 1;
     if (is_sparse(cfg.algo)) launch_sparse_decompress(lc, cfg.algo, gv, pl, W, alpha, G.k, ctx->epoch, ctx->sparse.tile_first,
-                                                    ctx->sparse.tile_last, ctx->d_status);
+                                                    ctx->sparse.tile_last, ctx->d_status, cfg.dgc_sample_ppm != 0);
     else {
         const uint32_t levels = cfg.algo == MC_ALGO_QSGD ? (1u << (cfg.qsgd_bits - 1)) - 1u : 0u;
         launch_dense_decompress(lc, cfg.algo, gv, pl, W, alpha, levels, ctx->d_status, ctx->d_tern_table);

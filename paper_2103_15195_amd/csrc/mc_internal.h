@@ -101,9 +101,10 @@ struct SparseScratch {
     uint64_t *tile_first, *tile_last;   // decompress: per worker and 4096-element tile, (epoch << 32 | entry) of its run
 };
 void launch_sparse_compress(const LaunchCtx &lc, int algo, const GroupView &g, bool ef, float *state_f, float momentum,
-                            uint64_t k, PayloadHeader *hdr, const SparseScratch &sc, uint64_t seed, uint32_t worker, uint32_t iter_lo);
+                            uint64_t k, PayloadHeader *hdr, const SparseScratch &sc, uint64_t seed, uint32_t worker, uint32_t iter_lo,
+                            uint32_t sample_stride, uint32_t sample_first, uint64_t sample_need);
 void launch_sparse_decompress(const LaunchCtx &lc, int algo, const GroupView &out, const PayloadPtrs &pl, int W,
                               float alpha, uint64_t k, uint32_t epoch, uint64_t *tile_first, uint64_t *tile_last,
-                              int *status);
+                              int *status, bool capped);
 
 }  // namespace mc

@@ -118,7 +118,7 @@ def run_parity(numel: Sequence[int], algo: str, y: int, W: int, iters: int,
         assert ctx.group_numel(j) == gn[j]
         assert ctx.payload_bytes(j) == O.payload_bytes(ocfg, gn[j])
         assert ctx.state_bytes(j) == 64 + 4 * O.state_floats(ocfg, gn[j])
-        assert ctx.group_k(j) == (O.topk_count(gn[j], ocfg.ratio_ppm) if algo in ("topk", "dgc", "randk") else 0)
+        assert ctx.group_k(j) == (O.sparse_capacity(ocfg, gn[j]) if algo in ("topk", "dgc", "randk") else 0)
 
     gstate = [[torch.zeros(ctx.state_bytes(j), dtype=torch.uint8, device=DEV) if ef else None for j in range(y)] for _ in workers]
     gpay = [[torch.full((ctx.payload_bytes(j),), 0xAB, dtype=torch.uint8, device=DEV) for j in range(y)] for _ in workers]

@@ -78,8 +78,8 @@ def test_ctx_create_rejects_bad_arguments_before_touching_a_device():
 
     def create(cfg, nm=numel, n=3, bd=bounds, y=1):
         return L.mc_ctx_create(C.byref(h), C.byref(cfg), nm, n, bd, y)
-    ok = dict(algo=1, use_ef=1, ratio_ppm=10000, qsgd_bits=8, dgc_momentum=0.9, reserved=0, seed=0)
-    for bad in (dict(algo=0), dict(algo=7), dict(use_ef=2), dict(reserved=1), dict(algo=3, use_ef=0),
+    ok = dict(algo=1, use_ef=1, ratio_ppm=10000, qsgd_bits=8, dgc_momentum=0.9, dgc_sample_ppm=0, seed=0)
+    for bad in (dict(algo=0), dict(algo=7), dict(use_ef=2), dict(dgc_sample_ppm=1), dict(algo=3, use_ef=0),
                 dict(algo=4, qsgd_bits=1), dict(algo=4, qsgd_bits=9), dict(algo=2, ratio_ppm=0),
                 dict(algo=2, ratio_ppm=1000001)):
         assert create(B.McConfig(**{**ok, **bad})) == B.MC_ERR_INVALID_ARG, bad

@@ -107,6 +107,13 @@ def test_config2_resnet50_sparse(algo, ppm, y):
     sparse_decompress_fullsize(wl, algo, y, 8, grads, ppm)
 
 
+def test_config2_resnet50_dgc_sampled_threshold():
+    """DGC 0.1 % with the threshold taken from a 1 % sample: payload, kept count and accumulators against the oracle,
+    then a decompress-and-sum over the W payloads the oracle wrote."""
+    st = compress_fullsize(2, "dgc", 1, 8, iters=2, oracle_workers=None, ppm=1000, dgc_sample_ppm=10000)
+    assert st.decompress_checks == 1
+
+
 # ---- fourth configuration: ResNet-101 shapes, y in {1,2,4}, W = 16; Top-k 0.1 % and EF-Sign ------------------------------------
 @pytest.mark.parametrize("y", [1, 2, 4])
 def test_config3_resnet101_efsign(y):

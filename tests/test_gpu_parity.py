@@ -146,6 +146,36 @@ def test_sparsifier_when_the_candidate_filter_misses(algo, use_ef):
     H.run_parity(numel, algo, 1, 2, 6, grads, ratio_ppm=300000, use_ef=use_ef, dgc_momentum=0.5)
 
 
+# ---- DGC with a threshold taken from a sample: variable number of kept entries, capacity 2k ---------------
+@pytest.mark.parametrize("sample_ppm", [1000000, 200000, 10000, 1000])
+def test_dgc_sampled_threshold(sample_ppm):
+    numel = [30000, 17, 5000, 12000, 1]
+    total = sum(numel)
+    for y, W in ((1, 3), (2, 2), (5, 2)):
+        st = H.run_parity(numel, "dgc", y, W, 3, normal_grads(total, seed=sample_ppm + y), ratio_ppm=20000, dgc_momentum=0.7,
+                          dgc_sample_ppm=sample_ppm, seed=31)
+        assert st.decompress_checks == y
+
+
+@pytest.mark.parametrize("kind", ["zeros", "all_equal", "ties", "wide"])
+def test_dgc_sampled_threshold_on_degenerate_values(kind):
+    """Tied values make far more than k elements reach the sampled threshold: the capacity rule decides."""
+    numel = [3000, 17, 5000, 1200]
+    H.run_parity(numel, "dgc", 2, 3, 3, special_grads(sum(numel), kind), ratio_ppm=30000, dgc_sample_ppm=50000, seed=5)
+    H.run_parity([4097], "dgc", 1, 2, 2, special_grads(4097, kind), ratio_ppm=500000, dgc_sample_ppm=100000, seed=6)
+
+
+def test_dgc_sampled_threshold_when_the_hint_misses():
+    numel = [30000, 17, 5000, 12000]
+    total = sum(numel)
+
+    def grads(w, it):
+        rng = np.random.default_rng([29, w, it])
+        scale = [1.0, 1e-3, 10.0, 1e-6, 1e-6, 1.0][it]
+        return rng.standard_normal(total, dtype=np.float32) * np.float32(scale)
+    H.run_parity(numel, "dgc", 2, 2, 6, grads, ratio_ppm=10000, dgc_momentum=0.3, dgc_sample_ppm=100000, seed=8)
+
+
 @pytest.mark.parametrize("bits", [2, 4, 7])
 def test_qsgd_code_widths(bits):
     H.run_parity([9000, 100], "qsgd", 1, 2, 2, normal_grads(9100, seed=bits), qsgd_bits=bits, seed=21)
