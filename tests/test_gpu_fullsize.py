@@ -107,6 +107,34 @@ def test_config2_resnet50_sparse(algo, ppm, y):
     sparse_decompress_fullsize(wl, algo, y, 8, grads, ppm)
 
 
+@pytest.mark.parametrize("algo,ppm", [("topk", 10000), ("dgc", 1000), ("randk", 10000)])
+def test_config2_resnet50_selection_settles_on_the_fast_route(algo, ppm):
+    """Several iterations of one worker at full size: the first calls leave the histogram window (error feedback
+    builds up, the threshold climbs), later ones fall inside it.  Every payload and the final state are compared with
+    the oracle, and the fast route must have been taken."""
+    wl, grads = grads_of(2)
+    numel = wl.numel.tolist()
+    ctx = B.Context(algo, numel, [0, len(numel)], ratio_ppm=ppm, seed=2021)
+    ocfg = O.Config(H.ALGOS[algo], ratio_ppm=ppm, seed=2021)
+    st = torch.zeros(ctx.state_bytes(0), dtype=torch.uint8, device=H.DEV)
+    pay = torch.zeros(ctx.payload_bytes(0), dtype=torch.uint8, device=H.DEV)
+    ost = O.new_state(ocfg, wl.total)
+    flat = grads(0, 0)
+    dev = H.device_tensors(flat, numel)
+    routes = []
+    for it in range(7):
+        ctx.mc_compress(0, 0, it, dev, st, pay)
+        routes.append(ctx.mc_last_select_route())
+        op, _ = O.compress(ocfg, flat, ost, worker=0, it=it)
+        assert np.array_equal(pay.cpu().numpy(), op), f"{algo} iteration {it} (route {routes[-1]}): payload differs"
+    e = torch.empty(O.state_floats(ocfg, wl.total), dtype=torch.float32, device=H.DEV)
+    ctx.mc_state_export_residual(0, st, e)
+    assert H.same_bits(e.cpu().numpy(), ost)
+    print(f"[config2 {algo}] routes {routes}", flush=True)
+    assert routes[0] == B.MC_SELECT_ABOVE and B.MC_SELECT_FAST in routes[2:]
+    ctx.close()
+
+
 def test_config2_resnet50_dgc_sampled_threshold():
     """DGC 0.1 % with the threshold taken from a 1 % sample: payload, kept count and accumulators against the oracle,
     then a decompress-and-sum over the W payloads the oracle wrote."""
