@@ -707,8 +707,9 @@ __global__ __launch_bounds__(kBlock) void sparse_decompress_k(GroupView out, Pay
         for (int b = 0; b < kSparseBatch; ++b) {
             lo[b] = hi[b] = 0;
             if (w0 + b < W) {
-                const uint64_t f = tile_first[(size_t)(w0 + b) * ntiles + blockIdx.x];
-                const uint64_t l = tile_last[(size_t)(w0 + b) * ntiles + blockIdx.x];
+                // block-uniform addresses, kept on the scalar path whatever the compiler makes of the rest
+                const uint64_t f = ld_uniform(tile_first + (size_t)(w0 + b) * ntiles + blockIdx.x);
+                const uint64_t l = ld_uniform(tile_last + (size_t)(w0 + b) * ntiles + blockIdx.x);
                 if ((uint32_t)(f >> 32) == epoch && (uint32_t)(l >> 32) == epoch) {      // else: no entry in this tile
                     lo[b] = (uint32_t)f < k ? (uint32_t)f : k;
                     hi[b] = (uint32_t)l < k ? (uint32_t)l : k;

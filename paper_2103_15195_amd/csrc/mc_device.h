@@ -50,6 +50,17 @@ __device__ __forceinline__ Chunk my_chunk(uint32_t n)
     return c;
 }
 
+// A load whose address is the same for the whole wavefront, forced onto the scalar path (constant address
+// space).  In a kernel that streams stores, loads on the vector path queue behind those stores; the scalar
+// cache does not.  (Measured: the same 16 table loads per wavefront cost the sparse decompress 5-7 us more
+// when the compiler happened to issue them as vector loads.)  Only for data no thread of this kernel writes.
+template <typename T>
+__device__ __forceinline__ T ld_uniform(const T *p)
+{
+    typedef const T __attribute__((address_space(4))) *const_ptr;
+    return *(const_ptr)(uintptr_t)p;
+}
+
 template <typename T>
 __device__ __forceinline__ T ld_stream(const T *p) { return __builtin_nontemporal_load(p); }
 template <typename T>
@@ -88,6 +99,10 @@ __device__ __forceinline__ void store_flat(T *buf, const Chunk &c, uint32_t n, c
     }
 }
 
+// The tabulated address of a chunk (0 = walk the segment table).  A kernel that has other loads to wait
+// for before it stores fetches this first, so that the two latencies overlap.
+__device__ __forceinline__ uintptr_t chunk_direct(const GroupView &g, const Chunk &c) { return ld_uniform(g.chunk_addr + (c.base >> 10)); }
+
 // ---- segmented (per-tensor) buffers ------------------------------------------
 // Fast path: the chunk lies inside one tensor and its address was tabulated when
 // the tensor address list was uploaded (one scalar load, then the data).
@@ -95,7 +110,7 @@ __device__ __forceinline__ void store_flat(T *buf, const Chunk &c, uint32_t n, c
 // tensor (flat indices of a lane only grow with j, so the cursor never moves back).
 __device__ __forceinline__ void load_seg(const GroupView &g, const Chunk &c, float (&v)[kSteps])
 {
-    const uintptr_t direct = g.chunk_addr[c.base >> 10];
+    const uintptr_t direct = chunk_direct(g, c);
     if (direct) {
         const float *p = reinterpret_cast<const float *>(direct) + c.lane;
 #pragma unroll
@@ -116,10 +131,6 @@ __device__ __forceinline__ void load_seg(const GroupView &g, const Chunk &c, flo
         }
     }
 }
-
-// The tabulated address of a chunk (0 = walk the segment table).  A kernel that has other loads to wait
-// for before it stores fetches this first, so that the two latencies overlap.
-__device__ __forceinline__ uintptr_t chunk_direct(const GroupView &g, const Chunk &c) { return g.chunk_addr[c.base >> 10]; }
 
 // (Measured on this part: a fill whose 256-byte wave stores miss a 64-byte boundary runs at about
 // two thirds of the aligned rate -- 102 MB into 161 tensors: 16 us aligned, 24 us not -- while loads
