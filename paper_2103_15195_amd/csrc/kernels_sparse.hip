@@ -47,7 +47,11 @@ constexpr int kBinsW = 2048, kBins1 = 2048, kBins2 = 1024, kBins3 = 1 << kWindow
 // the bins themselves are updated -- no shared summary counters -- and a level is
 // resolved by a wavefront that reads all its bins.
 constexpr int kHistW = 0, kHist1 = kHistW + kBinsW, kHist2 = kHist1 + kBins1, kHist3 = kHist2 + kBins2;
-static_assert(kHist3 + kBins3 == kHistWords, "histogram scratch layout");
+// The window's open last bin takes a count from nearly every block (all keys above the window), and
+// adds from thousands of blocks to one address queue up behind each other for tens of microseconds:
+// its count is spread over kOpenCopies words, chosen by the block index, which the seed sums.
+constexpr int kOpenCopies = 64, kHistOpen = kHist3 + kBins3;
+static_assert(kHistOpen + kOpenCopies == kHistWords, "histogram scratch layout");
 constexpr uint32_t kHintMargin = 3u << 19;   // 3/16 of an octave below the last threshold
 // The window spans 2^22 keys (half an octave) from the hint upward: it holds the new threshold if that
 // lies between 12 % below and 24 % above the last one (2^23 keys are one octave of magnitude).
@@ -169,7 +173,8 @@ __global__ __launch_bounds__(kBlock) void sparse_accum_k(GroupView g, float *st,
     __syncthreads();
     if (threadIdx.x == 0)       // candidates of the tile's four chunks, 16 bits each (a chunk holds at most 1024)
         sc.tile_runs[blockIdx.x] = (uint64_t)wcnt[0] | ((uint64_t)wcnt[1] << 16) | ((uint64_t)wcnt[2] << 32) | ((uint64_t)wcnt[3] << 48);
-    flush_fine(hist, sc.hist + kHistW, kBinsW);
+    flush_fine(hist, sc.hist + kHistW, kBinsW - 1);
+    if (threadIdx.x == kBlock - 1 && hist[kBinsW - 1]) atomicAdd(&sc.hist[kHistOpen + (blockIdx.x & (kOpenCopies - 1))], hist[kBinsW - 1]);
 }
 
 // ---------------------------------------------------------------------------
@@ -181,7 +186,8 @@ __global__ __launch_bounds__(kBlock) void sparse_accum_k(GroupView g, float *st,
 // histogram holds fewer than `need` keys.
 // ---------------------------------------------------------------------------
 template <int BINS>
-__device__ __forceinline__ bool resolve_wave(const uint32_t *fine, uint64_t need, uint32_t &bin, uint64_t &rest)
+__device__ __forceinline__ bool resolve_wave(const uint32_t *fine, uint64_t need, uint32_t &bin, uint64_t &rest,
+                                             uint32_t top_extra = 0u /* counted in the last bin besides fine[BINS - 1] */)
 {
     constexpr int kPer = BINS / 64;
     const uint32_t lane = threadIdx.x & 63u;
@@ -193,6 +199,7 @@ __device__ __forceinline__ bool resolve_wave(const uint32_t *fine, uint64_t need
         const uint4 x = src[i];
         h[4 * i] = x.x; h[4 * i + 1] = x.y; h[4 * i + 2] = x.z; h[4 * i + 3] = x.w;
     }
+    if (lane == 63u) h[kPer - 1] += top_extra;
 #pragma unroll
     for (int i = 0; i < kPer; ++i) own += h[i];
     uint64_t incl = own;                                    // inclusive suffix sum over lanes
@@ -321,7 +328,10 @@ __global__ __launch_bounds__(kSeedThreads) void sparse_seed_k(GroupView g, const
     if (wave == 0) {
         uint32_t bin;
         uint64_t rest;
-        const bool found = resolve_wave<kBinsW>(sc.hist + kHistW, k, bin, rest);
+        uint32_t open = sc.hist[kHistOpen + lane];
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) open += __shfl_xor(open, d, 64);
+        const bool found = resolve_wave<kBinsW>(sc.hist + kHistW, k, bin, rest, open);
         if (lane == 0) { verdict[0] = found; verdict[1] = bin; verdict[2] = (uint32_t)rest; verdict[3] = (uint32_t)(rest >> 32); }
     }
     for (int b = t; b < kBins1; b += kSeedThreads) hist[b] = 0u;
@@ -410,7 +420,7 @@ __global__ __launch_bounds__(kBlock) void cand_hist_k(uint32_t n, uint32_t ntile
     const SelectState s0 = sc.sel[0];
     if (LEVEL == 2) {
         if (blockIdx.x == 0)                // the seed is done with the window
-            for (int b = threadIdx.x; b < kBinsW; b += kBlock) sc.hist[kHistW + b] = 0u;
+            for (int b = threadIdx.x; b < kBinsW + kOpenCopies; b += kBlock) sc.hist[(b < kBinsW ? kHistW : kHistOpen - kBinsW) + b] = 0u;
         if (s0.mode & kModeFast) return;
     }
     const bool uniform = (s0.mode & kModeUniform) != 0u;
