@@ -95,10 +95,13 @@ def check_payload(algo: str, gpay: np.ndarray, opay: np.ndarray, what: str) -> b
 def run_parity(numel: Sequence[int], algo: str, y: int, W: int, iters: int,
                grads_fn: Callable[[int, int], np.ndarray], *, policy: int = B.MC_PART_EVEN_ELEMS,
                user_bounds: Optional[Sequence[int]] = None, oracle_workers: Optional[Sequence[int]] = None,
-               layout: str = "separate", alpha: float = 1.0, check_decompress: bool = True, **cfgkw) -> Stats:
+               layout: str = "separate", alpha: float = 1.0, check_decompress: bool = True,
+               prelude_fn: Optional[Callable[[int], np.ndarray]] = None, **cfgkw) -> Stats:
     """Full protocol on one (tensor list, algorithm, y): compress every (iteration, group, worker) on the GPU,
     compare payload and residual with the oracle for `oracle_workers` (default: all), then decompress-and-sum
-    the oracle's payloads on the GPU and compare with the oracle's aggregate."""
+    the oracle's payloads on the GPU and compare with the oracle's aggregate.
+    prelude_fn(w): gradients that the same context first compresses and decodes into throw-away buffers (nothing of
+    it is compared; what it leaves in the context must not disturb the calls that follow)."""
     stats = Stats()
     numel = [int(x) for x in numel]
     aid = ALGOS[algo]
@@ -124,6 +127,18 @@ def run_parity(numel: Sequence[int], algo: str, y: int, W: int, iters: int,
     gpay = [[torch.full((ctx.payload_bytes(j),), 0xAB, dtype=torch.uint8, device=DEV) for j in range(y)] for _ in workers]
     ostate: Dict[int, List[np.ndarray]] = {w: [O.new_state(ocfg, gn[j]) if ef else None for j in range(y)] for w in owork}
     opay: Dict[int, List[Optional[np.ndarray]]] = {w: [None] * y for w in owork}
+
+    if prelude_fn is not None:
+        for j in range(y):
+            pays = []
+            for w in workers:
+                d = device_tensors(prelude_fn(w), numel, layout)
+                st = torch.zeros(ctx.state_bytes(j), dtype=torch.uint8, device=DEV) if ef else None
+                pays.append(torch.zeros(ctx.payload_bytes(j), dtype=torch.uint8, device=DEV))
+                ctx.mc_compress(j, w, 1 << 20, d[bounds[j]:bounds[j + 1]], st, pays[-1])
+            sink = empty_like_list(device_tensors(np.zeros(int(offs[-1]), np.float32), numel, layout))
+            ctx.mc_decompress_sum(j, pays, alpha, sink[bounds[j]:bounds[j + 1]])
+            assert ctx.mc_last_device_status() == B.MC_OK
 
     for it in range(iters):
         flats = {w: grads_fn(w, it) for w in workers}

@@ -176,6 +176,31 @@ def test_dgc_sampled_threshold_when_the_hint_misses():
     H.run_parity(numel, "dgc", 2, 2, 6, grads, ratio_ppm=10000, dgc_momentum=0.3, dgc_sample_ppm=100000, seed=8)
 
 
+@pytest.mark.parametrize("algo", ALL)
+def test_non_finite_gradients_leave_the_context_usable(algo):
+    """Codes of non-finite values are unspecified, but such a call must end normally and what it leaves in the
+    context (candidate-filter hints, histograms, tables) must not change later results."""
+    numel = [5000, 77, 3000]
+
+    def poisoned(w):
+        g = normal_grads(8077, seed=70 + w)(w, 0)
+        g[w::97] = np.float32("nan")
+        g[5::131] = np.float32("inf")
+        g[9::89] = np.float32("-inf")
+        return g
+    H.run_parity(numel, algo, 1, 2, 2, normal_grads(8077, seed=71), ratio_ppm=20000, prelude_fn=poisoned)
+
+
+@pytest.mark.parametrize("algo", ["efsign", "topk", "qsgd"])
+def test_on_a_stream_of_the_caller(algo):
+    """All work is enqueued on the stream that the caller names (here: not the default one)."""
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        st = H.run_parity([5000, 77, 3000], algo, 2, 3, 2, normal_grads(8077, seed=72), ratio_ppm=20000)
+    side.synchronize()
+    assert st.compress_checks == 2 * 2 * 3
+
+
 @pytest.mark.parametrize("bits", [2, 4, 7])
 def test_qsgd_code_widths(bits):
     H.run_parity([9000, 100], "qsgd", 1, 2, 2, normal_grads(9100, seed=bits), qsgd_bits=bits, seed=21)
