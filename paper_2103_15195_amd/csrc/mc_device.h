@@ -132,11 +132,11 @@ __device__ __forceinline__ void load_seg(const GroupView &g, const Chunk &c, flo
     }
 }
 
-// (Measured on this part: a fill whose 256-byte wave stores miss a 64-byte boundary runs at about
-// two thirds of the aligned rate -- 102 MB into 161 tensors: 16 us aligned, 24 us not -- while loads
-// are not sensitive.  Rotating lanes to aligned windows does not pay: the partial windows at the
-// chunk ends cost more than they save.  Tensors whose flat offset is a multiple of 16 elements
-// keep the aligned rate.)
+// (Measured on this part: a bare fill whose 256-byte wave stores miss a 64-byte boundary runs at about
+// three quarters of the aligned rate -- 102 MB: 16 us aligned, 22 us not -- while loads are not
+// sensitive.  The decompress kernels that end in this store do not show it: they take the same time
+// for tensors packed on the chunk grid and for tensors 32 bytes off it, and rotating lanes to aligned
+// windows made them slower.)
 __device__ __forceinline__ void store_seg(const GroupView &g, const Chunk &c, const float (&v)[kSteps], uintptr_t direct)
 {
     if (direct) {
