@@ -95,7 +95,12 @@ class AlgoBench:
         self.grads = grads
         self.state = [[torch.zeros(self.ctx.state_bytes(j), dtype=torch.uint8, device=dev) for j in range(y)] for _ in range(W)]
         self.pay = [[torch.zeros(self.ctx.payload_bytes(j), dtype=torch.uint8, device=dev) for j in range(y)] for _ in range(W)]
-        self.outs = [torch.empty_like(t) for t in grads[0]]
+        if grads[0][0].data_ptr() + 4 * grads[0][0].numel() == grads[0][1].data_ptr():      # views of one packed buffer
+            flat = torch.empty(sum(numel), dtype=torch.float32, device=dev)
+            offs = np.concatenate([[0], np.cumsum(numel)])
+            self.outs = [flat[offs[t]:offs[t + 1]] for t in range(len(numel))]
+        else:
+            self.outs = [torch.empty_like(t) for t in grads[0]]
         b = self.bounds
         # address lists are marshalled once: the loop below measures the library, not Python
         self.grad_arr = [[B.ptr_array(grads[w][b[j]:b[j + 1]]) for j in range(y)] for w in range(W)]

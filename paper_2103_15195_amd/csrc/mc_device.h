@@ -132,11 +132,10 @@ __device__ __forceinline__ void load_seg(const GroupView &g, const Chunk &c, flo
     }
 }
 
-// (Measured on this part: a bare fill whose 256-byte wave stores miss a 64-byte boundary runs at about
-// three quarters of the aligned rate -- 102 MB: 16 us aligned, 22 us not -- while loads are not
-// sensitive.  The decompress kernels that end in this store do not show it: they take the same time
-// for tensors packed on the chunk grid and for tensors 32 bytes off it, and rotating lanes to aligned
-// windows made them slower.)
+// (Measured on this part: stores whose 256-byte wave windows miss a 64-byte boundary are slower -- a bare
+// 102 MB fill takes 16 us aligned and 22 us not, the plane decompress kernel 27 and 32 us -- while loads
+// are not sensitive.  Rotating lanes to aligned windows did not pay in these kernels.  Tensors whose flat
+// offset is a multiple of 16 elements keep the aligned rate.)
 __device__ __forceinline__ void store_seg(const GroupView &g, const Chunk &c, const float (&v)[kSteps], uintptr_t direct)
 {
     if (direct) {
