@@ -792,13 +792,15 @@ __global__ __launch_bounds__(kBlock) void plane_decompress_k(GroupView out, Payl
         c.lane = lane;
         c.full = c.base < out.n && out.n - c.base >= (uint32_t)kChunk;
         if (c.base < out.n) {
+            const uintptr_t direct = chunk_direct(out, c);
+            const uint32_t rot = TERN ? 0u : chunk_rotation(direct);     // measured: pays for the one-plane schemes only
             float v[kSteps];
 #pragma unroll
             for (int j = 0; j < kSteps; ++j) {
-                uint32_t i = 64 * j + lane;                              // element of this half
+                const uint32_t i = rotated(j, lane, rot);                // element of this half, rotated onto the lines
                 v[j] = mine[i + (i >> 5)];
             }
-            store_seg(out, c, v);
+            store_seg_rot(out, c, v, direct, rot);
         }
     }
 }
