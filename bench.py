@@ -136,6 +136,13 @@ def timed(torch, fn, reps):
     return (time.perf_counter() - t0) / reps
 
 
+def timed_median(torch, fn, reps, batches=5):
+    """Seconds per call as the median over `batches` runs of reps / batches calls each: the diagnostic per-algorithm
+    figures should not carry a single host stall (the headline keeps the plain K-step bracket)."""
+    per = max(1, reps // batches)
+    return float(np.median([timed(torch, lambda i, b=b: fn(b * per + i), per) for b in range(batches)]))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -212,8 +219,8 @@ def main():
 
     per_algo = {}
     for a in algos:
-        tc = timed(torch, lambda i: (setattr(benches[a], "it", benches[a].it + 1), benches[a].compress(i % W)), 50)
-        td = timed(torch, lambda i: benches[a].decompress(), 50)
+        tc = timed_median(torch, lambda i: (setattr(benches[a], "it", benches[a].it + 1), benches[a].compress(i % W)), 250)
+        td = timed_median(torch, lambda i: benches[a].decompress(), 250)
         bc, bd = CALL_BYTES.get(a, (None, None))
         entry = {"compress_us": tc * 1e6, "decompress_sum_us": td * 1e6, "gradient_GBps": 4.0 * D / (tc + td) * 1e-9}
         if bc is not None:
