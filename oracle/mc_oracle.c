@@ -42,7 +42,7 @@ enum { ALG_EFSIGN = 1, ALG_TOPK = 2, ALG_DGC = 3, ALG_QSGD = 4, ALG_TERNGRAD = 5
        ALG_SIGNSGD = 7, ALG_SIGNUM = 8, ALG_ONEBIT = 9, ALG_RANDK = 10 };
 enum { PART_EVEN_COUNT = 0, PART_EVEN_ELEMS = 1, PART_USER = 2 };
 
-#define HDR_BYTES 64u
+#define HDR_BYTES 128u   /* fields in the first 36 bytes, the rest zero: the body starts on a 128-byte line */
 #define MAGIC 0x3150434Du /* "MCP1" */
 
 typedef struct {

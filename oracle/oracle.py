@@ -24,7 +24,7 @@ EFSIGN, TOPK, DGC, QSGD, TERNGRAD, FP16, SIGNSGD, SIGNUM, ONEBIT, RANDK = 1, 2, 
 ALGO_NAMES = {EFSIGN: "efsign", TOPK: "topk", DGC: "dgc", QSGD: "qsgd", TERNGRAD: "terngrad", FP16: "fp16",
               SIGNSGD: "signsgd", SIGNUM: "signum", ONEBIT: "onebit", RANDK: "randk"}
 PART_EVEN_COUNT, PART_EVEN_ELEMS, PART_USER = 0, 1, 2
-HDR = 64
+HDR = 128
 
 
 def build(force: bool = False) -> str:
@@ -261,7 +261,7 @@ def f16_bits_to_f32(h: np.ndarray) -> np.ndarray:
     return x
 
 
-# ---- payload views (layout: 64-byte header, then the body) -----------------
+# ---- payload views (layout: 128-byte header, then the body) -----------------
 def header(payload: np.ndarray) -> dict:
     b = payload[:HDR].tobytes()
     return {

@@ -79,7 +79,7 @@ __device__ __forceinline__ void put_plain_header(PayloadHeader *hdr, uint32_t al
 {
     PayloadHeader h;
     h.magic = kMagic; h.algo = algo; h.n = n; h.k = 0; h.scale = scale; h.levels = 0;
-    for (int i = 0; i < 8; ++i) h.pad[i] = 0;
+    for (int i = 0; i < 24; ++i) h.pad[i] = 0;
     *hdr = h;
 }
 
@@ -220,7 +220,7 @@ __global__ __launch_bounds__(kFinalThreads) void scalar_finalize_k(const double 
             const float hi = n_hi > 0.0 ? (float)(S[0] / n_hi) : 0.0f, lo = n_lo > 0.0 ? (float)(S[1] / n_lo) : 0.0f;
             PayloadHeader h;
             h.magic = kMagic; h.algo = algo; h.n = n; h.k = k; h.scale = hi; h.levels = levels;
-            for (int i = 0; i < 8; ++i) h.pad[i] = 0;
+            for (int i = 0; i < 24; ++i) h.pad[i] = 0;
             h.pad[0] = __float_as_uint(lo);
             *hdr = h;
             if (state_scale) { state_scale[0] = hi; state_scale[1] = lo; }
@@ -261,7 +261,7 @@ __global__ __launch_bounds__(kFinalThreads) void scalar_finalize_k(const double 
         if (mode == RED_ONE) scale = 1.0f;
         PayloadHeader h;
         h.magic = kMagic; h.algo = algo; h.n = n; h.k = k; h.scale = scale; h.levels = levels;
-        for (int i = 0; i < 8; ++i) h.pad[i] = 0;
+        for (int i = 0; i < 24; ++i) h.pad[i] = 0;
         *hdr = h;
         if (state_scale) *state_scale = scale;
     }
@@ -863,7 +863,7 @@ __global__ __launch_bounds__(kBlock) void state_convert_k(int algo, int to_resid
 
 void launch_state_convert(const LaunchCtx &lc, int algo, bool to_residual, uint32_t nfloats, const void *src, void *dst)
 {
-    uint32_t work = nfloats > 16 ? nfloats : 16;
+    uint32_t work = nfloats > kHeaderBytes / 4 ? nfloats : kHeaderBytes / 4;     // the header is cleared too
     prof_begin(lc, K_STATE_CONVERT);
     MC_LAUNCH(state_convert_k, dim3((work + kBlock - 1) / kBlock), dim3(kBlock), lc, algo,
                        to_residual ? 1 : 0, nfloats, (const uint8_t *)src, (uint8_t *)dst);

@@ -588,7 +588,7 @@ __global__ __launch_bounds__(kBlock) void cand_emit_k(uint32_t n, uint32_t ntile
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         PayloadHeader h;
         h.magic = kMagic; h.algo = ALGO; h.n = n; h.k = kept; h.scale = 0.0f; h.levels = CAPPED ? (uint32_t)k : 0u;
-        for (int i = 0; i < 8; ++i) h.pad[i] = 0;
+        for (int i = 0; i < 24; ++i) h.pad[i] = 0;
         *hdr = h;
     }
     if (s3.mode & kModeUniform) job.runs = job.tile < ntiles ? uniform_runs(job.tile, n) : 0ull;

@@ -10,24 +10,24 @@
 namespace mc {
 
 constexpr uint32_t kMagic = 0x3150434Du;
-constexpr int kHeaderBytes = 64;
+constexpr int kHeaderBytes = 128;     // bodies of payload and state start on a 128-byte cache line
 constexpr int kMaxWorkers = 64;
 
-struct PayloadHeader {          // 64 bytes, see the layout in mergecomp.h
+struct PayloadHeader {          // one cache line, see the layout in mergecomp.h
     uint32_t magic, algo;
     uint64_t n, k;
     float scale;
     uint32_t levels;
-    uint32_t pad[8];
+    uint32_t pad[24];           // pad[0]: OneBit's mean of the negative class; the rest zero
 };
-static_assert(sizeof(PayloadHeader) == kHeaderBytes, "payload header is 64 bytes");
+static_assert(sizeof(PayloadHeader) == kHeaderBytes, "payload header is one 128-byte line");
 
-struct StateHeader {            // 64 bytes in front of the error-feedback floats
+struct StateHeader {            // one cache line in front of the error-feedback floats
     float scale;                // EF-Sign: scale of the last call; OneBit: mean of its upper class (0 after zero-fill / import)
     float scale_lo;             // OneBit: mean of the lower class of the last call
-    uint32_t pad[14];
+    uint32_t pad[30];
 };
-static_assert(sizeof(StateHeader) == kHeaderBytes, "state header is 64 bytes");
+static_assert(sizeof(StateHeader) == kHeaderBytes, "state header is one 128-byte line");
 
 struct PayloadPtrs { const uint8_t *p[kMaxWorkers]; };
 struct PtrChunk { uintptr_t p[256]; };

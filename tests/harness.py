@@ -78,7 +78,7 @@ def check_payload(algo: str, gpay: np.ndarray, opay: np.ndarray, what: str) -> b
     gh, oh = O.header(gpay), O.header(opay)
     for key in ("magic", "algo", "n", "k", "levels"):
         assert gh[key] == oh[key], f"{what}: header field {key}: gpu {gh[key]} oracle {oh[key]}"
-    assert not gpay[36 if algo == "onebit" else 32:64].any(), f"{what}: header padding not zero"
+    assert not gpay[36 if algo == "onebit" else 32:O.HDR].any(), f"{what}: header padding not zero"
     gs, os_ = np.float32(gh["scale"]), np.float32(oh["scale"])
     if algo == "onebit":                         # two scalars: the class means
         g2, o2 = np.float32(gh["scale2"]), np.float32(oh["scale2"])
@@ -120,7 +120,7 @@ def run_parity(numel: Sequence[int], algo: str, y: int, W: int, iters: int,
     for j in range(y):
         assert ctx.group_numel(j) == gn[j]
         assert ctx.payload_bytes(j) == O.payload_bytes(ocfg, gn[j])
-        assert ctx.state_bytes(j) == 64 + 4 * O.state_floats(ocfg, gn[j])
+        assert ctx.state_bytes(j) == O.HDR + 4 * O.state_floats(ocfg, gn[j])
         assert ctx.group_k(j) == (O.sparse_capacity(ocfg, gn[j]) if algo in ("topk", "dgc", "randk") else 0)
 
     gstate = [[torch.zeros(ctx.state_bytes(j), dtype=torch.uint8, device=DEV) if ef else None for j in range(y)] for _ in workers]

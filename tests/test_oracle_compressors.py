@@ -178,7 +178,7 @@ def test_topk_without_error_feedback_and_empty_group():
     idx, val = O.sparse_view(pay)
     assert np.array_equal(idx, argsort_topk(g, 50)) and np.array_equal(val, g[idx])
     pay, _ = O.compress(O.Config(O.TOPK), np.zeros(0, np.float32), np.zeros(0, np.float32))
-    assert pay.size == 64 and O.header(pay)["k"] == 0 and O.header(pay)["n"] == 0
+    assert pay.size == O.HDR and O.header(pay)["k"] == 0 and O.header(pay)["n"] == 0
 
 
 # ================================================================== DGC =====
@@ -368,7 +368,7 @@ def test_fp16_compress_residual_exact():
     st = e0.copy()
     pay, _ = O.compress(O.Config(O.FP16), g, st)
     p = g + e0
-    assert pay.size == 64 + (2 * n + 3) // 4 * 4
+    assert pay.size == O.HDR + (2 * n + 3) // 4 * 4
     h = pay[O.HDR:O.HDR + 2 * n].view(np.float16)
     assert np.array_equal(h.view(np.uint16), p.astype(np.float16).view(np.uint16))
     d = O.decode(pay, n)

@@ -144,7 +144,7 @@ def test_onebit_means_and_reconstruction(n):
     d = O.decode(pay, n)
     assert np.array_equal(d, np.where(pos, np.float32(h["scale"]), np.float32(h["scale2"])))
     assert np.array_equal(st, p - d)                   # residual: one fp32 subtraction
-    assert not pay[36:64].any()                        # rest of the header stays zero
+    assert not pay[36:O.HDR].any()                        # rest of the header stays zero
 
 
 def test_onebit_class_means_preserve_the_sum_and_minimise_the_error():

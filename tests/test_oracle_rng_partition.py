@@ -160,7 +160,7 @@ def test_payload_sizes_follow_paper_settings(golden_dir):
     n = WL.workload(2).total
     ppm = (100 - f["sparsity_percent"]) * 10000
     assert O.topk_count(n, ppm) == n // 100
-    assert O.payload_bytes(O.Config(O.QSGD, qsgd_bits=f["qsgd_bits_per_element"]), n) == 64 + n  # 8 bits / element
-    assert O.payload_bytes(O.Config(O.EFSIGN), n) == 64 + 4 * ((n + 31) // 32)                 # 1 bit / element
-    assert O.payload_bytes(O.Config(O.TOPK, ratio_ppm=ppm), n) == 64 + 8 * (n // 100)
+    assert O.payload_bytes(O.Config(O.QSGD, qsgd_bits=f["qsgd_bits_per_element"]), n) == O.HDR + n  # 8 bits / element
+    assert O.payload_bytes(O.Config(O.EFSIGN), n) == O.HDR + 4 * ((n + 31) // 32)                 # 1 bit / element
+    assert O.payload_bytes(O.Config(O.TOPK, ratio_ppm=ppm), n) == O.HDR + 8 * (n // 100)
     assert O.topk_count(50, 10000) == 1 and O.topk_count(0, 10000) == 0 and O.topk_count(3, 10 ** 6) == 3
