@@ -840,15 +840,18 @@ void launch_dense_decompress(const LaunchCtx &lc, int algo, const GroupView &out
 // the residual itself (p and the scalars of the last call); the other algorithms
 // copy (SigNUM: the momentum).
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void state_convert_k(int algo, int to_residual, uint32_t nfloats, const uint8_t *src, uint8_t *dst)
+__global__ __launch_bounds__(kBlock) void state_convert_k(int algo, int to_residual, uint32_t n, const uint8_t *src, uint8_t *dst)
 {
-    uint32_t i = blockIdx.x * kBlock + threadIdx.x;
+    // plain side: n floats (DGC: v[n] then u[n]); opaque side: header, then the same floats (DGC: u from dgc_u_offset(n))
+    const size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    const size_t nfloats = algo == MC_ALGO_DGC ? 2 * (size_t)n : (size_t)n;
+    const size_t at = algo == MC_ALGO_DGC && i >= n ? dgc_u_offset(n) + (i - n) : i;      // where float i lives in the state
     if (to_residual) {
         const StateHeader *h = reinterpret_cast<const StateHeader *>(src);
         const float *f = reinterpret_cast<const float *>(src + kHeaderBytes);
         float *e = reinterpret_cast<float *>(dst);
         if (i < nfloats) {
-            float v = f[i];
+            float v = f[at];
             if (algo == MC_ALGO_EFSIGN) { float sp = h->scale; v = v - (v >= 0.0f ? sp : -sp); }
             if (algo == MC_ALGO_ONEBIT) v = v - (v >= 0.0f ? h->scale : h->scale_lo);
             e[i] = v;
@@ -856,17 +859,19 @@ __global__ __launch_bounds__(kBlock) void state_convert_k(int algo, int to_resid
     } else {
         const float *e = reinterpret_cast<const float *>(src);
         float *f = reinterpret_cast<float *>(dst + kHeaderBytes);
-        if (i < nfloats) f[i] = e[i];       // EF-Sign, OneBit: p = e with scalars 0 re-derives exactly e
+        if (i < nfloats) f[at] = e[i];       // EF-Sign, OneBit: p = e with scalars 0 re-derives exactly e
         if (i < kHeaderBytes / 4) reinterpret_cast<uint32_t *>(dst)[i] = 0u;
+        if (algo == MC_ALGO_DGC && i >= n && i < dgc_u_offset(n)) f[i] = 0.0f;            // the gap between v and u
     }
 }
 
-void launch_state_convert(const LaunchCtx &lc, int algo, bool to_residual, uint32_t nfloats, const void *src, void *dst)
+void launch_state_convert(const LaunchCtx &lc, int algo, bool to_residual, uint32_t n, const void *src, void *dst)
 {
-    uint32_t work = nfloats > kHeaderBytes / 4 ? nfloats : kHeaderBytes / 4;     // the header is cleared too
+    const size_t nfloats = algo == MC_ALGO_DGC ? 2 * (size_t)n : (size_t)n;
+    const size_t work = nfloats > (size_t)kHeaderBytes / 4 ? nfloats : (size_t)kHeaderBytes / 4;     // the header is cleared too
     prof_begin(lc, K_STATE_CONVERT);
-    MC_LAUNCH(state_convert_k, dim3((work + kBlock - 1) / kBlock), dim3(kBlock), lc, algo,
-                       to_residual ? 1 : 0, nfloats, (const uint8_t *)src, (uint8_t *)dst);
+    MC_LAUNCH(state_convert_k, dim3((uint32_t)((work + kBlock - 1) / kBlock)), dim3(kBlock), lc, algo,
+                       to_residual ? 1 : 0, n, (const uint8_t *)src, (uint8_t *)dst);
     prof_end(lc, K_STATE_CONVERT);
 }
 

@@ -128,7 +128,7 @@ __global__ __launch_bounds__(kBlock) void sparse_accum_k(GroupView g, float *st,
         float p[kSteps];
         if (ALGO == MC_ALGO_DGC) {
             // momentum correction: u = m u + g ; v = v + u ; the vector compressed is v
-            float *vbuf = st, *ubuf = st + g.n;
+            float *vbuf = st, *ubuf = st + dgc_u_offset(g.n);
             float u[kSteps], v[kSteps];
             load_flat(ubuf, c, g.n, u, 0.0f);
             load_flat(vbuf, c, g.n, v, 0.0f);
@@ -604,7 +604,7 @@ __global__ __launch_bounds__(kBlock) void cand_emit_k(uint32_t n, uint32_t ntile
                 idx[pos] = i;
                 if (ALGO == MC_ALGO_RANDK) val[pos] = st[i];      // the candidate slot holds the random key: the value is p
                 else val[pos] = __uint_as_float(b);
-                if (ALGO == MC_ALGO_DGC) { st[i] = 0.0f; st[(size_t)n + i] = 0.0f; }   // momentum factor masking
+                if (ALGO == MC_ALGO_DGC) { st[i] = 0.0f; st[dgc_u_offset(n) + i] = 0.0f; }   // momentum factor masking
                 else if (EF) st[i] = 0.0f;
             }
         }

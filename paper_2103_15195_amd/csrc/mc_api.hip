@@ -445,6 +445,7 @@ size_t mc_state_bytes(const mc_ctx *ctx, int32_t group)
 {
     const Group *g = group_of(ctx, group);
     if (!g) return 0;
+    if (ctx->cfg.algo == MC_ALGO_DGC) return kHeaderBytes + sizeof(float) * (dgc_u_offset(g->n) + (size_t)g->n);
     return kHeaderBytes + sizeof(float) * (size_t)g->n * state_vectors(ctx->cfg.algo);
 }
 
@@ -597,13 +598,13 @@ static int state_convert(mc_ctx *ctx, int32_t group, const void *src, void *dst,
 {
     const Group *g = group_of(ctx, group);
     if (!g) return MC_ERR_INVALID_ARG;
-    const uint32_t nf = g->n * state_vectors(ctx->cfg.algo);
+    const size_t nf = (size_t)g->n * state_vectors(ctx->cfg.algo);
     // an empty group has no residual: the plain side may be null, the opaque side never
     if (!(to_residual ? src : dst) || (nf > 0 && !(to_residual ? dst : src))) return MC_ERR_INVALID_ARG;
     if (nf == 0 && to_residual) return MC_OK;
     LaunchCtx lc{static_cast<hipStream_t>(stream), &ctx->prof, nullptr, nullptr};
     (void)hipGetLastError();
-    launch_state_convert(lc, ctx->cfg.algo, to_residual, nf, src, dst);
+    launch_state_convert(lc, ctx->cfg.algo, to_residual, g->n, src, dst);
     return check_launch();
 }
 

@@ -29,6 +29,10 @@ struct StateHeader {            // one cache line in front of the error-feedback
 };
 static_assert(sizeof(StateHeader) == kHeaderBytes, "state header is one 128-byte line");
 
+// DGC keeps two vectors in the state: v[n] first, then u[n] from the next multiple of 32 floats on, so that both start
+// on a 128-byte line (a chunk's stores then cover whole lines).
+__host__ __device__ inline size_t dgc_u_offset(uint32_t n) { return ((size_t)n + 31u) & ~(size_t)31u; }
+
 struct PayloadPtrs { const uint8_t *p[kMaxWorkers]; };
 struct PtrChunk { uintptr_t p[256]; };
 
@@ -83,7 +87,7 @@ void launch_fp16_compress(const LaunchCtx &lc, const GroupView &g, bool ef, floa
                           uint16_t *halves);
 void launch_dense_decompress(const LaunchCtx &lc, int algo, const GroupView &out, const PayloadPtrs &pl, int W,
                              float alpha, uint32_t levels, int *status, float *tern_table);
-void launch_state_convert(const LaunchCtx &lc, int algo, bool to_residual, uint32_t nfloats, const void *src, void *dst);
+void launch_state_convert(const LaunchCtx &lc, int algo, bool to_residual, uint32_t n, const void *src, void *dst);
 
 // ---- sparse kernels (kernels_sparse.hip) ----------------------------------------
 constexpr int kHintWorkers = 64;                         // hints kept per group, one per worker id modulo this

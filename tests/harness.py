@@ -120,7 +120,8 @@ def run_parity(numel: Sequence[int], algo: str, y: int, W: int, iters: int,
     for j in range(y):
         assert ctx.group_numel(j) == gn[j]
         assert ctx.payload_bytes(j) == O.payload_bytes(ocfg, gn[j])
-        assert ctx.state_bytes(j) == O.HDR + 4 * O.state_floats(ocfg, gn[j])
+        pad = (-gn[j]) % 32 if algo == "dgc" else 0          # DGC's second vector starts on a 128-byte line
+        assert ctx.state_bytes(j) == O.HDR + 4 * (O.state_floats(ocfg, gn[j]) + pad)
         assert ctx.group_k(j) == (O.sparse_capacity(ocfg, gn[j]) if algo in ("topk", "dgc", "randk") else 0)
 
     gstate = [[torch.zeros(ctx.state_bytes(j), dtype=torch.uint8, device=DEV) if ef else None for j in range(y)] for _ in workers]
