@@ -518,19 +518,69 @@ __device__ __forceinline__ void check_header(const PayloadHeader *h, uint32_t al
 // Workers are taken in batches: all loads of a batch (header scalars and codes)
 // are issued before the first is used, so a wavefront pays the HBM latency once
 // per batch instead of once per worker.
+//
+// Two lane mappings.  Wide (QSGD, a full chunk inside one tensor whose address is 16-byte aligned):
+// lane l holds four consecutive elements in each of four steps, element (256 m + 4 l + rot) mod 1024
+// onward, so the codes of a worker arrive in 4 loads of 4 bytes per lane instead of 16 loads of one
+// byte, and the sums leave as 16-byte stores; rot puts the stores on the output's 128-byte lines.
+// Plain (FP16, and any other chunk): the usual element 64 j + l per step.  The work is elementwise,
+// so the mapping changes no result: every element still adds its workers' values in worker order.
+// (Measured, 8 workers, 25.6 M elements: QSGD 62.9 -> 54.6 us.  The same mapping with 8-byte loads
+// made FP16 slower, 80.3 -> 82.5..85 us with 2, 4 or 8 workers per batch, so FP16 stays plain.)
+typedef float float4v __attribute__((ext_vector_type(4)));
+
 template <int ALGO>
 __global__ __launch_bounds__(kBlock) void dense_decompress_k(GroupView out, PayloadPtrs pl, int W, float alpha,
                                                              uint32_t levels, int *status)
 {
-    constexpr int kBatch = (ALGO == MC_ALGO_EFSIGN || ALGO == MC_ALGO_TERNGRAD) ? 8 : 4;
+    static_assert(ALGO == MC_ALGO_QSGD || ALGO == MC_ALGO_FP16, "one code per element");
+    constexpr int kBatch = 4;
     const Chunk c = my_chunk(out.n);
     if (blockIdx.x == 0 && (int)threadIdx.x < W)
         check_header(reinterpret_cast<const PayloadHeader *>(pl.p[threadIdx.x]), ALGO, out.n, status);
     if (c.base >= out.n) return;
-    const uint32_t nwords = (out.n + 31u) >> 5;
-    const uint32_t wi = (c.base >> 5) + (c.lane & 31u);      // bit planes: lanes 0..31 hold the chunk's 32 words
-    const uint32_t sh = c.lane & 31u;
-    const bool upper = c.lane >= 32;
+    const uintptr_t direct = chunk_direct(out, c);
+    if (ALGO == MC_ALGO_QSGD && direct && !(direct & 15u)) {
+        const uint32_t rot = chunk_rotation(direct);            // a multiple of 4 here
+        uint32_t at[4];                                         // first of the lane's four elements in step m
+#pragma unroll
+        for (int m = 0; m < 4; ++m) at[m] = (256u * m + 4u * c.lane + rot) & (uint32_t)(kChunk - 1);
+        float acc[4][4];
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[m][e] = 0.0f;
+        for (int w0 = 0; w0 < W; w0 += kBatch) {
+            float scale[kBatch];
+#pragma unroll
+            for (int b = 0; b < kBatch; ++b)
+                scale[b] = w0 + b < W ? reinterpret_cast<const PayloadHeader *>(pl.p[w0 + b])->scale : 0.0f;
+            uint32_t cw[kBatch][4];
+#pragma unroll
+            for (int b = 0; b < kBatch; ++b) {
+                const uint8_t *codes = pl.p[w0 + b < W ? w0 + b : 0] + kHeaderBytes + c.base;
+#pragma unroll
+                for (int m = 0; m < 4; ++m) cw[b][m] = w0 + b < W ? ld_stream(reinterpret_cast<const uint32_t *>(codes + at[m])) : 0u;
+            }
+#pragma unroll
+            for (int b = 0; b < kBatch; ++b) {
+                if (w0 + b < W) {
+                    const float q = (float)((double)scale[b] / (double)(float)levels);
+#pragma unroll
+                    for (int m = 0; m < 4; ++m)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[m][e] = acc[m][e] + (float)(int8_t)(cw[b][m] >> (8 * e)) * q;
+                }
+            }
+        }
+        float *p = reinterpret_cast<float *>(direct);
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            float4v v = {alpha * acc[m][0], alpha * acc[m][1], alpha * acc[m][2], alpha * acc[m][3]};
+            __builtin_nontemporal_store(v, reinterpret_cast<float4v *>(p + at[m]));
+        }
+        return;
+    }
     float acc[kSteps];
 #pragma unroll
     for (int j = 0; j < kSteps; ++j) acc[j] = 0.0f;
@@ -539,50 +589,7 @@ __global__ __launch_bounds__(kBlock) void dense_decompress_k(GroupView out, Payl
 #pragma unroll
         for (int b = 0; b < kBatch; ++b)
             scale[b] = w0 + b < W ? reinterpret_cast<const PayloadHeader *>(pl.p[w0 + b])->scale : 0.0f;
-        if (ALGO == MC_ALGO_EFSIGN) {
-            uint32_t mine[kBatch];
-#pragma unroll
-            for (int b = 0; b < kBatch; ++b) {
-                mine[b] = 0u;
-                if (w0 + b < W && wi < nwords)
-                    mine[b] = ld_stream(reinterpret_cast<const uint32_t *>(pl.p[w0 + b] + kHeaderBytes) + wi);
-            }
-#pragma unroll
-            for (int b = 0; b < kBatch; ++b) {
-                if (w0 + b < W) {
-#pragma unroll
-                    for (int j = 0; j < kSteps; ++j) {
-                        uint32_t lo = __builtin_amdgcn_readlane(mine[b], 2 * j), hi = __builtin_amdgcn_readlane(mine[b], 2 * j + 1);
-                        float d = (((upper ? hi : lo) >> sh) & 1u) ? scale[b] : -scale[b];
-                        acc[j] = acc[j] + d;
-                    }
-                }
-            }
-        } else if (ALGO == MC_ALGO_TERNGRAD) {
-            uint32_t mnz[kBatch], mng[kBatch];
-#pragma unroll
-            for (int b = 0; b < kBatch; ++b) {
-                mnz[b] = 0u; mng[b] = 0u;
-                if (w0 + b < W && wi < nwords) {
-                    const uint32_t *nzp = reinterpret_cast<const uint32_t *>(pl.p[w0 + b] + kHeaderBytes);
-                    mnz[b] = ld_stream(nzp + wi);
-                    mng[b] = ld_stream(nzp + nwords + wi);
-                }
-            }
-#pragma unroll
-            for (int b = 0; b < kBatch; ++b) {
-                if (w0 + b < W) {
-#pragma unroll
-                    for (int j = 0; j < kSteps; ++j) {
-                        uint32_t nzl = __builtin_amdgcn_readlane(mnz[b], 2 * j), nzh = __builtin_amdgcn_readlane(mnz[b], 2 * j + 1);
-                        uint32_t ngl = __builtin_amdgcn_readlane(mng[b], 2 * j), ngh = __builtin_amdgcn_readlane(mng[b], 2 * j + 1);
-                        uint32_t nz = ((upper ? nzh : nzl) >> sh) & 1u, ng = ((upper ? ngh : ngl) >> sh) & 1u;
-                        float d = nz ? (ng ? -scale[b] : scale[b]) : 0.0f;
-                        acc[j] = acc[j] + d;
-                    }
-                }
-            }
-        } else if (ALGO == MC_ALGO_QSGD) {
+        if (ALGO == MC_ALGO_QSGD) {
             int8_t cd[kBatch][kSteps];
 #pragma unroll
             for (int b = 0; b < kBatch; ++b) {
@@ -613,7 +620,7 @@ __global__ __launch_bounds__(kBlock) void dense_decompress_k(GroupView out, Payl
     }
 #pragma unroll
     for (int j = 0; j < kSteps; ++j) acc[j] = alpha * acc[j];
-    store_seg(out, c, acc);
+    store_seg(out, c, acc, direct);
 }
 
 // ---------------------------------------------------------------------------
