@@ -53,7 +53,7 @@ CALL_BYTES = {
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None = not measured
 MEASURED_TRAFFIC = {        # profiles/bench_resnet50_efsign_topk.txt, read + write, scaled by the copy calibration
-    "efsign_compress": 316.22e6, "sparse_accum": 329.60e6, "dense_decompress": 133.28e6, "sparse_decompress": 135.53e6,
+    "efsign_compress": 313.61e6, "sparse_accum": 323.16e6, "dense_decompress": 128.44e6, "sparse_decompress": 136.12e6,
 }
 
 
