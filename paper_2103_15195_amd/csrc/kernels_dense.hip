@@ -659,32 +659,12 @@ __device__ __forceinline__ uint64_t gather_transpose(const uint32_t (&wd)[8], in
     return transpose8x8((uint64_t)lo | ((uint64_t)hi << 32));
 }
 
-constexpr int kTernCombos = 6561;          // 3^8 ternary digits of 8 workers
-
-// TERN = false: EF-Sign (one plane, 2^8 sums).  TERN = true: TernGrad (non-zero and negative planes;
-// a worker contributes 0, +s or -s, so the first 8 workers have 3^8 possible sums; the index is
-// sum_w digit_w 3^w with digit = nz + (nz & neg), formed from two small lookups of the bit bytes).
-// The 3^8 sums of the first (up to) 8 TernGrad workers, tabulated once per call: every entry is
-// the same sequence of fp32 additions ((0 + d_0) + d_1) + ... a per-element loop would perform.
-__global__ __launch_bounds__(kBlock) void tern_table_k(PayloadPtrs pl, int W, float alpha, float *table)
-{
-    const int Wt = W < 8 ? W : 8;
-    float sc[8];
-#pragma unroll
-    for (int b = 0; b < 8; ++b) sc[b] = b < Wt ? reinterpret_cast<const PayloadHeader *>(pl.p[b])->scale : 0.0f;
-    for (uint32_t idx = blockIdx.x * kBlock + threadIdx.x; idx < (uint32_t)kTernCombos; idx += gridDim.x * kBlock) {
-        float acc = 0.0f;
-        uint32_t rest = idx;
-#pragma unroll
-        for (int b = 0; b < 8; ++b) {
-            const uint32_t digit = rest % 3u;       // 0: nothing, 1: +s, 2: -s
-            rest /= 3u;
-            if (b < Wt) acc = acc + (digit == 0 ? 0.0f : digit == 1 ? sc[b] : -sc[b]);
-        }
-        table[idx] = W <= 8 ? alpha * acc : acc;
-    }
-}
-
+// TERN = false: the one-plane schemes (2^8 sums of the first 8 workers' +-level).  TERN = true: TernGrad
+// (non-zero and negative planes; a worker contributes 0, +s or -s): the table holds the 2^8 possible sums
+// of workers 0..3, indexed by their four non-zero and four negative bits, and workers 4..7 are added one
+// by one, so that every element sees the sequence of fp32 additions ((0 + d_0) + d_1) + ... of a plain
+// loop.  (A table of all 3^8 sums of 8 workers needs 26 KB of LDS per block and a kernel of its own to
+// fill it, and measured slower.)
 // what a set / clear bit of worker w decodes to (one-plane schemes)
 __device__ __forceinline__ void plane_levels(const PayloadHeader *h, int kind, float &hi, float &lo)
 {
@@ -698,10 +678,9 @@ __device__ __forceinline__ float vote_of(float tally) { return tally > 0.0f ? 1.
 //                                PLANE_VOTE   SignSGD / SigNUM, to +-1, and the sum becomes its sign (majority vote)
 template <bool TERN>
 __global__ __launch_bounds__(kBlock) void plane_decompress_k(GroupView out, PayloadPtrs pl, int W, float alpha, int *status,
-                                                             const float *tern_table, int algo, int kind)
+                                                             int algo, int kind)
 {
-    __shared__ float table[TERN ? kTernCombos : 256];
-    __shared__ uint16_t pow3[TERN ? 256 : 1];             // pow3[b] = sum over set bits w of b of 3^w
+    __shared__ float table[256];
     __shared__ float stage[kWavesPerBlock][kChunk + 32];
     const uint32_t t = threadIdx.x;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(t >> 6), lane = t & 63u;
@@ -722,17 +701,22 @@ __global__ __launch_bounds__(kBlock) void plane_decompress_k(GroupView out, Payl
             if (W <= 8 && kind == PLANE_VOTE) acc = vote_of(acc);
             table[t] = W <= 8 ? alpha * acc : acc;
         } else {
-            uint32_t p3 = 0, pw = 1;
+            // entry (nz bits of workers 0..3) | (negative bits of workers 0..3) << 4: their sum, in worker order
+            float acc = 0.0f;
 #pragma unroll
-            for (int b = 0; b < 8; ++b) { if ((t >> b) & 1u) p3 += pw; pw *= 3u; }
-            pow3[t] = (uint16_t)p3;
-            constexpr int kPer = (kTernCombos + kBlock - 1) / kBlock;
-            float v[kPer];
-#pragma unroll
-            for (int i = 0; i < kPer; ++i) v[i] = t + i * kBlock < (uint32_t)kTernCombos ? tern_table[t + i * kBlock] : 0.0f;
-#pragma unroll
-            for (int i = 0; i < kPer; ++i) if (t + i * kBlock < (uint32_t)kTernCombos) table[t + i * kBlock] = v[i];
+            for (int b = 0; b < 4; ++b) {
+                if (b < Wt) {
+                    const float sc = reinterpret_cast<const PayloadHeader *>(pl.p[b])->scale;
+                    acc = acc + (((t >> b) & 1u) ? (((t >> (4 + b)) & 1u) ? -sc : sc) : 0.0f);
+                }
+            }
+            table[t] = acc;
         }
+    }
+    float s47[4] = {0.0f, 0.0f, 0.0f, 0.0f};               // TernGrad: scales of workers 4..7, added one by one
+    if (TERN) {
+#pragma unroll
+        for (int b = 4; b < 8; ++b) if (b < Wt) s47[b - 4] = reinterpret_cast<const PayloadHeader *>(pl.p[b])->scale;
     }
     __syncthreads();
     const uint32_t wbase = blockIdx.x * (uint32_t)kSignTile + wave * (uint32_t)kSignWaveElems;
@@ -760,8 +744,18 @@ __global__ __launch_bounds__(kBlock) void plane_decompress_k(GroupView out, Payl
         } else {
             const uint64_t y = gather_transpose(wn, q) & x;           // negative only counts where non-zero
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                acc[8 * q + e] = table[(uint32_t)pow3[(uint32_t)(x >> (8 * e)) & 0xFFu] + pow3[(uint32_t)(y >> (8 * e)) & 0xFFu]];
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t xe = (uint32_t)(x >> (8 * e)) & 0xFFu, ye = (uint32_t)(y >> (8 * e)) & 0xFFu;
+                float a = table[(xe & 15u) | ((ye & 15u) << 4)];
+#pragma unroll
+                for (int b = 4; b < 8; ++b) {
+                    if (b < Wt) {
+                        const float sc = s47[b - 4];
+                        a = a + (((xe >> b) & 1u) ? (((ye >> b) & 1u) ? -sc : sc) : 0.0f);
+                    }
+                }
+                acc[8 * q + e] = a;
+            }
         }
     }
     if (W > 8) {
@@ -780,6 +774,8 @@ __global__ __launch_bounds__(kBlock) void plane_decompress_k(GroupView out, Payl
                 acc[e] = acc[e] + d;
             }
         }
+    }
+    if (W > 8 || TERN) {
 #pragma unroll
         for (int e = 0; e < 32; ++e) acc[e] = alpha * (!TERN && kind == PLANE_VOTE ? vote_of(acc[e]) : acc[e]);
     }
@@ -800,7 +796,7 @@ __global__ __launch_bounds__(kBlock) void plane_decompress_k(GroupView out, Payl
         c.full = c.base < out.n && out.n - c.base >= (uint32_t)kChunk;
         if (c.base < out.n) {
             const uintptr_t direct = chunk_direct(out, c);
-            const uint32_t rot = TERN ? 0u : chunk_rotation(direct);     // measured: pays for the one-plane schemes only
+            const uint32_t rot = TERN ? 0u : chunk_rotation(direct);     // measured: no gain for TernGrad, whose decode is bound by the vector ALU
             float v[kSteps];
 #pragma unroll
             for (int j = 0; j < kSteps; ++j) {
@@ -813,15 +809,10 @@ __global__ __launch_bounds__(kBlock) void plane_decompress_k(GroupView out, Payl
 }
 
 void launch_dense_decompress(const LaunchCtx &lc, int algo, const GroupView &out, const PayloadPtrs &pl, int W,
-                             float alpha, uint32_t levels, int *status, float *tern_table)
+                             float alpha, uint32_t levels, int *status)
 {
     if (out.n == 0) return;
     dim3 grid(tiles_of(out.n)), block(kBlock);
-    if (algo == MC_ALGO_TERNGRAD) {
-        prof_begin(lc, K_TERN_TABLE);
-        MC_LAUNCH(tern_table_k, dim3(8), block, lc, pl, W, alpha, tern_table);
-        prof_end(lc, K_TERN_TABLE);
-    }
     prof_begin(lc, K_DENSE_DECOMPRESS);
     switch (algo) {
     case MC_ALGO_EFSIGN:
@@ -829,12 +820,12 @@ void launch_dense_decompress(const LaunchCtx &lc, int algo, const GroupView &out
     case MC_ALGO_SIGNSGD:
     case MC_ALGO_SIGNUM:
         MC_LAUNCH(plane_decompress_k<false>, dim3((uint32_t)(((uint64_t)out.n + kSignTile - 1) / kSignTile)), block, lc, out, pl, W,
-                  alpha, status, tern_table, algo,
+                  alpha, status, algo,
                   algo == MC_ALGO_EFSIGN ? PLANE_SCALE : algo == MC_ALGO_ONEBIT ? PLANE_MEANS : PLANE_VOTE);
         break;
     case MC_ALGO_TERNGRAD:
         MC_LAUNCH(plane_decompress_k<true>, dim3((uint32_t)(((uint64_t)out.n + kSignTile - 1) / kSignTile)), block, lc, out, pl, W,
-                  alpha, status, tern_table, algo, PLANE_SCALE);
+                  alpha, status, algo, PLANE_SCALE);
         break;
     case MC_ALGO_QSGD: MC_LAUNCH(dense_decompress_k<MC_ALGO_QSGD>, grid, block, lc, out, pl, W, alpha, levels, status); break;
     default: MC_LAUNCH(dense_decompress_k<MC_ALGO_FP16>, grid, block, lc, out, pl, W, alpha, levels, status); break;

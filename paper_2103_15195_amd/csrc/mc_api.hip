@@ -58,7 +58,6 @@ struct mc_ctx {
     SparseScratch sparse{};
     uint32_t *d_hints = nullptr;        // candidate-filter hints: kHintWorkers per group (worker id modulo that)
     int *d_status = nullptr;
-    float *d_tern_table = nullptr;      // TernGrad: the 3^8 sums of the first 8 workers of the current decompress call
     std::vector<PtrSlot> slots;
     uint64_t clock = 0;
     uint32_t epoch = 0;                 // stamps the sparse decompress tile table; 0 is never used
@@ -99,7 +98,7 @@ void prof_end(const LaunchCtx &lc, int id)
 static const char *kKernelNames[K_COUNT] = {
     "upload_ptrs", "efsign_compress", "scalar_finalize", "accum_reduce", "qsgd_encode", "tern_encode",
     "fp16_compress", "dense_decompress", "sparse_accum", "sparse_seed", "cand_hist2", "cand_hist3", "cand_count",
-    "cand_emit", "sparse_index", "sparse_decompress", "state_convert", "tern_table"};
+    "cand_emit", "sparse_index", "sparse_decompress", "state_convert"};
 
 static void prof_drain(Profiler &p)
 {
@@ -302,7 +301,6 @@ int mc_ctx_destroy(mc_ctx *ctx)
                            ctx->sparse.tile_last};
     for (void *b : sparse_bufs) if (b) (void)hipFree(b);
     if (ctx->d_status) (void)hipFree(ctx->d_status);
-    if (ctx->d_tern_table) (void)hipFree(ctx->d_tern_table);
     if (switched) (void)hipSetDevice(prev);
     delete ctx;
     return MC_OK;
@@ -374,7 +372,6 @@ int mc_ctx_create(mc_ctx **out, const mc_config *cfg, const int64_t *numel, int3
         if (rc == MC_OK && hipMalloc(&ctx->d_partial, 3 * tiles * sizeof(double)) != hipSuccess) rc = MC_ERR_ALLOC;
         if (rc == MC_OK && hipMalloc(&ctx->d_status, sizeof(int)) != hipSuccess) rc = MC_ERR_ALLOC;
         if (rc == MC_OK && hipMemset(ctx->d_status, 0, sizeof(int)) != hipSuccess) rc = MC_ERR_DEVICE;
-        if (rc == MC_OK && cfg->algo == MC_ALGO_TERNGRAD && hipMalloc(&ctx->d_tern_table, 6561 * sizeof(float)) != hipSuccess) rc = MC_ERR_ALLOC;
         if (rc == MC_OK && is_sparse(cfg->algo)) {
             SparseScratch &sp = ctx->sparse;
             const size_t hist_bytes = kHistWords * sizeof(uint32_t);
@@ -589,7 +586,7 @@ int mc_decompress_sum(mc_ctx *ctx, int32_t group, const void *const *payloads, i
                                                     ctx->sparse.tile_last, ctx->d_status, cfg.dgc_sample_ppm != 0);
     else {
         const uint32_t levels = cfg.algo == MC_ALGO_QSGD ? (1u << (cfg.qsgd_bits - 1)) - 1u : 0u;
-        launch_dense_decompress(lc, cfg.algo, gv, pl, W, alpha, levels, ctx->d_status, ctx->d_tern_table);
+        launch_dense_decompress(lc, cfg.algo, gv, pl, W, alpha, levels, ctx->d_status);
     }
     return check_launch();
 }

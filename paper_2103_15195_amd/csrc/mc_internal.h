@@ -47,7 +47,7 @@ struct SelectState {
 enum KernelId {
     K_UPLOAD = 0, K_EFSIGN_COMPRESS, K_SCALAR_FINALIZE, K_ACCUM_REDUCE, K_QSGD_ENCODE, K_TERN_ENCODE,
     K_FP16_COMPRESS, K_DENSE_DECOMPRESS, K_SPARSE_ACCUM, K_SPARSE_SEED, K_CAND_HIST2, K_CAND_HIST3, K_CAND_COUNT,
-    K_CAND_EMIT, K_SPARSE_INDEX, K_SPARSE_DECOMPRESS, K_STATE_CONVERT, K_TERN_TABLE, K_COUNT
+    K_CAND_EMIT, K_SPARSE_INDEX, K_SPARSE_DECOMPRESS, K_STATE_CONVERT, K_COUNT
 };
 
 // reduction kinds of the two-pass quantizers
@@ -86,7 +86,7 @@ void launch_tern_encode(const LaunchCtx &lc, const GroupView &g, bool ef, float 
 void launch_fp16_compress(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, PayloadHeader *hdr,
                           uint16_t *halves);
 void launch_dense_decompress(const LaunchCtx &lc, int algo, const GroupView &out, const PayloadPtrs &pl, int W,
-                             float alpha, uint32_t levels, int *status, float *tern_table);
+                             float alpha, uint32_t levels, int *status);
 void launch_state_convert(const LaunchCtx &lc, int algo, bool to_residual, uint32_t n, const void *src, void *dst);
 
 // ---- sparse kernels (kernels_sparse.hip) ----------------------------------------
