@@ -34,7 +34,7 @@ void launch_upload_ptrs(const LaunchCtx &lc, const uintptr_t *host, uintptr_t *d
 }
 
 // Per-chunk address table of a freshly uploaded tensor address list: the address of
-// the chunk's first element when all 1024 elements lie in one tensor, else 0.
+// the chunk's first element when all 1024 elements lie in one tensor, else 2 s + 1 with s the tensor of its first element.
 __global__ __launch_bounds__(kBlock) void expand_ptrs_k(GroupView g, uintptr_t *chunk_addr)
 {
     const uint32_t nchunks = (g.n + (uint32_t)kChunk - 1u) / (uint32_t)kChunk;
@@ -43,7 +43,7 @@ __global__ __launch_bounds__(kBlock) void expand_ptrs_k(GroupView g, uintptr_t *
     const uint32_t base = c * (uint32_t)kChunk;
     const uint32_t s = g.chunk_seg[c];
     const uint32_t beg = g.seg_off[s], end = g.seg_off[s + 1];
-    uintptr_t a = 0;
+    uintptr_t a = ((uintptr_t)s << 1) | 1u;            // not an address: where the loop over the chunk's tensors starts
     if (g.n - base >= (uint32_t)kChunk && end - base >= (uint32_t)kChunk) a = g.ptrs[s] + (uintptr_t)(base - beg) * sizeof(float);
     chunk_addr[c] = a;
 }
@@ -139,13 +139,13 @@ __global__ __launch_bounds__(kBlock) void sign_compress_k(GroupView g, float *st
     }
     if (MODE == SIGN_EF || MODE == SIGN_MEANS) {
         double t = block_sum(acc, red);
-        if (threadIdx.x == 0) partial[blockIdx.x] = t;
+        if (threadIdx.x == 0) partial[my_tile_index()] = t;
     }
     if (MODE == SIGN_MEANS) {
         double t = block_sum(acc_lo, red);
-        if (threadIdx.x == 0) partial[gridDim.x + blockIdx.x] = t;
+        if (threadIdx.x == 0) partial[gridDim.x + my_tile_index()] = t;
         t = block_sum(cnt_hi, red);
-        if (threadIdx.x == 0) partial[2 * gridDim.x + blockIdx.x] = t;
+        if (threadIdx.x == 0) partial[2 * gridDim.x + my_tile_index()] = t;
     }
 }
 
@@ -307,10 +307,10 @@ __global__ __launch_bounds__(kBlock) void accum_reduce_k(GroupView g, float *st,
     }
     if (MODE == RED_L2) {
         double t = block_sum(acc, red);
-        if (threadIdx.x == 0) partial[blockIdx.x] = t;
+        if (threadIdx.x == 0) partial[my_tile_index()] = t;
     } else {
         float t = block_max(mx, redf);
-        if (threadIdx.x == 0) partial[blockIdx.x] = (double)t;
+        if (threadIdx.x == 0) partial[my_tile_index()] = (double)t;
     }
 }
 
@@ -539,9 +539,9 @@ __global__ __launch_bounds__(kBlock) void dense_decompress_k(GroupView out, Payl
     if (blockIdx.x == 0 && (int)threadIdx.x < W)
         check_header(reinterpret_cast<const PayloadHeader *>(pl.p[threadIdx.x]), ALGO, out.n, status);
     if (c.base >= out.n) return;
-    const uintptr_t direct = chunk_direct(out, c);
-    if (ALGO == MC_ALGO_QSGD && direct && !(direct & 15u)) {
-        const uint32_t rot = chunk_rotation(direct);            // a multiple of 4 here
+    const uintptr_t entry = chunk_entry(out, c);
+    if (ALGO == MC_ALGO_QSGD && !(entry & 15u)) {               // an address (even), and 16-byte aligned
+        const uint32_t rot = chunk_rotation(entry);             // a multiple of 4 here
         uint32_t at[4];                                         // first of the lane's four elements in step m
 #pragma unroll
         for (int m = 0; m < 4; ++m) at[m] = (256u * m + 4u * c.lane + rot) & (uint32_t)(kChunk - 1);
@@ -573,7 +573,7 @@ __global__ __launch_bounds__(kBlock) void dense_decompress_k(GroupView out, Payl
                 }
             }
         }
-        float *p = reinterpret_cast<float *>(direct);
+        float *p = reinterpret_cast<float *>(entry);
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
             float4v v = {alpha * acc[m][0], alpha * acc[m][1], alpha * acc[m][2], alpha * acc[m][3]};
@@ -620,7 +620,7 @@ __global__ __launch_bounds__(kBlock) void dense_decompress_k(GroupView out, Payl
     }
 #pragma unroll
     for (int j = 0; j < kSteps; ++j) acc[j] = alpha * acc[j];
-    store_seg(out, c, acc, direct);
+    store_seg(out, c, acc, entry);
 }
 
 // ---------------------------------------------------------------------------
@@ -719,7 +719,7 @@ __global__ __launch_bounds__(kBlock) void plane_decompress_k(GroupView out, Payl
         for (int b = 4; b < 8; ++b) if (b < Wt) s47[b - 4] = reinterpret_cast<const PayloadHeader *>(pl.p[b])->scale;
     }
     __syncthreads();
-    const uint32_t wbase = blockIdx.x * (uint32_t)kSignTile + wave * (uint32_t)kSignWaveElems;
+    const uint32_t wbase = my_tile_index() * (uint32_t)kSignTile + wave * (uint32_t)kSignWaveElems;
     if (wbase >= out.n) return;
     const uint32_t nwords = (out.n + 31u) >> 5;
     const uint32_t wi = (wbase >> 5) + lane;
@@ -795,15 +795,15 @@ __global__ __launch_bounds__(kBlock) void plane_decompress_k(GroupView out, Payl
         c.lane = lane;
         c.full = c.base < out.n && out.n - c.base >= (uint32_t)kChunk;
         if (c.base < out.n) {
-            const uintptr_t direct = chunk_direct(out, c);
-            const uint32_t rot = TERN ? 0u : chunk_rotation(direct);     // measured: no gain for TernGrad, whose decode is bound by the vector ALU
+            const uintptr_t entry = chunk_entry(out, c);
+            const uint32_t rot = TERN ? 0u : chunk_rotation(entry);     // measured: no gain for TernGrad, whose decode is bound by the vector ALU
             float v[kSteps];
 #pragma unroll
             for (int j = 0; j < kSteps; ++j) {
                 const uint32_t i = rotated(j, lane, rot);                // element of this half, rotated onto the lines
                 v[j] = mine[i + (i >> 5)];
             }
-            store_seg_rot(out, c, v, direct, rot);
+            store_seg_rot(out, c, v, entry, rot);
         }
     }
 }

@@ -172,7 +172,7 @@ __global__ __launch_bounds__(kBlock) void sparse_accum_k(GroupView g, float *st,
     if (c.lane == 0) wcnt[threadIdx.x >> 6] = run;
     __syncthreads();
     if (threadIdx.x == 0)       // candidates of the tile's four chunks, 16 bits each (a chunk holds at most 1024)
-        sc.tile_runs[blockIdx.x] = (uint64_t)wcnt[0] | ((uint64_t)wcnt[1] << 16) | ((uint64_t)wcnt[2] << 32) | ((uint64_t)wcnt[3] << 48);
+        sc.tile_runs[my_tile_index()] = (uint64_t)wcnt[0] | ((uint64_t)wcnt[1] << 16) | ((uint64_t)wcnt[2] << 32) | ((uint64_t)wcnt[3] << 48);
     flush_fine(hist, sc.hist + kHistW, kBinsW - 1);
     if (threadIdx.x == kBlock - 1 && hist[kBinsW - 1]) atomicAdd(&sc.hist[kHistOpen + (blockIdx.x & (kOpenCopies - 1))], hist[kBinsW - 1]);
 }
@@ -706,10 +706,11 @@ __global__ __launch_bounds__(kBlock) void sparse_decompress_k(GroupView out, Pay
 {
     __shared__ float acc[kTile];
     const uint32_t k = (uint32_t)k64;
-    const uint32_t tb = blockIdx.x * (uint32_t)kTile;
+    const uint32_t tile = my_tile_index();
+    const uint32_t tb = tile * (uint32_t)kTile;
     const uint32_t t = threadIdx.x;
-    const Chunk c = my_chunk(out.n);
-    const uintptr_t direct = chunk_direct(out, c);      // needed last, asked for first: overlaps with the table loads
+    const Chunk c = my_chunk(out.n, tile);
+    const uintptr_t entry = chunk_entry(out, c);        // needed last, asked for first: overlaps with the table loads
     for (int w0 = 0; w0 < W; w0 += kSparseBatch) {
         // issue the loads of a batch of workers before the first LDS update
         uint32_t lo[kSparseBatch], hi[kSparseBatch];
@@ -718,8 +719,8 @@ __global__ __launch_bounds__(kBlock) void sparse_decompress_k(GroupView out, Pay
             lo[b] = hi[b] = 0;
             if (w0 + b < W) {
                 // block-uniform addresses, kept on the scalar path whatever the compiler makes of the rest
-                const uint64_t f = ld_uniform(tile_first + (size_t)(w0 + b) * ntiles + blockIdx.x);
-                const uint64_t l = ld_uniform(tile_last + (size_t)(w0 + b) * ntiles + blockIdx.x);
+                const uint64_t f = ld_uniform(tile_first + (size_t)(w0 + b) * ntiles + tile);
+                const uint64_t l = ld_uniform(tile_last + (size_t)(w0 + b) * ntiles + tile);
                 if ((uint32_t)(f >> 32) == epoch && (uint32_t)(l >> 32) == epoch) {      // else: no entry in this tile
                     lo[b] = (uint32_t)f < k ? (uint32_t)f : k;
                     hi[b] = (uint32_t)l < k ? (uint32_t)l : k;
@@ -738,7 +739,7 @@ __global__ __launch_bounds__(kBlock) void sparse_decompress_k(GroupView out, Pay
 #pragma unroll
                 for (int j = 0; j < kSteps; ++j) z[j] = alpha * 0.0f;
                 // whole lines per wave store (measured: -0.5 us; the same rotation on the path below costs 3 us)
-                store_seg_rot(out, c, z, direct, chunk_rotation(direct));
+                store_seg_rot(out, c, z, entry, chunk_rotation(entry));
                 return;
             }
         }
@@ -786,7 +787,7 @@ __global__ __launch_bounds__(kBlock) void sparse_decompress_k(GroupView out, Pay
     const float *mine = acc + (c.base - tb) + c.lane;
 #pragma unroll
     for (int j = 0; j < kSteps; ++j) v[j] = alpha * mine[64 * j];
-    store_seg(out, c, v, direct);
+    store_seg(out, c, v, entry);
 }
 
 void launch_sparse_decompress(const LaunchCtx &lc, int algo, const GroupView &out, const PayloadPtrs &pl, int W,

@@ -28,7 +28,7 @@ struct GroupView {
     const uint32_t *seg_off;
     const uint32_t *chunk_seg;   // tensor that holds the first element of each 1024-element chunk
     const uintptr_t *ptrs;
-    const uintptr_t *chunk_addr; // address of each chunk's first element if the whole chunk lies in one tensor, else 0
+    const uintptr_t *chunk_addr; // per chunk: its address if the whole chunk lies in one tensor, else 2 * first tensor + 1 (chunk_entry)
     uint32_t nseg;
     uint32_t n;
     uint64_t goff;   // model-global flat index of element 0 (random streams only)
@@ -40,15 +40,22 @@ struct Chunk {
     bool full;       // the whole chunk lies below n
 };
 
-__device__ __forceinline__ Chunk my_chunk(uint32_t n)
+// Tiles are handed out last first (block 0 takes the last tile).  The chunks that straddle tensors are the slow
+// ones, and in a model's gradient list they crowd where the small tensors are -- at the end, when the list is in
+// the order the gradients become ready, the first layers last.  Started first, they are hidden behind the rest
+// (read-only pass over the ResNet-50 list: 18.0 us instead of 19.5; 17.1 with no such chunk at all).
+__device__ __forceinline__ uint32_t my_tile_index() { return gridDim.x - 1u - blockIdx.x; }
+
+__device__ __forceinline__ Chunk my_chunk(uint32_t n, uint32_t tile)
 {
     Chunk c;
     uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    c.base = blockIdx.x * (uint32_t)kTile + wave * (uint32_t)kChunk;
+    c.base = tile * (uint32_t)kTile + wave * (uint32_t)kChunk;
     c.lane = threadIdx.x & 63u;
     c.full = c.base < n && n - c.base >= (uint32_t)kChunk;
     return c;
 }
+__device__ __forceinline__ Chunk my_chunk(uint32_t n) { return my_chunk(n, my_tile_index()); }
 
 // A load whose address is the same for the whole wavefront, forced onto the scalar path (constant address
 // space).  In a kernel that streams stores, loads on the vector path queue behind those stores; the scalar
@@ -65,12 +72,6 @@ template <typename T>
 __device__ __forceinline__ T ld_stream(const T *p) { return __builtin_nontemporal_load(p); }
 template <typename T>
 __device__ __forceinline__ void st_stream(T *p, T v) { __builtin_nontemporal_store(v, p); }
-
-// tensor that holds the first element of the chunk (chunks start at multiples of 1024)
-__device__ __forceinline__ uint32_t seg_of_chunk(const GroupView &g, const Chunk &c)
-{
-    return __builtin_amdgcn_readfirstlane(g.chunk_seg[c.base >> 10]);
-}
 
 // ---- flat (contiguous) buffers -------------------------------------------
 template <typename T>
@@ -113,9 +114,9 @@ __device__ __forceinline__ void store_flat(T *buf, const Chunk &c, uint32_t n, c
 // too (they then straddle lines) and gain or lose about 1 us when only the sums are rotated with
 // ds_bpermute: those keep the plain mapping.)
 constexpr uint32_t kLineElems = 32;        // 128-byte cache line
-__device__ __forceinline__ uint32_t chunk_rotation(uintptr_t direct)
+__device__ __forceinline__ uint32_t chunk_rotation(uintptr_t entry)       // 0 for a chunk without an address of its own
 {
-    return direct ? (kLineElems - (uint32_t)((direct >> 2) & (kLineElems - 1u))) & (kLineElems - 1u) : 0u;
+    return (entry & 1u) ? 0u : (kLineElems - (uint32_t)((entry >> 2) & (kLineElems - 1u))) & (kLineElems - 1u);
 }
 __device__ __forceinline__ uint32_t rotated(int j, uint32_t lane, uint32_t rot)
 {
@@ -123,9 +124,11 @@ __device__ __forceinline__ uint32_t rotated(int j, uint32_t lane, uint32_t rot)
     return j == kSteps - 1 ? i & (uint32_t)(kChunk - 1) : i;
 }
 
-// The tabulated address of a chunk (0 = walk the segment table).  A kernel that has other loads to wait
-// for before it stores fetches this first, so that the two latencies overlap.
-__device__ __forceinline__ uintptr_t chunk_direct(const GroupView &g, const Chunk &c) { return ld_uniform(g.chunk_addr + (c.base >> 10)); }
+// The per-chunk table entry: the address of the chunk's first element when all 1024 elements lie in one
+// tensor (even: tensors are 4-byte aligned), else 2 s + 1 with s the tensor that holds the chunk's first
+// element (where the loop over the chunk's tensors starts).  Never 0.  A kernel that has other loads to
+// wait for before it stores fetches this first, so that the two latencies overlap.
+__device__ __forceinline__ uintptr_t chunk_entry(const GroupView &g, const Chunk &c) { return ld_uniform(g.chunk_addr + (c.base >> 10)); }
 
 // ---- segmented (per-tensor) buffers ------------------------------------------
 // Fast path: the chunk lies inside one tensor and its address was tabulated when
@@ -138,10 +141,9 @@ __device__ __forceinline__ uintptr_t chunk_direct(const GroupView &g, const Chun
 // boundary, made the ~100 such chunks of the ResNet-50 list the last to finish: 21
 // instead of 17 us for a read-only pass over the 102 MB.)
 template <typename Body>
-__device__ __forceinline__ void for_each_tensor_of_chunk(const GroupView &g, const Chunk &c, Body body)
+__device__ __forceinline__ void for_each_tensor_of_chunk(const GroupView &g, const Chunk &c, uint32_t s0, Body body)
 {
     const uint32_t lim = g.n - c.base >= (uint32_t)kChunk ? c.base + (uint32_t)kChunk : g.n;     // end of the chunk
-    uint32_t s0 = seg_of_chunk(g, c);
     for (;;) {
         const uint32_t t = s0 + c.lane;
         const uint32_t beg = g.seg_off[t < g.nseg ? t : g.nseg];                 // seg_off has nseg + 1 entries, the last is n
@@ -161,15 +163,15 @@ __device__ __forceinline__ void for_each_tensor_of_chunk(const GroupView &g, con
 
 __device__ __forceinline__ void load_seg(const GroupView &g, const Chunk &c, float (&v)[kSteps])
 {
-    const uintptr_t direct = chunk_direct(g, c);
-    if (direct) {
-        const float *p = reinterpret_cast<const float *>(direct) + c.lane;
+    const uintptr_t entry = chunk_entry(g, c);
+    if (!(entry & 1u)) {
+        const float *p = reinterpret_cast<const float *>(entry) + c.lane;
 #pragma unroll
         for (int j = 0; j < kSteps; ++j) v[j] = ld_stream(p + 64 * j);
     } else {
 #pragma unroll
         for (int j = 0; j < kSteps; ++j) v[j] = 0.0f;
-        for_each_tensor_of_chunk(g, c, [&](uint32_t beg, uint32_t end, uintptr_t ptr) {
+        for_each_tensor_of_chunk(g, c, (uint32_t)(entry >> 1), [&](uint32_t beg, uint32_t end, uintptr_t ptr) {
             const float *p = reinterpret_cast<const float *>(ptr);
 #pragma unroll
             for (int j = 0; j < kSteps; ++j) {
@@ -184,14 +186,14 @@ __device__ __forceinline__ void load_seg(const GroupView &g, const Chunk &c, flo
 // 102 MB fill takes 16 us aligned and 22 us not, the plane decompress kernel 27 and 32 us -- while loads
 // are not sensitive.  Rotating lanes to aligned windows did not pay in these kernels.  Tensors whose flat
 // offset is a multiple of 16 elements keep the aligned rate.)
-__device__ __forceinline__ void store_seg(const GroupView &g, const Chunk &c, const float (&v)[kSteps], uintptr_t direct)
+__device__ __forceinline__ void store_seg(const GroupView &g, const Chunk &c, const float (&v)[kSteps], uintptr_t entry)
 {
-    if (direct) {
-        float *p = reinterpret_cast<float *>(direct) + c.lane;
+    if (!(entry & 1u)) {
+        float *p = reinterpret_cast<float *>(entry) + c.lane;
 #pragma unroll
         for (int j = 0; j < kSteps; ++j) st_stream(p + 64 * j, v[j]);
     } else {
-        for_each_tensor_of_chunk(g, c, [&](uint32_t beg, uint32_t end, uintptr_t ptr) {
+        for_each_tensor_of_chunk(g, c, (uint32_t)(entry >> 1), [&](uint32_t beg, uint32_t end, uintptr_t ptr) {
             float *p = reinterpret_cast<float *>(ptr);
 #pragma unroll
             for (int j = 0; j < kSteps; ++j) {
@@ -203,19 +205,19 @@ __device__ __forceinline__ void store_seg(const GroupView &g, const Chunk &c, co
 }
 __device__ __forceinline__ void store_seg(const GroupView &g, const Chunk &c, const float (&v)[kSteps])
 {
-    store_seg(g, c, v, chunk_direct(g, c));
+    store_seg(g, c, v, chunk_entry(g, c));
 }
-// v in the rotated mapping, rot = chunk_rotation(direct) (0 when the chunk has no tabulated address)
-__device__ __forceinline__ void store_seg_rot(const GroupView &g, const Chunk &c, const float (&v)[kSteps], uintptr_t direct, uint32_t rot)
+// v in the rotated mapping, rot = chunk_rotation(entry) (0 when the chunk has no address of its own)
+__device__ __forceinline__ void store_seg_rot(const GroupView &g, const Chunk &c, const float (&v)[kSteps], uintptr_t entry, uint32_t rot)
 {
-    if (direct) {
+    if (!(entry & 1u)) {
         // steps 0..14 at constant offsets from one address (they fold into the instructions), step 15 may wrap
-        float *p = reinterpret_cast<float *>(direct), *q = p + (c.lane + rot);
+        float *p = reinterpret_cast<float *>(entry), *q = p + (c.lane + rot);
 #pragma unroll
         for (int j = 0; j < kSteps - 1; ++j) st_stream(q + 64 * j, v[j]);
         st_stream(p + rotated(kSteps - 1, c.lane, rot), v[kSteps - 1]);
     } else {
-        store_seg(g, c, v, 0);
+        store_seg(g, c, v, entry);
     }
 }
 
