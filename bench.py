@@ -53,7 +53,7 @@ CALL_BYTES = {
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None = not measured
 MEASURED_TRAFFIC = {        # profiles/bench_resnet50_efsign_topk.txt, read + write, scaled by the copy calibration
-    "efsign_compress": 313.61e6, "sparse_accum": 323.16e6, "dense_decompress": 128.44e6, "sparse_decompress": 136.12e6,
+    "efsign_compress": 313.59e6, "sparse_accum": 322.77e6, "dense_decompress": 129.22e6, "sparse_decompress": 136.23e6,
 }
 
 
