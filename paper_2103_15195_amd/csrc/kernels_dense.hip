@@ -337,8 +337,9 @@ __device__ __forceinline__ void load_p(const GroupView &g, const float *st, cons
     else load_seg(g, c, p);
 }
 
-// Store one narrow code per element (int8 / binary16) of a chunk.  Codes are
-// staged through LDS so that each lane writes 16 contiguous bytes.
+// Store one one-byte code per element of a chunk.  Codes are staged through LDS so that each lane
+// writes 16 contiguous bytes (a wave store of 64 single bytes covers only half a cache line, and
+// measured slower; the two-byte codes of FP16 cover a whole line and are stored directly).
 template <typename T>
 __device__ __forceinline__ void store_codes(T *codes, uint32_t n, uint32_t n_padded, const Chunk &c,
                                             const T (&v)[kSteps], T *stage /* kChunk entries, wave-private */)
