@@ -186,9 +186,11 @@ size_t mc_state_bytes(const mc_ctx *ctx, int32_t group);
  *   state         device, mc_state_bytes() bytes, 16-byte aligned (128-byte alignment is fastest: the
  *                 floats then start on a cache line), zero-filled by the caller
  *                 before the first iteration and otherwise opaque: a 128-byte header followed by
- *                 n floats (DGC: v[n], then u[n] from the next multiple of 32 floats on).  For EF-Sign the floats hold p = g + e of the
- *                 last call and the header its scale, from which the residual is re-derived;
- *                 use mc_state_export_residual to read e.  May be NULL when use_ef = 0.
+ *                 n floats (DGC: v[n], then u[n] from the next multiple of 32 floats on).  For EF-Sign,
+ *                 OneBit, QSGD and TernGrad the floats hold p = g + e of the last call and the header
+ *                 its group scalars (QSGD, TernGrad: also whose random stream it drew from), from which
+ *                 the residual is re-derived; use mc_state_export_residual to read e.
+ *                 May be NULL when use_ef = 0.
  *   payload_out   device, mc_payload_bytes() bytes, 16-byte aligned; fully overwritten
  */
 int mc_compress(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter,

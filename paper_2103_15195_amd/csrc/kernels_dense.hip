@@ -277,12 +277,54 @@ void launch_scalar_finalize(const LaunchCtx &lc, const double *partial, uint32_t
     prof_end(lc, K_SCALAR_FINALIZE);
 }
 
+// The two stochastic quantizers, one element: what is sent and what the receiver reconstructs from it.
+// QSGD with a = |p| s / norm:  level = floor(a) + [u < a - floor(a)], code = sgn(p) level, d = code * (norm / s).
+// The two per-group divisions are taken in fp64 and rounded once, which equals the correctly rounded
+// fp32 quotient of two fp32 numbers.
+struct QsgdScale {
+    float norm, sf, r, q;
+    int levels;
+    __device__ __forceinline__ QsgdScale(float norm_, uint32_t levels_)
+        : norm(norm_), sf((float)levels_), r(norm_ > 0.0f ? (float)((double)(float)levels_ / (double)norm_) : 0.0f),
+          q((float)((double)norm_ / (double)(float)levels_)), levels((int)levels_) {}
+};
+__device__ __forceinline__ int qsgd_code(const QsgdScale &k, float p, float u)
+{
+    int xi = 0;
+    if (k.norm > 0.0f) {
+        float a = fabsf(p) * k.r;
+        if (a < k.sf) {
+            float l = floorf(a);
+            float f = a - l;
+            xi = (int)l + (u < f ? 1 : 0);
+            xi = xi > k.levels ? k.levels : xi;
+        } else xi = k.levels;
+    }
+    return p < 0.0f ? -xi : xi;
+}
+__device__ __forceinline__ float qsgd_decode(const QsgdScale &k, int code) { return (float)code * k.q; }
+// TernGrad: nz = [u * smax < |p|] (Bernoulli(|p| / smax) without a division), d = +-smax or 0
+__device__ __forceinline__ float tern_decode(float smax, float p, float u, bool valid, bool &nz, bool &neg)
+{
+    nz = valid && (u * smax < fabsf(p));
+    neg = nz && p < 0.0f;
+    return nz ? (neg ? -smax : smax) : 0.0f;
+}
+
 // ---------------------------------------------------------------------------
-// Pass A of the two-pass quantizers: p = g + e (kept in the state in place of
-// e), per-block partial of sum p^2 (QSGD) or max |p| (TernGrad).
+// Pass A of the two-pass quantizers: p = g + e, kept in the state; per-block partial of
+// sum p^2 (QSGD) or max |p| (TernGrad).
+// The state never holds e itself: what pass B sends is a function of p, of the group
+// scalar and of the random stream (worker, iteration) alone, so the residual of the last
+// call is re-derived here as  e = p_prev - d(p_prev)  by quantizing p_prev again with the
+// scalar and the stream that the state header recorded -- the same fp32 operations an
+// explicit update would have used.  Pass B then writes no residual (17 instead of 21
+// bytes per element over the two passes).  A zero-filled or imported state has scalar 0,
+// for which d = 0 and e = p.
 // ---------------------------------------------------------------------------
 template <bool EF, int MODE>
-__global__ __launch_bounds__(kBlock) void accum_reduce_k(GroupView g, float *st, double *partial)
+__global__ __launch_bounds__(kBlock) void accum_reduce_k(GroupView g, float *st, const StateHeader *prev, uint32_t levels, uint64_t seed,
+                                                         double *partial)
 {
     __shared__ double red[kWavesPerBlock];
     __shared__ float redf[kWavesPerBlock];
@@ -293,10 +335,21 @@ __global__ __launch_bounds__(kBlock) void accum_reduce_k(GroupView g, float *st,
         float p[kSteps];
         load_seg(g, c, p);
         if (EF) {
-            float e[kSteps];
-            load_flat(st, c, g.n, e, 0.0f);
+            const float sprev = prev->scale;
+            const uint32_t wprev = prev->prev_worker, iprev = prev->prev_iter;
+            float q[kSteps], uni[kSteps];
+            load_flat(st, c, g.n, q, 0.0f);
+            chunk_uniforms(seed, wprev, iprev, g.goff + c.base, c.lane, uni);
+            const QsgdScale ks(MODE == RED_L2 ? sprev : 0.0f, levels);
 #pragma unroll
-            for (int j = 0; j < kSteps; ++j) p[j] = p[j] + e[j];
+            for (int j = 0; j < kSteps; ++j) {
+                float d;
+                if (MODE == RED_L2) d = qsgd_decode(ks, qsgd_code(ks, q[j], uni[j]));
+                else { bool nz, neg; d = tern_decode(sprev, q[j], uni[j], true, nz, neg); }
+                const float e = q[j] - d;
+                // past the end of the group there is nothing (QSGD with a subnormal norm decodes even a 0 to +-norm there)
+                p[j] = c.full || c.base + 64 * j + c.lane < g.n ? p[j] + e : 0.0f;
+            }
             store_flat(st, c, g.n, p);
         }
 #pragma unroll
@@ -314,17 +367,18 @@ __global__ __launch_bounds__(kBlock) void accum_reduce_k(GroupView g, float *st,
     }
 }
 
-void launch_accum_reduce(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, int mode, double *partial)
+void launch_accum_reduce(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, const StateHeader *prev, int mode,
+                         uint32_t levels, uint64_t seed, double *partial)
 {
     if (g.n == 0) return;
     dim3 grid(tiles_of(g.n)), block(kBlock);
     prof_begin(lc, K_ACCUM_REDUCE);
     if (mode == RED_L2) {
-        if (ef) MC_LAUNCH((accum_reduce_k<true, RED_L2>), grid, block, lc, g, state_f, partial);
-        else MC_LAUNCH((accum_reduce_k<false, RED_L2>), grid, block, lc, g, state_f, partial);
+        if (ef) MC_LAUNCH((accum_reduce_k<true, RED_L2>), grid, block, lc, g, state_f, prev, levels, seed, partial);
+        else MC_LAUNCH((accum_reduce_k<false, RED_L2>), grid, block, lc, g, state_f, prev, levels, seed, partial);
     } else {
-        if (ef) MC_LAUNCH((accum_reduce_k<true, RED_MAX_ABS>), grid, block, lc, g, state_f, partial);
-        else MC_LAUNCH((accum_reduce_k<false, RED_MAX_ABS>), grid, block, lc, g, state_f, partial);
+        if (ef) MC_LAUNCH((accum_reduce_k<true, RED_MAX_ABS>), grid, block, lc, g, state_f, prev, levels, seed, partial);
+        else MC_LAUNCH((accum_reduce_k<false, RED_MAX_ABS>), grid, block, lc, g, state_f, prev, levels, seed, partial);
     }
     prof_end(lc, K_ACCUM_REDUCE);
 }
@@ -365,102 +419,84 @@ __device__ __forceinline__ void store_codes(T *codes, uint32_t n, uint32_t n_pad
 }
 
 // ---------------------------------------------------------------------------
-// QSGD pass B.  With a = |p| s / norm:  level = floor(a) + [u < a - floor(a)],
-// code = sgn(p) level, decode d = code * (norm / s), e <- p - d.
-// The two per-group divisions are taken in fp64 and rounded once, which equals
-// the correctly rounded fp32 quotient of two fp32 numbers.
+// Pass B of the two-pass quantizers: the codes of p.  With error feedback p stays in the state
+// as it is, and one thread records the group scalar and the random stream of this call in the
+// state header, from which the next call's pass A re-derives the residual (see there).
 // ---------------------------------------------------------------------------
+__device__ __forceinline__ void remember_call(StateHeader *sh, float scale, uint32_t worker, uint32_t iter_lo)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        sh->scale = scale; sh->scale_lo = 0.0f; sh->prev_worker = worker; sh->prev_iter = iter_lo;
+    }
+}
+
 template <bool EF>
-__global__ __launch_bounds__(kBlock) void qsgd_encode_k(GroupView g, float *st, const PayloadHeader *hdr, int8_t *codes,
-                                                        uint32_t levels, uint64_t seed, uint32_t worker, uint32_t iter_lo)
+__global__ __launch_bounds__(kBlock) void qsgd_encode_k(GroupView g, const float *st, StateHeader *sh, const PayloadHeader *hdr,
+                                                        int8_t *codes, uint32_t levels, uint64_t seed, uint32_t worker, uint32_t iter_lo)
 {
     __shared__ __attribute__((aligned(16))) int8_t stage[kWavesPerBlock][kChunk];
     const Chunk c = my_chunk(g.n);
-    if (c.base >= g.n) return;
     const float norm = hdr->scale;
-    const float sf = (float)levels;
-    const float r = norm > 0.0f ? (float)((double)sf / (double)norm) : 0.0f;
-    const float q = (float)((double)norm / (double)sf);
+    if (EF) remember_call(sh, norm, worker, iter_lo);
+    if (c.base >= g.n) return;
+    const QsgdScale ks(norm, levels);
     float p[kSteps];
     load_p<EF>(g, st, c, p);
     float uni[kSteps];
     chunk_uniforms(seed, worker, iter_lo, g.goff + c.base, c.lane, uni);
     int8_t code[kSteps];
-    float e[kSteps];
 #pragma unroll
-    for (int j = 0; j < kSteps; ++j) {
-        int xi = 0;
-        if (norm > 0.0f) {
-            float a = fabsf(p[j]) * r;
-            if (a < sf) {
-                float l = floorf(a);
-                float f = a - l;
-                xi = (int)l + (uni[j] < f ? 1 : 0);
-                xi = xi > (int)levels ? (int)levels : xi;
-            } else xi = (int)levels;
-        }
-        int cd = p[j] < 0.0f ? -xi : xi;
-        code[j] = (int8_t)cd;
-        float d = (float)cd * q;
-        e[j] = p[j] - d;
-    }
-    if (EF) store_flat(st, c, g.n, e);
+    for (int j = 0; j < kSteps; ++j) code[j] = (int8_t)qsgd_code(ks, p[j], uni[j]);
     store_codes<int8_t>(codes, g.n, (g.n + 3u) & ~3u, c, code, stage[threadIdx.x >> 6]);
 }
 
-void launch_qsgd_encode(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, const PayloadHeader *hdr,
+void launch_qsgd_encode(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, StateHeader *sh, const PayloadHeader *hdr,
                         int8_t *codes, uint32_t levels, uint64_t seed, uint32_t worker, uint32_t iter_lo)
 {
     if (g.n == 0) return;
     dim3 grid(tiles_of(g.n)), block(kBlock);
     prof_begin(lc, K_QSGD_ENCODE);
-    if (ef) MC_LAUNCH(qsgd_encode_k<true>, grid, block, lc, g, state_f, hdr, codes, levels, seed, worker, iter_lo);
-    else MC_LAUNCH(qsgd_encode_k<false>, grid, block, lc, g, state_f, hdr, codes, levels, seed, worker, iter_lo);
+    if (ef) MC_LAUNCH(qsgd_encode_k<true>, grid, block, lc, g, state_f, sh, hdr, codes, levels, seed, worker, iter_lo);
+    else MC_LAUNCH(qsgd_encode_k<false>, grid, block, lc, g, state_f, sh, hdr, codes, levels, seed, worker, iter_lo);
     prof_end(lc, K_QSGD_ENCODE);
 }
 
-// ---------------------------------------------------------------------------
-// TernGrad pass B.  nz = [u * smax < |p|] (Bernoulli(|p|/smax) without a
-// division), neg = nz and p < 0, d = +-smax or 0, e <- p - d.  Two bit planes.
-// ---------------------------------------------------------------------------
+// TernGrad: two bit planes (non-zero, negative)
 template <bool EF>
-__global__ __launch_bounds__(kBlock) void tern_encode_k(GroupView g, float *st, const PayloadHeader *hdr, uint32_t *planes,
-                                                        uint32_t nwords, uint64_t seed, uint32_t worker, uint32_t iter_lo)
+__global__ __launch_bounds__(kBlock) void tern_encode_k(GroupView g, const float *st, StateHeader *sh, const PayloadHeader *hdr,
+                                                        uint32_t *planes, uint32_t nwords, uint64_t seed, uint32_t worker, uint32_t iter_lo)
 {
     __shared__ uint64_t stage[kWavesPerBlock][kSteps];
     const Chunk c = my_chunk(g.n);
-    if (c.base >= g.n) return;
     const float smax = hdr->scale;
+    if (EF) remember_call(sh, smax, worker, iter_lo);
+    if (c.base >= g.n) return;
     float p[kSteps];
     load_p<EF>(g, st, c, p);
     float uni[kSteps];
     chunk_uniforms(seed, worker, iter_lo, g.goff + c.base, c.lane, uni);
     uint64_t bnz[kSteps], bng[kSteps];
-    float e[kSteps];
 #pragma unroll
     for (int j = 0; j < kSteps; ++j) {
         uint32_t i = c.base + 64 * j + c.lane;
         bool valid = c.full || i < g.n;
-        bool nz = valid && (uni[j] * smax < fabsf(p[j]));
-        bool neg = nz && p[j] < 0.0f;
+        bool nz, neg;
+        (void)tern_decode(smax, p[j], uni[j], valid, nz, neg);
         bnz[j] = __builtin_amdgcn_ballot_w64(nz);
         bng[j] = __builtin_amdgcn_ballot_w64(neg);
-        float d = nz ? (neg ? -smax : smax) : 0.0f;
-        e[j] = p[j] - d;
     }
-    if (EF) store_flat(st, c, g.n, e);
     store_plane(planes, nwords, c, bnz, stage[threadIdx.x >> 6]);
     store_plane(planes + nwords, nwords, c, bng, stage[threadIdx.x >> 6]);
 }
 
-void launch_tern_encode(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, const PayloadHeader *hdr,
+void launch_tern_encode(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, StateHeader *sh, const PayloadHeader *hdr,
                         uint32_t *planes, uint32_t nwords, uint64_t seed, uint32_t worker, uint32_t iter_lo)
 {
     if (g.n == 0) return;
     dim3 grid(tiles_of(g.n)), block(kBlock);
     prof_begin(lc, K_TERN_ENCODE);
-    if (ef) MC_LAUNCH(tern_encode_k<true>, grid, block, lc, g, state_f, hdr, planes, nwords, seed, worker, iter_lo);
-    else MC_LAUNCH(tern_encode_k<false>, grid, block, lc, g, state_f, hdr, planes, nwords, seed, worker, iter_lo);
+    if (ef) MC_LAUNCH(tern_encode_k<true>, grid, block, lc, g, state_f, sh, hdr, planes, nwords, seed, worker, iter_lo);
+    else MC_LAUNCH(tern_encode_k<false>, grid, block, lc, g, state_f, sh, hdr, planes, nwords, seed, worker, iter_lo);
     prof_end(lc, K_TERN_ENCODE);
 }
 
@@ -848,11 +884,11 @@ void launch_dense_decompress(const LaunchCtx &lc, int algo, const GroupView &out
 }
 
 // ---------------------------------------------------------------------------
-// State <-> plain residual.  Only EF-Sign and OneBit keep something other than
-// the residual itself (p and the scalars of the last call); the other algorithms
-// copy (SigNUM: the momentum).
+// State <-> plain residual.  EF-Sign, OneBit, QSGD and TernGrad keep p and the scalars
+// of the last call instead of the residual; the other algorithms copy (SigNUM: the momentum).
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void state_convert_k(int algo, int to_residual, uint32_t n, const uint8_t *src, uint8_t *dst)
+__global__ __launch_bounds__(kBlock) void state_convert_k(int algo, int to_residual, uint32_t n, const uint8_t *src, uint8_t *dst,
+                                                          uint32_t levels, uint64_t seed, uint64_t goff)
 {
     // plain side: n floats (DGC: v[n] then u[n]); opaque side: header, then the same floats (DGC: u from dgc_u_offset(n))
     const size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x;
@@ -866,24 +902,36 @@ __global__ __launch_bounds__(kBlock) void state_convert_k(int algo, int to_resid
             float v = f[at];
             if (algo == MC_ALGO_EFSIGN) { float sp = h->scale; v = v - (v >= 0.0f ? sp : -sp); }
             if (algo == MC_ALGO_ONEBIT) v = v - (v >= 0.0f ? h->scale : h->scale_lo);
+            if (algo == MC_ALGO_QSGD || algo == MC_ALGO_TERNGRAD) {
+                // what the last call sent of p is quantized once more, with its scalar and its random stream
+                uint32_t w[4];
+                philox4x32_10(seed, h->prev_worker, h->prev_iter, (goff + i) >> 2, w);
+                const uint32_t word = (goff + i) & 3u;
+                const float u = u01(word == 0 ? w[0] : word == 1 ? w[1] : word == 2 ? w[2] : w[3]);
+                float d;
+                if (algo == MC_ALGO_QSGD) { const QsgdScale ks(h->scale, levels); d = qsgd_decode(ks, qsgd_code(ks, v, u)); }
+                else { bool nz, neg; d = tern_decode(h->scale, v, u, true, nz, neg); }
+                v = v - d;
+            }
             e[i] = v;
         }
     } else {
         const float *e = reinterpret_cast<const float *>(src);
         float *f = reinterpret_cast<float *>(dst + kHeaderBytes);
-        if (i < nfloats) f[at] = e[i];       // EF-Sign, OneBit: p = e with scalars 0 re-derives exactly e
+        if (i < nfloats) f[at] = e[i];       // EF-Sign, OneBit, QSGD, TernGrad: p = e with scalars 0 re-derives exactly e
         if (i < kHeaderBytes / 4) reinterpret_cast<uint32_t *>(dst)[i] = 0u;
         if (algo == MC_ALGO_DGC && i >= n && i < dgc_u_offset(n)) f[i] = 0.0f;            // the gap between v and u
     }
 }
 
-void launch_state_convert(const LaunchCtx &lc, int algo, bool to_residual, uint32_t n, const void *src, void *dst)
+void launch_state_convert(const LaunchCtx &lc, int algo, bool to_residual, uint32_t n, const void *src, void *dst, uint32_t levels,
+                          uint64_t seed, uint64_t goff)
 {
     const size_t nfloats = algo == MC_ALGO_DGC ? 2 * (size_t)n : (size_t)n;
     const size_t work = nfloats > (size_t)kHeaderBytes / 4 ? nfloats : (size_t)kHeaderBytes / 4;     // the header is cleared too
     prof_begin(lc, K_STATE_CONVERT);
     MC_LAUNCH(state_convert_k, dim3((uint32_t)((work + kBlock - 1) / kBlock)), dim3(kBlock), lc, algo,
-                       to_residual ? 1 : 0, n, (const uint8_t *)src, (uint8_t *)dst);
+                       to_residual ? 1 : 0, n, (const uint8_t *)src, (uint8_t *)dst, levels, seed, goff);
     prof_end(lc, K_STATE_CONVERT);
 }
 

@@ -526,14 +526,14 @@ int mc_compress(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter, cons
                              reinterpret_cast<uint32_t *>(body), nwords, ctx->d_partial, hdr, (uint32_t)cfg.algo);
         break;
     case MC_ALGO_QSGD:
-        launch_accum_reduce(lc, gv, ef, sf, RED_L2, ctx->d_partial);
+        launch_accum_reduce(lc, gv, ef, sf, sh, RED_L2, levels, cfg.seed, ctx->d_partial);
         launch_scalar_finalize(lc, ctx->d_partial, tiles, RED_L2, n, hdr, MC_ALGO_QSGD, 0, levels, nullptr);
-        launch_qsgd_encode(lc, gv, ef, sf, hdr, reinterpret_cast<int8_t *>(body), levels, cfg.seed, worker, (uint32_t)iter);
+        launch_qsgd_encode(lc, gv, ef, sf, sh, hdr, reinterpret_cast<int8_t *>(body), levels, cfg.seed, worker, (uint32_t)iter);
         break;
     case MC_ALGO_TERNGRAD:
-        launch_accum_reduce(lc, gv, ef, sf, RED_MAX_ABS, ctx->d_partial);
+        launch_accum_reduce(lc, gv, ef, sf, sh, RED_MAX_ABS, 0, cfg.seed, ctx->d_partial);
         launch_scalar_finalize(lc, ctx->d_partial, tiles, RED_MAX_ABS, n, hdr, MC_ALGO_TERNGRAD, 0, 0, nullptr);
-        launch_tern_encode(lc, gv, ef, sf, hdr, reinterpret_cast<uint32_t *>(body), nwords, cfg.seed, worker, (uint32_t)iter);
+        launch_tern_encode(lc, gv, ef, sf, sh, hdr, reinterpret_cast<uint32_t *>(body), nwords, cfg.seed, worker, (uint32_t)iter);
         break;
     case MC_ALGO_FP16:
         launch_fp16_compress(lc, gv, ef, sf, hdr, reinterpret_cast<uint16_t *>(body));
@@ -601,7 +601,8 @@ static int state_convert(mc_ctx *ctx, int32_t group, const void *src, void *dst,
     if (nf == 0 && to_residual) return MC_OK;
     LaunchCtx lc{static_cast<hipStream_t>(stream), &ctx->prof, nullptr, nullptr};
     (void)hipGetLastError();
-    launch_state_convert(lc, ctx->cfg.algo, to_residual, g->n, src, dst);
+    const uint32_t levels = ctx->cfg.algo == MC_ALGO_QSGD ? (1u << (ctx->cfg.qsgd_bits - 1)) - 1u : 0u;
+    launch_state_convert(lc, ctx->cfg.algo, to_residual, g->n, src, dst, levels, ctx->cfg.seed, g->goff);
     return check_launch();
 }
 

@@ -25,7 +25,8 @@ static_assert(sizeof(PayloadHeader) == kHeaderBytes, "payload header is one 128-
 struct StateHeader {            // one cache line in front of the error-feedback floats
     float scale;                // EF-Sign: scale of the last call; OneBit: mean of its upper class (0 after zero-fill / import)
     float scale_lo;             // OneBit: mean of the lower class of the last call
-    uint32_t pad[30];
+    uint32_t prev_worker, prev_iter;   // QSGD / TernGrad: whose random stream the last call drew from (scale: its norm / max)
+    uint32_t pad[28];
 };
 static_assert(sizeof(StateHeader) == kHeaderBytes, "state header is one 128-byte line");
 
@@ -78,16 +79,18 @@ void launch_sign_compress(const LaunchCtx &lc, int mode, const GroupView &g, boo
                           float beta, uint32_t *words, uint32_t nwords, double *partial, PayloadHeader *hdr, uint32_t algo);
 void launch_scalar_finalize(const LaunchCtx &lc, const double *partial, uint32_t nblocks, int mode, uint32_t n,
                             PayloadHeader *hdr, uint32_t algo, uint64_t k, uint32_t levels, float *state_scale);
-void launch_accum_reduce(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, int mode, double *partial);
-void launch_qsgd_encode(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, const PayloadHeader *hdr,
+void launch_accum_reduce(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, const StateHeader *prev, int mode,
+                         uint32_t levels, uint64_t seed, double *partial);
+void launch_qsgd_encode(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, StateHeader *sh, const PayloadHeader *hdr,
                         int8_t *codes, uint32_t levels, uint64_t seed, uint32_t worker, uint32_t iter_lo);
-void launch_tern_encode(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, const PayloadHeader *hdr,
+void launch_tern_encode(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, StateHeader *sh, const PayloadHeader *hdr,
                         uint32_t *planes, uint32_t nwords, uint64_t seed, uint32_t worker, uint32_t iter_lo);
 void launch_fp16_compress(const LaunchCtx &lc, const GroupView &g, bool ef, float *state_f, PayloadHeader *hdr,
                           uint16_t *halves);
 void launch_dense_decompress(const LaunchCtx &lc, int algo, const GroupView &out, const PayloadPtrs &pl, int W,
                              float alpha, uint32_t levels, int *status);
-void launch_state_convert(const LaunchCtx &lc, int algo, bool to_residual, uint32_t n, const void *src, void *dst);
+void launch_state_convert(const LaunchCtx &lc, int algo, bool to_residual, uint32_t n, const void *src, void *dst, uint32_t levels,
+                          uint64_t seed, uint64_t goff);
 
 // ---- sparse kernels (kernels_sparse.hip) ----------------------------------------
 constexpr int kHintWorkers = 64;                         // hints kept per group, one per worker id modulo this
