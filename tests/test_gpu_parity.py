@@ -59,6 +59,7 @@ RAGGED = [
     [1], [63], [64], [65], [1023], [1024], [1025], [4095], [4096], [4097], [12289],
     [3, 1, 1, 2], [10, 2560, 256, 65536, 7, 1000, 91], [5, 0, 0, 1031, 0, 2],
     [33] * 130,                    # many small tensors inside one chunk
+    [7] * 300 + [0, 3, 0] * 20 + [2000],     # more than 64 tensors inside one chunk (the tensor loop takes them 64 at a time)
     [4096, 1, 4095, 8191],
 ]
 
