@@ -46,7 +46,12 @@ constexpr int kBinsW = 2048, kBins1 = 2048, kBins2 = 1024, kBins3 = 1 << kWindow
 // atomics on one address serialise (tens of nanoseconds each on this part), so only
 // the bins themselves are updated -- no shared summary counters -- and a level is
 // resolved by a wavefront that reads all its bins.
-constexpr int kHistW = 0, kHist1 = kHistW + kBinsW, kHist2 = kHist1 + kBins1, kHist3 = kHist2 + kBins2;
+// The window's bins lie kWinStride words apart, one per 128-byte line.  The flush of the streaming pass is millions
+// of adds when the candidates are spread evenly over the tiles (every block then holds some of nearly every bin
+// between the hint and the threshold), and adds to one line queue up behind each other: with all tensors of one
+// scale the pass took 132 us with packed bins and 62 us with one bin per line (54 us with candidates that cluster
+// in a few tensors, 56 us strided; the seed pays 1.5 us for gathering the 2048 lines).
+constexpr int kHistW = 0, kHist1 = kHistW + kBinsW * kWinStride, kHist2 = kHist1 + kBins1, kHist3 = kHist2 + kBins2;
 // The window's open last bin takes a count from nearly every block (all keys above the window), and
 // adds from thousands of blocks to one address queue up behind each other for tens of microseconds:
 // its count is spread over kOpenCopies words, chosen by the block index, which the seed sums.
@@ -173,7 +178,10 @@ __global__ __launch_bounds__(kBlock) void sparse_accum_k(GroupView g, float *st,
     __syncthreads();
     if (threadIdx.x == 0)       // candidates of the tile's four chunks, 16 bits each (a chunk holds at most 1024)
         sc.tile_runs[my_tile_index()] = (uint64_t)wcnt[0] | ((uint64_t)wcnt[1] << 16) | ((uint64_t)wcnt[2] << 32) | ((uint64_t)wcnt[3] << 48);
-    flush_fine(hist, sc.hist + kHistW, kBinsW - 1);
+    for (int b = threadIdx.x; b < kBinsW - 1; b += kBlock) {
+        const uint32_t h = hist[b];
+        if (h) atomicAdd(&sc.hist[kHistW + b * kWinStride], h);
+    }
     if (threadIdx.x == kBlock - 1 && hist[kBinsW - 1]) atomicAdd(&sc.hist[kHistOpen + (blockIdx.x & (kOpenCopies - 1))], hist[kBinsW - 1]);
 }
 
@@ -322,16 +330,19 @@ __global__ __launch_bounds__(kSeedThreads) void sparse_seed_k(GroupView g, const
                                                               SampleRule smp)
 {
     __shared__ uint32_t hist[kBins1];
+    __shared__ __attribute__((aligned(16))) uint32_t wbins[kBinsW];
     __shared__ uint32_t verdict[4];              // found, bin, rest lo, rest hi
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const uint32_t hint = *sc.hint;
+    for (int b = t; b < kBinsW; b += kSeedThreads) wbins[b] = sc.hist[kHistW + b * kWinStride];      // gather the strided bins
+    __syncthreads();
     if (wave == 0) {
         uint32_t bin;
         uint64_t rest;
         uint32_t open = sc.hist[kHistOpen + lane];
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) open += __shfl_xor(open, d, 64);
-        const bool found = resolve_wave<kBinsW>(sc.hist + kHistW, k, bin, rest, open);
+        const bool found = resolve_wave<kBinsW>(wbins, k, bin, rest, open);
         if (lane == 0) { verdict[0] = found; verdict[1] = bin; verdict[2] = (uint32_t)rest; verdict[3] = (uint32_t)(rest >> 32); }
     }
     for (int b = t; b < kBins1; b += kSeedThreads) hist[b] = 0u;
@@ -420,7 +431,7 @@ __global__ __launch_bounds__(kBlock) void cand_hist_k(uint32_t n, uint32_t ntile
     const SelectState s0 = sc.sel[0];
     if (LEVEL == 2) {
         if (blockIdx.x == 0)                // the seed is done with the window
-            for (int b = threadIdx.x; b < kBinsW + kOpenCopies; b += kBlock) sc.hist[(b < kBinsW ? kHistW : kHistOpen - kBinsW) + b] = 0u;
+            for (int b = threadIdx.x; b < kBinsW + kOpenCopies; b += kBlock) sc.hist[b < kBinsW ? kHistW + b * kWinStride : kHistOpen - kBinsW + b] = 0u;
         if (s0.mode & kModeFast) return;
     }
     const bool uniform = (s0.mode & kModeUniform) != 0u;
