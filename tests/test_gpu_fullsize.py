@@ -135,6 +135,32 @@ def test_config2_resnet50_selection_settles_on_the_fast_route(algo, ppm):
     ctx.close()
 
 
+def test_config2_resnet50_topk_when_candidates_spread_over_every_tile():
+    """All tensors of one scale and a static gradient: under error feedback every element's |p| creeps up to the
+    threshold, so the candidates (and the kept entries) are spread evenly over the tiles instead of clustering in
+    the tensors of large scale -- the case that loads the window histogram's flush most."""
+    wl = WL.workload(2)
+    numel = wl.numel.tolist()
+    flat = np.random.default_rng([41, 0]).standard_normal(wl.total, dtype=np.float32) * np.float32(0.01)
+    ctx = B.Context("topk", numel, [0, len(numel)], ratio_ppm=10000, seed=9)
+    ocfg = O.Config(O.TOPK, ratio_ppm=10000, seed=9)
+    st = torch.zeros(ctx.state_bytes(0), dtype=torch.uint8, device=H.DEV)
+    pay = torch.zeros(ctx.payload_bytes(0), dtype=torch.uint8, device=H.DEV)
+    ost = O.new_state(ocfg, wl.total)
+    dev = H.device_tensors(flat, numel)
+    routes = []
+    for it in range(6):
+        ctx.mc_compress(0, 0, it, dev, st, pay)
+        routes.append(ctx.mc_last_select_route())
+        op, _ = O.compress(ocfg, flat, ost, worker=0, it=it)
+        assert np.array_equal(pay.cpu().numpy(), op), f"iteration {it} (route {routes[-1]}): payload differs"
+    e = torch.empty(wl.total, dtype=torch.float32, device=H.DEV)
+    ctx.mc_state_export_residual(0, st, e)
+    assert H.same_bits(e.cpu().numpy(), ost)
+    print(f"[config2 topk, one scale] routes {routes}", flush=True)
+    ctx.close()
+
+
 def test_config2_resnet50_dgc_sampled_threshold():
     """DGC 0.1 % with the threshold taken from a 1 % sample: payload, kept count and accumulators against the oracle,
     then a decompress-and-sum over the W payloads the oracle wrote."""
