@@ -49,6 +49,8 @@ CALL_BYTES = {
     "onebit": (12.125, lambda W: W / 8.0 + 4.0), "randk": (12.08, lambda W: 4.0 + 0.08 * W),
     # DGC 0.1 % with the threshold taken from a 1 % sample (about k entries kept, room for 2k)
     "dgc-sampled": (20.008, lambda W: 4.0 + 0.008 * W),
+    # Top-k 1 % on tensors of one scale (`topk-even`: candidates spread over every tile)
+    "topk-even": (12.08, lambda W: 4.0 + 0.08 * W),
 }
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None = not measured
@@ -178,7 +180,17 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    benches = {a: AlgoBench(B, torch, a, numel, args.y, W, grads) for a in algos}
+    grads_even = None
+    if any(a.endswith("-even") for a in algos):
+        # all tensors of one scale: under error feedback every element's |p| creeps up to the threshold, and the
+        # sparsifiers' candidates spread evenly over the tiles instead of clustering in the tensors of large scale
+        grads_even = []
+        for w in range(W):
+            f = np.random.default_rng([77, w]).standard_normal(int(D), dtype=np.float32) * np.float32(0.01)
+            grads_even.append([torch.from_numpy(f[offs[t]:offs[t + 1]]).to("cuda:0") for t in range(len(numel))])
+    def grads_for(a):
+        return grads_even if a.endswith("-even") else grads
+    benches = {a: AlgoBench(B, torch, a, numel, args.y, W, grads_for(a)) for a in algos}
 
     def step(i):
         for a in algos:
@@ -236,7 +248,7 @@ def main():
         for a in algos:
             pts = []
             for y in wl.ys:
-                ab = benches[a] if y == args.y else AlgoBench(B, torch, a, numel, y, W, grads)
+                ab = benches[a] if y == args.y else AlgoBench(B, torch, a, numel, y, W, grads_for(a))
                 if ab is not benches[a]:
                     for i in range(8 * W):            # let the new context's state and hints settle
                         ab.it += 1
@@ -260,7 +272,7 @@ def main():
         layerwise = {}
         N = len(numel)
         for a in algos:
-            lb = AlgoBench(B, torch, a, numel, N, W, grads)
+            lb = AlgoBench(B, torch, a, numel, N, W, grads_for(a))
             for i in range(4 * W):
                 lb.it += 1
                 lb.compress(i % W)

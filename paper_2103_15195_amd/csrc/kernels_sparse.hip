@@ -62,6 +62,10 @@ constexpr uint32_t kHintMargin = 3u << 19;   // 3/16 of an octave below the last
 // lies between 12 % below and 24 % above the last one (2^23 keys are one octave of magnitude).
 
 // seed result (SelectState::mode)
+// hint record of a (group, worker): the filter key, how many times the margin below the threshold was halved,
+// and for how many calls it stays at the full margin after a miss
+constexpr int kHintShift = 1, kHintHold = 2;
+constexpr uint32_t kHintShiftMax = 3u, kHintHoldCalls = 8u;
 constexpr uint32_t kModeFast = 1u;      // lo / need are those of level 3 already
 constexpr uint32_t kModeUniform = 2u;   // after a refill: every element is a candidate, chunk c holds 1024 c ...
 
@@ -195,7 +199,8 @@ __global__ __launch_bounds__(kBlock) void sparse_accum_k(GroupView g, float *st,
 // ---------------------------------------------------------------------------
 template <int BINS>
 __device__ __forceinline__ bool resolve_wave(const uint32_t *fine, uint64_t need, uint32_t &bin, uint64_t &rest,
-                                             uint32_t top_extra = 0u /* counted in the last bin besides fine[BINS - 1] */)
+                                             uint32_t top_extra = 0u /* counted in the last bin besides fine[BINS - 1] */,
+                                             uint64_t *total = nullptr /* out: the sum of all bins */)
 {
     constexpr int kPer = BINS / 64;
     const uint32_t lane = threadIdx.x & 63u;
@@ -216,6 +221,7 @@ __device__ __forceinline__ bool resolve_wave(const uint32_t *fine, uint64_t need
         uint64_t o = __shfl_down(incl, d, 64);
         if (lane + d < 64) incl += o;
     }
+    if (total) *total = __shfl(incl, 0, 64);
     uint64_t run = incl - own;                              // keys in the bins of higher lanes
     const bool mine = run < need && need <= incl;
     uint32_t b = 0;
@@ -331,7 +337,7 @@ __global__ __launch_bounds__(kSeedThreads) void sparse_seed_k(GroupView g, const
 {
     __shared__ uint32_t hist[kBins1];
     __shared__ __attribute__((aligned(16))) uint32_t wbins[kBinsW];
-    __shared__ uint32_t verdict[4];              // found, bin, rest lo, rest hi
+    __shared__ uint32_t verdict[6];              // found, bin, rest lo, rest hi, candidates lo, hi
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const uint32_t hint = *sc.hint;
     for (int b = t; b < kBinsW; b += kSeedThreads) wbins[b] = sc.hist[kHistW + b * kWinStride];      // gather the strided bins
@@ -342,8 +348,12 @@ __global__ __launch_bounds__(kSeedThreads) void sparse_seed_k(GroupView g, const
         uint32_t open = sc.hist[kHistOpen + lane];
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) open += __shfl_xor(open, d, 64);
-        const bool found = resolve_wave<kBinsW>(wbins, k, bin, rest, open);
-        if (lane == 0) { verdict[0] = found; verdict[1] = bin; verdict[2] = (uint32_t)rest; verdict[3] = (uint32_t)(rest >> 32); }
+        uint64_t cands;
+        const bool found = resolve_wave<kBinsW>(wbins, k, bin, rest, open, &cands);
+        if (lane == 0) {
+            verdict[0] = found; verdict[1] = bin; verdict[2] = (uint32_t)rest; verdict[3] = (uint32_t)(rest >> 32);
+            verdict[4] = (uint32_t)cands; verdict[5] = (uint32_t)(cands >> 32);
+        }
     }
     for (int b = t; b < kBins1; b += kSeedThreads) hist[b] = 0u;
     __syncthreads();
@@ -354,9 +364,21 @@ __global__ __launch_bounds__(kSeedThreads) void sparse_seed_k(GroupView g, const
             SelectState s;
             s.lo = hint + (bin << kWindowShift); s.mode = kModeFast; s.need = (uint64_t)verdict[2] | ((uint64_t)verdict[3] << 32);
             sc.sel[0] = s;
+            // How far below the threshold the next call starts filtering.  Under error feedback the values pile up just
+            // below the threshold, in the long run those of every tensor, and a fixed margin lets through many times k
+            // of them (each costs the streaming pass a store and the histogram an add): the margin is halved while the
+            // filter passes more than 4 k and doubled again when it passes fewer than 1.5 k; a miss resets it (below).
+            const uint64_t cands = (uint64_t)verdict[4] | ((uint64_t)verdict[5] << 32);
+            uint32_t shift = sc.hint[kHintShift], hold = sc.hint[kHintHold];
+            if (hold) --hold;
+            else if (cands > 4u * k && shift < kHintShiftMax) ++shift;
+            if (2u * cands < 3u * k && shift) --shift;
+            sc.hint[kHintShift] = shift; sc.hint[kHintHold] = hold;
         }
         return;
     }
+    // missed: the next calls filter with the full margin again, and keep it for a while
+    if (blockIdx.x == 0 && t == 0) { sc.hint[kHintShift] = 0u; sc.hint[kHintHold] = kHintHoldCalls; }
     const uint32_t ntiles = (g.n + (uint32_t)kTile - 1u) / (uint32_t)kTile;
     const uint32_t uwave = __builtin_amdgcn_readfirstlane(wave), waves = kSeedThreads / 64;
     if (found) {
@@ -505,7 +527,8 @@ __global__ __launch_bounds__(kBlock) void cand_count_k(uint32_t n, uint32_t ntil
             SelectState s;
             s.lo = T; s.mode = s2.mode; s.need = rest;
             sc.sel[3] = s;
-            *sc.hint = T > kHintMargin ? T - kHintMargin : 0u;      // where the next call starts filtering
+            const uint32_t margin = kHintMargin >> sc.hint[kHintShift];
+            *sc.hint = T > margin ? T - margin : 0u;                // where the next call starts filtering
         }
         for (int b = threadIdx.x; b < kBins2; b += kBlock) sc.hist[kHist2 + b] = 0u;   // level 3 is done with level 2
     }

@@ -378,7 +378,7 @@ int mc_ctx_create(mc_ctx **out, const mc_config *cfg, const int64_t *numel, int3
             const size_t chunks = tiles * kWavesPerBlock, slots = chunks * kChunk;
             const size_t off_words = (size_t)kMaxWorkers * tiles;
             if (hipMalloc(&sp.hist, hist_bytes) != hipSuccess || hipMalloc(&sp.sel, 4 * sizeof(SelectState)) != hipSuccess ||
-                hipMalloc(&ctx->d_hints, (size_t)y * kHintWorkers * sizeof(uint32_t)) != hipSuccess ||
+                hipMalloc(&ctx->d_hints, (size_t)y * kHintWorkers * kHintWords * sizeof(uint32_t)) != hipSuccess ||
                 hipMalloc(&sp.cand_bits, slots * sizeof(uint32_t)) != hipSuccess ||
                 hipMalloc(&sp.cand_loc, slots * sizeof(uint16_t)) != hipSuccess ||
                 hipMalloc(&sp.tile_runs, tiles * sizeof(uint64_t)) != hipSuccess ||
@@ -387,7 +387,7 @@ int mc_ctx_create(mc_ctx **out, const mc_config *cfg, const int64_t *numel, int3
                 hipMalloc(&sp.tile_first, off_words * sizeof(uint64_t)) != hipSuccess ||
                 hipMalloc(&sp.tile_last, off_words * sizeof(uint64_t)) != hipSuccess) rc = MC_ERR_ALLOC;
             else if (hipMemset(sp.hist, 0, hist_bytes) != hipSuccess || hipMemset(sp.sel, 0, 4 * sizeof(SelectState)) != hipSuccess ||
-                     hipMemset(ctx->d_hints, 0, (size_t)y * kHintWorkers * sizeof(uint32_t)) != hipSuccess ||
+                     hipMemset(ctx->d_hints, 0, (size_t)y * kHintWorkers * kHintWords * sizeof(uint32_t)) != hipSuccess ||
                      hipMemset(sp.tile_runs, 0, tiles * sizeof(uint64_t)) != hipSuccess ||
                      hipMemset(sp.tile_first, 0, off_words * sizeof(uint64_t)) != hipSuccess ||
                      hipMemset(sp.tile_last, 0, off_words * sizeof(uint64_t)) != hipSuccess) rc = MC_ERR_DEVICE;
@@ -544,7 +544,7 @@ int mc_compress(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter, cons
     {
         SparseScratch sp = ctx->sparse;
         // a context may compress for several simulated workers whose thresholds differ: each keeps its own hint
-        sp.hint = ctx->d_hints + (size_t)group * kHintWorkers + worker % kHintWorkers;
+        sp.hint = ctx->d_hints + ((size_t)group * kHintWorkers + worker % kHintWorkers) * kHintWords;
         uint32_t stride = 0, first = 0;
         uint64_t need = 0;
         if (cfg.dgc_sample_ppm) {       // sample: every stride-th element from `first`; threshold = its need-th largest key

@@ -94,13 +94,14 @@ void launch_state_convert(const LaunchCtx &lc, int algo, bool to_residual, uint3
 
 // ---- sparse kernels (kernels_sparse.hip) ----------------------------------------
 constexpr int kHintWorkers = 64;                         // hints kept per group, one per worker id modulo this
+constexpr int kHintWords = 4;                            // words of a hint record (filter key, margin shift, hold, unused)
 constexpr int kWinStride = 32;                               // words between two bins of the window histogram: one bin per 128-byte line
 constexpr int kHistWords = 2048 * kWinStride + 2048 + 1024 + 2048 + 64;   // bins of the window and of the three radix levels, copies of the window's open bin
 
 struct SparseScratch {
     uint32_t *hist;        // kHistWords counters; each level is cleared by a later kernel of the same call
     SelectState *sel;      // [0]: after the seed, [1..3]: after each radix level
-    uint32_t *hint;        // this group's candidate filter: keys >= hint are candidates (0 = everything)
+    uint32_t *hint;        // this (group, worker)'s hint record; word 0: keys >= it are candidates (0 = everything)
     uint32_t *cand_bits;   // candidate values (fp32 bit patterns), 1024 slots per chunk, filled from the front
     uint16_t *cand_loc;    // candidate positions inside their chunk
     uint64_t *tile_runs;   // candidates of the four chunks of every tile, 16 bits each
