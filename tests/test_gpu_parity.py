@@ -322,6 +322,35 @@ def test_profile_hooks_count_launches():
     ctx.close()
 
 
+def test_filter_margin_tightens_and_recovers_from_a_miss():
+    """A static gradient under error feedback piles the values up below the threshold: the library narrows its
+    candidate filter call by call.  Then the residual is dropped, the threshold falls far below the filter (a miss),
+    and the calls after it must be exact again and return to the fast route."""
+    n, tensors = 200000, [150000, 50000]
+    ctx = B.Context("topk", tensors, [0, 2], ratio_ppm=10000, seed=4)
+    ocfg = O.Config(O.TOPK, ratio_ppm=10000, seed=4)
+    st = torch.zeros(ctx.state_bytes(0), dtype=torch.uint8, device=H.DEV)
+    pay = torch.zeros(ctx.payload_bytes(0), dtype=torch.uint8, device=H.DEV)
+    ost = O.new_state(ocfg, n)
+    g = (np.random.default_rng(5).standard_normal(n, dtype=np.float32) * np.float32(0.01)).astype(np.float32)
+    dev = H.device_tensors(g, tensors)
+    routes = []
+    for it in range(40):
+        if it == 24:                      # forget the accumulated residual
+            st.zero_()
+            ost[:] = 0
+        ctx.mc_compress(0, 0, it, dev, st, pay)
+        routes.append(ctx.mc_last_select_route())
+        op, _ = O.compress(ocfg, g, ost, group_off=0, worker=0, it=it)
+        assert np.array_equal(pay.cpu().numpy(), op), f"call {it} (route {routes[-1]}): payload differs"
+    e = torch.empty(n, dtype=torch.float32, device=H.DEV)
+    ctx.mc_state_export_residual(0, st, e)
+    assert H.same_bits(e.cpu().numpy(), ost)
+    print("routes", routes, flush=True)
+    assert B.MC_SELECT_FAST in routes[4:24] and routes[24] == B.MC_SELECT_REFILL and routes[-1] == B.MC_SELECT_FAST
+    ctx.close()
+
+
 @pytest.mark.parametrize("algo", ["topk", "dgc"])
 def test_selection_routes_are_all_taken_and_exact(algo):
     """The exact selection has three routes: the threshold key T falls inside the histogram window that the
