@@ -46,12 +46,15 @@ constexpr int kBinsW = 2048, kBins1 = 2048, kBins2 = 1024, kBins3 = 1 << kWindow
 // atomics on one address serialise (tens of nanoseconds each on this part), so only
 // the bins themselves are updated -- no shared summary counters -- and a level is
 // resolved by a wavefront that reads all its bins.
-// The window's bins lie kWinStride words apart, one per 128-byte line.  The flush of the streaming pass is millions
-// of adds when the candidates are spread evenly over the tiles (every block then holds some of nearly every bin
-// between the hint and the threshold), and adds to one line queue up behind each other: with all tensors of one
-// scale the pass took 132 us with packed bins and 62 us with one bin per line (54 us with candidates that cluster
-// in a few tensors, 56 us strided; the seed pays 1.5 us for gathering the 2048 lines).
-constexpr int kHistW = 0, kHist1 = kHistW + kBinsW * kWinStride, kHist2 = kHist1 + kBins1, kHist3 = kHist2 + kBins2;
+// The window histogram is kept in kWinCopies copies, a block adding to the copy of its index, and the seed sums
+// them.  The flush of the streaming pass is one multi-lane add per block and 128-byte line of bins, and adds to one
+// line queue up behind each other (about 5 ns each): when the candidates are spread evenly over the tiles, every
+// block holds some of nearly every bin between the hint and the threshold, and with a single copy the pass took
+// 132 us instead of 54 (all tensors of one scale).  One bin per line was tried first (62 us, but the adds of a wave
+// no longer coalesce: +2..4 us on clustered candidates and a 2048-line gather in the seed); copies keep the adds
+// coalesced.  Measured, Top-k compress on clustered / evenly spread candidates: 2 copies 87.6 / 125.6 us, 4 copies
+// 88.4 / 97.5, 8 copies 89.7 / 99.0, 16 copies 93.3 / 101.7, 32 copies 106 / 114 (the seed reads them all).
+constexpr int kHistW = 0, kHist1 = kHistW + kBinsW * kWinCopies, kHist2 = kHist1 + kBins1, kHist3 = kHist2 + kBins2;
 // The window's open last bin takes a count from nearly every block (all keys above the window), and
 // adds from thousands of blocks to one address queue up behind each other for tens of microseconds:
 // its count is spread over kOpenCopies words, chosen by the block index, which the seed sums.
@@ -182,10 +185,7 @@ __global__ __launch_bounds__(kBlock) void sparse_accum_k(GroupView g, float *st,
     __syncthreads();
     if (threadIdx.x == 0)       // candidates of the tile's four chunks, 16 bits each (a chunk holds at most 1024)
         sc.tile_runs[my_tile_index()] = (uint64_t)wcnt[0] | ((uint64_t)wcnt[1] << 16) | ((uint64_t)wcnt[2] << 32) | ((uint64_t)wcnt[3] << 48);
-    for (int b = threadIdx.x; b < kBinsW - 1; b += kBlock) {
-        const uint32_t h = hist[b];
-        if (h) atomicAdd(&sc.hist[kHistW + b * kWinStride], h);
-    }
+    flush_fine(hist, sc.hist + kHistW + (blockIdx.x % kWinCopies) * kBinsW, kBinsW - 1);
     if (threadIdx.x == kBlock - 1 && hist[kBinsW - 1]) atomicAdd(&sc.hist[kHistOpen + (blockIdx.x & (kOpenCopies - 1))], hist[kBinsW - 1]);
 }
 
@@ -340,7 +340,12 @@ __global__ __launch_bounds__(kSeedThreads) void sparse_seed_k(GroupView g, const
     __shared__ uint32_t verdict[6];              // found, bin, rest lo, rest hi, candidates lo, hi
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const uint32_t hint = *sc.hint;
-    for (int b = t; b < kBinsW; b += kSeedThreads) wbins[b] = sc.hist[kHistW + b * kWinStride];      // gather the strided bins
+    for (int b = t; b < kBinsW; b += kSeedThreads) {          // the window: the sum of its copies
+        uint32_t sum = 0;
+#pragma unroll
+        for (int r = 0; r < kWinCopies; ++r) sum += sc.hist[kHistW + r * kBinsW + b];
+        wbins[b] = sum;
+    }
     __syncthreads();
     if (wave == 0) {
         uint32_t bin;
@@ -453,7 +458,8 @@ __global__ __launch_bounds__(kBlock) void cand_hist_k(uint32_t n, uint32_t ntile
     const SelectState s0 = sc.sel[0];
     if (LEVEL == 2) {
         if (blockIdx.x == 0)                // the seed is done with the window
-            for (int b = threadIdx.x; b < kBinsW + kOpenCopies; b += kBlock) sc.hist[b < kBinsW ? kHistW + b * kWinStride : kHistOpen - kBinsW + b] = 0u;
+            for (int b = threadIdx.x; b < kWinCopies * kBinsW + kOpenCopies; b += kBlock)
+                sc.hist[b < kWinCopies * kBinsW ? kHistW + b : kHistOpen - kWinCopies * kBinsW + b] = 0u;
         if (s0.mode & kModeFast) return;
     }
     const bool uniform = (s0.mode & kModeUniform) != 0u;
