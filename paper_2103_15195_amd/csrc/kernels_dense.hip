@@ -887,19 +887,20 @@ void launch_dense_decompress(const LaunchCtx &lc, int algo, const GroupView &out
 // State <-> plain residual.  EF-Sign, OneBit, QSGD and TernGrad keep p and the scalars
 // of the last call instead of the residual; the other algorithms copy (SigNUM: the momentum).
 // ---------------------------------------------------------------------------
+// One thread per element of the group (a launch holds fewer than 2^32 threads, and DGC's two vectors together
+// may hold more floats than that): the thread of element i converts float i of every vector.
 __global__ __launch_bounds__(kBlock) void state_convert_k(int algo, int to_residual, uint32_t n, const uint8_t *src, uint8_t *dst,
                                                           uint32_t levels, uint64_t seed, uint64_t goff)
 {
     // plain side: n floats (DGC: v[n] then u[n]); opaque side: header, then the same floats (DGC: u from dgc_u_offset(n))
     const size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    const size_t nfloats = algo == MC_ALGO_DGC ? 2 * (size_t)n : (size_t)n;
-    const size_t at = algo == MC_ALGO_DGC && i >= n ? dgc_u_offset(n) + (i - n) : i;      // where float i lives in the state
+    const size_t uoff = dgc_u_offset(n);
     if (to_residual) {
         const StateHeader *h = reinterpret_cast<const StateHeader *>(src);
         const float *f = reinterpret_cast<const float *>(src + kHeaderBytes);
         float *e = reinterpret_cast<float *>(dst);
-        if (i < nfloats) {
-            float v = f[at];
+        if (i < n) {
+            float v = f[i];
             if (algo == MC_ALGO_EFSIGN) { float sp = h->scale; v = v - (v >= 0.0f ? sp : -sp); }
             if (algo == MC_ALGO_ONEBIT) v = v - (v >= 0.0f ? h->scale : h->scale_lo);
             if (algo == MC_ALGO_QSGD || algo == MC_ALGO_TERNGRAD) {
@@ -914,21 +915,25 @@ __global__ __launch_bounds__(kBlock) void state_convert_k(int algo, int to_resid
                 v = v - d;
             }
             e[i] = v;
+            if (algo == MC_ALGO_DGC) e[(size_t)n + i] = f[uoff + i];
         }
     } else {
         const float *e = reinterpret_cast<const float *>(src);
         float *f = reinterpret_cast<float *>(dst + kHeaderBytes);
-        if (i < nfloats) f[at] = e[i];       // EF-Sign, OneBit, QSGD, TernGrad: p = e with scalars 0 re-derives exactly e
+        if (i < n) {
+            f[i] = e[i];                      // EF-Sign, OneBit, QSGD, TernGrad: p = e with scalars 0 re-derives exactly e
+            if (algo == MC_ALGO_DGC) f[uoff + i] = e[(size_t)n + i];
+        }
         if (i < kHeaderBytes / 4) reinterpret_cast<uint32_t *>(dst)[i] = 0u;
-        if (algo == MC_ALGO_DGC && i >= n && i < dgc_u_offset(n)) f[i] = 0.0f;            // the gap between v and u
+        if (algo == MC_ALGO_DGC && i >= n && i < uoff) f[i] = 0.0f;                       // the gap between v and u
     }
 }
 
 void launch_state_convert(const LaunchCtx &lc, int algo, bool to_residual, uint32_t n, const void *src, void *dst, uint32_t levels,
                           uint64_t seed, uint64_t goff)
 {
-    const size_t nfloats = algo == MC_ALGO_DGC ? 2 * (size_t)n : (size_t)n;
-    const size_t work = nfloats > (size_t)kHeaderBytes / 4 ? nfloats : (size_t)kHeaderBytes / 4;     // the header is cleared too
+    // the header is cleared too, and so is DGC's gap (fewer than 32 floats past n)
+    const size_t work = (size_t)n + 32u > (size_t)kHeaderBytes / 4 ? (size_t)n + 32u : (size_t)kHeaderBytes / 4;
     prof_begin(lc, K_STATE_CONVERT);
     MC_LAUNCH(state_convert_k, dim3((uint32_t)((work + kBlock - 1) / kBlock)), dim3(kBlock), lc, algo,
                        to_residual ? 1 : 0, n, (const uint8_t *)src, (uint8_t *)dst, levels, seed, goff);
