@@ -74,6 +74,19 @@ def test_ragged_and_unaligned(algo, layout):
                          ratio_ppm=100000, seed=99, alpha=0.5)
 
 
+@pytest.mark.parametrize("algo", ["efsign", "topk", "qsgd", "fp16"])
+def test_thousands_of_tensors(algo):
+    """6000 tensors of 0..2000 elements, each its own allocation: the address list of a group is uploaded in many
+    pieces, most chunks straddle tensors, and a chunk can hold more tensors than a wavefront has lanes."""
+    rng = np.random.default_rng(6000)
+    numel = rng.integers(0, 2001, 6000)
+    numel[rng.integers(0, 6000, 600)] = rng.integers(0, 8, 600)       # runs of tiny and empty tensors
+    numel[1000:1200] = rng.integers(0, 4, 200)
+    numel = numel.tolist()
+    st = H.run_parity(numel, algo, 3, 2, 2, normal_grads(sum(numel), seed=60), ratio_ppm=10000, seed=6, alpha=0.5)
+    assert st.compress_checks == 2 * 3 * 2
+
+
 @pytest.mark.parametrize("algo", ALL)
 def test_groups_made_of_empty_tensors(algo):
     numel = [0, 0, 100, 0, 5000, 0]
