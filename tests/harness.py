@@ -96,7 +96,8 @@ def run_parity(numel: Sequence[int], algo: str, y: int, W: int, iters: int,
                grads_fn: Callable[[int, int], np.ndarray], *, policy: int = B.MC_PART_EVEN_ELEMS,
                user_bounds: Optional[Sequence[int]] = None, oracle_workers: Optional[Sequence[int]] = None,
                layout: str = "separate", alpha: float = 1.0, check_decompress: bool = True,
-               prelude_fn: Optional[Callable[[int], np.ndarray]] = None, **cfgkw) -> Stats:
+               prelude_fn: Optional[Callable[[int], np.ndarray]] = None,
+               worker_id: Callable[[int], int] = lambda w: w, iter0: int = 0, **cfgkw) -> Stats:
     """Full protocol on one (tensor list, algorithm, y): compress every (iteration, group, worker) on the GPU,
     compare payload and residual with the oracle for `oracle_workers` (default: all), then decompress-and-sum
     the oracle's payloads on the GPU and compare with the oracle's aggregate.
@@ -146,14 +147,14 @@ def run_parity(numel: Sequence[int], algo: str, y: int, W: int, iters: int,
         dev = {w: device_tensors(flats[w], numel, layout) for w in workers}
         for j in range(y):
             for w in workers:
-                ctx.mc_compress(j, w, it, dev[w][bounds[j]:bounds[j + 1]], gstate[w][j], gpay[w][j])
+                ctx.mc_compress(j, worker_id(w), iter0 + it, dev[w][bounds[j]:bounds[j + 1]], gstate[w][j], gpay[w][j])
         torch.cuda.synchronize()
         for j in range(y):
             for w in owork:
                 what = f"{algo} y={y} it={it} group={j} worker={w}"
                 g = flats[w][goff[j]:goff[j] + gn[j]]
                 before = None if not ef else ostate[w][j].copy()
-                op, _ = O.compress(ocfg, g, ostate[w][j], group_off=goff[j], worker=w, it=it)
+                op, _ = O.compress(ocfg, g, ostate[w][j], group_off=goff[j], worker=worker_id(w), it=iter0 + it)
                 gp = gpay[w][j].cpu().numpy()
                 if not check_payload(algo, gp, op, what):
                     stats.conditional += 1
@@ -161,7 +162,7 @@ def run_parity(numel: Sequence[int], algo: str, y: int, W: int, iters: int,
                     if ef:
                         ostate[w][j][:] = before
                     gh = O.header(gp)
-                    op, _ = O.compress(ocfg, g, ostate[w][j], group_off=goff[j], worker=w, it=it,
+                    op, _ = O.compress(ocfg, g, ostate[w][j], group_off=goff[j], worker=worker_id(w), it=iter0 + it,
                                        scale_in=(gh["scale"], gh["scale2"]) if algo == "onebit" else gh["scale"])
                 assert gp.size == op.size
                 if not np.array_equal(gp, op):

@@ -231,6 +231,16 @@ def test_worker_counts(algo, W):
     H.run_parity([5000, 77], algo, 1, W, 1, normal_grads(5077, seed=W), ratio_ppm=50000, alpha=1.0 / W)
 
 
+@pytest.mark.parametrize("algo", ["qsgd", "terngrad", "randk", "topk", "dgc"])
+def test_worker_and_iteration_numbers_beyond_the_usual(algo):
+    """Worker numbers that share a hint record (equal modulo 64) or do not fit 31 bits, iteration numbers around
+    2^32 (the random stream takes their low word): the random draws follow the oracle's, and a shared hint never
+    changes a result."""
+    ids = [0, 64, 128, (1 << 31) + 5, (1 << 32) - 1]
+    H.run_parity([5000, 77, 4096], algo, 2, len(ids), 3, normal_grads(9173, seed=31), ratio_ppm=20000, seed=(1 << 63) + 12345,
+                 worker_id=lambda w: ids[w], iter0=(1 << 32) - 2)
+
+
 # ---- determinism, state conversion, error reporting ------------------------------------------
 @pytest.mark.parametrize("algo", ALL)
 def test_bit_reproducible_runs(algo):
