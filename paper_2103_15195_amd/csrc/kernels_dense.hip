@@ -714,7 +714,8 @@ __device__ __forceinline__ uint64_t gather_transpose(const uint32_t (&wd)[8], in
 // of workers 0..3, indexed by their four non-zero and four negative bits, and workers 4..7 are added one
 // by one, so that every element sees the sequence of fp32 additions ((0 + d_0) + d_1) + ... of a plain
 // loop.  (A table of all 3^8 sums of 8 workers needs 26 KB of LDS per block and a kernel of its own to
-// fill it, and measured slower.)
+// fill it, and measured slower; a second table over workers 0..5, 4096 entries filled from the first,
+// 35.5 against 36.0 us.)
 // what a set / clear bit of worker w decodes to (one-plane schemes)
 __device__ __forceinline__ void plane_levels(const PayloadHeader *h, int kind, float &hi, float &lo)
 {
@@ -726,6 +727,25 @@ __device__ __forceinline__ float vote_of(float tally) { return tally > 0.0f ? 1.
 // kind (one-plane schemes only): PLANE_SCALE  EF-Sign, a bit decodes to +-scale
 //                                PLANE_MEANS  OneBit, to the mean of its class
 //                                PLANE_VOTE   SignSGD / SigNUM, to +-1, and the sum becomes its sign (majority vote)
+// Bit e of a TernGrad worker's two plane words -> what the worker adds to element e: 0, +s or -s, as bit
+// operations on s (a one-bit field, sign-extended, is the mask).  The masks pass through an empty asm so that the
+// compiler does not turn them back into compares and selects (9 issue slots with their wait states instead of 5).
+__device__ __forceinline__ float tern_term(uint32_t nzw, uint32_t ngw, int e, float sc)
+{
+    uint32_t mx = (uint32_t)__builtin_amdgcn_sbfe((int)nzw, e, 1), my = (uint32_t)__builtin_amdgcn_sbfe((int)ngw, e, 1);
+    asm("" : "+v"(mx));
+    asm("" : "+v"(my));
+    return __uint_as_float((__float_as_uint(sc) ^ (my & 0x80000000u)) & mx);
+}
+
+// bit e of a one-plane worker's word -> the level it decodes to, the same way
+__device__ __forceinline__ float plane_term(uint32_t word, int e, float hi, float lo)
+{
+    uint32_t m = (uint32_t)__builtin_amdgcn_sbfe((int)word, e, 1);
+    asm("" : "+v"(m));
+    return __uint_as_float((__float_as_uint(hi) & m) | (__float_as_uint(lo) & ~m));
+}
+
 template <bool TERN>
 __global__ __launch_bounds__(kBlock) void plane_decompress_k(GroupView out, PayloadPtrs pl, int W, float alpha, int *status,
                                                              int algo, int kind)
@@ -784,26 +804,25 @@ __global__ __launch_bounds__(kBlock) void plane_decompress_k(GroupView out, Payl
         }
     }
     float acc[32];
+    // TernGrad: only workers 0..3 enter the transposes
+    const uint32_t wlow[8] = {wd[0], wd[1], wd[2], wd[3], 0u, 0u, 0u, 0u}, nlow[8] = {wn[0], wn[1], wn[2], wn[3], 0u, 0u, 0u, 0u};
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         // byte q of the 8 words -> rows of an 8x8 bit matrix (row = worker, column = element 8q + c)
-        const uint64_t x = gather_transpose(wd, q);
+        const uint64_t x = TERN ? gather_transpose(wlow, q) : gather_transpose(wd, q);
         if (!TERN) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[8 * q + e] = table[(uint32_t)(x >> (8 * e)) & 0xFFu];
         } else {
-            const uint64_t y = gather_transpose(wn, q) & x;           // negative only counts where non-zero
+            // workers 0..3 through the table (their bits transposed into an index), workers 4..7 straight from their
+            // words.  An absent worker (W < 8: words and scale 0) adds +0, which changes no sum: none is ever -0.
+            const uint64_t y = gather_transpose(nlow, q) & x;         // negative only counts where non-zero
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const uint32_t xe = (uint32_t)(x >> (8 * e)) & 0xFFu, ye = (uint32_t)(y >> (8 * e)) & 0xFFu;
-                float a = table[(xe & 15u) | ((ye & 15u) << 4)];
+                const uint32_t xe = (uint32_t)(x >> (8 * e)) & 15u, ye = (uint32_t)(y >> (8 * e)) & 15u;
+                float a = table[xe | (ye << 4)];
 #pragma unroll
-                for (int b = 4; b < 8; ++b) {
-                    if (b < Wt) {
-                        const float sc = s47[b - 4];
-                        a = a + (((xe >> b) & 1u) ? (((ye >> b) & 1u) ? -sc : sc) : 0.0f);
-                    }
-                }
+                for (int b = 4; b < 8; ++b) a = a + tern_term(wd[b], wn[b], 8 * q + e, s47[b - 4]);
                 acc[8 * q + e] = a;
             }
         }
@@ -817,10 +836,9 @@ __global__ __launch_bounds__(kBlock) void plane_decompress_k(GroupView out, Payl
             const uint32_t neg = TERN && wi < nwords ? ld_stream(plane + nwords + wi) : 0u;
 #pragma unroll
             for (int e = 0; e < 32; ++e) {
-                const bool on = (word >> e) & 1u;
                 float d;
-                if (!TERN) d = on ? sc : sl;
-                else d = on ? (((neg >> e) & 1u) ? -sc : sc) : 0.0f;
+                if (!TERN) d = plane_term(word, e, sc, sl);
+                else d = tern_term(word, neg, e, sc);
                 acc[e] = acc[e] + d;
             }
         }
