@@ -457,9 +457,10 @@ __global__ __launch_bounds__(kBlock) void cand_hist_k(uint32_t n, uint32_t ntile
     __shared__ uint32_t hist[kBins];
     const SelectState s0 = sc.sel[0];
     if (LEVEL == 2) {
-        if (blockIdx.x == 0)                // the seed is done with the window
-            for (int b = threadIdx.x; b < kWinCopies * kBinsW + kOpenCopies; b += kBlock)
-                sc.hist[b < kWinCopies * kBinsW ? kHistW + b : kHistOpen - kWinCopies * kBinsW + b] = 0u;
+        // the seed is done with the window: all blocks clear it together (one block alone is the whole duration of
+        // this kernel on the fast route: 1.5 us)
+        for (uint32_t b = blockIdx.x * kBlock + threadIdx.x; b < (uint32_t)(kWinCopies * kBinsW + kOpenCopies); b += gridDim.x * kBlock)
+            sc.hist[b < (uint32_t)(kWinCopies * kBinsW) ? kHistW + b : kHistOpen - kWinCopies * kBinsW + b] = 0u;
         if (s0.mode & kModeFast) return;
     }
     const bool uniform = (s0.mode & kModeUniform) != 0u;
