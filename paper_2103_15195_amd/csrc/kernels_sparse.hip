@@ -251,7 +251,7 @@ __device__ __forceinline__ void load_sel(const GroupView &g, const float *st, co
 // ---------------------------------------------------------------------------
 // The candidates of one tile, walked by one wavefront in index order.  `runs`
 // holds the candidate counts of the tile's four chunks (16 bits each); the slots of
-// chunk c are cand[1024 c ...].  Sixteen rounds of 64 candidates are fetched together,
+// chunk c are cand[1024 c ...].  Up to twelve rounds of 64 candidates are fetched together,
 // so a tile of a tensor that holds most of the kept entries (several hundred
 // candidates) costs the wavefront one memory latency.
 // `body(valid, chunk, bits, loc)` is called by all 64 lanes (it may use ballots).
@@ -274,38 +274,54 @@ __device__ __forceinline__ uint64_t uniform_runs(uint32_t tile, uint32_t n)
     return r;
 }
 
+// One batch of the walk: rounds [f0, f0 + 64 ROUNDS) of the tile's candidates, all loads issued before the first use.
+template <bool WITH_LOC, int ROUNDS, typename Body>
+__device__ __forceinline__ void tile_batch(const SparseScratch &sc, uint32_t tile, uint32_t r0, uint32_t r1, uint32_t r2, uint32_t total,
+                                           uint32_t f0, Body body)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    uint32_t ch[ROUNDS], bits[ROUNDS], loc[ROUNDS];
+    size_t slot[ROUNDS];
+    bool valid[ROUNDS];
+#pragma unroll
+    for (int u = 0; u < ROUNDS; ++u) {
+        const uint32_t f = f0 + 64 * u + lane;
+        valid[u] = f < total;
+        const uint32_t sub = (f >= r0) + (f >= r1) + (f >= r2);          // chunk of the tile, then slot inside it
+        const uint32_t off = f - (sub == 0 ? 0u : sub == 1 ? r0 : sub == 2 ? r1 : r2);
+        ch[u] = tile * kWavesPerBlock + (valid[u] ? sub : 0u);
+        slot[u] = valid[u] ? (size_t)ch[u] * kChunk + off : (size_t)tile * kTile;
+    }
+#pragma unroll
+    for (int u = 0; u < ROUNDS; ++u) {
+        bits[u] = 0u; loc[u] = 0u;
+        if (valid[u]) {
+            bits[u] = sc.cand_bits[slot[u]];
+            if (WITH_LOC) loc[u] = sc.cand_loc[slot[u]];
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < ROUNDS; ++u)
+        if (f0 + 64 * u < total) body(valid[u], ch[u], bits[u], loc[u]);
+}
+
+// A tile with at most 256 candidates -- nearly every tile when the candidates are spread over the whole group -- takes
+// one batch of four rounds: the slot arithmetic of sixteen rounds, most of them empty, was a third of what the
+// count kernel did.  Other tiles take batches of twelve rounds (with sixteen the level-3 and emit kernels need 81 .. 83
+// registers and five wavefronts fit a SIMD; with twelve, seven or eight do; eight rounds measure the same but would
+// cost a tile full of candidates eight dependent batches).  Top-k compress, evenly spread / clustered candidates:
+// 98.2 -> 89.7 us / 88.6 -> 88.1; Rand-k 97.7 -> 90.0; DGC 114.1 -> 111.4.
+// Fetching the four rounds ahead of what else a kernel waits for (its resolve, its prefix sum) gained another 1 us on
+// spread candidates and lost as much on clustered ones, whose heavy tiles then wait for their candidate counts before
+// anything else is asked for: not kept.
 template <bool WITH_LOC, typename Body>
 __device__ __forceinline__ void tile_walk(const SparseScratch &sc, uint32_t tile, uint64_t runs, Body body)
 {
-    constexpr int kRounds = 16;
-    const uint32_t lane = threadIdx.x & 63u;
+    constexpr int kRounds = 12, kFew = 4;
     const uint32_t r0 = (uint32_t)(runs & 0xFFFFu), r1 = r0 + (uint32_t)((runs >> 16) & 0xFFFFu),
                    r2 = r1 + (uint32_t)((runs >> 32) & 0xFFFFu), total = r2 + (uint32_t)(runs >> 48);
-    for (uint32_t f0 = 0; f0 < total; f0 += 64 * kRounds) {
-        uint32_t ch[kRounds], bits[kRounds], loc[kRounds];
-        size_t slot[kRounds];
-        bool valid[kRounds];
-#pragma unroll
-        for (int u = 0; u < kRounds; ++u) {
-            const uint32_t f = f0 + 64 * u + lane;
-            valid[u] = f < total;
-            const uint32_t sub = (f >= r0) + (f >= r1) + (f >= r2);          // chunk of the tile, then slot inside it
-            const uint32_t off = f - (sub == 0 ? 0u : sub == 1 ? r0 : sub == 2 ? r1 : r2);
-            ch[u] = tile * kWavesPerBlock + (valid[u] ? sub : 0u);
-            slot[u] = valid[u] ? (size_t)ch[u] * kChunk + off : (size_t)tile * kTile;
-        }
-#pragma unroll
-        for (int u = 0; u < kRounds; ++u) {
-            bits[u] = 0u; loc[u] = 0u;
-            if (valid[u]) {
-                bits[u] = sc.cand_bits[slot[u]];
-                if (WITH_LOC) loc[u] = sc.cand_loc[slot[u]];
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < kRounds; ++u)
-            if (f0 + 64 * u < total) body(valid[u], ch[u], bits[u], loc[u]);
-    }
+    if (total <= 64u * kFew) { tile_batch<WITH_LOC, kFew>(sc, tile, r0, r1, r2, total, 0u, body); return; }
+    for (uint32_t f0 = 0; f0 < total; f0 += 64 * kRounds) tile_batch<WITH_LOC, kRounds>(sc, tile, r0, r1, r2, total, f0, body);
 }
 
 // the tile of this wavefront in the kernels that walk the candidates, and its runs
@@ -511,6 +527,8 @@ __global__ __launch_bounds__(kBlock) void cand_hist_k(uint32_t n, uint32_t ntile
 // count: resolve level 3 -> threshold key T and `need` (keys == T to take, in
 // index order); candidates above / equal to T per tile and per block of four tiles.
 // ---------------------------------------------------------------------------
+// (six wavefronts per SIMD hold all tiles of the ResNet-50 buffer at once; left alone the compiler takes 102 registers: four)
+__attribute__((amdgpu_waves_per_eu(6, 6)))
 __global__ __launch_bounds__(kBlock) void cand_count_k(uint32_t n, uint32_t ntiles, SparseScratch sc)
 {
     __shared__ uint32_t wgt[kWavesPerBlock], weq[kWavesPerBlock];
