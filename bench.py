@@ -55,7 +55,7 @@ CALL_BYTES = {
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None = not measured
 MEASURED_TRAFFIC = {        # profiles/bench_resnet50_efsign_topk.txt, read + write, scaled by the copy calibration
-    "efsign_compress": 313.59e6, "sparse_accum": 321.69e6, "dense_decompress": 129.24e6, "sparse_decompress": 136.68e6,
+    "efsign_compress": 313.58e6, "sparse_accum": 321.69e6, "dense_decompress": 129.23e6, "sparse_decompress": 136.86e6,
 }
 
 
