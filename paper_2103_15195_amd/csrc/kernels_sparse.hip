@@ -355,7 +355,9 @@ __global__ __launch_bounds__(kSeedThreads) void sparse_seed_k(GroupView g, const
     __shared__ __attribute__((aligned(16))) uint32_t wbins[kBinsW];
     __shared__ uint32_t verdict[6];              // found, bin, rest lo, rest hi, candidates lo, hi
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
-    const uint32_t hint = *sc.hint;
+    // everything the verdict and its record need is asked for up front: one memory latency, not three in a row
+    const uint32_t hint = *sc.hint, hint_shift = sc.hint[kHintShift], hint_hold = sc.hint[kHintHold];
+    uint32_t open = wave == 0 ? sc.hist[kHistOpen + lane] : 0u;
     for (int b = t; b < kBinsW; b += kSeedThreads) {          // the window: the sum of its copies
         uint32_t sum = 0;
 #pragma unroll
@@ -366,7 +368,6 @@ __global__ __launch_bounds__(kSeedThreads) void sparse_seed_k(GroupView g, const
     if (wave == 0) {
         uint32_t bin;
         uint64_t rest;
-        uint32_t open = sc.hist[kHistOpen + lane];
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) open += __shfl_xor(open, d, 64);
         uint64_t cands;
@@ -390,7 +391,7 @@ __global__ __launch_bounds__(kSeedThreads) void sparse_seed_k(GroupView g, const
             // of them (each costs the streaming pass a store and the histogram an add): the margin is halved while the
             // filter passes more than 4 k and doubled again when it passes fewer than 1.5 k; a miss resets it (below).
             const uint64_t cands = (uint64_t)verdict[4] | ((uint64_t)verdict[5] << 32);
-            uint32_t shift = sc.hint[kHintShift], hold = sc.hint[kHintHold];
+            uint32_t shift = hint_shift, hold = hint_hold;
             if (hold) --hold;
             else if (cands > 4u * k && shift < kHintShiftMax) ++shift;
             if (2u * cands < 3u * k && shift) --shift;
@@ -535,6 +536,7 @@ __global__ __launch_bounds__(kBlock) void cand_count_k(uint32_t n, uint32_t ntil
     __shared__ uint32_t res[3];
     TileJob job = my_tile(sc, n, ntiles);
     const SelectState s2 = sc.sel[2];
+    const uint32_t hint_shift = sc.hint[kHintShift];        // (asked for now: block 0 would wait for it later)
     // one wavefront reads the bins for the block: every wavefront doing so would move the histogram
     // once per tile of the group
     if (threadIdx.x < 64) {
@@ -552,7 +554,7 @@ __global__ __launch_bounds__(kBlock) void cand_count_k(uint32_t n, uint32_t ntil
             SelectState s;
             s.lo = T; s.mode = s2.mode; s.need = rest;
             sc.sel[3] = s;
-            const uint32_t margin = kHintMargin >> sc.hint[kHintShift];
+            const uint32_t margin = kHintMargin >> hint_shift;
             *sc.hint = T > margin ? T - margin : 0u;                // where the next call starts filtering
         }
         for (int b = threadIdx.x; b < kBins2; b += kBlock) sc.hist[kHist2 + b] = 0u;   // level 3 is done with level 2
