@@ -286,6 +286,17 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t ballot)
 // ---- Philox-4x32-10 (Salmon et al., SC'11) --------------------------------------
 // Counter = (J lo, J hi, worker, iteration), J = global element index / 4, key =
 // seed; the element takes output word (index % 4), top 24 bits scaled to [0, 1).
+// a ^ b ^ k in one instruction (the three-input bit operation with the truth table of xor); k is the same for the
+// whole wavefront (a round key: it lives in a scalar register).  The compiler emits two two-input operations for
+// the same expression, and where the quantizers' pass over p is bound by the vector ALU that shows: QSGD compress
+// 84.2 -> 82.4 us.
+__device__ __forceinline__ uint32_t xor3_uniform(uint32_t a, uint32_t b, uint32_t k)
+{
+    uint32_t r;
+    asm("v_bitop3_b32 %0, %1, %2, %3 bitop3:0x96" : "=v"(r) : "v"(a), "v"(b), "s"(k));
+    return r;
+}
+
 __device__ __forceinline__ void philox4x32_10(uint64_t seed, uint32_t worker, uint32_t iter_lo, uint64_t J, uint32_t (&out)[4])
 {
     uint32_t c0 = (uint32_t)J, c1 = (uint32_t)(J >> 32), c2 = worker, c3 = iter_lo;
@@ -295,9 +306,9 @@ __device__ __forceinline__ void philox4x32_10(uint64_t seed, uint32_t worker, ui
         // one 32 x 32 -> 64 multiply each (two instructions instead of four on the quarter-rate multiplier)
         const uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
         const uint32_t hi0 = (uint32_t)(p0 >> 32), lo0 = (uint32_t)p0, hi1 = (uint32_t)(p1 >> 32), lo1 = (uint32_t)p1;
-        c0 = hi1 ^ c1 ^ k0;
+        c0 = xor3_uniform(hi1, c1, k0);
         c1 = lo1;
-        c2 = hi0 ^ c3 ^ k1;
+        c2 = xor3_uniform(hi0, c3, k1);
         c3 = lo0;
         k0 += 0x9E3779B9u;
         k1 += 0xBB67AE85u;
