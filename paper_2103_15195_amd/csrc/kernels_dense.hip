@@ -90,6 +90,7 @@ __global__ __launch_bounds__(kBlock) void sign_compress_k(GroupView g, float *st
 {
     __shared__ uint64_t stage[kWavesPerBlock][kSteps];
     __shared__ double red[kWavesPerBlock];
+    __shared__ double red3[MODE == SIGN_MEANS ? 3 : 1][kWavesPerBlock];
     const Chunk c = my_chunk(g.n);
     // SignSGD, SigNUM: the decoded values are +-1, no finalize kernel follows
     if ((MODE == SIGN_PLAIN || MODE == SIGN_MOMENTUM) && blockIdx.x == 0 && threadIdx.x == 0) put_plain_header(hdr, algo, g.n, 1.0f);
@@ -137,15 +138,16 @@ __global__ __launch_bounds__(kBlock) void sign_compress_k(GroupView g, float *st
         }
         store_plane(words, nwords, c, b, stage[threadIdx.x >> 6]);
     }
-    if (MODE == SIGN_EF || MODE == SIGN_MEANS) {
+    if (MODE == SIGN_EF) {
         double t = block_sum(acc, red);
         if (threadIdx.x == 0) partial[my_tile_index()] = t;
     }
-    if (MODE == SIGN_MEANS) {
-        double t = block_sum(acc_lo, red);
-        if (threadIdx.x == 0) partial[gridDim.x + my_tile_index()] = t;
-        t = block_sum(cnt_hi, red);
-        if (threadIdx.x == 0) partial[2 * gridDim.x + my_tile_index()] = t;
+    if (MODE == SIGN_MEANS) {       // the three sums behind one pair of barriers, each combined in block_sum's order
+        acc = wave_sum(acc); acc_lo = wave_sum(acc_lo); cnt_hi = wave_sum(cnt_hi);
+        if ((threadIdx.x & 63) == 0) { red3[0][threadIdx.x >> 6] = acc; red3[1][threadIdx.x >> 6] = acc_lo; red3[2][threadIdx.x >> 6] = cnt_hi; }
+        __syncthreads();
+        if (threadIdx.x < 3)
+            partial[threadIdx.x * gridDim.x + my_tile_index()] = (red3[threadIdx.x][0] + red3[threadIdx.x][1]) + (red3[threadIdx.x][2] + red3[threadIdx.x][3]);
     }
 }
 
@@ -192,27 +194,36 @@ __global__ __launch_bounds__(kFinalThreads) void scalar_finalize_k(const double 
 {
     __shared__ double red[kFinalThreads / 64];
     if (mode == RED_MEANS) {
-        // the three sums one after the other, each in the fixed order of the single-sum case
-        double S[3];
-        for (int a = 0; a < 3; ++a) {
-            double acc = 0.0;
-            for (uint32_t base = 0; base < nblocks; base += 8 * kFinalThreads) {
-                double v[8];
+        // the three sums side by side (their loads in flight together, one barrier), each in the fixed order of the
+        // single-sum case
+        __shared__ double red3[3][kFinalThreads / 64];
+        double acc3[3] = {0.0, 0.0, 0.0};
+        for (uint32_t base = 0; base < nblocks; base += 8 * kFinalThreads) {
+            double v[3][8];
+#pragma unroll
+            for (int a = 0; a < 3; ++a)
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
                     uint32_t i = base + u * kFinalThreads + threadIdx.x;
-                    v[u] = i < nblocks ? partial[(size_t)a * nblocks + i] : 0.0;
+                    v[a][u] = i < nblocks ? partial[(size_t)a * nblocks + i] : 0.0;
                 }
 #pragma unroll
-                for (int u = 0; u < 8; ++u) acc += v[u];
-            }
+            for (int a = 0; a < 3; ++a)
 #pragma unroll
-            for (int m = 32; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
-            __syncthreads();
-            if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
-            __syncthreads();
-            double T = red[0];
-            for (int w = 1; w < kFinalThreads / 64; ++w) T += red[w];
+                for (int u = 0; u < 8; ++u) acc3[a] += v[a][u];
+        }
+#pragma unroll
+        for (int a = 0; a < 3; ++a) {
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) acc3[a] += __shfl_xor(acc3[a], m, 64);
+            if ((threadIdx.x & 63) == 0) red3[a][threadIdx.x >> 6] = acc3[a];
+        }
+        __syncthreads();
+        double S[3];
+#pragma unroll
+        for (int a = 0; a < 3; ++a) {
+            double T = red3[a][0];
+            for (int w = 1; w < kFinalThreads / 64; ++w) T += red3[a][w];
             S[a] = T;
         }
         if (threadIdx.x == 0) {
