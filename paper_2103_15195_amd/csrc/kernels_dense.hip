@@ -303,13 +303,13 @@ __device__ __forceinline__ int qsgd_code(const QsgdScale &k, float p, float u)
 {
     int xi = 0;
     if (k.norm > 0.0f) {
-        float a = fabsf(p) * k.r;
-        if (a < k.sf) {
-            float l = floorf(a);
-            float f = a - l;
-            xi = (int)l + (u < f ? 1 : 0);
-            xi = xi > k.levels ? k.levels : xi;
-        } else xi = k.levels;
+        // a >= s (or not a number) means level s: clamped to s, the steps below give exactly that (floor s, fraction 0,
+        // and no u lies below 0), and below s the level cannot exceed s -- one minimum instead of a compare, a select
+        // and a second clamp
+        const float a = fminf(fabsf(p) * k.r, k.sf);
+        const float l = floorf(a);
+        const float f = a - l;
+        xi = (int)l + (u < f ? 1 : 0);
     }
     return p < 0.0f ? -xi : xi;
 }
