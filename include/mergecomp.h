@@ -19,6 +19,11 @@
  *     back.  All calls that use one context must be issued in stream order
  *     (one stream, or streams the caller has ordered with events): the context
  *     scratch and its cached pointer tables are shared between calls.
+ *     The calls are not meant to be recorded into a HIP graph: iteration and
+ *     worker numbers, the tensor addresses and a per-call stamp of the sparse
+ *     decompress travel as kernel arguments, so a replay would repeat the
+ *     random stream of the recorded call, and a replayed sparse decompress
+ *     would take tile entries of the previous replay for its own.
  *   - A group is addressed as the flat fp32 vector obtained by concatenating
  *     its tensors in list order, each tensor contiguous; nothing is copied to
  *     build it, kernels walk a segment table.  Flat index i of group j has the
