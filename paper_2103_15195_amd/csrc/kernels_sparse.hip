@@ -747,15 +747,32 @@ __global__ __launch_bounds__(kBlock) void sparse_index_k(int algo, uint32_t n, P
     }
     const uint32_t k = fits ? (uint32_t)held : 0u;          // a payload that does not fit contributes nothing
     const uint32_t *idx = reinterpret_cast<const uint32_t *>(pl.p[w] + kHeaderBytes);
-    const uint32_t e = blockIdx.x * kBlock + threadIdx.x;
-    if (e >= k) return;
+    // four consecutive entries per thread (one 16-byte load: the body of a payload is 16-byte aligned) and the
+    // entries before and after them
+    const uint32_t e0 = (blockIdx.x * kBlock + threadIdx.x) * 4u;
+    if (e0 >= k) return;
+    uint32_t v[6];
+    if (k - e0 >= 4u) {
+        const uint4 x = *reinterpret_cast<const uint4 *>(idx + e0);
+        v[1] = x.x; v[2] = x.y; v[3] = x.z; v[4] = x.w;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[1 + i] = e0 + i < k ? idx[e0 + i] : 0u;
+    }
+    v[0] = e0 > 0u ? idx[e0 - 1] : 0u;
+    v[5] = k - e0 > 4u ? idx[e0 + 4] : 0u;
     // the first entry of a tile's run records where the run starts, the last one where it ends;
     // both are stamped with this call's epoch, so tiles without entries need no clearing
-    const uint32_t tile = idx[e] >> 12;
-    if (tile >= ntiles) return;
     const uint64_t stamp = (uint64_t)epoch << 32;
-    if (e == 0 || (idx[e - 1] >> 12) != tile) tile_first[(size_t)w * ntiles + tile] = stamp | e;
-    if (e == k - 1 || (idx[e + 1] >> 12) != tile) tile_last[(size_t)w * ntiles + tile] = stamp | (e + 1);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t e = e0 + i;
+        if (e >= k) break;
+        const uint32_t tile = v[1 + i] >> 12;
+        if (tile >= ntiles) continue;
+        if (e == 0 || (v[i] >> 12) != tile) tile_first[(size_t)w * ntiles + tile] = stamp | e;
+        if (e == k - 1 || (v[2 + i] >> 12) != tile) tile_last[(size_t)w * ntiles + tile] = stamp | (e + 1);
+    }
 }
 
 constexpr int kSparseBatch = 8;    // workers whose entries are in flight together
@@ -896,7 +913,7 @@ void launch_sparse_decompress(const LaunchCtx &lc, int algo, const GroupView &ou
     if (out.n == 0) return;
     const uint32_t nt = tiles_of(out.n);
     prof_begin(lc, K_SPARSE_INDEX);
-    MC_LAUNCH(sparse_index_k, dim3((uint32_t)((k + kBlock - 1) / kBlock), W), dim3(kBlock), lc, algo,
+    MC_LAUNCH(sparse_index_k, dim3((uint32_t)((k + 4 * kBlock - 1) / (4 * kBlock)), W), dim3(kBlock), lc, algo,
                        out.n, pl, W, k, nt, epoch, tile_first, tile_last, status, capped ? 1 : 0);
     prof_end(lc, K_SPARSE_INDEX);
     prof_begin(lc, K_SPARSE_DECOMPRESS);
