@@ -334,6 +334,45 @@ def test_stochastic_draws_do_not_depend_on_partition():
     assert not np.array_equal(O.decode(whole, n), O.decode(other, n))
 
 
+def test_qsgd_draw_is_the_elements_own_philox_uniform():
+    """Which draw an element rounds with: the Philox uniform of (seed, worker, iteration, model-global index), the keying
+    of the random streams that the benchmark fixes ("keyed on (seed, worker, element)").  The level rule is retyped here
+    on top of O.uniform, whose counter / key layout the published Philox vectors and test_uniform_range_mean_and_keying
+    pin; group_off is no multiple of 4, worker and iteration are not 0, so a draw that drops any of them differs."""
+    n, goff, worker, it, seed, s = 3001, 1234567 * 4 + 3, 5, 9, 0x1234567890ABCDEF, 127
+    g = rand_group(n, 61, 0.05)
+    pay, norm = O.compress(O.Config(O.QSGD, use_ef=0, seed=seed), g, None, group_off=goff, worker=worker, it=it)
+    code = pay[O.HDR:O.HDR + n].view(np.int8).astype(np.int64)
+    r = np.float32(s) / np.float32(norm)
+    a = np.abs(g) * r                                  # fp32 product, as the rule states it
+    lo = np.floor(a)
+    frac = (a - lo).astype(np.float32)
+
+    def levels(w, i, off):
+        u = f32([O.uniform(seed, w, i, off + j) for j in range(n)])
+        return np.minimum(lo.astype(np.int64) + (u < frac), s)
+
+    want = levels(worker, it, goff)
+    assert np.array_equal(np.abs(code), want)
+    # the check can tell the streams apart: dropping the worker, the iteration or the group's offset changes levels
+    for w, i, off in ((0, it, goff), (worker, 0, goff), (worker, it, 0), (worker, it, goff - 3), (0, 0, 0)):
+        assert not np.array_equal(levels(w, i, off), want), (w, i, off)
+
+
+def test_qsgd_draws_do_not_depend_on_partition():
+    n, cut = 1000, 373          # cut not a multiple of 4: Philox blocks straddle the boundary
+    g = rand_group(n, 53, 0.1)
+    cfg = O.Config(O.QSGD, use_ef=0, seed=78)
+    norm = float(np.float32(np.linalg.norm(g.astype(np.float64))))
+    whole, _ = O.compress(cfg, g, None, group_off=8, worker=3, it=5, scale_in=norm)
+    a, _ = O.compress(cfg, g[:cut], None, group_off=8, worker=3, it=5, scale_in=norm)
+    b, _ = O.compress(cfg, g[cut:], None, group_off=8 + cut, worker=3, it=5, scale_in=norm)
+    assert np.array_equal(whole[O.HDR:O.HDR + n], np.concatenate([a[O.HDR:O.HDR + cut], b[O.HDR:O.HDR + n - cut]]))
+    for kw in (dict(worker=4, it=5), dict(worker=3, it=6)):
+        other, _ = O.compress(cfg, g, None, group_off=8, scale_in=norm, **kw)
+        assert not np.array_equal(whole[O.HDR:O.HDR + n], other[O.HDR:O.HDR + n])
+
+
 @pytest.mark.parametrize("algo", [O.EFSIGN, O.TOPK, O.DGC, O.QSGD, O.TERNGRAD, O.FP16])
 def test_all_zero_group_gives_zero_output(algo):
     n = 100
