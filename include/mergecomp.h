@@ -15,8 +15,9 @@
  *     tables and scratch allocated in mc_ctx_create, freed in mc_ctx_destroy).
  *   - mc_compress / mc_decompress_sum only enqueue kernels on the caller's HIP
  *     stream (void* = hipStream_t, NULL = the default stream).  They allocate
- *     nothing, never synchronise the host with the device and read nothing
- *     back.  All calls that use one context must be issued in stream order
+ *     nothing on the device or the host (the optional per-kernel profiler
+ *     creates HIP events while it is enabled), never synchronise the host with
+ *     the device and read nothing back.  All calls that use one context must be issued in stream order
  *     (one stream, or streams the caller has ordered with events): the context
  *     scratch and its cached pointer tables are shared between calls.
  *     The calls are not meant to be recorded into a HIP graph: iteration and
@@ -127,7 +128,7 @@ int mc_partition(const int64_t *numel, int32_t n_tensors, int32_t y, int32_t pol
 /*
  * Iteration-time model of Section 4.3 and the partition search of Algorithm 2.  Host-only.
  *
- * F(X_y) = A + sum h(x_i) + sum g(x_i) - sum p(x_i) with the linear overheads of Assumption 1,
+ * F(X_y) = A + sum h(x_i) + sum g(x_i) - sum p(x_i) with the linear overheads of Assumption 5 (Section 4.3),
  * h(x) = B_h + gamma_h x (compression) and g(x) = B_g + gamma_g x (communication), x in elements.
  * The overlap p is not given in closed form by the paper; the schedule it describes (wait-free
  * back-propagation, proof of Theorem 3) is evaluated directly: the GPU runs the forward pass
@@ -165,14 +166,23 @@ int mc_partition_search(const int64_t *numel, const double *bwd_time, int32_t n_
 /*
  * Create a context for one (config, tensor list, partition) on the current HIP
  * device.  All arrays are host memory and are copied.  Allocates the device
- * segment tables and scratch for every group.
+ * segment tables and scratch for every group, and reserves the host-side lists the
+ * hot calls fill, so that those allocate nothing.
+ * Device memory held by a context, with T = tiles of 4096 elements of its largest group:
+ *   every algorithm   24 T bytes of reduction partials; up to 64 cached tensor-address lists with one
+ *                     8-byte address per 1024 elements each (32 T bytes per list, 256 MiB at most in all)
+ *   sparsifiers       6 bytes per element of the largest group for candidate values and positions
+ *                     (24576 T; 153 MB for a 25.6 M element group), 1024 T + 16 T bytes of per-worker tile
+ *                     tables for the decompress, histograms and counters of about 100 KB
  */
 int mc_ctx_create(mc_ctx **out, const mc_config *cfg, const int64_t *numel, int32_t n_tensors,
                   const int32_t *bounds, int32_t y);
 int mc_ctx_destroy(mc_ctx *ctx);
 
-/* Elements n of a group / kept entries k = min(n, max(1, floor(n*ppm/1e6))) of a
- * sparsifier (0 for other algorithms) / number of tensors of the group. */
+/* Elements n of a group / entries of a sparsifier's payload (0 for other algorithms) / number of
+ * tensors of the group.  mc_group_k is the exact kept count k = min(n, max(1, floor(n*ppm/1e6))); for DGC
+ * with a sampled threshold (dgc_sample_ppm != 0) it is the payload's capacity min(n, 2k), of which the
+ * header of each payload says how many entries are in use. */
 int64_t mc_group_numel(const mc_ctx *ctx, int32_t group);
 int64_t mc_group_k(const mc_ctx *ctx, int32_t group);
 int32_t mc_group_tensors(const mc_ctx *ctx, int32_t group);
@@ -185,7 +195,9 @@ size_t mc_state_bytes(const mc_ctx *ctx, int32_t group);
 /*
  * delta = C(g) for one group of one worker (Algorithm 1), fused with the
  * error-feedback update (Section 3.2: error feedback costs another decode).
- *   worker, iter  only select the random stream of QSGD / TernGrad
+ *   worker, iter  select the random stream of QSGD / TernGrad / Rand-k / the sampled DGC (counter words: worker, and
+ *                 the low 32 bits of iter: streams repeat after 2^32 iterations); a sparsifier also keeps its
+ *                 candidate-filter hint per (group, worker modulo 64)
  *   grad_ptrs     host array, one DEVICE pointer per tensor of the group (fp32, contiguous,
  *                 4-byte aligned; 16-byte alignment enables the fastest path); read only
  *   state         device, mc_state_bytes() bytes, 16-byte aligned (128-byte alignment is fastest: the
@@ -204,7 +216,7 @@ int mc_compress(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter,
 /*
  * g~ = aggregate(C^-1(Delta)) for one group (Algorithm 1): decode the W workers'
  * payloads and write  out_i = alpha * (((0 + d_0,i) + d_1,i) + ... + d_{W-1,i})  in fp32.
- *   payloads   host array of W DEVICE pointers to payloads of this group
+ *   payloads   host array of W DEVICE pointers to payloads of this group, 1 <= W <= 64 (MC_ERR_RANGE above)
  *   out_ptrs   host array, one DEVICE pointer per tensor of the group; fully overwritten
  * A payload whose header does not match (magic, algorithm, n, k) is reported through
  * mc_last_device_status; out-of-range sparse indices are ignored, never written.

@@ -128,7 +128,7 @@ int orc_partition(const int64_t *numel, int32_t N, int32_t y, int32_t policy,
 
 /* ------------------------------------------------------------------------ */
 /* Iteration time of a partition (Section 4.3): F(X_y) = A + sum h(x_i) +      */
-/* sum g(x_i) - sum p(x_i) with linear h and g (Assumption 1).  The paper      */
+/* sum g(x_i) - sum p(x_i) with linear h and g (Assumption 5).  The paper      */
 /* gives no formula for the overlap p; it describes the schedule (wait-free    */
 /* back-propagation, proof of Theorem 3), which is simulated here:             */
 /*   - the GPU runs forward, then back-propagation tensor by tensor in list    */

@@ -338,10 +338,10 @@ __device__ __forceinline__ TileJob my_tile(const SparseScratch &sc, uint32_t n, 
 // ---------------------------------------------------------------------------
 // seed: 1024 threads per block.  Wavefront 0 of every block resolves the window
 // histogram; all blocks reach the same verdict.
-//   fast      the threshold lies in window bin b < 2047: block 0 records lo = hint + 1024 b
+//   fast      the threshold lies in window bin b < 2047: block 0 records lo = hint + 2048 b
 //             and the entries to take from that bin; everybody leaves
 //   above     it lies above the window: all blocks histogram bits 30..20 of key - lo of
-//             the candidates with key >= lo = hint + 1024 * 2047
+//             the candidates with key >= lo = hint + 2048 * 2047
 //   refill    fewer than k candidates: every element becomes a candidate (chunk c holds
 //             candidates 1024 c ...) and joins the level-1 histogram of the plain keys
 // ---------------------------------------------------------------------------

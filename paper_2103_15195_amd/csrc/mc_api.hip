@@ -59,6 +59,7 @@ struct mc_ctx {
     uint32_t *d_hints = nullptr;        // candidate-filter hints: kHintWorkers per group (worker id modulo that)
     int *d_status = nullptr;
     std::vector<PtrSlot> slots;
+    std::vector<uintptr_t> want;        // the address list of the call in progress (reserved at creation)
     uint64_t clock = 0;
     uint32_t epoch = 0;                 // stamps the sparse decompress tile table; 0 is never used
     Profiler prof;
@@ -139,6 +140,17 @@ static uint32_t philox_word(uint64_t seed, uint32_t worker, uint32_t iter_lo, ui
     }
     return c[global_index & 3u];
 }
+
+// makes the context's device current for the duration of a call that synchronises or copies
+struct DeviceGuard {
+    int prev = -1;
+    bool switched = false;
+    explicit DeviceGuard(int device)
+    {
+        if (hipGetDevice(&prev) == hipSuccess && prev != device) switched = hipSetDevice(device) == hipSuccess;
+    }
+    ~DeviceGuard() { if (switched) (void)hipSetDevice(prev); }
+};
 
 static bool is_sparse(int algo) { return algo == MC_ALGO_TOPK || algo == MC_ALGO_DGC || algo == MC_ALGO_RANDK; }
 // n-element vectors of a group's state: the residual (DGC: v and u; SigNUM: the momentum; SignSGD: nothing)
@@ -401,6 +413,9 @@ int mc_ctx_create(mc_ctx **out, const mc_config *cfg, const int64_t *numel, int3
                     hipMalloc(&s.dev_chunk, tiles * kWavesPerBlock * sizeof(uintptr_t)) != hipSuccess) { rc = MC_ERR_ALLOC; break; }
                 s.host.reserve(ctx->max_live);
             }
+            ctx->want.reserve(ctx->max_live);
+            ctx->prof.pending.reserve(1024);
+            ctx->prof.pool.reserve(2048);
         }
         if (rc == MC_OK && hipDeviceSynchronize() != hipSuccess) rc = MC_ERR_DEVICE;
     } catch (const std::bad_alloc &) {
@@ -453,7 +468,7 @@ size_t mc_state_bytes(const mc_ctx *ctx, int32_t group)
 // will read it.
 static GroupView group_view(mc_ctx *ctx, const LaunchCtx &lc, int32_t group, const Group &g, const void *const *ptrs)
 {
-    static thread_local std::vector<uintptr_t> want;
+    std::vector<uintptr_t> &want = ctx->want;     // capacity max_live: no allocation here
     want.clear();
     for (int32_t rel : g.live) want.push_back(reinterpret_cast<uintptr_t>(ptrs[rel]));
     GroupView gv{g.d_seg_off, g.d_chunk_seg, nullptr, nullptr, (uint32_t)g.live.size(), g.n, g.goff};
@@ -598,7 +613,9 @@ static int state_convert(mc_ctx *ctx, int32_t group, const void *src, void *dst,
     const size_t nf = (size_t)g->n * state_vectors(ctx->cfg.algo);
     // an empty group has no residual: the plain side may be null, the opaque side never
     if (!(to_residual ? src : dst) || (nf > 0 && !(to_residual ? dst : src))) return MC_ERR_INVALID_ARG;
-    if (nf == 0 && to_residual) return MC_OK;
+    // Nothing to convert (an empty group, or SignSGD, which keeps no state vector): neither side is touched.  The
+    // kernel below indexes by the group's n, so it must never run for an algorithm without state vectors.
+    if (nf == 0) return MC_OK;
     LaunchCtx lc{static_cast<hipStream_t>(stream), &ctx->prof, nullptr, nullptr};
     (void)hipGetLastError();
     const uint32_t levels = ctx->cfg.algo == MC_ALGO_QSGD ? (1u << (ctx->cfg.qsgd_bits - 1)) - 1u : 0u;
@@ -620,6 +637,7 @@ int mc_last_device_status(mc_ctx *ctx)
 {
     if (!ctx) return MC_ERR_INVALID_ARG;
     int flag = 0;
+    DeviceGuard on(ctx->device);
     if (hipDeviceSynchronize() != hipSuccess) return MC_ERR_DEVICE;
     if (hipMemcpy(&flag, ctx->d_status, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess) return MC_ERR_DEVICE;
     if (flag && hipMemset(ctx->d_status, 0, sizeof(int)) != hipSuccess) return MC_ERR_DEVICE;
@@ -630,6 +648,7 @@ int mc_last_select_route(mc_ctx *ctx)
 {
     if (!ctx || !is_sparse(ctx->cfg.algo) || !ctx->sparse.sel) return MC_ERR_INVALID_ARG;
     SelectState s;
+    DeviceGuard on(ctx->device);
     if (hipDeviceSynchronize() != hipSuccess) return MC_ERR_DEVICE;
     if (hipMemcpy(&s, ctx->sparse.sel, sizeof(s), hipMemcpyDeviceToHost) != hipSuccess) return MC_ERR_DEVICE;
     return (s.mode & 1u) ? MC_SELECT_FAST : (s.mode & 2u) ? MC_SELECT_REFILL : MC_SELECT_ABOVE;
