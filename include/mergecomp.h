@@ -214,6 +214,26 @@ int mc_compress(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter,
                 const float *const *grad_ptrs, void *state, void *payload_out, void *stream);
 
 /*
+ * mc_compress for callers that cannot allocate device memory and must not have it allocated on their behalf
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc).  Same arguments, same
+ * payload and state, bit for bit; the difference is where the kernels keep their per-tile reduction partials:
+ * not in the context's scratch but in a device array of fixed size that is part of the library's code object
+ * (mc_static_scratch_bytes() = 384 KiB, held by every GPU the library runs on until the process ends).  Calls
+ * neither hipMalloc nor hipFree nor any allocating routine, and records no profiler events.
+ *   Limits   a group of at most mc_static_max_elems() = 2^26 elements (MC_ERR_RANGE above);
+ *            EF-Sign, OneBit, SignSGD, SigNUM, QSGD, TernGrad, FP16 only: the sparsifiers return
+ *            MC_ERR_INVALID_ARG (their candidate scratch grows with 6 bytes per element and stays in
+ *            the context)
+ *   Sharing  all calls on one GPU, from every context, use the same array: calls that may overlap on one
+ *            GPU (different streams without ordering, several host threads) race on it and must be ordered
+ *            by the caller.  Nothing in it has to start at zero: every call overwrites what it reads.
+ */
+int mc_compress_static(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter,
+                       const float *const *grad_ptrs, void *state, void *payload_out, void *stream);
+size_t mc_static_scratch_bytes(void);
+int64_t mc_static_max_elems(void);
+
+/*
  * g~ = aggregate(C^-1(Delta)) for one group (Algorithm 1): decode the W workers'
  * payloads and write  out_i = alpha * (((0 + d_0,i) + d_1,i) + ... + d_{W-1,i})  in fp32.
  *   payloads   host array of W DEVICE pointers to payloads of this group, 1 <= W <= 64 (MC_ERR_RANGE above)

@@ -24,7 +24,8 @@ MC_OK, MC_ERR_INVALID_ARG, MC_ERR_RANGE, MC_ERR_ALLOC, MC_ERR_DEVICE, MC_ERR_PAY
 
 EXPORTS = [
     "mc_partition", "mc_partition_cost", "mc_partition_search", "mc_ctx_create", "mc_ctx_destroy", "mc_group_numel", "mc_group_k", "mc_group_tensors",
-    "mc_payload_bytes", "mc_state_bytes", "mc_compress", "mc_decompress_sum", "mc_state_export_residual",
+    "mc_payload_bytes", "mc_state_bytes", "mc_compress", "mc_compress_static", "mc_static_scratch_bytes", "mc_static_max_elems",
+    "mc_decompress_sum", "mc_state_export_residual",
     "mc_state_import_residual", "mc_last_device_status", "mc_last_select_route", "mc_profile_enable", "mc_profile_select", "mc_profile_reset",
     "mc_profile_kernels", "mc_profile_read", "mc_strerror", "mc_version",
 ]
@@ -73,6 +74,11 @@ def lib():
             f.argtypes = [vp, i32]
             f.restype = C.c_size_t
         L.mc_compress.argtypes = [vp, i32, u32, u64, vp, vp, vp, vp]
+        L.mc_compress_static.argtypes = [vp, i32, u32, u64, vp, vp, vp, vp]
+        L.mc_static_scratch_bytes.argtypes = []
+        L.mc_static_scratch_bytes.restype = C.c_size_t
+        L.mc_static_max_elems.argtypes = []
+        L.mc_static_max_elems.restype = i64
         L.mc_decompress_sum.argtypes = [vp, i32, vp, i32, C.c_float, vp, vp]
         L.mc_state_export_residual.argtypes = [vp, i32, vp, vp, vp]
         L.mc_state_import_residual.argtypes = [vp, i32, vp, vp, vp]
@@ -198,6 +204,12 @@ class Context:
         _check(lib().mc_compress(self._h, group, worker, it, _ptr_array(grads),
                                  None if state is None else state.data_ptr(), payload.data_ptr(),
                                  _stream_handle(stream)), "mc_compress")
+
+    def mc_compress_static(self, group: int, worker: int, it: int, grads: Sequence, state, payload, stream=None) -> None:
+        """mc_compress with the reduction partials in the library's static device array (allocates nothing)."""
+        _check(lib().mc_compress_static(self._h, group, worker, it, _ptr_array(grads),
+                                        None if state is None else state.data_ptr(), payload.data_ptr(),
+                                        _stream_handle(stream)), "mc_compress_static")
 
     def mc_decompress_sum(self, group: int, payloads: Sequence, alpha: float, outs: Sequence, stream=None) -> None:
         W = len(payloads)

@@ -4,6 +4,7 @@
 // values; every step of the path runs in the kernels.
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <limits>
 #include <vector>
@@ -35,6 +36,35 @@ struct PtrSlot {
     uintptr_t *dev_chunk = nullptr;      // per-chunk direct addresses derived from them
 };
 
+// ---- scratch of the allocation-free entry point (mc_compress_static) ------------------------------------
+// The per-tile reduction partials of the dense compressors (three arrays of one double per 4096-element tile:
+// OneBit reduces two sums and a count) for groups of up to kStaticMaxElems elements, in a file-scope device
+// array that every GPU the library runs on holds from the moment the code object is loaded.  The array's name
+// is only a host-side handle: its device address is looked up once per device (static_scratch_for) and it is
+// that pointer which the kernels receive.
+constexpr uint64_t kStaticMaxElems = 1ull << 26;
+constexpr size_t kStaticMaxTiles = (size_t)(kStaticMaxElems / kTile);
+constexpr size_t kStaticScratchBytes = 3 * kStaticMaxTiles * sizeof(double);        // 384 KiB
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_static_mutex;
+static void *g_static_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on `device`, which must be the current device (each GPU holds its own copy of the
+// array at its own address).  Looked up on the first call for a device, then served from the table.
+static void *static_scratch_for(int device)
+{
+    if (device < 0 || device >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[device]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+        g_static_ptr[device] = ptr;
+    }
+    return g_static_ptr[device];
+}
+
 struct ProfEvent { int id; hipEvent_t a, b; };
 
 struct Profiler {
@@ -58,6 +88,7 @@ struct mc_ctx {
     SparseScratch sparse{};
     uint32_t *d_hints = nullptr;        // candidate-filter hints: kHintWorkers per group (worker id modulo that)
     int *d_status = nullptr;
+    void *static_scratch = nullptr;     // this device's copy of the file-scope scratch array (mc_compress_static)
     std::vector<PtrSlot> slots;
     std::vector<uintptr_t> want;        // the address list of the call in progress (reserved at creation)
     uint64_t clock = 0;
@@ -417,6 +448,8 @@ int mc_ctx_create(mc_ctx **out, const mc_config *cfg, const int64_t *numel, int3
             ctx->prof.pending.reserve(1024);
             ctx->prof.pool.reserve(2048);
         }
+        // the device address of the static scratch array, looked up here with the context's device current
+        if (rc == MC_OK && !(ctx->static_scratch = static_scratch_for(ctx->device))) rc = MC_ERR_DEVICE;
         if (rc == MC_OK && hipDeviceSynchronize() != hipSuccess) rc = MC_ERR_DEVICE;
     } catch (const std::bad_alloc &) {
         rc = MC_ERR_ALLOC;
@@ -497,8 +530,10 @@ static GroupView group_view(mc_ctx *ctx, const LaunchCtx &lc, int32_t group, con
 
 static int check_launch() { return hipGetLastError() == hipSuccess ? MC_OK : MC_ERR_DEVICE; }
 
-int mc_compress(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter, const float *const *grad_ptrs, void *state,
-                void *payload_out, void *stream)
+// partial: the per-tile reduction partials (three arrays of one double per tile of the group); prof: the context's
+// profiler, or null for a call that must not create events
+static int compress_impl(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter, const float *const *grad_ptrs, void *state,
+                         void *payload_out, void *stream, double *partial, Profiler *prof)
 {
     const Group *gp = group_of(ctx, group);
     if (!gp || !payload_out) return MC_ERR_INVALID_ARG;
@@ -510,7 +545,7 @@ int mc_compress(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter, cons
     for (int32_t rel : G.live) if (!grad_ptrs[rel] || (reinterpret_cast<uintptr_t>(grad_ptrs[rel]) & 3u)) return MC_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(payload_out) & 15u) || (reinterpret_cast<uintptr_t>(state) & 15u)) return MC_ERR_INVALID_ARG;
 
-    LaunchCtx lc{static_cast<hipStream_t>(stream), &ctx->prof, nullptr, nullptr};
+    LaunchCtx lc{static_cast<hipStream_t>(stream), prof, nullptr, nullptr};
     (void)hipGetLastError();
     PayloadHeader *hdr = static_cast<PayloadHeader *>(payload_out);
     uint8_t *body = static_cast<uint8_t *>(payload_out) + kHeaderBytes;
@@ -522,32 +557,32 @@ int mc_compress(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter, cons
 
     if (n == 0) {   // nothing to encode: the payload is its header
         const bool votes = cfg.algo == MC_ALGO_SIGNSGD || cfg.algo == MC_ALGO_SIGNUM;
-        launch_scalar_finalize(lc, ctx->d_partial, 0, votes ? RED_ONE : -1, 0, hdr, (uint32_t)cfg.algo, 0, levels, nullptr);
+        launch_scalar_finalize(lc, partial, 0, votes ? RED_ONE : -1, 0, hdr, (uint32_t)cfg.algo, 0, levels, nullptr);
         return check_launch();
     }
     GroupView gv = group_view(ctx, lc, group, G, reinterpret_cast<const void *const *>(grad_ptrs));
     switch (cfg.algo) {
     case MC_ALGO_EFSIGN:
-        launch_sign_compress(lc, SIGN_EF, gv, ef, sf, sh, 0.0f, reinterpret_cast<uint32_t *>(body), nwords, ctx->d_partial, hdr, MC_ALGO_EFSIGN);
-        launch_scalar_finalize(lc, ctx->d_partial, tiles, RED_MEAN_ABS, n, hdr, MC_ALGO_EFSIGN, 0, 0, ef ? &sh->scale : nullptr);
+        launch_sign_compress(lc, SIGN_EF, gv, ef, sf, sh, 0.0f, reinterpret_cast<uint32_t *>(body), nwords, partial, hdr, MC_ALGO_EFSIGN);
+        launch_scalar_finalize(lc, partial, tiles, RED_MEAN_ABS, n, hdr, MC_ALGO_EFSIGN, 0, 0, ef ? &sh->scale : nullptr);
         break;
     case MC_ALGO_ONEBIT:
-        launch_sign_compress(lc, SIGN_MEANS, gv, ef, sf, sh, 0.0f, reinterpret_cast<uint32_t *>(body), nwords, ctx->d_partial, hdr, MC_ALGO_ONEBIT);
-        launch_scalar_finalize(lc, ctx->d_partial, tiles, RED_MEANS, n, hdr, MC_ALGO_ONEBIT, 0, 0, ef ? &sh->scale : nullptr);
+        launch_sign_compress(lc, SIGN_MEANS, gv, ef, sf, sh, 0.0f, reinterpret_cast<uint32_t *>(body), nwords, partial, hdr, MC_ALGO_ONEBIT);
+        launch_scalar_finalize(lc, partial, tiles, RED_MEANS, n, hdr, MC_ALGO_ONEBIT, 0, 0, ef ? &sh->scale : nullptr);
         break;
     case MC_ALGO_SIGNSGD:
     case MC_ALGO_SIGNUM:
         launch_sign_compress(lc, cfg.algo == MC_ALGO_SIGNSGD ? SIGN_PLAIN : SIGN_MOMENTUM, gv, ef, sf, sh, cfg.dgc_momentum,
-                             reinterpret_cast<uint32_t *>(body), nwords, ctx->d_partial, hdr, (uint32_t)cfg.algo);
+                             reinterpret_cast<uint32_t *>(body), nwords, partial, hdr, (uint32_t)cfg.algo);
         break;
     case MC_ALGO_QSGD:
-        launch_accum_reduce(lc, gv, ef, sf, sh, RED_L2, levels, cfg.seed, ctx->d_partial);
-        launch_scalar_finalize(lc, ctx->d_partial, tiles, RED_L2, n, hdr, MC_ALGO_QSGD, 0, levels, nullptr);
+        launch_accum_reduce(lc, gv, ef, sf, sh, RED_L2, levels, cfg.seed, partial);
+        launch_scalar_finalize(lc, partial, tiles, RED_L2, n, hdr, MC_ALGO_QSGD, 0, levels, nullptr);
         launch_qsgd_encode(lc, gv, ef, sf, sh, hdr, reinterpret_cast<int8_t *>(body), levels, cfg.seed, worker, (uint32_t)iter);
         break;
     case MC_ALGO_TERNGRAD:
-        launch_accum_reduce(lc, gv, ef, sf, sh, RED_MAX_ABS, 0, cfg.seed, ctx->d_partial);
-        launch_scalar_finalize(lc, ctx->d_partial, tiles, RED_MAX_ABS, n, hdr, MC_ALGO_TERNGRAD, 0, 0, nullptr);
+        launch_accum_reduce(lc, gv, ef, sf, sh, RED_MAX_ABS, 0, cfg.seed, partial);
+        launch_scalar_finalize(lc, partial, tiles, RED_MAX_ABS, n, hdr, MC_ALGO_TERNGRAD, 0, 0, nullptr);
         launch_tern_encode(lc, gv, ef, sf, sh, hdr, reinterpret_cast<uint32_t *>(body), nwords, cfg.seed, worker, (uint32_t)iter);
         break;
     case MC_ALGO_FP16:
@@ -576,6 +611,31 @@ int mc_compress(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter, cons
     }
     return check_launch();
 }
+
+int mc_compress(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter, const float *const *grad_ptrs, void *state,
+                void *payload_out, void *stream)
+{
+    if (!ctx) return MC_ERR_INVALID_ARG;
+    return compress_impl(ctx, group, worker, iter, grad_ptrs, state, payload_out, stream, ctx->d_partial, &ctx->prof);
+}
+
+int mc_compress_static(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t iter, const float *const *grad_ptrs, void *state,
+                       void *payload_out, void *stream)
+{
+    const Group *gp = group_of(ctx, group);
+    if (!gp) return MC_ERR_INVALID_ARG;
+    // the sparsifiers' scratch (candidate slots, 6 bytes per element) is not what the static array holds
+    if (is_sparse(ctx->cfg.algo)) return MC_ERR_INVALID_ARG;
+    if ((uint64_t)gp->n > kStaticMaxElems) return MC_ERR_RANGE;
+    if (!ctx->static_scratch) return MC_ERR_DEVICE;
+    // every tile's partial is written by the compress kernel before the one-block combine reads it: nothing in the
+    // array has to start at zero, whatever an earlier call left there
+    return compress_impl(ctx, group, worker, iter, grad_ptrs, state, payload_out, stream,
+                         static_cast<double *>(ctx->static_scratch), nullptr);
+}
+
+size_t mc_static_scratch_bytes(void) { return kStaticScratchBytes; }
+int64_t mc_static_max_elems(void) { return (int64_t)kStaticMaxElems; }
 
 int mc_decompress_sum(mc_ctx *ctx, int32_t group, const void *const *payloads, int32_t W, float alpha,
                       float *const *out_ptrs, void *stream)
