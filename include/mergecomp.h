@@ -266,8 +266,20 @@ int mc_last_device_status(mc_ctx *ctx);
  *                     streamed a second time
  * The result of mc_compress is identical on all routes; only its cost differs.
  * Returns the route, or a negative mc_status (MC_ERR_INVALID_ARG for a dense algorithm). */
-enum { MC_SELECT_ABOVE = 0, MC_SELECT_FAST = 1, MC_SELECT_REFILL = 2 };
+enum { MC_SELECT_ABOVE = 0, MC_SELECT_FAST = 1, MC_SELECT_REFILL = 2, MC_SELECT_DENSE = 3 };
 int mc_last_select_route(mc_ctx *ctx);
+
+/* Counts of mc_compress calls by the route their selection took (indexed by the MC_SELECT_ values) since
+ * the context was created or the counts were last reset, for the sparsifiers without a sampled threshold;
+ * and, of the most recent call, the number of keys that shared the threshold's window bin (the two-kernel
+ * route lists them: at most 2048) and of elements that passed the candidate filter (modulo 2^32).
+ * Synchronises the context's device.  Errors: MC_ERR_INVALID_ARG (null, dense algorithm). */
+typedef struct {
+    int64_t calls[4];
+    int64_t last_bin_keys;
+    int64_t last_candidates;
+} mc_select_counts;
+int mc_select_stats(mc_ctx *ctx, mc_select_counts *out, int32_t reset);
 
 /*
  * Per-kernel timing with HIP events recorded on the caller's stream around each

@@ -19,14 +19,14 @@ MC_ALGO_SIGNSGD, MC_ALGO_SIGNUM, MC_ALGO_ONEBIT, MC_ALGO_RANDK = 7, 8, 9, 10
 ALGO_IDS = {"efsign": 1, "topk": 2, "dgc": 3, "qsgd": 4, "terngrad": 5, "fp16": 6,
             "signsgd": 7, "signum": 8, "onebit": 9, "randk": 10}
 MC_PART_EVEN_COUNT, MC_PART_EVEN_ELEMS, MC_PART_USER = 0, 1, 2
-MC_SELECT_ABOVE, MC_SELECT_FAST, MC_SELECT_REFILL = 0, 1, 2
+MC_SELECT_ABOVE, MC_SELECT_FAST, MC_SELECT_REFILL, MC_SELECT_DENSE = 0, 1, 2, 3
 MC_OK, MC_ERR_INVALID_ARG, MC_ERR_RANGE, MC_ERR_ALLOC, MC_ERR_DEVICE, MC_ERR_PAYLOAD = 0, -1, -2, -3, -4, -5
 
 EXPORTS = [
     "mc_partition", "mc_partition_cost", "mc_partition_search", "mc_ctx_create", "mc_ctx_destroy", "mc_group_numel", "mc_group_k", "mc_group_tensors",
     "mc_payload_bytes", "mc_state_bytes", "mc_compress", "mc_compress_static", "mc_static_scratch_bytes", "mc_static_max_elems",
     "mc_decompress_sum", "mc_state_export_residual",
-    "mc_state_import_residual", "mc_last_device_status", "mc_last_select_route", "mc_profile_enable", "mc_profile_select", "mc_profile_reset",
+    "mc_state_import_residual", "mc_last_device_status", "mc_last_select_route", "mc_select_stats", "mc_profile_enable", "mc_profile_select", "mc_profile_reset",
     "mc_profile_kernels", "mc_profile_read", "mc_strerror", "mc_version",
 ]
 
@@ -39,6 +39,10 @@ class McConfig(C.Structure):
 class McTimeModel(C.Structure):
     _fields_ = [("fwd_time", C.c_double), ("B_h", C.c_double), ("gamma_h", C.c_double), ("B_g", C.c_double),
                 ("gamma_g", C.c_double)]
+
+
+class McSelectCounts(C.Structure):
+    _fields_ = [("calls", C.c_int64 * 4), ("last_bin_keys", C.c_int64), ("last_candidates", C.c_int64)]
 
 
 class McError(RuntimeError):
@@ -84,6 +88,7 @@ def lib():
         L.mc_state_import_residual.argtypes = [vp, i32, vp, vp, vp]
         L.mc_last_device_status.argtypes = [vp]
         L.mc_last_select_route.argtypes = [vp]
+        L.mc_select_stats.argtypes = [vp, C.POINTER(McSelectCounts), i32]
         L.mc_profile_enable.argtypes = [vp, i32]
         L.mc_profile_select.argtypes = [vp, u64]
         L.mc_profile_reset.argtypes = [vp]
@@ -233,6 +238,12 @@ class Context:
         if r < 0:
             raise McError(r, "mc_last_select_route")
         return r
+
+    def mc_select_stats(self, reset: bool = False) -> dict:
+        c = McSelectCounts()
+        _check(lib().mc_select_stats(self._h, C.byref(c), 1 if reset else 0), "mc_select_stats")
+        return {"above": c.calls[0], "fast": c.calls[1], "refill": c.calls[2], "dense": c.calls[3],
+                "last_bin_keys": c.last_bin_keys, "last_candidates": c.last_candidates}
 
     # profiling ------------------------------------------------------------------
     def profile_enable(self, on: bool, all_kernels: bool = False) -> None:

@@ -33,6 +33,8 @@
 // wavefront: tiles are independent until the emit kernel adds up the kept counts
 // of the tiles before its own.  No kernel waits on another block: every dependency
 // is a kernel boundary.
+#include <algorithm>
+
 #include "mc_internal.h"
 
 namespace mc {
@@ -71,6 +73,8 @@ constexpr int kHintShift = 1, kHintHold = 2;
 constexpr uint32_t kHintShiftMax = 3u, kHintHoldCalls = 8u;
 constexpr uint32_t kModeFast = 1u;      // lo / need are those of level 3 already
 constexpr uint32_t kModeUniform = 2u;   // after a refill: every element is a candidate, chunk c holds 1024 c ...
+constexpr uint32_t kModeLean = 4u;      // fast, and the keys of the threshold's window bin were listed: the emit kernel finishes alone
+constexpr uint32_t kModeDense = 8u;     // fast, but that bin holds too many keys to list: its 2048 keys were histogrammed instead
 
 __device__ __forceinline__ uint32_t key_of(float x) { return __float_as_uint(x) & 0x7FFFFFFFu; }
 
@@ -135,6 +139,9 @@ __global__ __launch_bounds__(kBlock) void sparse_accum_k(GroupView g, float *st,
     __syncthreads();
     const Chunk c = my_chunk(g.n);
     const uint32_t hint = *sc.hint;
+    // the emit kernel of the call before is done with the list of keys in the threshold's bin: its sublists are empty again
+    if (blockIdx.x == 0 && threadIdx.x < (uint32_t)kUSub) sc.ucount[threadIdx.x * kUCountStride] = 0u;
+    if (blockIdx.x == 0 && threadIdx.x == 0) sc.sync[0] = 0u;       // and nobody waits at a grid-wide barrier of that call any more
     uint32_t run = 0;
     if (c.base < g.n) {
         float p[kSteps];
@@ -235,6 +242,48 @@ __device__ __forceinline__ bool resolve_wave(const uint32_t *fine, uint64_t need
     }
     const uint64_t hit = __builtin_amdgcn_ballot_w64(mine);
     const uint32_t src_lane = hit ? (uint32_t)__builtin_ctzll(hit) : 0u;     // an inconsistent histogram still gives a defined bin
+    bin = __shfl(b, src_lane, 64);
+    rest = __shfl(r, src_lane, 64);
+    return hit != 0;
+}
+
+// The same for a histogram in LDS.  There the adjacent bins of a lane would all fall into the banks that every
+// other lane's bins fall into (a lane owns BINS / 64 = 32 consecutive words: 64 lanes, one bank group), and the
+// reads of a wavefront would be served one lane at a time -- measured: the resolve of a 2048-bin histogram by
+// all four wavefronts of all blocks made the emit kernel twice as long.  Each lane therefore reads its bins in
+// an order rotated by its lane number, which spreads every read over all banks; the lane in which the count
+// crosses `need` reads its bins once more, in order.
+template <int BINS>
+__device__ __forceinline__ bool resolve_lds(const uint32_t *fine, uint64_t need, uint32_t &bin, uint64_t &rest,
+                                            uint32_t top_extra = 0u, uint64_t *total = nullptr)
+{
+    constexpr int kPer = BINS / 64;
+    static_assert((kPer & (kPer - 1)) == 0, "rotation needs a power of two");
+    const uint32_t lane = threadIdx.x & 63u;
+    uint64_t own = 0;
+#pragma unroll 4              // (a few reads in flight are enough; all 32 at once cost the calling kernel its registers)
+    for (int i = 0; i < kPer; ++i) own += fine[lane * kPer + ((i + lane) & (kPer - 1))];
+    if (lane == 63u) own += top_extra;
+    uint64_t incl = own;                                    // inclusive suffix sum over lanes
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        uint64_t o = __shfl_down(incl, d, 64);
+        if (lane + d < 64) incl += o;
+    }
+    if (total) *total = __shfl(incl, 0, 64);
+    uint64_t run = incl - own;                              // keys in the bins of higher lanes
+    const bool mine = run < need && need <= incl;
+    uint32_t b = 0;
+    uint64_t r = 0;
+    if (mine) {
+        for (int i = kPer - 1; i >= 0; --i) {
+            const uint64_t h = (uint64_t)fine[lane * kPer + i] + (lane == 63u && i == kPer - 1 ? top_extra : 0u);
+            if (run < need && need <= run + h) { b = lane * kPer + i; r = need - run; }
+            run += h;
+        }
+    }
+    const uint64_t hit = __builtin_amdgcn_ballot_w64(mine);
+    const uint32_t src_lane = hit ? (uint32_t)__builtin_ctzll(hit) : 0u;
     bin = __shfl(b, src_lane, 64);
     rest = __shfl(r, src_lane, 64);
     return hit != 0;
@@ -371,7 +420,7 @@ __global__ __launch_bounds__(kSeedThreads) void sparse_seed_k(GroupView g, const
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) open += __shfl_xor(open, d, 64);
         uint64_t cands;
-        const bool found = resolve_wave<kBinsW>(wbins, k, bin, rest, open, &cands);
+        const bool found = resolve_lds<kBinsW>(wbins, k, bin, rest, open, &cands);
         if (lane == 0) {
             verdict[0] = found; verdict[1] = bin; verdict[2] = (uint32_t)rest; verdict[3] = (uint32_t)(rest >> 32);
             verdict[4] = (uint32_t)cands; verdict[5] = (uint32_t)(cands >> 32);
@@ -582,6 +631,33 @@ __global__ __launch_bounds__(kBlock) void cand_count_k(uint32_t n, uint32_t ntil
 //   (#kept before it) = (#above before it) + min(#equal before it, need).
 // Every block adds up the counts of the blocks before it; nothing waits.
 // ---------------------------------------------------------------------------
+// The walk of one tile's candidates that both emit kernels share: gt_before / eq_before are the numbers of keys
+// above / equal to T among all candidates before this tile.
+template <int ALGO, bool EF>
+__device__ __forceinline__ void emit_tile(const SparseScratch &sc, uint32_t tile, uint64_t runs, uint32_t n, uint64_t k, float *st,
+                                          uint32_t *idx, float *val, uint32_t T, uint64_t need, uint64_t gt_before, uint64_t eq_before)
+{
+    tile_walk<true>(sc, tile, runs, [&](bool valid, uint32_t chunk, uint32_t b, uint32_t loc) {
+        const uint32_t key = b & 0x7FFFFFFFu;
+        const bool is_gt = valid && key > T, is_eq = valid && key == T;
+        const uint64_t bgt = __builtin_amdgcn_ballot_w64(is_gt), beq = __builtin_amdgcn_ballot_w64(is_eq);
+        const uint64_t gtb = gt_before + lanes_below(bgt), eqb = eq_before + lanes_below(beq);
+        if (is_gt || (is_eq && eqb < need)) {
+            const uint64_t pos = gtb + (eqb < need ? eqb : need);
+            const uint32_t i = chunk * (uint32_t)kChunk + loc;
+            if (pos < k && i < n) {                  // exact selection: always true for consistent scratch; CAPPED: room left
+                idx[pos] = i;
+                if (ALGO == MC_ALGO_RANDK) val[pos] = st[i];      // the candidate slot holds the random key: the value is p
+                else val[pos] = __uint_as_float(b);
+                if (ALGO == MC_ALGO_DGC) { st[i] = 0.0f; st[dgc_u_offset(n) + i] = 0.0f; }   // momentum factor masking
+                else if (EF) st[i] = 0.0f;
+            }
+        }
+        gt_before += __popcll(bgt);
+        eq_before += __popcll(beq);
+    });
+}
+
 // CAPPED (DGC with a sampled threshold): T comes from the sample, so the number of keys >= T varies.
 // k is then the payload's capacity: all keys above T are kept in index order while there is room, then
 // keys equal to T; the header records how many entries were kept and unused entries are zeroed.
@@ -653,30 +729,632 @@ __global__ __launch_bounds__(kBlock) void cand_emit_k(uint32_t n, uint32_t ntile
         *hdr = h;
     }
     if (s3.mode & kModeUniform) job.runs = job.tile < ntiles ? uniform_runs(job.tile, n) : 0ull;
-    tile_walk<true>(sc, job.tile, job.runs, [&](bool valid, uint32_t chunk, uint32_t b, uint32_t loc) {
-        const uint32_t key = b & 0x7FFFFFFFu;
+    emit_tile<ALGO, EF>(sc, job.tile, job.runs, n, k, st, idx, val, T, need, gt_before, eq_before);
+}
+
+// ---------------------------------------------------------------------------
+// The two-kernel tail (everything but DGC with a sampled threshold).
+//
+//   select   every block (16 wavefronts, one 4096-element tile each) resolves the window on its own -- no
+//            kernel in between just to reduce 2048 bins -- and all blocks reach the same verdict:
+//     lean     the threshold lies in window bin b, which holds at most kUCap keys.  Every key above the
+//              bin is kept whatever the threshold turns out to be: their number per tile and per block is
+//              all the emit kernel needs of them.  The keys inside the bin -- a few hundred out of
+//              millions -- are appended to a list.
+//     dense    bin b holds more than kUCap keys (heavy ties, or a pile of values just under the
+//              threshold): the blocks histogram its 2048 keys, as level 3 of a radix select
+//     above    the threshold lies above the window: level 1 (bits 30..20 above the window's top) over
+//              the candidates
+//     refill   fewer than k candidates: every element becomes a candidate, level 1 over all keys
+//   emit     lean: every block reads the whole list (it is small), finds the threshold key T and the
+//            number of keys equal to T to take with a histogram in LDS, counts the list's kept keys
+//            that lie before each of its tiles, adds the kept counts of the blocks before it, and
+//            compacts its tiles' kept candidates into the payload.  One kernel after the select: no
+//            level-3 pass, no counting pass.
+//            Otherwise the remaining radix levels, the per-tile counts and the compaction run as steps
+//            of this same kernel on as many blocks as the device surely holds at once, separated by
+//            grid-wide barriers: the rare routes cost no launch on the usual one.
+// Both kernels are bound by memory latency, not by traffic, so each asks for its tile's candidates as soon
+// as it knows how many there are, before it waits for anything else.
+// ---------------------------------------------------------------------------
+constexpr int kSelThreads = 1024, kSelWaves = kSelThreads / 64;      // select: 16 tiles per block (the window is read once per block)
+constexpr int kEmitThreads = kBlock, kEmitWaves = kWavesPerBlock;    // emit: 4 tiles per block
+constexpr int kUKeep = 2;              // list entries that a thread of an emit block keeps in registers between its two walks of the list
+constexpr int kSyncArrive = 0, kSyncRoutes = 32, kSyncLastBin = 40, kSyncLastCands = 41;     // words of SparseScratch::sync (mc_api.hip reads the last three)
+constexpr int kFewRounds = 4;          // a tile with at most 256 candidates is fetched whole
+constexpr int kHeavyRounds = 8;        // other tiles 512 candidates at a time (emit)
+constexpr int kDeepRounds = 8;         // select: 512 candidates at a time, the first 512 asked for before the verdict is known
+
+struct TileRuns { uint32_t r0, r1, r2, total; };       // running sums of the candidates of a tile's four chunks
+__device__ __forceinline__ TileRuns decode_runs(uint64_t runs)
+{
+    TileRuns r;
+    r.r0 = (uint32_t)(runs & 0xFFFFu); r.r1 = r.r0 + (uint32_t)((runs >> 16) & 0xFFFFu);
+    r.r2 = r.r1 + (uint32_t)((runs >> 32) & 0xFFFFu); r.total = r.r2 + (uint32_t)(runs >> 48);
+    return r;
+}
+
+// ROUNDS rounds of 64 of a tile's candidates, from candidate number f0 on; candidate f0 + 64 u + lane is there if
+// that number is below the tile's total.  at: group-relative index of the element.
+template <int ROUNDS>
+struct CandBatch { uint32_t bits[ROUNDS], at[ROUNDS]; };
+
+template <int ROUNDS, bool WITH_AT>
+__device__ __forceinline__ void fetch_batch(const SparseScratch &sc, uint32_t tile, const TileRuns &r, uint32_t f0, CandBatch<ROUNDS> &c)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    size_t slot[ROUNDS];
+    bool valid[ROUNDS];
+#pragma unroll
+    for (int u = 0; u < ROUNDS; ++u) {
+        const uint32_t f = f0 + 64 * u + lane;
+        valid[u] = f < r.total;
+        const uint32_t s = (f >= r.r0) + (f >= r.r1) + (f >= r.r2);          // chunk of the tile, then slot inside it
+        const uint32_t off = f - (s == 0 ? 0u : s == 1 ? r.r0 : s == 2 ? r.r1 : r.r2);
+        const uint32_t ch = tile * (uint32_t)kWavesPerBlock + (valid[u] ? s : 0u);
+        slot[u] = valid[u] ? (size_t)ch * kChunk + off : (size_t)tile * kTile;
+        c.at[u] = ch * (uint32_t)kChunk;
+    }
+#pragma unroll
+    for (int u = 0; u < ROUNDS; ++u) {
+        c.bits[u] = 0u;
+        if (valid[u]) {
+            c.bits[u] = sc.cand_bits[slot[u]];
+            if (WITH_AT) c.at[u] += sc.cand_loc[slot[u]];
+        }
+    }
+}
+
+// Walk of a tile's candidates, 256 at a time (the slow routes: one memory latency per batch).  body(valid, bits, at).
+template <bool WITH_AT, typename Body>
+__device__ __forceinline__ void walk_small(const SparseScratch &sc, uint32_t tile, uint64_t runs, Body body)
+{
+    const TileRuns r = decode_runs(runs);
+    const uint32_t lane = threadIdx.x & 63u;
+    for (uint32_t f0 = 0; f0 < r.total; f0 += 64 * kFewRounds) {
+        CandBatch<kFewRounds> c;
+        fetch_batch<kFewRounds, WITH_AT>(sc, tile, r, f0, c);
+#pragma unroll
+        for (int u = 0; u < kFewRounds; ++u)
+            if (f0 + 64 * u < r.total) body(f0 + 64 * u + lane < r.total, c.bits[u], c.at[u]);
+    }
+}
+
+// Select.  The keys inside the threshold's bin [lo, lo + 2048) -- rarely more than a few per tile -- are collected
+// in a buffer of the wavefront's own in LDS and appended to sublist `sub` with one atomic add per tile (per 64
+// entries when there are more): an add per batch of candidates put its latency between the batches.
+constexpr int kMemberBuf = 64;
+struct MemberBuf { UEntry *buf; uint32_t held; };
+
+__device__ __forceinline__ void flush_members(const SparseScratch &sc, MemberBuf &m, uint32_t sub)
+{
+    if (!m.held) return;
+    const uint32_t lane = threadIdx.x & 63u;
+    uint32_t base = 0;
+    if (lane == 0) base = atomicAdd(&sc.ucount[sub * kUCountStride], m.held);
+    base = __builtin_amdgcn_readfirstlane(base);
+    __builtin_amdgcn_wave_barrier();
+    if (lane < m.held && base + lane < kUCap) sc.ulist[(size_t)sub * kUCap + base + lane] = m.buf[lane];   // (always in range: the bin holds at most kUCap keys)
+    __builtin_amdgcn_wave_barrier();
+    m.held = 0u;
+}
+
+// One batch: counts the keys above the bin, buffers those inside it.
+template <int ROUNDS>
+__device__ __forceinline__ uint32_t select_apply(const SparseScratch &sc, const CandBatch<ROUNDS> &c, uint32_t total, uint32_t f0,
+                                                 uint32_t lo, uint32_t sub, MemberBuf &m)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    uint32_t above = 0;
+#pragma unroll
+    for (int u = 0; u < ROUNDS; ++u) {
+        if (f0 + 64 * u >= total) break;
+        const uint32_t key = c.bits[u] & 0x7FFFFFFFu;
+        const bool reach = f0 + 64 * u + lane < total && key >= lo;
+        const bool inside = reach && key - lo < (1u << kWindowShift);
+        const uint64_t mb = __builtin_amdgcn_ballot_w64(inside);
+        above += __popcll(__builtin_amdgcn_ballot_w64(reach && key - lo >= (1u << kWindowShift)));
+        if (mb) {
+            const uint32_t cnt = __popcll(mb);
+            if (m.held + cnt > (uint32_t)kMemberBuf) flush_members(sc, m, sub);
+            if (inside) { UEntry e; e.idx = c.at[u]; e.bits = c.bits[u]; m.buf[m.held + lanes_below(mb)] = e; }
+            m.held += cnt;
+        }
+    }
+    return above;
+}
+
+// Emit, one batch: a candidate is kept if its key is above T, or equal to T and among the first `need` such keys in
+// index order; its place in the payload is (keys above T before it) + min(keys equal to T before it, need).
+template <int ALGO, bool EF, int ROUNDS>
+__device__ __forceinline__ void emit_apply(const CandBatch<ROUNDS> &c, uint32_t total, uint32_t f0, uint32_t n, uint64_t k, float *st,
+                                           uint32_t *idx, float *val, uint32_t T, uint64_t need, uint64_t &gt_before, uint64_t &eq_before)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+#pragma unroll
+    for (int u = 0; u < ROUNDS; ++u) {
+        if (f0 + 64 * u >= total) break;
+        const bool valid = f0 + 64 * u + lane < total;
+        const uint32_t key = c.bits[u] & 0x7FFFFFFFu;
         const bool is_gt = valid && key > T, is_eq = valid && key == T;
         const uint64_t bgt = __builtin_amdgcn_ballot_w64(is_gt), beq = __builtin_amdgcn_ballot_w64(is_eq);
         const uint64_t gtb = gt_before + lanes_below(bgt), eqb = eq_before + lanes_below(beq);
         if (is_gt || (is_eq && eqb < need)) {
             const uint64_t pos = gtb + (eqb < need ? eqb : need);
-            const uint32_t i = chunk * (uint32_t)kChunk + loc;
-            if (pos < k && i < n) {                  // exact selection: always true for consistent scratch; CAPPED: room left
+            const uint32_t i = c.at[u];
+            if (pos < k && i < n) {                  // always true for consistent scratch
                 idx[pos] = i;
                 if (ALGO == MC_ALGO_RANDK) val[pos] = st[i];      // the candidate slot holds the random key: the value is p
-                else val[pos] = __uint_as_float(b);
+                else val[pos] = __uint_as_float(c.bits[u]);
                 if (ALGO == MC_ALGO_DGC) { st[i] = 0.0f; st[dgc_u_offset(n) + i] = 0.0f; }   // momentum factor masking
                 else if (EF) st[i] = 0.0f;
             }
         }
         gt_before += __popcll(bgt);
         eq_before += __popcll(beq);
-    });
+    }
+}
+
+__device__ __forceinline__ void put_sparse_header(PayloadHeader *hdr, uint32_t algo, uint32_t n, uint64_t k)
+{
+    PayloadHeader h;
+    h.magic = kMagic; h.algo = algo; h.n = n; h.k = k; h.scale = 0.0f; h.levels = 0u;
+    for (int i = 0; i < 24; ++i) h.pad[i] = 0;
+    *hdr = h;
+}
+// where the next call of this (group, worker) starts filtering: a margin below this call's threshold key
+__device__ __forceinline__ void publish_hint(const SparseScratch &sc, uint32_t T)
+{
+    const uint32_t margin = kHintMargin >> sc.hint[kHintShift];
+    *sc.hint = T > margin ? T - margin : 0u;
+}
+
+// Grid-wide barrier of the slow routes, for the first `blocks` blocks of the grid, all of which the device
+// holds at once (one per compute unit at most): arrivals are counted in one word (cleared by the streaming pass),
+// the `round`-th barrier is passed when it reaches round * blocks.  The release / acquire pair makes what every
+// block wrote before the barrier visible to every block after it.  The wait is bounded: should the count never
+// come (it always does when the blocks are resident together), the block flags the failure and leaves, and so
+// does every later wait.
+__device__ __forceinline__ bool grid_barrier(uint32_t *arrive, uint32_t blocks, uint32_t round, uint32_t *dead /* LDS */, int *status)
+{
+    __syncthreads();
+    if (threadIdx.x == 0 && !*dead) {
+        __hip_atomic_fetch_add(arrive, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t target = round * blocks;
+        uint32_t spins = 0;
+        while (__hip_atomic_load(arrive, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < target) {
+            __builtin_amdgcn_s_sleep(16);
+            if (++spins > (1u << 21)) { *dead = 1u; *status = 2; break; }
+        }
+    }
+    __syncthreads();
+    return *dead == 0u;
+}
+
+// a radix level resolved for the whole block by its first wavefront
+template <int BINS>
+__device__ __forceinline__ void resolve_block(const uint32_t *fine, uint64_t need, uint32_t &bin, uint64_t &rest, uint32_t *res /* 3 words of LDS */)
+{
+    if (threadIdx.x < 64) {
+        uint32_t b;
+        uint64_t r;
+        resolve_wave<BINS>(fine, need, b, r);
+        if (threadIdx.x == 0) { res[0] = b; res[1] = (uint32_t)r; res[2] = (uint32_t)(r >> 32); }
+    }
+    __syncthreads();
+    bin = res[0];
+    rest = (uint64_t)res[1] | ((uint64_t)res[2] << 32);
+    __syncthreads();
+}
+
+constexpr int kRoundTiles = 4096;      // tiles per round of the slow routes' compaction: 256 blocks of 16 wavefronts at most
+
+// The routes that need more than the window: all radix levels still open, the per-tile counts and the ordered
+// compaction, as steps of one kernel of `blocks` blocks (which the device holds at once), each
+// wavefront taking tiles gw, gw + nw, ...  `mode`: what the window said (kModeFast | kModeDense: the threshold's
+// bin [lo, lo + 2048) is known but too full to list; 0: the threshold lies above lo, the window's top;
+// kModeUniform: too few candidates, every element becomes one).  Nothing that the verdict was derived from is
+// written here (the next call's hint is published by the emit kernel): a block of the grid that only starts when
+// these have finished still reaches the same verdict and leaves.
+template <int ALGO, bool EF, bool FROM_STATE, bool RANDOM>
+__device__ __forceinline__ void slow_routes(const GroupView &g, float *st, PayloadHeader *hdr, uint64_t k, const SparseScratch &sc,
+                                            const RngKey &rng, uint32_t mode, uint32_t lo, uint64_t need, uint32_t blocks, int *status,
+                                            uint32_t *hist /* 2048 words of LDS */, uint32_t *pfx /* 2 * kRoundTiles words of LDS */,
+                                            uint32_t *small /* 64 words of LDS */)
+{
+    uint32_t *res = small, *dead = small + 4, *wsum = small + 8;      // wsum: 2 * kSelWaves words
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const uint32_t n = g.n, ntiles = (n + (uint32_t)kTile - 1u) / (uint32_t)kTile;
+    const uint32_t nw = blocks * kSelWaves, gw = blockIdx.x * kSelWaves + wave;
+    const bool uniform = (mode & kModeUniform) != 0u;
+    if (t == 0) *dead = 0u;
+    uint32_t round = 0, T, bin;
+    auto runs_of = [&](uint32_t tile) { return uniform ? uniform_runs(tile, n) : sc.tile_runs[tile]; };
+    for (int b = t; b < kBins1; b += kSelThreads) hist[b] = 0u;
+    __syncthreads();
+    if (!(mode & kModeFast)) {
+        // ---- level 1: bits 30..20 of key - lo
+        if (!uniform) {
+            for (uint32_t tile = gw; tile < ntiles; tile += nw)
+                walk_small<false>(sc, tile, runs_of(tile), [&](bool valid, uint32_t bits, uint32_t) {
+                    const uint32_t key = bits & 0x7FFFFFFFu;
+                    if (valid && key >= lo) atomicAdd(&hist[(key - lo) >> 20], 1u);
+                });
+        } else {
+            // refill: every element becomes a candidate (chunk c holds candidates 1024 c ...)
+            const uint32_t nch = (n + (uint32_t)kChunk - 1u) / (uint32_t)kChunk;
+            for (uint32_t ch = gw; ch < nch; ch += nw) {
+                Chunk c;
+                c.base = ch * (uint32_t)kChunk;
+                c.lane = lane;
+                c.full = n - c.base >= (uint32_t)kChunk;
+                uint32_t bits[kSteps];
+                if (RANDOM) {
+                    chunk_words(rng.seed, rng.worker, rng.iter_lo, g.goff + c.base, c.lane, bits);
+#pragma unroll
+                    for (int j = 0; j < kSteps; ++j) bits[j] >>= 1;
+                } else {
+                    float v[kSteps];
+                    load_sel<FROM_STATE>(g, st, c, v);
+#pragma unroll
+                    for (int j = 0; j < kSteps; ++j) bits[j] = __float_as_uint(v[j]);
+                }
+#pragma unroll
+                for (int j = 0; j < kSteps; ++j) {
+                    const uint32_t i = c.base + 64 * j + c.lane;
+                    if (c.full || i < n) {
+                        sc.cand_bits[i] = bits[j];
+                        sc.cand_loc[i] = (uint16_t)(64 * j + c.lane);
+                        atomicAdd(&hist[(bits[j] & 0x7FFFFFFFu) >> 20], 1u);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        flush_fine(hist, sc.hist + kHist1, kBins1);
+        if (!grid_barrier(sc.sync + kSyncArrive, blocks, ++round, dead, status)) return;
+        resolve_block<kBins1>(sc.hist + kHist1, need, bin, need, res);
+        lo += bin << 20;
+        // ---- level 2: bits 19..10
+        for (int b = t; b < kBins2; b += kSelThreads) hist[b] = 0u;
+        __syncthreads();
+        for (uint32_t tile = gw; tile < ntiles; tile += nw)
+            walk_small<false>(sc, tile, runs_of(tile), [&](bool valid, uint32_t bits, uint32_t) {
+                const uint32_t key = bits & 0x7FFFFFFFu;
+                if (valid && key >= lo && key - lo < (1u << 20)) atomicAdd(&hist[(key - lo) >> 10], 1u);
+            });
+        __syncthreads();
+        flush_fine(hist, sc.hist + kHist2, kBins2);
+        if (!grid_barrier(sc.sync + kSyncArrive, blocks, ++round, dead, status)) return;
+        if (blockIdx.x == 0) for (int b = t; b < kBins1; b += kSelThreads) sc.hist[kHist1 + b] = 0u;    // every block has resolved level 1
+        resolve_block<kBins2>(sc.hist + kHist2, need, bin, need, res);
+        lo += bin << 10;
+        for (int b = t; b < kBins3; b += kSelThreads) hist[b] = 0u;
+        __syncthreads();
+    }
+    // ---- level 3: the bits still open (10 after level 2, the 11 of a window bin otherwise)
+    const uint32_t open = (mode & kModeFast) ? 1u << kWindowShift : 1u << 10;
+    for (uint32_t tile = gw; tile < ntiles; tile += nw)
+        walk_small<false>(sc, tile, runs_of(tile), [&](bool valid, uint32_t bits, uint32_t) {
+            const uint32_t key = bits & 0x7FFFFFFFu;
+            if (valid && key >= lo && key - lo < open) atomicAdd(&hist[key - lo], 1u);
+        });
+    __syncthreads();
+    flush_fine(hist, sc.hist + kHist3, kBins3);
+    if (!grid_barrier(sc.sync + kSyncArrive, blocks, ++round, dead, status)) return;
+    if (!(mode & kModeFast) && blockIdx.x == 0) for (int b = t; b < kBins2; b += kSelThreads) sc.hist[kHist2 + b] = 0u;
+    resolve_block<kBins3>(sc.hist + kHist3, need, bin, need, res);
+    T = lo + bin;
+    // ---- kept candidates per tile
+    for (uint32_t tile = gw; tile < ntiles; tile += nw) {
+        uint32_t ngt = 0, neq = 0;
+        walk_small<false>(sc, tile, runs_of(tile), [&](bool valid, uint32_t bits, uint32_t) {
+            const uint32_t key = bits & 0x7FFFFFFFu;
+            ngt += __popcll(__builtin_amdgcn_ballot_w64(valid && key > T));
+            neq += __popcll(__builtin_amdgcn_ballot_w64(valid && key == T));
+        });
+        if (lane == 0) sc.tile_cnt[tile] = ngt | (neq << 16);              // a tile holds at most 4096 candidates
+    }
+    if (!grid_barrier(sc.sync + kSyncArrive, blocks, ++round, dead, status)) return;
+    if (blockIdx.x == 0) for (int b = t; b < kBins3; b += kSelThreads) sc.hist[kHist3 + b] = 0u;
+    uint32_t *idx = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(hdr) + kHeaderBytes);
+    float *val = reinterpret_cast<float *>(idx + k);
+    if (blockIdx.x == 0 && t == 0) {
+        put_sparse_header(hdr, ALGO, n, k);
+        SelectState s;
+        s.lo = T; s.mode = mode; s.need = need;
+        sc.sel[3] = s;                                                      // the emit kernel derives the next call's hint from it
+    }
+    // ---- ordered compaction, kRoundTiles tiles at a time: every block scans the round's counts (in LDS) for the
+    // keys kept before each tile, and carries the totals of the rounds before
+    uint64_t base_gt = 0, base_eq = 0;
+    constexpr int kPer = kRoundTiles / kSelThreads;
+    for (uint32_t r0 = 0; r0 < ntiles; r0 += kRoundTiles) {
+        uint32_t cg[kPer], ce[kPer], sg = 0, se = 0;
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const uint32_t tile = r0 + t * kPer + i;
+            const uint32_t x = tile < ntiles ? sc.tile_cnt[tile] : 0u;
+            cg[i] = x & 0xFFFFu; ce[i] = x >> 16;
+            sg += cg[i]; se += ce[i];
+        }
+        uint32_t ig = sg, ie = se;                                          // inclusive scan over the block's threads
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t og = __shfl_up(ig, d, 64), oe = __shfl_up(ie, d, 64);
+            if (lane >= (uint32_t)d) { ig += og; ie += oe; }
+        }
+        if (lane == 63u) { wsum[wave] = ig; wsum[kSelWaves + wave] = ie; }
+        __syncthreads();
+        uint32_t wg = 0, we = 0, tg = 0, te = 0;
+#pragma unroll
+        for (int w = 0; w < kSelWaves; ++w) {
+            if ((uint32_t)w < wave) { wg += wsum[w]; we += wsum[kSelWaves + w]; }
+            tg += wsum[w]; te += wsum[kSelWaves + w];
+        }
+        uint32_t xg = wg + ig - sg, xe = we + ie - se;                       // kept before this thread's first tile, inside the round
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            pfx[t * kPer + i] = xg; pfx[kRoundTiles + t * kPer + i] = xe;
+            xg += cg[i]; xe += ce[i];
+        }
+        __syncthreads();
+        for (uint32_t p = gw; p < (uint32_t)kRoundTiles && r0 + p < ntiles; p += nw) {
+            const uint32_t tile = r0 + p;
+            const TileRuns tr = decode_runs(runs_of(tile));
+            uint64_t gtb = base_gt + pfx[p], eqb = base_eq + pfx[kRoundTiles + p];
+            for (uint32_t f0 = 0; f0 < tr.total; f0 += 64 * kFewRounds) {
+                CandBatch<kFewRounds> c;
+                fetch_batch<kFewRounds, true>(sc, tile, tr, f0, c);
+                emit_apply<ALGO, EF, kFewRounds>(c, tr.total, f0, n, k, st, idx, val, T, need, gtb, eqb);
+            }
+        }
+        base_gt += tg; base_eq += te;
+        __syncthreads();
+    }
+}
+
+#ifdef MC_SEL_WPE
+__attribute__((amdgpu_waves_per_eu(MC_SEL_WPE, MC_SEL_WPE)))
+#endif
+__global__ __launch_bounds__(kSelThreads) void lean_select_k(GroupView g, uint64_t k, SparseScratch sc)
+{
+    __shared__ __attribute__((aligned(16))) uint32_t bins[kBinsW];     // the window summed over its copies; then this block's level histogram
+    __shared__ uint32_t verdict[8];              // found, bin, rest lo, rest hi, candidates lo, hi, keys in the bin
+    __shared__ uint32_t wabove[kSelWaves];
+    __shared__ UEntry members[kSelWaves][kMemberBuf];
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const uint32_t ntiles = (g.n + (uint32_t)kTile - 1u) / (uint32_t)kTile;
+    const uint32_t tile = blockIdx.x * kSelWaves + wave;
+    // everything is asked for up front: the hint record, the window, and -- two loads deep -- the tile's candidates
+    const uint64_t runs = tile < ntiles ? sc.tile_runs[tile] : 0ull;
+    const uint32_t hint = *sc.hint, hint_shift = sc.hint[kHintShift], hint_hold = sc.hint[kHintHold];
+    uint32_t open = wave == 0 ? sc.hist[kHistOpen + lane] : 0u;
+    uint2 wsum = {0u, 0u};                       // window bins 2 t and 2 t + 1
+#pragma unroll
+    for (int r = 0; r < kWinCopies; ++r) {
+        const uint2 x = *reinterpret_cast<const uint2 *>(sc.hist + kHistW + r * kBinsW + 2 * t);
+        wsum.x += x.x; wsum.y += x.y;
+    }
+    // the tile's first 512 candidates (all of them, for nearly every tile) are on their way before the verdict is known
+    const TileRuns tr = decode_runs(runs);
+    CandBatch<kDeepRounds> db;
+    fetch_batch<kDeepRounds, true>(sc, tile, tr, 0u, db);
+    *reinterpret_cast<uint2 *>(bins + 2 * t) = wsum;
+    __syncthreads();
+    if (wave == 0) {
+        uint32_t bin;
+        uint64_t rest, cands;
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) open += __shfl_xor(open, d, 64);
+        const bool found = resolve_lds<kBinsW>(bins, k, bin, rest, open, &cands);
+        if (lane == 0) {
+            verdict[0] = found; verdict[1] = bin; verdict[2] = (uint32_t)rest; verdict[3] = (uint32_t)(rest >> 32);
+            verdict[4] = (uint32_t)cands; verdict[5] = (uint32_t)(cands >> 32); verdict[6] = bins[bin];
+        }
+    }
+    __syncthreads();
+    const bool found = verdict[0] != 0u;
+    const uint32_t bin = verdict[1];
+    const bool first = blockIdx.x == 0 && t == 0;
+    if (first) {
+        sc.sync[kSyncLastBin] = found ? verdict[6] : 0u;                // diagnostics (mc_select_stats)
+        sc.sync[kSyncLastCands] = verdict[4];
+    }
+    if (found && bin < (uint32_t)kBinsW - 1u) {
+        const uint32_t lo = hint + (bin << kWindowShift);
+        const bool lean = verdict[6] <= kUCap;
+        if (first) {
+            SelectState s;
+            s.lo = lo; s.mode = kModeFast | (lean ? kModeLean : kModeDense); s.need = (uint64_t)verdict[2] | ((uint64_t)verdict[3] << 32);
+            sc.sel[0] = s;
+            // How far below the threshold the next call starts filtering.  Under error feedback the values pile up just
+            // below the threshold, in the long run those of every tensor, and a fixed margin lets through many times k
+            // of them (each costs the streaming pass a store and the histogram an add): the margin is halved while the
+            // filter passes more than 4 k and doubled again when it passes fewer than 1.5 k; a miss resets it (below).
+            const uint64_t cands = (uint64_t)verdict[4] | ((uint64_t)verdict[5] << 32);
+            uint32_t shift = hint_shift, hold = hint_hold;
+            if (hold) --hold;
+            else if (cands > 4u * k && shift < kHintShiftMax) ++shift;
+            if (2u * cands < 3u * k && shift) --shift;
+            sc.hint[kHintShift] = shift; sc.hint[kHintHold] = hold;
+            atomicAdd(&sc.sync[kSyncRoutes + (lean ? MC_SELECT_FAST : MC_SELECT_DENSE)], 1u);
+        }
+        if (lean) {
+            const uint32_t sub = tile & (uint32_t)(kUSub - 1);
+            MemberBuf mb{members[wave], 0u};
+            uint32_t above = select_apply<kDeepRounds>(sc, db, tr.total, 0u, lo, sub, mb);
+            for (uint32_t f0 = 64 * kDeepRounds; f0 < tr.total; f0 += 64 * kDeepRounds) {
+                fetch_batch<kDeepRounds, true>(sc, tile, tr, f0, db);
+                above += select_apply<kDeepRounds>(sc, db, tr.total, f0, lo, sub, mb);
+            }
+            flush_members(sc, mb, sub);
+            if (lane == 0) {
+                wabove[wave] = above;
+                if (tile < ntiles) sc.tile_cnt[tile] = above;
+            }
+            __syncthreads();
+            if (t == 0) {
+                uint32_t sum = 0;
+#pragma unroll
+                for (int w = 0; w < kSelWaves; ++w) sum += wabove[w];
+                sc.blk_cnt[blockIdx.x] = sum;                          // sixteen tiles hold at most 65536 candidates
+            }
+            return;
+        }
+        return;          // dense bin: too many keys to list; the slow-route kernel resolves its 2048 keys as a radix level
+    }
+    // missed: the next calls filter with the full margin again, and keep it for a while
+    if (first) {
+        sc.hint[kHintShift] = 0u; sc.hint[kHintHold] = kHintHoldCalls;
+        SelectState s;
+        s.lo = found ? hint + (((uint32_t)kBinsW - 1u) << kWindowShift) : 0u; s.mode = found ? 0u : kModeUniform; s.need = k;
+        sc.sel[0] = s;
+        atomicAdd(&sc.sync[kSyncRoutes + (found ? MC_SELECT_ABOVE : MC_SELECT_REFILL)], 1u);
+    }
+}
+
+// The slow routes, in a kernel of their own so that their registers do not weigh on the two kernels of the usual
+// route (with them inside, the select kernel needed 128 registers and only one of its blocks fitted a compute unit:
+// its 390 blocks for the ResNet-50 buffer then ran in two rounds).  On the lean route it reads one word and leaves.
+template <int ALGO, bool EF, bool FROM_STATE, bool RANDOM>
+__global__ __launch_bounds__(kSelThreads) void sparse_slow_k(GroupView g, float *st, PayloadHeader *hdr, uint64_t k, SparseScratch sc,
+                                                             RngKey rng, int *status)
+{
+    __shared__ __attribute__((aligned(16))) uint32_t hist[kBins1];
+    __shared__ uint32_t pfx[2 * kRoundTiles];
+    __shared__ uint32_t small[64];
+    const SelectState s0 = sc.sel[0];
+    if (s0.mode & kModeLean) return;
+    slow_routes<ALGO, EF, FROM_STATE, RANDOM>(g, st, hdr, k, sc, rng, s0.mode, s0.lo, s0.need, gridDim.x, status, hist, pfx, small);
+}
+
+template <int ALGO, bool EF>
+#ifdef MC_EMIT_WPE
+__attribute__((amdgpu_waves_per_eu(MC_EMIT_WPE, MC_EMIT_WPE)))
+#endif
+__global__ __launch_bounds__(kEmitThreads) void lean_emit_k(uint32_t n, uint32_t ntiles, float *st, PayloadHeader *hdr, uint64_t k,
+                                                            SparseScratch sc)
+{
+    __shared__ __attribute__((aligned(16))) uint32_t hist[kBins3];
+    __shared__ uint32_t small[4];
+    __shared__ uint32_t upre[kUSub + 1];
+    __shared__ uint32_t cgt[kEmitWaves + 1], ceq[kEmitWaves + 1];
+    __shared__ uint64_t red[kEmitWaves];
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const uint32_t tile = blockIdx.x * kEmitWaves + wave;
+    // asked for first, needed last: the tile's candidates, two loads deep
+    const uint64_t runs = tile < ntiles ? sc.tile_runs[tile] : 0ull;
+    const SelectState s0 = sc.sel[0];
+    const uint32_t ucnt = wave == 0 ? sc.ucount[lane * kUCountStride] : 0u;
+    // the select kernel is done with the window: all blocks clear it together
+    for (uint32_t b = blockIdx.x * kEmitThreads + t; b < (uint32_t)(kWinCopies * kBinsW + kOpenCopies); b += gridDim.x * kEmitThreads)
+        sc.hist[b < (uint32_t)(kWinCopies * kBinsW) ? kHistW + b : kHistOpen - kWinCopies * kBinsW + b] = 0u;
+    if (!(s0.mode & kModeLean)) {
+        // the select kernel went all the way on one of its slow routes; what is left is the next call's hint
+        if (blockIdx.x == 0 && t == 0) publish_hint(sc, sc.sel[3].lo);
+        return;
+    }
+    const uint32_t lo = s0.lo;
+    // keys above the bin in the select blocks (sixteen tiles each) before this tile's, then in the tiles before it in its own
+    const uint32_t sblock = tile / (uint32_t)kSelWaves, sfirst = sblock * (uint32_t)kSelWaves;
+    uint64_t before = 0;
+    for (uint32_t b = t; b < blockIdx.x / (uint32_t)(kSelWaves / kEmitWaves); b += kEmitThreads) before += sc.blk_cnt[b];
+    uint32_t mine = tile < ntiles && sfirst + lane < tile ? sc.tile_cnt[sfirst + lane] : 0u;
+    const TileRuns tr = decode_runs(runs);
+    const bool few = tr.total <= 64u * kFewRounds;
+    CandBatch<kFewRounds> cb;
+    if (few) fetch_batch<kFewRounds, true>(sc, tile, tr, 0u, cb);
+    // ---- the list: lengths of the sublists, then its entries, spread over the block's threads
+    if (wave == 0) {
+        uint32_t inc = min(ucnt, kUCap);
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t o = __shfl_up(inc, d, 64);
+            if (lane >= (uint32_t)d) inc += o;
+        }
+        upre[lane + 1] = inc;
+        if (lane == 0) upre[0] = 0u;
+    }
+    for (int b = t; b < kBins3; b += kEmitThreads) hist[b] = 0u;
+    if (t <= (uint32_t)kEmitWaves) { cgt[t] = 0u; ceq[t] = 0u; }
+    __syncthreads();
+    const uint32_t total = min(upre[kUSub], kUCap);
+    // entry e of the concatenated sublists (the first kUKeep of a thread stay in registers for the second walk)
+    auto entry = [&](uint32_t e) {
+        uint32_t s = 0;                                    // the sublist that holds entry e: the last one that starts at or before it
+#pragma unroll
+        for (int step = kUSub / 2; step >= 1; step >>= 1) if (upre[s + step] <= e) s += step;
+        return sc.ulist[(size_t)s * kUCap + (e - upre[s])];
+    };
+    UEntry ent[kUKeep];
+#pragma unroll
+    for (int j = 0; j < kUKeep; ++j) {
+        const uint32_t e = t + (uint32_t)kEmitThreads * j;
+        ent[j].idx = 0u; ent[j].bits = 0u;
+        if (e < total) ent[j] = entry(e);
+    }
+#pragma unroll
+    for (int j = 0; j < kUKeep; ++j) {
+        const uint32_t d = (ent[j].bits & 0x7FFFFFFFu) - lo;
+        if (t + (uint32_t)kEmitThreads * j < total && d < (uint32_t)kBins3) atomicAdd(&hist[d], 1u);
+    }
+    for (uint32_t e = t + (uint32_t)kEmitThreads * kUKeep; e < total; e += kEmitThreads) {
+        const uint32_t d = (entry(e).bits & 0x7FFFFFFFu) - lo;
+        if (d < (uint32_t)kBins3) atomicAdd(&hist[d], 1u);
+    }
+    __syncthreads();
+    // threshold key and the number of keys equal to it to take
+    if (wave == 0) {
+        uint32_t b;
+        uint64_t r;
+        if (!resolve_lds<kBins3>(hist, s0.need, b, r)) { b = 0u; r = 0u; }
+        if (lane == 0) { small[0] = b; small[1] = (uint32_t)r; }      // (at most kUCap keys in the bin)
+    }
+    __syncthreads();
+    const uint32_t T = lo + small[0];
+    const uint64_t need = small[1];
+    // the list's kept keys, by where they lie: before this block, or in its tile j (bucket j + 1)
+    const uint32_t first = blockIdx.x * (uint32_t)(kEmitWaves * kTile);
+    auto classify = [&](const UEntry &x) {
+        const uint32_t key = x.bits & 0x7FFFFFFFu;
+        if (key >= T) {
+            const uint32_t bucket = x.idx < first ? 0u : ((x.idx - first) >> 12) + 1u;
+            if (bucket <= (uint32_t)kEmitWaves) atomicAdd(key > T ? &cgt[bucket] : &ceq[bucket], 1u);
+        }
+    };
+#pragma unroll
+    for (int j = 0; j < kUKeep; ++j) if (t + (uint32_t)kEmitThreads * j < total) classify(ent[j]);
+    for (uint32_t e = t + (uint32_t)kEmitThreads * kUKeep; e < total; e += kEmitThreads) classify(entry(e));
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) { before += __shfl_xor(before, m, 64); mine += __shfl_xor(mine, m, 64); }
+    if (lane == 0) red[wave] = before;
+    __syncthreads();
+    uint64_t gt_before = mine, eq_before = 0;
+#pragma unroll
+    for (int w = 0; w < kEmitWaves; ++w) gt_before += red[w];
+    {
+        uint32_t g2 = lane <= wave ? cgt[lane] : 0u, e2 = lane <= wave ? ceq[lane] : 0u;
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) { g2 += __shfl_xor(g2, m, 64); e2 += __shfl_xor(e2, m, 64); }
+        gt_before += g2; eq_before = e2;
+    }
+    uint32_t *idx = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(hdr) + kHeaderBytes);
+    float *val = reinterpret_cast<float *>(idx + k);
+    if (blockIdx.x == 0 && t == 0) { put_sparse_header(hdr, ALGO, n, k); publish_hint(sc, T); }
+    if (few) emit_apply<ALGO, EF, kFewRounds>(cb, tr.total, 0u, n, k, st, idx, val, T, need, gt_before, eq_before);
+    else
+        for (uint32_t f0 = 0; f0 < tr.total; f0 += 64 * kHeavyRounds) {
+            CandBatch<kHeavyRounds> hb;
+            fetch_batch<kHeavyRounds, true>(sc, tile, tr, f0, hb);
+            emit_apply<ALGO, EF, kHeavyRounds>(hb, tr.total, f0, n, k, st, idx, val, T, need, gt_before, eq_before);
+        }
 }
 
 template <int ALGO, bool EF, bool CAPPED>
 static void sparse_compress_t(const LaunchCtx &lc, const GroupView &g, float *st, float momentum, uint64_t k, uint64_t need,
-                              PayloadHeader *hdr, const SparseScratch &sc, const RngKey &rng, const SampleRule &smp)
+                              PayloadHeader *hdr, const SparseScratch &sc, const RngKey &rng, const SampleRule &smp,
+                              uint32_t sync_blocks, int *status)
 {
     constexpr bool FS = (ALGO == MC_ALGO_DGC) || EF;
     constexpr bool RND = ALGO == MC_ALGO_RANDK;
@@ -686,6 +1364,21 @@ static void sparse_compress_t(const LaunchCtx &lc, const GroupView &g, float *st
     prof_begin(lc, K_SPARSE_ACCUM);
     MC_LAUNCH((sparse_accum_k<ALGO, EF>), grid, block, lc, g, st, momentum, sc, rng, smp);
     prof_end(lc, K_SPARSE_ACCUM);
+    if (!CAPPED) {
+        // the two-kernel tail; its slow routes run on at most `sync_blocks` blocks, which the device holds at once
+        const uint32_t sblocks = (nt + kSelWaves - 1) / kSelWaves, eblocks = (nt + kEmitWaves - 1) / kEmitWaves;
+        const uint32_t sync = std::max(1u, std::min(std::min(sync_blocks, sblocks), (uint32_t)(kRoundTiles / kSelWaves)));
+        prof_begin(lc, K_LEAN_SELECT);
+        MC_LAUNCH(lean_select_k, dim3(sblocks), dim3(kSelThreads), lc, g, k, sc);
+        prof_end(lc, K_LEAN_SELECT);
+        prof_begin(lc, K_SPARSE_SLOW);
+        MC_LAUNCH((sparse_slow_k<ALGO, EF, FS, RND>), dim3(sync), dim3(kSelThreads), lc, g, st, hdr, k, sc, rng, status);
+        prof_end(lc, K_SPARSE_SLOW);
+        prof_begin(lc, K_LEAN_EMIT);
+        MC_LAUNCH((lean_emit_k<ALGO, EF>), dim3(eblocks), dim3(kEmitThreads), lc, g.n, nt, st, hdr, k, sc);
+        prof_end(lc, K_LEAN_EMIT);
+        return;
+    }
     prof_begin(lc, K_SPARSE_SEED);
     MC_LAUNCH((sparse_seed_k<FS, RND>), dim3(sblocks), dim3(kSeedThreads), lc, g, st, need, sc, rng, smp);
     prof_end(lc, K_SPARSE_SEED);
@@ -708,7 +1401,7 @@ static void sparse_compress_t(const LaunchCtx &lc, const GroupView &g, float *st
 // sample_need-th largest key
 void launch_sparse_compress(const LaunchCtx &lc, int algo, const GroupView &g, bool ef, float *state_f, float momentum,
                             uint64_t k, PayloadHeader *hdr, const SparseScratch &sc, uint64_t seed, uint32_t worker, uint32_t iter_lo,
-                            uint32_t sample_stride, uint32_t sample_first, uint64_t sample_need)
+                            uint32_t sample_stride, uint32_t sample_first, uint64_t sample_need, uint32_t sync_blocks, int *status)
 {
     if (g.n == 0) return;
     const RngKey rng{seed, worker, iter_lo};
@@ -716,11 +1409,11 @@ void launch_sparse_compress(const LaunchCtx &lc, int algo, const GroupView &g, b
     if (algo == MC_ALGO_DGC && sample_stride) {
         smp.stride = sample_stride; smp.first = sample_first;
         smp.inv = sample_stride > 1 ? (uint32_t)((1ull << 32) / sample_stride) : 0u;
-        sparse_compress_t<MC_ALGO_DGC, true, true>(lc, g, state_f, momentum, k, sample_need, hdr, sc, rng, smp);
-    } else if (algo == MC_ALGO_DGC) sparse_compress_t<MC_ALGO_DGC, true, false>(lc, g, state_f, momentum, k, k, hdr, sc, rng, smp);
-    else if (algo == MC_ALGO_RANDK) sparse_compress_t<MC_ALGO_RANDK, true, false>(lc, g, state_f, momentum, k, k, hdr, sc, rng, smp);
-    else if (ef) sparse_compress_t<MC_ALGO_TOPK, true, false>(lc, g, state_f, momentum, k, k, hdr, sc, rng, smp);
-    else sparse_compress_t<MC_ALGO_TOPK, false, false>(lc, g, state_f, momentum, k, k, hdr, sc, rng, smp);
+        sparse_compress_t<MC_ALGO_DGC, true, true>(lc, g, state_f, momentum, k, sample_need, hdr, sc, rng, smp, sync_blocks, status);
+    } else if (algo == MC_ALGO_DGC) sparse_compress_t<MC_ALGO_DGC, true, false>(lc, g, state_f, momentum, k, k, hdr, sc, rng, smp, sync_blocks, status);
+    else if (algo == MC_ALGO_RANDK) sparse_compress_t<MC_ALGO_RANDK, true, false>(lc, g, state_f, momentum, k, k, hdr, sc, rng, smp, sync_blocks, status);
+    else if (ef) sparse_compress_t<MC_ALGO_TOPK, true, false>(lc, g, state_f, momentum, k, k, hdr, sc, rng, smp, sync_blocks, status);
+    else sparse_compress_t<MC_ALGO_TOPK, false, false>(lc, g, state_f, momentum, k, k, hdr, sc, rng, smp, sync_blocks, status);
 }
 
 // ---------------------------------------------------------------------------

@@ -93,6 +93,7 @@ struct mc_ctx {
     std::vector<uintptr_t> want;        // the address list of the call in progress (reserved at creation)
     uint64_t clock = 0;
     uint32_t epoch = 0;                 // stamps the sparse decompress tile table; 0 is never used
+    uint32_t sync_blocks = 1;           // blocks of 1024 threads the device holds at once for sure: one per compute unit
     Profiler prof;
 };
 
@@ -130,7 +131,7 @@ void prof_end(const LaunchCtx &lc, int id)
 static const char *kKernelNames[K_COUNT] = {
     "upload_ptrs", "efsign_compress", "scalar_finalize", "accum_reduce", "qsgd_encode", "tern_encode",
     "fp16_compress", "dense_decompress", "sparse_accum", "sparse_seed", "cand_hist2", "cand_hist3", "cand_count",
-    "cand_emit", "sparse_index", "sparse_decompress", "state_convert"};
+    "cand_emit", "sparse_index", "sparse_decompress", "state_convert", "lean_select", "lean_emit", "sparse_slow"};
 
 static void prof_drain(Profiler &p)
 {
@@ -341,7 +342,7 @@ int mc_ctx_destroy(mc_ctx *ctx)
     if (ctx->d_partial) (void)hipFree(ctx->d_partial);
     void *sparse_bufs[] = {ctx->sparse.hist, ctx->sparse.sel, ctx->d_hints, ctx->sparse.cand_bits, ctx->sparse.cand_loc,
                            ctx->sparse.tile_runs, ctx->sparse.tile_cnt, ctx->sparse.blk_cnt, ctx->sparse.tile_first,
-                           ctx->sparse.tile_last};
+                           ctx->sparse.tile_last, ctx->sparse.ulist, ctx->sparse.ucount, ctx->sparse.sync};
     for (void *b : sparse_bufs) if (b) (void)hipFree(b);
     if (ctx->d_status) (void)hipFree(ctx->d_status);
     if (switched) (void)hipSetDevice(prev);
@@ -428,12 +429,20 @@ int mc_ctx_create(mc_ctx **out, const mc_config *cfg, const int64_t *numel, int3
                 hipMalloc(&sp.tile_cnt, tiles * sizeof(uint32_t)) != hipSuccess ||
                 hipMalloc(&sp.blk_cnt, (tiles + kWavesPerBlock - 1) / kWavesPerBlock * sizeof(uint32_t)) != hipSuccess ||
                 hipMalloc(&sp.tile_first, off_words * sizeof(uint64_t)) != hipSuccess ||
-                hipMalloc(&sp.tile_last, off_words * sizeof(uint64_t)) != hipSuccess) rc = MC_ERR_ALLOC;
+                hipMalloc(&sp.tile_last, off_words * sizeof(uint64_t)) != hipSuccess ||
+                hipMalloc(&sp.ulist, (size_t)kUSub * kUCap * sizeof(UEntry)) != hipSuccess ||
+                hipMalloc(&sp.ucount, (size_t)kUSub * kUCountStride * sizeof(uint32_t)) != hipSuccess ||
+                hipMalloc(&sp.sync, 64 * sizeof(uint32_t)) != hipSuccess) rc = MC_ERR_ALLOC;
             else if (hipMemset(sp.hist, 0, hist_bytes) != hipSuccess || hipMemset(sp.sel, 0, 4 * sizeof(SelectState)) != hipSuccess ||
                      hipMemset(ctx->d_hints, 0, (size_t)y * kHintWorkers * kHintWords * sizeof(uint32_t)) != hipSuccess ||
                      hipMemset(sp.tile_runs, 0, tiles * sizeof(uint64_t)) != hipSuccess ||
                      hipMemset(sp.tile_first, 0, off_words * sizeof(uint64_t)) != hipSuccess ||
-                     hipMemset(sp.tile_last, 0, off_words * sizeof(uint64_t)) != hipSuccess) rc = MC_ERR_DEVICE;
+                     hipMemset(sp.tile_last, 0, off_words * sizeof(uint64_t)) != hipSuccess ||
+                     hipMemset(sp.ucount, 0, (size_t)kUSub * kUCountStride * sizeof(uint32_t)) != hipSuccess ||
+                     hipMemset(sp.sync, 0, 64 * sizeof(uint32_t)) != hipSuccess) rc = MC_ERR_DEVICE;
+            int cus = 0;
+            if (rc == MC_OK && (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ctx->device) != hipSuccess || cus < 1)) rc = MC_ERR_DEVICE;
+            ctx->sync_blocks = (uint32_t)std::max(cus, 1);
         }
         if (rc == MC_OK) {
             // the per-chunk address tables of all slots together stay below 256 MiB
@@ -604,7 +613,7 @@ static int compress_impl(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t i
             need = m ? std::max<uint64_t>(1, (uint64_t)(((unsigned __int128)m * cfg.ratio_ppm) / 1000000u)) : 0;
         }
         launch_sparse_compress(lc, cfg.algo, gv, ef, sf, cfg.dgc_momentum, G.k, hdr, sp, cfg.seed, worker, (uint32_t)iter,
-                               stride, first, need);
+                               stride, first, need, ctx->sync_blocks, ctx->d_status);
     }
         break;
     default: return MC_ERR_INVALID_ARG;
@@ -701,7 +710,7 @@ int mc_last_device_status(mc_ctx *ctx)
     if (hipDeviceSynchronize() != hipSuccess) return MC_ERR_DEVICE;
     if (hipMemcpy(&flag, ctx->d_status, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess) return MC_ERR_DEVICE;
     if (flag && hipMemset(ctx->d_status, 0, sizeof(int)) != hipSuccess) return MC_ERR_DEVICE;
-    return flag ? MC_ERR_PAYLOAD : MC_OK;
+    return flag == 2 ? MC_ERR_DEVICE : flag ? MC_ERR_PAYLOAD : MC_OK;
 }
 
 int mc_last_select_route(mc_ctx *ctx)
@@ -711,7 +720,21 @@ int mc_last_select_route(mc_ctx *ctx)
     DeviceGuard on(ctx->device);
     if (hipDeviceSynchronize() != hipSuccess) return MC_ERR_DEVICE;
     if (hipMemcpy(&s, ctx->sparse.sel, sizeof(s), hipMemcpyDeviceToHost) != hipSuccess) return MC_ERR_DEVICE;
-    return (s.mode & 1u) ? MC_SELECT_FAST : (s.mode & 2u) ? MC_SELECT_REFILL : MC_SELECT_ABOVE;
+    return (s.mode & 8u) ? MC_SELECT_DENSE : (s.mode & 1u) ? MC_SELECT_FAST : (s.mode & 2u) ? MC_SELECT_REFILL : MC_SELECT_ABOVE;
+}
+
+int mc_select_stats(mc_ctx *ctx, mc_select_counts *out, int32_t reset)
+{
+    if (!ctx || !out || !is_sparse(ctx->cfg.algo) || !ctx->sparse.sync) return MC_ERR_INVALID_ARG;
+    uint32_t w[16] = {};
+    DeviceGuard on(ctx->device);
+    if (hipDeviceSynchronize() != hipSuccess) return MC_ERR_DEVICE;
+    if (hipMemcpy(w, ctx->sparse.sync + 32, sizeof(w), hipMemcpyDeviceToHost) != hipSuccess) return MC_ERR_DEVICE;
+    for (int r = 0; r < 4; ++r) out->calls[r] = w[r];
+    out->last_bin_keys = w[8];
+    out->last_candidates = w[9];
+    if (reset && hipMemset(ctx->sparse.sync + 32, 0, 4 * sizeof(uint32_t)) != hipSuccess) return MC_ERR_DEVICE;
+    return MC_OK;
 }
 
 int mc_profile_enable(mc_ctx *ctx, int32_t on)

@@ -48,7 +48,7 @@ struct SelectState {
 enum KernelId {
     K_UPLOAD = 0, K_EFSIGN_COMPRESS, K_SCALAR_FINALIZE, K_ACCUM_REDUCE, K_QSGD_ENCODE, K_TERN_ENCODE,
     K_FP16_COMPRESS, K_DENSE_DECOMPRESS, K_SPARSE_ACCUM, K_SPARSE_SEED, K_CAND_HIST2, K_CAND_HIST3, K_CAND_COUNT,
-    K_CAND_EMIT, K_SPARSE_INDEX, K_SPARSE_DECOMPRESS, K_STATE_CONVERT, K_COUNT
+    K_CAND_EMIT, K_SPARSE_INDEX, K_SPARSE_DECOMPRESS, K_STATE_CONVERT, K_LEAN_SELECT, K_LEAN_EMIT, K_SPARSE_SLOW, K_COUNT
 };
 
 // reduction kinds of the two-pass quantizers
@@ -98,6 +98,15 @@ constexpr int kHintWords = 4;                            // words of a hint reco
 constexpr int kWinCopies = 8;                                // copies of the window histogram (a block adds to the copy of its index)
 constexpr int kHistWords = 2048 * kWinCopies + 2048 + 1024 + 2048 + 64;   // bins of the window and of the three radix levels, copies of the window's open bin
 
+// The keys that share the threshold's window bin (the only candidates whose fate the window does not settle) are
+// handed from the select kernel to the emit kernel as an unordered list, appended to by wave-wide atomic adds.
+// Adds to one address queue up behind each other, so the list is kept in kUSub sublists (a wavefront appends to the
+// one of its tile index) whose counters sit on cache lines of their own.
+constexpr int kUSub = 64;
+constexpr uint32_t kUCap = 2048;      // keys in the threshold's window bin that the two-kernel route takes; a sublist holds as many
+constexpr int kUCountStride = 32;     // words between sublist counters (one 128-byte line each)
+struct UEntry { uint32_t idx, bits; };       // group-relative index, candidate bits
+
 struct SparseScratch {
     uint32_t *hist;        // kHistWords counters; each level is cleared by a later kernel of the same call
     SelectState *sel;      // [0]: after the seed, [1..3]: after each radix level
@@ -108,10 +117,15 @@ struct SparseScratch {
     uint32_t *tile_cnt;    // per tile: candidates above (low 16 bits) / equal to (high 16 bits) the threshold
     uint32_t *blk_cnt;     // the same per block of four tiles
     uint64_t *tile_first, *tile_last;   // decompress: per worker and 4096-element tile, (epoch << 32 | entry) of its run
+    UEntry *ulist;         // kUSub sublists of kUCap entries: the candidates in the threshold's window bin
+    uint32_t *ucount;      // their lengths, kUCountStride words apart; cleared by the streaming pass of the next call
+    uint32_t *sync;        // [0]: arrivals at the grid-wide barriers of the slow routes (cleared by the select kernel); [32..36): calls per route
 };
+// sync_blocks: how many blocks of 1024 threads the device surely holds at once (one per compute unit): the slow routes
+// of the selection run on that many blocks with grid-wide barriers between their steps
 void launch_sparse_compress(const LaunchCtx &lc, int algo, const GroupView &g, bool ef, float *state_f, float momentum,
                             uint64_t k, PayloadHeader *hdr, const SparseScratch &sc, uint64_t seed, uint32_t worker, uint32_t iter_lo,
-                            uint32_t sample_stride, uint32_t sample_first, uint64_t sample_need);
+                            uint32_t sample_stride, uint32_t sample_first, uint64_t sample_need, uint32_t sync_blocks, int *status);
 void launch_sparse_decompress(const LaunchCtx &lc, int algo, const GroupView &out, const PayloadPtrs &pl, int W,
                               float alpha, uint64_t k, uint32_t epoch, uint64_t *tile_first, uint64_t *tile_last,
                               int *status, bool capped);
