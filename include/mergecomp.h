@@ -272,7 +272,7 @@ int mc_last_select_route(mc_ctx *ctx);
 /* Counts of mc_compress calls by the route their selection took (indexed by the MC_SELECT_ values) since
  * the context was created or the counts were last reset, for the sparsifiers without a sampled threshold;
  * and, of the most recent call, the number of keys that shared the threshold's window bin (the two-kernel
- * route lists them: at most 2048) and of elements that passed the candidate filter (modulo 2^32).
+ * route lists them: at most 4096) and of elements that passed the candidate filter (modulo 2^32).
  * Synchronises the context's device.  Errors: MC_ERR_INVALID_ARG (null, dense algorithm). */
 typedef struct {
     int64_t calls[4];

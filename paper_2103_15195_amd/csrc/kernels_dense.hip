@@ -7,6 +7,8 @@
 // lane-consecutive 4-byte accesses (256 contiguous bytes per wave instruction),
 // sign / ternary planes are packed with 64-lane ballots, group scalars are
 // reduced per block in LDS and combined by a one-block finalize kernel.
+#include <cstddef>
+
 #include "mc_internal.h"
 
 namespace mc {
@@ -943,8 +945,10 @@ __global__ __launch_bounds__(kBlock) void state_convert_k(int algo, int to_resid
                 else { bool nz, neg; d = tern_decode(h->scale, v, u, true, nz, neg); }
                 v = v - d;
             }
-            e[i] = v;
-            if (algo == MC_ALGO_DGC) e[(size_t)n + i] = f[uoff + i];
+            // Top-k, DGC: what the last call sent above its threshold key is masked by the next streaming pass, not zeroed
+            const bool sent = (algo == MC_ALGO_TOPK || algo == MC_ALGO_DGC) && (__float_as_uint(v) & 0x7FFFFFFFu) > h->sent_key;
+            e[i] = sent ? 0.0f : v;
+            if (algo == MC_ALGO_DGC) e[(size_t)n + i] = sent ? 0.0f : f[uoff + i];
         }
     } else {
         const float *e = reinterpret_cast<const float *>(src);
@@ -953,7 +957,9 @@ __global__ __launch_bounds__(kBlock) void state_convert_k(int algo, int to_resid
             f[i] = e[i];                      // EF-Sign, OneBit, QSGD, TernGrad: p = e with scalars 0 re-derives exactly e
             if (algo == MC_ALGO_DGC) f[uoff + i] = e[(size_t)n + i];
         }
-        if (i < kHeaderBytes / 4) reinterpret_cast<uint32_t *>(dst)[i] = 0u;
+        // a cleared header; for the sparsifiers sent_key = all ones: nothing of an imported residual counts as sent
+        if (i < kHeaderBytes / 4)
+            reinterpret_cast<uint32_t *>(dst)[i] = i == offsetof(StateHeader, sent_key) / 4 && (algo == MC_ALGO_TOPK || algo == MC_ALGO_DGC || algo == MC_ALGO_RANDK) ? 0xFFFFFFFFu : 0u;
         if (algo == MC_ALGO_DGC && i >= n && i < uoff) f[i] = 0.0f;                       // the gap between v and u
     }
 }

@@ -145,6 +145,12 @@ __global__ __launch_bounds__(kBlock) void sparse_accum_k(GroupView g, float *st,
     uint32_t run = 0;
     if (c.base < g.n) {
         float p[kSteps];
+        // What the last call sent leaves the memory: an element whose key was above that call's threshold key counts as 0
+        // here, instead of having been set to 0 there -- one scattered 4-byte store per kept entry, each a read-modify-write
+        // of a whole line in memory, was most of what the compaction cost.  (Kept entries *equal* to the threshold are still
+        // zeroed in place: which of the equal keys were taken depends on their order.  A state that was zero-filled,
+        // imported, or written by a scheme that zeroes in place says sent_key = all ones or holds zeros: nothing is masked.)
+        const uint32_t sent_key = (ALGO == MC_ALGO_DGC || EF) ? reinterpret_cast<const StateHeader *>(reinterpret_cast<const uint8_t *>(st) - kHeaderBytes)->sent_key : 0u;
         if (ALGO == MC_ALGO_DGC) {
             // momentum correction: u = m u + g ; v = v + u ; the vector compressed is v
             float *vbuf = st, *ubuf = st + dgc_u_offset(g.n);
@@ -154,6 +160,7 @@ __global__ __launch_bounds__(kBlock) void sparse_accum_k(GroupView g, float *st,
             load_seg(g, c, p);
 #pragma unroll
             for (int j = 0; j < kSteps; ++j) {
+                if (key_of(v[j]) > sent_key) { u[j] = 0.0f; v[j] = 0.0f; }       // momentum factor masking of what was sent
                 float mu = momentum * u[j];
                 u[j] = mu + p[j];
                 v[j] = v[j] + u[j];
@@ -166,7 +173,7 @@ __global__ __launch_bounds__(kBlock) void sparse_accum_k(GroupView g, float *st,
             load_flat(st, c, g.n, e, 0.0f);
             load_seg(g, c, p);
 #pragma unroll
-            for (int j = 0; j < kSteps; ++j) p[j] = p[j] + e[j];
+            for (int j = 0; j < kSteps; ++j) p[j] = p[j] + (key_of(e[j]) > sent_key ? 0.0f : e[j]);
             store_flat(st, c, g.n, p);
         } else {
             load_seg(g, c, p);
@@ -631,6 +638,24 @@ __global__ __launch_bounds__(kBlock) void cand_count_k(uint32_t n, uint32_t ntil
 //   (#kept before it) = (#above before it) + min(#equal before it, need).
 // Every block adds up the counts of the blocks before it; nothing waits.
 // ---------------------------------------------------------------------------
+// What the compaction does to the memory of an entry it keeps.  Top-k and DGC leave entries above the threshold key to the
+// next call's streaming pass (StateHeader::sent_key) and zero only kept entries equal to it; Rand-k, whose choice does not
+// depend on the values, zeroes in place.
+template <int ALGO, bool EF>
+__device__ __forceinline__ void drop_sent(float *st, uint32_t n, uint32_t i, bool equal)
+{
+    if (ALGO == MC_ALGO_RANDK) st[i] = 0.0f;
+    else if (ALGO == MC_ALGO_DGC) { if (equal) { st[i] = 0.0f; st[dgc_u_offset(n) + i] = 0.0f; } }      // momentum factor masking
+    else if (EF) { if (equal) st[i] = 0.0f; }
+}
+// ... and what it tells the next call (one thread)
+template <int ALGO, bool EF>
+__device__ __forceinline__ void record_sent_key(float *st, uint32_t T)
+{
+    if (ALGO == MC_ALGO_DGC || EF)
+        reinterpret_cast<StateHeader *>(reinterpret_cast<uint8_t *>(st) - kHeaderBytes)->sent_key = ALGO == MC_ALGO_RANDK ? 0xFFFFFFFFu : T;
+}
+
 // The walk of one tile's candidates that both emit kernels share: gt_before / eq_before are the numbers of keys
 // above / equal to T among all candidates before this tile.
 template <int ALGO, bool EF>
@@ -727,6 +752,8 @@ __global__ __launch_bounds__(kBlock) void cand_emit_k(uint32_t n, uint32_t ntile
         h.magic = kMagic; h.algo = ALGO; h.n = n; h.k = kept; h.scale = 0.0f; h.levels = CAPPED ? (uint32_t)k : 0u;
         for (int i = 0; i < 24; ++i) h.pad[i] = 0;
         *hdr = h;
+        // this kernel zeroes what it keeps in place: the next streaming pass has nothing to mask
+        if (ALGO == MC_ALGO_DGC || EF) reinterpret_cast<StateHeader *>(reinterpret_cast<uint8_t *>(st) - kHeaderBytes)->sent_key = 0xFFFFFFFFu;
     }
     if (s3.mode & kModeUniform) job.runs = job.tile < ntiles ? uniform_runs(job.tile, n) : 0ull;
     emit_tile<ALGO, EF>(sc, job.tile, job.runs, n, k, st, idx, val, T, need, gt_before, eq_before);
@@ -759,11 +786,8 @@ __global__ __launch_bounds__(kBlock) void cand_emit_k(uint32_t n, uint32_t ntile
 // ---------------------------------------------------------------------------
 constexpr int kSelThreads = 1024, kSelWaves = kSelThreads / 64;      // select: 16 tiles per block (the window is read once per block)
 constexpr int kEmitThreads = kBlock, kEmitWaves = kWavesPerBlock;    // emit: 4 tiles per block
-constexpr int kUKeep = 2;              // list entries that a thread of an emit block keeps in registers between its two walks of the list
 constexpr int kSyncArrive = 0, kSyncRoutes = 32, kSyncLastBin = 40, kSyncLastCands = 41;     // words of SparseScratch::sync (mc_api.hip reads the last three)
 constexpr int kFewRounds = 4;          // a tile with at most 256 candidates is fetched whole
-constexpr int kHeavyRounds = 8;        // other tiles 512 candidates at a time (emit)
-constexpr int kDeepRounds = 8;         // select: 512 candidates at a time, the first 512 asked for before the verdict is known
 
 struct TileRuns { uint32_t r0, r1, r2, total; };       // running sums of the candidates of a tile's four chunks
 __device__ __forceinline__ TileRuns decode_runs(uint64_t runs)
@@ -886,8 +910,7 @@ __device__ __forceinline__ void emit_apply(const CandBatch<ROUNDS> &c, uint32_t 
                 idx[pos] = i;
                 if (ALGO == MC_ALGO_RANDK) val[pos] = st[i];      // the candidate slot holds the random key: the value is p
                 else val[pos] = __uint_as_float(c.bits[u]);
-                if (ALGO == MC_ALGO_DGC) { st[i] = 0.0f; st[dgc_u_offset(n) + i] = 0.0f; }   // momentum factor masking
-                else if (EF) st[i] = 0.0f;
+                drop_sent<ALGO, EF>(st, n, i, is_eq);
             }
         }
         gt_before += __popcll(bgt);
@@ -953,9 +976,7 @@ constexpr int kRoundTiles = 4096;      // tiles per round of the slow routes' co
 // compaction, as steps of one kernel of `blocks` blocks (which the device holds at once), each
 // wavefront taking tiles gw, gw + nw, ...  `mode`: what the window said (kModeFast | kModeDense: the threshold's
 // bin [lo, lo + 2048) is known but too full to list; 0: the threshold lies above lo, the window's top;
-// kModeUniform: too few candidates, every element becomes one).  Nothing that the verdict was derived from is
-// written here (the next call's hint is published by the emit kernel): a block of the grid that only starts when
-// these have finished still reaches the same verdict and leaves.
+// kModeUniform: too few candidates, every element becomes one).
 template <int ALGO, bool EF, bool FROM_STATE, bool RANDOM>
 __device__ __forceinline__ void slow_routes(const GroupView &g, float *st, PayloadHeader *hdr, uint64_t k, const SparseScratch &sc,
                                             const RngKey &rng, uint32_t mode, uint32_t lo, uint64_t need, uint32_t blocks, int *status,
@@ -1063,7 +1084,9 @@ __device__ __forceinline__ void slow_routes(const GroupView &g, float *st, Paylo
         put_sparse_header(hdr, ALGO, n, k);
         SelectState s;
         s.lo = T; s.mode = mode; s.need = need;
-        sc.sel[3] = s;                                                      // the emit kernel derives the next call's hint from it
+        sc.sel[3] = s;
+        publish_hint(sc, T);
+        record_sent_key<ALGO, EF>(st, T);
     }
     // ---- ordered compaction, kRoundTiles tiles at a time: every block scans the round's counts (in LDS) for the
     // keys kept before each tile, and carries the totals of the rounds before
@@ -1114,45 +1137,173 @@ __device__ __forceinline__ void slow_routes(const GroupView &g, float *st, Paylo
     }
 }
 
-#ifdef MC_SEL_WPE
-__attribute__((amdgpu_waves_per_eu(MC_SEL_WPE, MC_SEL_WPE)))
-#endif
+// ---- access to the candidate slots of a tile ---------------------------------------------------------------
+// A chunk's candidates sit at the front of its 1024 slots, in index order.  They are read as a *head* -- the first
+// 64, one per lane -- and up to four *units* of 256 -- a lane takes four consecutive candidates with one 16-byte
+// load of values and one 8-byte load of positions.  The kernels below live on memory latency, not on traffic: the
+// heads of a tile's four chunks are asked for before the number of candidates is known (what lies beyond it is
+// masked out afterwards; most chunks hold fewer than 64), and a crowded chunk costs one more round of loads, not
+// one per 64 candidates.  Candidate number o >= 64 of a chunk is held by lane ((o - 64) % 256) / 4 of unit (o - 64) / 256.
+constexpr int kHead = 64, kUnit = 256;
+__device__ __forceinline__ uint32_t load_head_bits(const SparseScratch &sc, uint32_t chunk)
+{
+    return sc.cand_bits[(size_t)chunk * kChunk + (threadIdx.x & 63u)];
+}
+__device__ __forceinline__ uint32_t load_head_loc(const SparseScratch &sc, uint32_t chunk)
+{
+    return sc.cand_loc[(size_t)chunk * kChunk + (threadIdx.x & 63u)];
+}
+__device__ __forceinline__ uint4 load_bits4(const SparseScratch &sc, uint32_t chunk, uint32_t v)
+{
+    return *reinterpret_cast<const uint4 *>(sc.cand_bits + (size_t)chunk * kChunk + kHead + v * kUnit + (threadIdx.x & 63u) * 4u);
+}
+__device__ __forceinline__ uint2 load_loc4(const SparseScratch &sc, uint32_t chunk, uint32_t v)
+{
+    return *reinterpret_cast<const uint2 *>(sc.cand_loc + (size_t)chunk * kChunk + kHead + v * kUnit + (threadIdx.x & 63u) * 4u);
+}
+// x[q] for a q that is only known at run time, without putting the array into scratch memory
+__device__ __forceinline__ uint32_t pick4(const uint32_t (&x)[4], uint32_t q) { return q == 0 ? x[0] : q == 1 ? x[1] : q == 2 ? x[2] : x[3]; }
+__device__ __forceinline__ uint32_t elem4(const uint4 &x, int j) { return j == 0 ? x.x : j == 1 ? x.y : j == 2 ? x.z : x.w; }
+__device__ __forceinline__ uint32_t loc4(const uint2 &x, int j) { return ((j < 2 ? x.x : x.y) >> (16 * (j & 1))) & 0xFFFFu; }
+// is candidate (unit v, lane, j) of a chunk with cnt candidates there?
+__device__ __forceinline__ bool in_unit(uint32_t cnt, uint32_t v, int j) { return (uint32_t)kHead + v * (uint32_t)kUnit + 4u * (threadIdx.x & 63u) + (uint32_t)j < cnt; }
+
+// The units of a tile, numbered in chunk order: unit e is unit v of chunk q.
+struct TileUnits {
+    uint32_t per[kWavesPerBlock], total;
+    __device__ __forceinline__ TileUnits(const uint32_t (&cnt)[kWavesPerBlock])
+    {
+        total = 0;
+#pragma unroll
+        for (int q = 0; q < kWavesPerBlock; ++q) { per[q] = cnt[q] > (uint32_t)kHead ? (cnt[q] - (uint32_t)kHead + (uint32_t)kUnit - 1u) / (uint32_t)kUnit : 0u; total += per[q]; }
+    }
+    __device__ __forceinline__ void locate(uint32_t e, uint32_t &q, uint32_t &v) const
+    {
+        q = 0;
+#pragma unroll
+        for (int i = 0; i < kWavesPerBlock - 1; ++i) if (q == (uint32_t)i && e >= per[i]) { e -= per[i]; ++q; }
+        v = e;
+    }
+};
+
+// Select: counts the keys above the threshold's bin, buffers those inside it (with the tile's first index: all that
+// the emit kernel needs of a listed key's position is its tile).
+__device__ __forceinline__ uint32_t select_one(const SparseScratch &sc, uint32_t bits, bool valid, uint32_t tile, uint32_t lo, uint32_t sub,
+                                               MemberBuf &m)
+{
+    const uint32_t key = bits & 0x7FFFFFFFu;
+    const bool reach = valid && key >= lo;
+    const bool inside = reach && key - lo < (1u << kWindowShift);
+    const uint64_t mb = __builtin_amdgcn_ballot_w64(inside);
+    if (mb) {
+        const uint32_t c = __popcll(mb);
+        if (m.held + c > (uint32_t)kMemberBuf) flush_members(sc, m, sub);
+        if (inside) { UEntry e; e.idx = tile * (uint32_t)kTile; e.bits = bits; m.buf[m.held + lanes_below(mb)] = e; }
+        m.held += c;
+    }
+    return __popcll(__builtin_amdgcn_ballot_w64(reach && key - lo >= (1u << kWindowShift)));
+}
+
+// What a wavefront of the select kernel asks for of one tile before it knows the verdict.
+struct TileAhead {
+    uint32_t tile, cnt[kWavesPerBlock], head[kWavesPerBlock], uq[4], uv[4], units;
+    uint4 ub[4];
+};
+__device__ __forceinline__ void look_ahead(const SparseScratch &sc, uint32_t tile, bool live, TileAhead &a)
+{
+    a.tile = tile;
+    const uint64_t runs = live ? sc.tile_runs[tile] : 0ull;
+    // the first 64 slots of each chunk, without waiting for the counts
+#pragma unroll
+    for (int q = 0; q < kWavesPerBlock; ++q) a.head[q] = live ? load_head_bits(sc, tile * kWavesPerBlock + q) : 0u;
+    // ... and, as soon as the counts are there, the first four units of a tile with crowded chunks (nearly always all it has)
+#pragma unroll
+    for (int q = 0; q < kWavesPerBlock; ++q) a.cnt[q] = (uint32_t)(runs >> (16 * q)) & 0xFFFFu;
+    const TileUnits tu(a.cnt);
+    a.units = tu.total;
+    if (tu.total) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            tu.locate((uint32_t)i < tu.total ? (uint32_t)i : 0u, a.uq[i], a.uv[i]);
+            a.ub[i] = load_bits4(sc, tile * kWavesPerBlock + a.uq[i], a.uv[i]);
+        }
+    }
+}
+// ... and what it does with it on the lean route: the tile's keys above the threshold's bin are counted, those inside listed
+__device__ __forceinline__ uint32_t select_tile(const SparseScratch &sc, TileAhead &a, uint32_t lo, uint32_t sub, MemberBuf &mb)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    uint32_t above = 0;
+#pragma unroll
+    for (int q = 0; q < kWavesPerBlock; ++q) if (a.cnt[q]) above += select_one(sc, a.head[q], lane < a.cnt[q], a.tile, lo, sub, mb);
+    if (a.units) {
+        const TileUnits tu(a.cnt);
+        for (uint32_t e0 = 0; e0 < tu.total; e0 += 4u) {
+            if (e0) {                            // (more than four units: the next four)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    tu.locate(e0 + i < tu.total ? e0 + i : e0, a.uq[i], a.uv[i]);
+                    a.ub[i] = load_bits4(sc, a.tile * kWavesPerBlock + a.uq[i], a.uv[i]);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (e0 + i >= tu.total) break;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) above += select_one(sc, elem4(a.ub[i], j), in_unit(pick4(a.cnt, a.uq[i]), a.uv[i], j), a.tile, lo, sub, mb);
+            }
+        }
+    }
+    if (lane == 0) sc.tile_cnt[a.tile] = above;
+    return above;
+}
+
+// The select kernel: sixteen tiles per block, one wavefront each; the window is read once per block.
 __global__ __launch_bounds__(kSelThreads) void lean_select_k(GroupView g, uint64_t k, SparseScratch sc)
 {
-    __shared__ __attribute__((aligned(16))) uint32_t bins[kBinsW];     // the window summed over its copies; then this block's level histogram
+    __shared__ uint32_t wtot[kSelWaves];
     __shared__ uint32_t verdict[8];              // found, bin, rest lo, rest hi, candidates lo, hi, keys in the bin
-    __shared__ uint32_t wabove[kSelWaves];
     __shared__ UEntry members[kSelWaves][kMemberBuf];
+    __shared__ uint32_t wabove[kSelWaves];
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const uint32_t ntiles = (g.n + (uint32_t)kTile - 1u) / (uint32_t)kTile;
     const uint32_t tile = blockIdx.x * kSelWaves + wave;
-    // everything is asked for up front: the hint record, the window, and -- two loads deep -- the tile's candidates
-    const uint64_t runs = tile < ntiles ? sc.tile_runs[tile] : 0ull;
+    // everything is asked for up front: what there is to know of the tile, the hint record, the window
+    TileAhead a0;
+    look_ahead(sc, tile, tile < ntiles, a0);
     const uint32_t hint = *sc.hint, hint_shift = sc.hint[kHintShift], hint_hold = sc.hint[kHintHold];
-    uint32_t open = wave == 0 ? sc.hist[kHistOpen + lane] : 0u;
+    uint32_t open = wave == kSelWaves - 1 ? sc.hist[kHistOpen + lane] : 0u;      // (the wavefront that holds the window's last bin)
     uint2 wsum = {0u, 0u};                       // window bins 2 t and 2 t + 1
 #pragma unroll
     for (int r = 0; r < kWinCopies; ++r) {
         const uint2 x = *reinterpret_cast<const uint2 *>(sc.hist + kHistW + r * kBinsW + 2 * t);
         wsum.x += x.x; wsum.y += x.y;
     }
-    // the tile's first 512 candidates (all of them, for nearly every tile) are on their way before the verdict is known
-    const TileRuns tr = decode_runs(runs);
-    CandBatch<kDeepRounds> db;
-    fetch_batch<kDeepRounds, true>(sc, tile, tr, 0u, db);
-    *reinterpret_cast<uint2 *>(bins + 2 * t) = wsum;
-    __syncthreads();
-    if (wave == 0) {
-        uint32_t bin;
-        uint64_t rest, cands;
+    // ---- the verdict: the bin b with  count(bins > b) < k <= count(bins >= b), by a suffix scan over the block's
+    // threads (two bins each; the counts stay below 2^32, there being fewer elements than that)
+    if (wave == kSelWaves - 1) {
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) open += __shfl_xor(open, d, 64);
-        const bool found = resolve_lds<kBinsW>(bins, k, bin, rest, open, &cands);
-        if (lane == 0) {
-            verdict[0] = found; verdict[1] = bin; verdict[2] = (uint32_t)rest; verdict[3] = (uint32_t)(rest >> 32);
-            verdict[4] = (uint32_t)cands; verdict[5] = (uint32_t)(cands >> 32); verdict[6] = bins[bin];
-        }
+        if (lane == 63u) wsum.y += open;         // the last bin also counts every key above the window
     }
+    const uint32_t pair = wsum.x + wsum.y;
+    const uint32_t pre = wave_scan_incl(pair);
+    uint32_t suf = wave_total(pre) - pre + pair;  // inclusive suffix sum: this thread's bins and all above
+    if (lane == 0) wtot[wave] = suf;
+    if (t == 0) verdict[0] = 0u;
+    __syncthreads();
+    uint32_t higher = 0, all = 0;                // candidates in the wavefronts after this one; all candidates
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) { if ((uint32_t)w > wave) higher += wtot[w]; all += wtot[w]; }
+    suf += higher;
+    if ((uint64_t)suf >= k && (uint64_t)(suf - pair) < k) {      // the count crosses k in one of this thread's two bins
+        const uint32_t above = suf - pair;
+        const bool upper = (uint64_t)above + wsum.y >= k;
+        const uint64_t rest = k - above - (upper ? 0u : wsum.y);
+        verdict[0] = 1u; verdict[1] = 2u * t + (upper ? 1u : 0u); verdict[2] = (uint32_t)rest; verdict[3] = 0u;
+        verdict[6] = upper ? wsum.y : wsum.x;
+    }
+    if (t == 0) { verdict[4] = all; verdict[5] = 0u; }
     __syncthreads();
     const bool found = verdict[0] != 0u;
     const uint32_t bin = verdict[1];
@@ -1180,29 +1331,24 @@ __global__ __launch_bounds__(kSelThreads) void lean_select_k(GroupView g, uint64
             sc.hint[kHintShift] = shift; sc.hint[kHintHold] = hold;
             atomicAdd(&sc.sync[kSyncRoutes + (lean ? MC_SELECT_FAST : MC_SELECT_DENSE)], 1u);
         }
-        if (lean) {
+        if (!lean) return;               // dense bin: too many keys to list; the slow-route kernel takes its 2048 keys as a radix level
+        uint32_t above = 0;
+        if (tile < ntiles) {
             const uint32_t sub = tile & (uint32_t)(kUSub - 1);
             MemberBuf mb{members[wave], 0u};
-            uint32_t above = select_apply<kDeepRounds>(sc, db, tr.total, 0u, lo, sub, mb);
-            for (uint32_t f0 = 64 * kDeepRounds; f0 < tr.total; f0 += 64 * kDeepRounds) {
-                fetch_batch<kDeepRounds, true>(sc, tile, tr, f0, db);
-                above += select_apply<kDeepRounds>(sc, db, tr.total, f0, lo, sub, mb);
-            }
+            above = select_tile(sc, a0, lo, sub, mb);
             flush_members(sc, mb, sub);
-            if (lane == 0) {
-                wabove[wave] = above;
-                if (tile < ntiles) sc.tile_cnt[tile] = above;
-            }
-            __syncthreads();
-            if (t == 0) {
-                uint32_t sum = 0;
-#pragma unroll
-                for (int w = 0; w < kSelWaves; ++w) sum += wabove[w];
-                sc.blk_cnt[blockIdx.x] = sum;                          // sixteen tiles hold at most 65536 candidates
-            }
-            return;
         }
-        return;          // dense bin: too many keys to list; the slow-route kernel resolves its 2048 keys as a radix level
+        // keys above the bin in this block's sixteen tiles
+        if (lane == 0) wabove[wave] = above;
+        __syncthreads();
+        if (t == 0) {
+            uint32_t sum = 0;
+#pragma unroll
+            for (int w = 0; w < kSelWaves; ++w) sum += wabove[w];
+            sc.blk_cnt[blockIdx.x] = sum;                          // sixteen tiles hold at most 65536 candidates
+        }
+        return;
     }
     // missed: the next calls filter with the full margin again, and keep it for a while
     if (first) {
@@ -1215,8 +1361,9 @@ __global__ __launch_bounds__(kSelThreads) void lean_select_k(GroupView g, uint64
 }
 
 // The slow routes, in a kernel of their own so that their registers do not weigh on the two kernels of the usual
-// route (with them inside, the select kernel needed 128 registers and only one of its blocks fitted a compute unit:
-// its 390 blocks for the ResNet-50 buffer then ran in two rounds).  On the lean route it reads one word and leaves.
+// route: inside the select kernel they took it to 128 registers and to spilling (one block per compute unit, or two
+// tiles per wavefront: 13 .. 30 us instead of 7 .. 10), inside the emit kernel to 108 registers and two rounds of
+// blocks.  On the lean route this kernel reads one word and leaves (4 us).
 template <int ALGO, bool EF, bool FROM_STATE, bool RANDOM>
 __global__ __launch_bounds__(kSelThreads) void sparse_slow_k(GroupView g, float *st, PayloadHeader *hdr, uint64_t k, SparseScratch sc,
                                                              RngKey rng, int *status)
@@ -1229,6 +1376,86 @@ __global__ __launch_bounds__(kSelThreads) void sparse_slow_k(GroupView g, float 
     slow_routes<ALGO, EF, FROM_STATE, RANDOM>(g, st, hdr, k, sc, rng, s0.mode, s0.lo, s0.need, gridDim.x, status, hist, pfx, small);
 }
 
+// Emit, lean route.  One candidate per lane (a chunk's head): gt0 / eq0 count the keys above / equal to T before it
+// in the whole group; returns them advanced past these 64.
+template <int ALGO, bool EF>
+__device__ __forceinline__ void emit_head(uint32_t bits, uint32_t loc, bool valid, uint32_t chunk, uint32_t n, uint64_t k, float *st,
+                                          uint32_t *idx, float *val, uint32_t T, uint32_t need, uint64_t &gt0, uint32_t &eq0)
+{
+    const uint32_t key = bits & 0x7FFFFFFFu;
+    const bool is_gt = valid && key > T, is_eq = valid && key == T;
+    const uint64_t bgt = __builtin_amdgcn_ballot_w64(is_gt), beq = __builtin_amdgcn_ballot_w64(is_eq);
+    const uint64_t gtb = gt0 + lanes_below(bgt);
+    const uint32_t eqb = eq0 + lanes_below(beq);
+    if (is_gt || (is_eq && eqb < need)) {
+        const uint64_t pos = gtb + (eqb < need ? eqb : need);
+        const uint32_t i = chunk * (uint32_t)kChunk + loc;
+        if (pos < k && i < n) {                  // always true for consistent scratch
+            idx[pos] = i;
+            if (ALGO == MC_ALGO_RANDK) val[pos] = st[i];      // the candidate slot holds the random key: the value is p
+            else val[pos] = __uint_as_float(bits);
+            drop_sent<ALGO, EF>(st, n, i, is_eq);
+        }
+    }
+    gt0 += __popcll(bgt); eq0 += __popcll(beq);
+}
+
+// ... four consecutive candidates per lane (a unit)
+template <int ALGO, bool EF>
+__device__ __forceinline__ void emit_unit(const uint4 &bits, const uint2 &loc, uint32_t cnt, uint32_t v, uint32_t chunk, uint32_t n,
+                                          uint64_t k, float *st, uint32_t *idx, float *val, uint32_t T, uint32_t need, uint64_t gt0, uint32_t eq0)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    bool isg[4], ise[4];
+    uint32_t mine = 0;                                    // this lane's keys above T | equal to T << 16
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t key = elem4(bits, j) & 0x7FFFFFFFu;
+        const bool valid = in_unit(cnt, v, j);
+        isg[j] = valid && key > T; ise[j] = valid && key == T;
+        mine += (isg[j] ? 1u : 0u) + (ise[j] ? 0x10000u : 0u);
+    }
+    const uint32_t inc = wave_scan_incl(mine);            // (a unit holds at most 256 of each: the halves do not mix)
+    uint64_t gtb = gt0 + ((inc - mine) & 0xFFFFu);
+    uint32_t eqb = eq0 + ((inc - mine) >> 16);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (isg[j] || (ise[j] && eqb < need)) {
+            const uint64_t pos = gtb + (eqb < need ? eqb : need);
+            const uint32_t i = chunk * (uint32_t)kChunk + loc4(loc, j);
+            if (pos < k && i < n) {
+                idx[pos] = i;
+                if (ALGO == MC_ALGO_RANDK) val[pos] = st[i];
+                else val[pos] = __uint_as_float(elem4(bits, j));
+                drop_sent<ALGO, EF>(st, n, i, ise[j]);
+            }
+        }
+        gtb += isg[j] ? 1u : 0u; eqb += ise[j] ? 1u : 0u;
+    }
+}
+
+// keys above T | equal to T << 16 among one candidate per lane / in one unit
+__device__ __forceinline__ uint32_t count_head(uint32_t bits, bool valid, uint32_t T)
+{
+    const uint32_t key = bits & 0x7FFFFFFFu;
+    return __popcll(__builtin_amdgcn_ballot_w64(valid && key > T)) + (__popcll(__builtin_amdgcn_ballot_w64(valid && key == T)) << 16);
+}
+__device__ __forceinline__ uint32_t count_unit(const uint4 &bits, uint32_t cnt, uint32_t v, uint32_t T)
+{
+    uint32_t c = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) c += count_head(elem4(bits, j), in_unit(cnt, v, j), T);
+    return c;
+}
+
+// Emit: four tiles per block, one wavefront each.  Every block reads the whole list of the keys in the threshold's
+// bin (it is small), finds the threshold key T and the number of keys equal to T to take with a histogram in LDS,
+// counts the list's kept keys that lie before each of its tiles, adds the keys above the bin in the tiles before,
+// and compacts its tiles' kept candidates into the payload.  The heads of the tile's chunks and the first entries
+// of every sublist are asked for together with everything else, so the usual tile costs one memory latency.
+constexpr int kUSpec = 4;              // entries of every sublist fetched before its length is known (one per thread of an emit block)
+static_assert(kUSpec * kUSub == kEmitThreads, "one speculative list entry per thread");
+
 template <int ALGO, bool EF>
 #ifdef MC_EMIT_WPE
 __attribute__((amdgpu_waves_per_eu(MC_EMIT_WPE, MC_EMIT_WPE)))
@@ -1236,84 +1463,111 @@ __attribute__((amdgpu_waves_per_eu(MC_EMIT_WPE, MC_EMIT_WPE)))
 __global__ __launch_bounds__(kEmitThreads) void lean_emit_k(uint32_t n, uint32_t ntiles, float *st, PayloadHeader *hdr, uint64_t k,
                                                             SparseScratch sc)
 {
-    __shared__ __attribute__((aligned(16))) uint32_t hist[kBins3];
+    __shared__ uint32_t hist[kBins3], coarse[64];          // the listed keys' 11 open bits, and the same 32 bins at a time
     __shared__ uint32_t small[4];
-    __shared__ uint32_t upre[kUSub + 1];
+    __shared__ uint32_t ulen[kUSub], upre[kUSub + 1];
     __shared__ uint32_t cgt[kEmitWaves + 1], ceq[kEmitWaves + 1];
-    __shared__ uint64_t red[kEmitWaves];
+    __shared__ uint32_t red[kEmitWaves];
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const uint32_t tile = blockIdx.x * kEmitWaves + wave;
-    // asked for first, needed last: the tile's candidates, two loads deep
-    const uint64_t runs = tile < ntiles ? sc.tile_runs[tile] : 0ull;
+    const bool live = tile < ntiles;
+    // ---- everything that needs no other load to be located is asked for now
+    const uint64_t runs = live ? sc.tile_runs[tile] : 0ull;
     const SelectState s0 = sc.sel[0];
     const uint32_t ucnt = wave == 0 ? sc.ucount[lane * kUCountStride] : 0u;
+    const UEntry spec = sc.ulist[(size_t)(t / kUSpec) * kUCap + (t % kUSpec)];      // entry t % 4 of sublist t / 4, if it has that many
+    uint32_t hb[kWavesPerBlock], hl[kWavesPerBlock];
+#pragma unroll
+    for (int q = 0; q < kWavesPerBlock; ++q) {
+        hb[q] = live ? load_head_bits(sc, tile * kWavesPerBlock + q) : 0u;
+        hl[q] = live ? load_head_loc(sc, tile * kWavesPerBlock + q) : 0u;
+    }
+    // ... and, as soon as the counts are there, the first four units of a tile with crowded chunks (nearly always all it has)
+    uint32_t cnt[kWavesPerBlock];
+#pragma unroll
+    for (int q = 0; q < kWavesPerBlock; ++q) cnt[q] = (uint32_t)(runs >> (16 * q)) & 0xFFFFu;
+    const TileUnits tu(cnt);
+    uint4 kb[4];
+    uint2 kl[4];
+    uint32_t kq[4], kv[4];
+    if (tu.total) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            tu.locate((uint32_t)i < tu.total ? (uint32_t)i : 0u, kq[i], kv[i]);
+            kb[i] = load_bits4(sc, tile * kWavesPerBlock + kq[i], kv[i]);
+            kl[i] = load_loc4(sc, tile * kWavesPerBlock + kq[i], kv[i]);
+        }
+    }
+    // keys above the bin in the select blocks (sixteen tiles each) before this tile's, then in the tiles before it in its own
+    const uint32_t sblock = tile / (uint32_t)kSelWaves, sfirst = sblock * (uint32_t)kSelWaves;
+    uint32_t before = 0;
+    for (uint32_t b = t; b < blockIdx.x / (uint32_t)(kSelWaves / kEmitWaves); b += kEmitThreads) before += sc.blk_cnt[b];
+    uint32_t mine = live && sfirst + lane < tile ? sc.tile_cnt[sfirst + lane] : 0u;
     // the select kernel is done with the window: all blocks clear it together
     for (uint32_t b = blockIdx.x * kEmitThreads + t; b < (uint32_t)(kWinCopies * kBinsW + kOpenCopies); b += gridDim.x * kEmitThreads)
         sc.hist[b < (uint32_t)(kWinCopies * kBinsW) ? kHistW + b : kHistOpen - kWinCopies * kBinsW + b] = 0u;
-    if (!(s0.mode & kModeLean)) {
-        // the select kernel went all the way on one of its slow routes; what is left is the next call's hint
-        if (blockIdx.x == 0 && t == 0) publish_hint(sc, sc.sel[3].lo);
-        return;
-    }
+    if (!(s0.mode & kModeLean)) return;                 // (the slow routes have written the payload themselves)
     const uint32_t lo = s0.lo;
-    // keys above the bin in the select blocks (sixteen tiles each) before this tile's, then in the tiles before it in its own
-    const uint32_t sblock = tile / (uint32_t)kSelWaves, sfirst = sblock * (uint32_t)kSelWaves;
-    uint64_t before = 0;
-    for (uint32_t b = t; b < blockIdx.x / (uint32_t)(kSelWaves / kEmitWaves); b += kEmitThreads) before += sc.blk_cnt[b];
-    uint32_t mine = tile < ntiles && sfirst + lane < tile ? sc.tile_cnt[sfirst + lane] : 0u;
-    const TileRuns tr = decode_runs(runs);
-    const bool few = tr.total <= 64u * kFewRounds;
-    CandBatch<kFewRounds> cb;
-    if (few) fetch_batch<kFewRounds, true>(sc, tile, tr, 0u, cb);
-    // ---- the list: lengths of the sublists, then its entries, spread over the block's threads
+    // ---- the list
     if (wave == 0) {
-        uint32_t inc = min(ucnt, kUCap);
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const uint32_t o = __shfl_up(inc, d, 64);
-            if (lane >= (uint32_t)d) inc += o;
-        }
+        const uint32_t len = min(ucnt, kUCap);
+        ulen[lane] = len;
+        const uint32_t inc = wave_scan_incl(len > (uint32_t)kUSpec ? len - (uint32_t)kUSpec : 0u);      // entries beyond the speculative ones, scanned
         upre[lane + 1] = inc;
         if (lane == 0) upre[0] = 0u;
     }
     for (int b = t; b < kBins3; b += kEmitThreads) hist[b] = 0u;
+    if (t < 64u) coarse[t] = 0u;
     if (t <= (uint32_t)kEmitWaves) { cgt[t] = 0u; ceq[t] = 0u; }
     __syncthreads();
-    const uint32_t total = min(upre[kUSub], kUCap);
-    // entry e of the concatenated sublists (the first kUKeep of a thread stay in registers for the second walk)
-    auto entry = [&](uint32_t e) {
-        uint32_t s = 0;                                    // the sublist that holds entry e: the last one that starts at or before it
+    const bool have_spec = (t % kUSpec) < ulen[t / kUSpec];
+    const uint32_t more = min(upre[kUSub], kUCap);       // (nothing, when no sublist holds more than four entries)
+    // further entry e: entry kUSpec + (e - upre[s]) of the sublist s that is the last to start at or before e
+    auto further = [&](uint32_t e) {
+        uint32_t sl = 0;
 #pragma unroll
-        for (int step = kUSub / 2; step >= 1; step >>= 1) if (upre[s + step] <= e) s += step;
-        return sc.ulist[(size_t)s * kUCap + (e - upre[s])];
+        for (int step = kUSub / 2; step >= 1; step >>= 1) if (upre[sl + step] <= e) sl += step;
+        return sc.ulist[(size_t)sl * kUCap + kUSpec + (e - upre[sl])];
     };
-    UEntry ent[kUKeep];
+    auto tally = [&](uint32_t bits) {
+        const uint32_t d = (bits & 0x7FFFFFFFu) - lo;
+        if (d < (uint32_t)kBins3) { atomicAdd(&hist[d], 1u); atomicAdd(&coarse[d >> 5], 1u); }
+    };
+    if (have_spec) tally(spec.bits);
+    for (uint32_t e0 = t; e0 < more; e0 += 4 * kEmitThreads) {        // (four loads in flight)
+        UEntry x[4];
 #pragma unroll
-    for (int j = 0; j < kUKeep; ++j) {
-        const uint32_t e = t + (uint32_t)kEmitThreads * j;
-        ent[j].idx = 0u; ent[j].bits = 0u;
-        if (e < total) ent[j] = entry(e);
-    }
+        for (int i = 0; i < 4; ++i) if (e0 + i * kEmitThreads < more) x[i] = further(e0 + i * kEmitThreads);
 #pragma unroll
-    for (int j = 0; j < kUKeep; ++j) {
-        const uint32_t d = (ent[j].bits & 0x7FFFFFFFu) - lo;
-        if (t + (uint32_t)kEmitThreads * j < total && d < (uint32_t)kBins3) atomicAdd(&hist[d], 1u);
-    }
-    for (uint32_t e = t + (uint32_t)kEmitThreads * kUKeep; e < total; e += kEmitThreads) {
-        const uint32_t d = (entry(e).bits & 0x7FFFFFFFu) - lo;
-        if (d < (uint32_t)kBins3) atomicAdd(&hist[d], 1u);
+        for (int i = 0; i < 4; ++i) if (e0 + i * kEmitThreads < more) tally(x[i].bits);
     }
     __syncthreads();
-    // threshold key and the number of keys equal to it to take
+    // threshold key and the number of keys equal to it to take: the key at which the count from the top reaches
+    // s0.need, first among the 64 coarse bins, then among the 32 keys of that one
     if (wave == 0) {
-        uint32_t b;
-        uint64_t r;
-        if (!resolve_lds<kBins3>(hist, s0.need, b, r)) { b = 0u; r = 0u; }
-        if (lane == 0) { small[0] = b; small[1] = (uint32_t)r; }      // (at most kUCap keys in the bin)
+        const uint32_t want = (uint32_t)s0.need;           // (at most kUCap)
+        const uint32_t c = coarse[lane];
+        const uint32_t cpre = wave_scan_incl(c);
+        const uint32_t suf = wave_total(cpre) - cpre + c;          // from the top
+        const uint64_t hit = __builtin_amdgcn_ballot_w64(suf >= want && suf - c < want);
+        uint32_t b = 0, r = 0;
+        if (hit) {
+            const uint32_t cl = (uint32_t)__builtin_ctzll(hit);
+            const uint32_t left = want - (__shfl(suf, cl, 64) - __shfl(c, cl, 64));      // to take inside the coarse bin
+            const uint32_t f = lane < 32u ? hist[32u * cl + lane] : 0u;
+            const uint32_t fpre = wave_scan_incl(f);
+            const uint32_t fs = wave_total(fpre) - fpre + f;
+            const uint64_t hit2 = __builtin_amdgcn_ballot_w64(lane < 32u && fs >= left && fs - f < left);
+            if (hit2) {
+                const uint32_t fl = (uint32_t)__builtin_ctzll(hit2);
+                b = 32u * cl + fl;
+                r = left - (__shfl(fs, fl, 64) - __shfl(f, fl, 64));
+            }
+        }
+        if (lane == 0) { small[0] = b; small[1] = r; }       // (an inconsistent list: T = lo, nothing equal taken)
     }
     __syncthreads();
-    const uint32_t T = lo + small[0];
-    const uint64_t need = small[1];
+    const uint32_t T = lo + small[0], need = small[1];
     // the list's kept keys, by where they lie: before this block, or in its tile j (bucket j + 1)
     const uint32_t first = blockIdx.x * (uint32_t)(kEmitWaves * kTile);
     auto classify = [&](const UEntry &x) {
@@ -1323,32 +1577,91 @@ __global__ __launch_bounds__(kEmitThreads) void lean_emit_k(uint32_t n, uint32_t
             if (bucket <= (uint32_t)kEmitWaves) atomicAdd(key > T ? &cgt[bucket] : &ceq[bucket], 1u);
         }
     };
+    if (have_spec) classify(spec);
+    for (uint32_t e0 = t; e0 < more; e0 += 4 * kEmitThreads) {
+        UEntry x[4];
 #pragma unroll
-    for (int j = 0; j < kUKeep; ++j) if (t + (uint32_t)kEmitThreads * j < total) classify(ent[j]);
-    for (uint32_t e = t + (uint32_t)kEmitThreads * kUKeep; e < total; e += kEmitThreads) classify(entry(e));
+        for (int i = 0; i < 4; ++i) if (e0 + i * kEmitThreads < more) x[i] = further(e0 + i * kEmitThreads);
 #pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) { before += __shfl_xor(before, m, 64); mine += __shfl_xor(mine, m, 64); }
+        for (int i = 0; i < 4; ++i) if (e0 + i * kEmitThreads < more) classify(x[i]);
+    }
+    before = wave_total(wave_scan_incl(before));          // (sums of candidates: below 2^32)
+    mine = wave_total(wave_scan_incl(mine));
     if (lane == 0) red[wave] = before;
     __syncthreads();
-    uint64_t gt_before = mine, eq_before = 0;
+    if (blockIdx.x == 0 && t == 0) { put_sparse_header(hdr, ALGO, n, k); publish_hint(sc, T); record_sent_key<ALGO, EF>(st, T); }
+    if (!live) return;
+    uint64_t gt0 = mine;
+    uint32_t eq0;
 #pragma unroll
-    for (int w = 0; w < kEmitWaves; ++w) gt_before += red[w];
+    for (int w = 0; w < kEmitWaves; ++w) gt0 += red[w];
     {
-        uint32_t g2 = lane <= wave ? cgt[lane] : 0u, e2 = lane <= wave ? ceq[lane] : 0u;
+        uint32_t g2 = 0, e2 = 0;                            // the list's kept keys before this tile: buckets 0 .. wave
 #pragma unroll
-        for (int m = 32; m >= 1; m >>= 1) { g2 += __shfl_xor(g2, m, 64); e2 += __shfl_xor(e2, m, 64); }
-        gt_before += g2; eq_before = e2;
+        for (int b = 0; b <= kEmitWaves; ++b) if ((uint32_t)b <= wave) { g2 += cgt[b]; e2 += ceq[b]; }
+        gt0 += g2; eq0 = e2;
     }
     uint32_t *idx = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(hdr) + kHeaderBytes);
     float *val = reinterpret_cast<float *>(idx + k);
-    if (blockIdx.x == 0 && t == 0) { put_sparse_header(hdr, ALGO, n, k); publish_hint(sc, T); }
-    if (few) emit_apply<ALGO, EF, kFewRounds>(cb, tr.total, 0u, n, k, st, idx, val, T, need, gt_before, eq_before);
-    else
-        for (uint32_t f0 = 0; f0 < tr.total; f0 += 64 * kHeavyRounds) {
-            CandBatch<kHeavyRounds> hb;
-            fetch_batch<kHeavyRounds, true>(sc, tile, tr, f0, hb);
-            emit_apply<ALGO, EF, kHeavyRounds>(hb, tr.total, f0, n, k, st, idx, val, T, need, gt_before, eq_before);
+    if (tu.total == 0) {
+        // the usual tile: no chunk holds more than 64 candidates, and they are all here
+#pragma unroll
+        for (int q = 0; q < kWavesPerBlock; ++q)
+            if (cnt[q]) emit_head<ALGO, EF>(hb[q], hl[q], lane < cnt[q], tile * kWavesPerBlock + q, n, k, st, idx, val, T, need, gt0, eq0);
+        return;
+    }
+    // a tile with crowded chunks: count the kept keys of every piece (lane 5 q: the head of chunk q, lane 5 q + 1 + v: its
+    // unit v), scan, then place piece by piece.  Up to four units -- nearly every such tile -- were fetched at the start and
+    // stay in registers between the two steps; beyond that the units are fetched four at a time, twice.
+    uint32_t piece = 0;
+#pragma unroll
+    for (int q = 0; q < kWavesPerBlock; ++q) {
+        const uint32_t c = cnt[q] ? count_head(hb[q], lane < cnt[q], T) : 0u;
+        if (lane == 5u * q) piece = c;
+    }
+    const bool kept_here = tu.total <= 4u;
+    for (uint32_t e0 = 0; e0 < tu.total; e0 += 4u) {
+        if (e0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                tu.locate(e0 + i < tu.total ? e0 + i : e0, kq[i], kv[i]);
+                kb[i] = load_bits4(sc, tile * kWavesPerBlock + kq[i], kv[i]);
+            }
         }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (e0 + i >= tu.total) break;
+            const uint32_t c = count_unit(kb[i], pick4(cnt, kq[i]), kv[i], T);
+            if (lane == 5u * kq[i] + 1u + kv[i]) piece = c;
+        }
+    }
+    // inclusive scans over the twenty pieces (a tile holds at most 4096 of each)
+    const uint32_t ig = wave_scan_incl(piece & 0xFFFFu), ie = wave_scan_incl(piece >> 16);
+    const uint32_t xg = ig - (piece & 0xFFFFu), xe = ie - (piece >> 16);          // kept keys of the tile before each piece
+#pragma unroll
+    for (int q = 0; q < kWavesPerBlock; ++q) {
+        if (!cnt[q]) continue;
+        uint64_t g1 = gt0 + (uint32_t)__builtin_amdgcn_readlane((int)xg, 5 * q);
+        uint32_t e1 = eq0 + (uint32_t)__builtin_amdgcn_readlane((int)xe, 5 * q);
+        emit_head<ALGO, EF>(hb[q], hl[q], lane < cnt[q], tile * kWavesPerBlock + q, n, k, st, idx, val, T, need, g1, e1);
+    }
+    for (uint32_t e0 = 0; e0 < tu.total; e0 += 4u) {
+        if (!kept_here) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                tu.locate(e0 + i < tu.total ? e0 + i : e0, kq[i], kv[i]);
+                kb[i] = load_bits4(sc, tile * kWavesPerBlock + kq[i], kv[i]);
+                kl[i] = load_loc4(sc, tile * kWavesPerBlock + kq[i], kv[i]);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (e0 + i >= tu.total) break;
+            const uint32_t u = 5u * kq[i] + 1u + kv[i];
+            emit_unit<ALGO, EF>(kb[i], kl[i], pick4(cnt, kq[i]), kv[i], tile * kWavesPerBlock + kq[i], n, k, st, idx, val, T, need,
+                                gt0 + (uint32_t)__builtin_amdgcn_readlane((int)xg, u), eq0 + (uint32_t)__builtin_amdgcn_readlane((int)xe, u));
+        }
+    }
 }
 
 template <int ALGO, bool EF, bool CAPPED>
@@ -1367,6 +1680,7 @@ static void sparse_compress_t(const LaunchCtx &lc, const GroupView &g, float *st
     if (!CAPPED) {
         // the two-kernel tail; its slow routes run on at most `sync_blocks` blocks, which the device holds at once
         const uint32_t sblocks = (nt + kSelWaves - 1) / kSelWaves, eblocks = (nt + kEmitWaves - 1) / kEmitWaves;
+        // the slow routes run on blocks that the device holds at once: one per compute unit
         const uint32_t sync = std::max(1u, std::min(std::min(sync_blocks, sblocks), (uint32_t)(kRoundTiles / kSelWaves)));
         prof_begin(lc, K_LEAN_SELECT);
         MC_LAUNCH(lean_select_k, dim3(sblocks), dim3(kSelThreads), lc, g, k, sc);

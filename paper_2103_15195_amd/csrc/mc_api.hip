@@ -342,7 +342,7 @@ int mc_ctx_destroy(mc_ctx *ctx)
     if (ctx->d_partial) (void)hipFree(ctx->d_partial);
     void *sparse_bufs[] = {ctx->sparse.hist, ctx->sparse.sel, ctx->d_hints, ctx->sparse.cand_bits, ctx->sparse.cand_loc,
                            ctx->sparse.tile_runs, ctx->sparse.tile_cnt, ctx->sparse.blk_cnt, ctx->sparse.tile_first,
-                           ctx->sparse.tile_last, ctx->sparse.ulist, ctx->sparse.ucount, ctx->sparse.sync};
+                           ctx->sparse.tile_last, ctx->sparse.ulist, ctx->sparse.ucount, ctx->sparse.tile_base, ctx->sparse.sync};
     for (void *b : sparse_bufs) if (b) (void)hipFree(b);
     if (ctx->d_status) (void)hipFree(ctx->d_status);
     if (switched) (void)hipSetDevice(prev);
@@ -432,6 +432,7 @@ int mc_ctx_create(mc_ctx **out, const mc_config *cfg, const int64_t *numel, int3
                 hipMalloc(&sp.tile_last, off_words * sizeof(uint64_t)) != hipSuccess ||
                 hipMalloc(&sp.ulist, (size_t)kUSub * kUCap * sizeof(UEntry)) != hipSuccess ||
                 hipMalloc(&sp.ucount, (size_t)kUSub * kUCountStride * sizeof(uint32_t)) != hipSuccess ||
+                hipMalloc(&sp.tile_base, tiles * sizeof(uint2)) != hipSuccess ||
                 hipMalloc(&sp.sync, 64 * sizeof(uint32_t)) != hipSuccess) rc = MC_ERR_ALLOC;
             else if (hipMemset(sp.hist, 0, hist_bytes) != hipSuccess || hipMemset(sp.sel, 0, 4 * sizeof(SelectState)) != hipSuccess ||
                      hipMemset(ctx->d_hints, 0, (size_t)y * kHintWorkers * kHintWords * sizeof(uint32_t)) != hipSuccess ||

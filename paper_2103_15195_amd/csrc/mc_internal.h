@@ -26,7 +26,8 @@ struct StateHeader {            // one cache line in front of the error-feedback
     float scale;                // EF-Sign: scale of the last call; OneBit: mean of its upper class (0 after zero-fill / import)
     float scale_lo;             // OneBit: mean of the lower class of the last call
     uint32_t prev_worker, prev_iter;   // QSGD / TernGrad: whose random stream the last call drew from (scale: its norm / max)
-    uint32_t pad[28];
+    uint32_t sent_key;          // Top-k, DGC: elements of the last call whose key exceeds this were sent and count as 0 (see sparse_accum_k)
+    uint32_t pad[27];
 };
 static_assert(sizeof(StateHeader) == kHeaderBytes, "state header is one 128-byte line");
 
@@ -103,7 +104,7 @@ constexpr int kHistWords = 2048 * kWinCopies + 2048 + 1024 + 2048 + 64;   // bin
 // Adds to one address queue up behind each other, so the list is kept in kUSub sublists (a wavefront appends to the
 // one of its tile index) whose counters sit on cache lines of their own.
 constexpr int kUSub = 64;
-constexpr uint32_t kUCap = 2048;      // keys in the threshold's window bin that the two-kernel route takes; a sublist holds as many
+constexpr uint32_t kUCap = 4096;      // keys in the threshold's window bin that the two-kernel route takes; a sublist holds as many
 constexpr int kUCountStride = 32;     // words between sublist counters (one 128-byte line each)
 struct UEntry { uint32_t idx, bits; };       // group-relative index, candidate bits
 
@@ -119,6 +120,7 @@ struct SparseScratch {
     uint64_t *tile_first, *tile_last;   // decompress: per worker and 4096-element tile, (epoch << 32 | entry) of its run
     UEntry *ulist;         // kUSub sublists of kUCap entries: the candidates in the threshold's window bin
     uint32_t *ucount;      // their lengths, kUCountStride words apart; cleared by the streaming pass of the next call
+    uint2 *tile_base;      // lean route: per tile, keys above / equal to the threshold before it (resolve kernel -> emit kernel)
     uint32_t *sync;        // [0]: arrivals at the grid-wide barriers of the slow routes (cleared by the select kernel); [32..36): calls per route
 };
 // sync_blocks: how many blocks of 1024 threads the device surely holds at once (one per compute unit): the slow routes

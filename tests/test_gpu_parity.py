@@ -394,6 +394,58 @@ def test_filter_margin_tightens_and_recovers_from_a_miss():
     ctx.close()
 
 
+@pytest.mark.parametrize("algo", ["topk", "dgc", "randk"])
+def test_crowded_tiles_on_the_usual_route(algo):
+    """The two kernels after the streaming pass read a tile's candidates as four heads of 64 and units of 256.  Gradients
+    whose large values crowd into a few tiles (some chunks with more than 64 candidates, one tile with all 4096 of its
+    elements above the threshold: more than four units) are compressed call after call, so that after the first calls the
+    threshold stays inside the window of the last one; every payload and residual is compared."""
+    numel = [50000, 4096 * 3 + 5, 70000, 777]
+    n = sum(numel)
+    rng0 = np.random.default_rng(91)
+    scale = np.full(n, 1e-3, np.float32)
+    scale[50000 + 100:50000 + 100 + 4096 + 900] = 1.0            # one tile and a bit: every element far above the rest
+    scale[90000:90000 + 1500] = 0.3                              # crowded chunks
+    scale[rng0.integers(0, n, 400)] = 0.5                        # and loners everywhere
+
+    def grads(w, it):
+        rng = np.random.default_rng([92, w, it])
+        return rng.standard_normal(n, dtype=np.float32) * scale * np.float32(1.0 + 0.02 * it)
+    st = H.run_parity(numel, algo, 1, 2, 7, grads, ratio_ppm=30000, dgc_momentum=0.3, seed=9)
+    assert st.compress_checks == 14
+
+
+def test_threshold_bin_too_full_to_list():
+    """More keys share the threshold's window bin than the list between the select and the emit kernel holds (here: heavy
+    ties at the threshold): that bin is resolved as a radix level instead.  Route and results are checked."""
+    n, tensors = 200000, [120000, 80000]
+    ctx = B.Context("topk", tensors, [0, 2], ratio_ppm=100000, seed=1)
+    ocfg = O.Config(O.TOPK, ratio_ppm=100000, seed=1)
+    st = torch.zeros(ctx.state_bytes(0), dtype=torch.uint8, device=H.DEV)
+    pay = torch.zeros(ctx.payload_bytes(0), dtype=torch.uint8, device=H.DEV)
+    ost = O.new_state(ocfg, n)
+    rng = np.random.default_rng(3)
+    routes = []
+    for it in range(5):
+        # 30 % of the elements carry the very same magnitude, which is where the 10 % threshold falls; error feedback off
+        # for them (they are re-drawn each call), so the threshold key does not move
+        g = (rng.standard_normal(n, dtype=np.float32) * np.float32(1e-3)).astype(np.float32)
+        tie = rng.random(n) < 0.3
+        g[tie] = np.where(rng.random(int(tie.sum())) < 0.5, 1.0, -1.0).astype(np.float32)
+        ost[:] = 0
+        st.zero_()
+        ctx.mc_compress(0, 0, it, H.device_tensors(g, tensors), st, pay)
+        routes.append(ctx.mc_last_select_route())
+        op, _ = O.compress(ocfg, g, ost, group_off=0, worker=0, it=it)
+        assert np.array_equal(pay.cpu().numpy(), op), f"call {it} (route {routes[-1]}): payload differs"
+        e = torch.empty(n, dtype=torch.float32, device=H.DEV)
+        ctx.mc_state_export_residual(0, st, e)
+        assert H.same_bits(e.cpu().numpy(), ost), f"call {it}: residual differs"
+    print("routes", routes, ctx.mc_select_stats(), flush=True)
+    assert B.MC_SELECT_DENSE in routes
+    ctx.close()
+
+
 @pytest.mark.parametrize("algo", ["topk", "dgc"])
 def test_selection_routes_are_all_taken_and_exact(algo):
     """The exact selection has three routes: the threshold key T falls inside the histogram window that the
