@@ -237,6 +237,24 @@ int64_t orc_sparse_capacity(const orc_config *c, int64_t n)
     return k;
 }
 
+/* A sparse payload ends with a directory of its ascending index list: entry t counts the kept entries whose
+ * index lies below t * DIR_SPAN, for t = 0 .. ceil(n / DIR_SPAN) (so the first is 0 and the last the number of
+ * kept entries; an empty group has no directory).  It adds nothing to what the payload says; a receiver that sums
+ * many such lists span by span finds each list's share of a span without searching.  (Wire layout, which the paper
+ * leaves open.) */
+#define DIR_SPAN 4096
+int64_t orc_dir_spans(int64_t n) { return (n + DIR_SPAN - 1) / DIR_SPAN; }
+static void put_directory(uint8_t *payload, int64_t n, int64_t cap, const uint32_t *idx, int64_t kept)
+{
+    if (n <= 0) return;
+    uint32_t *dir = (uint32_t *)(payload + HDR_BYTES + 8 * cap);
+    int64_t j = 0;
+    for (int64_t t = 0; t <= orc_dir_spans(n); ++t) {
+        while (j < kept && (int64_t)idx[j] < t * DIR_SPAN) ++j;
+        dir[t] = (uint32_t)j;
+    }
+}
+
 static int64_t words32(int64_t n) { return (n + 31) / 32; }
 static int64_t pad4(int64_t b) { return (b + 3) / 4 * 4; }
 
@@ -252,7 +270,7 @@ int64_t orc_payload_bytes(const orc_config *c, int64_t n)
     case ALG_FP16:     return HDR_BYTES + pad4(2 * n);
     case ALG_TOPK:
     case ALG_DGC:
-    case ALG_RANDK:    return HDR_BYTES + 8 * orc_sparse_capacity(c, n);
+    case ALG_RANDK:    return HDR_BYTES + 8 * orc_sparse_capacity(c, n) + (n > 0 ? 4 * (orc_dir_spans(n) + 1) : 0);
     }
     return -1;
 }
@@ -518,6 +536,7 @@ int orc_compress(const orc_config *c, int64_t n, uint64_t group_off, uint32_t wo
             float *v = state, *u = state + n;
             for (int64_t i = 0; i < n; ++i)
                 if (sel[i]) { idx[j] = (uint32_t)i; val[j] = p[i]; ++j; v[i] = 0.0f; u[i] = 0.0f; }
+            put_directory(payload, n, cap, idx, kept);
             free(sel);
             break;
         }
@@ -541,6 +560,7 @@ int orc_compress(const orc_config *c, int64_t n, uint64_t group_off, uint32_t wo
         for (int64_t i = 0; i < n; ++i) {           /* ascending index order */
             if (sel[i]) { idx[j] = (uint32_t)i; val[j] = p[i]; ++j; }
         }
+        put_directory(payload, n, k, idx, k);
         if (c->algo == ALG_DGC) {
             /* selected entries leave both accumulators (momentum factor masking) */
             float *v = state, *u = state + n;

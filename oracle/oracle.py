@@ -275,6 +275,33 @@ def header(payload: np.ndarray) -> dict:
     }
 
 
+DIR_SPAN = 4096
+
+
+def sparse_directory(payload: np.ndarray) -> np.ndarray:
+    """The directory that ends a sparse payload: entry t = kept entries with index below t * DIR_SPAN."""
+    h = header(payload)
+    cap = h["levels"] or h["k"]
+    spans = (h["n"] + DIR_SPAN - 1) // DIR_SPAN
+    return payload[HDR + 8 * cap:HDR + 8 * cap + (4 * (spans + 1) if h["n"] else 0)].view(np.uint32)
+
+
+def with_directory(algo: int, n: int, idx: np.ndarray, val: np.ndarray) -> np.ndarray:
+    """A sparse payload (exact-k layout) built from an ascending index list and its values: header, lists, directory."""
+    k = int(idx.size)
+    spans = (n + DIR_SPAN - 1) // DIR_SPAN
+    assert n > 0
+    pay = np.zeros(HDR + 8 * k + 4 * (spans + 1), np.uint8)
+    pay[0:4] = np.frombuffer(np.uint32(0x3150434D).tobytes(), np.uint8)
+    pay[4:8] = np.frombuffer(np.uint32(algo).tobytes(), np.uint8)
+    pay[8:16] = np.frombuffer(np.uint64(n).tobytes(), np.uint8)
+    pay[16:24] = np.frombuffer(np.uint64(k).tobytes(), np.uint8)
+    pay[HDR:HDR + 4 * k] = np.ascontiguousarray(idx, np.uint32).view(np.uint8)
+    pay[HDR + 4 * k:HDR + 8 * k] = np.ascontiguousarray(val, np.float32).view(np.uint8)
+    pay[HDR + 8 * k:] = np.searchsorted(idx, np.arange(spans + 1, dtype=np.int64) * DIR_SPAN, side="left").astype(np.uint32).view(np.uint8)
+    return pay
+
+
 def sparse_view(payload: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
     """(indices, values) of the kept entries; a payload with a capacity (sampled DGC) holds k <= capacity of them."""
     h = header(payload)

@@ -230,6 +230,30 @@ def test_dgc_momentum_closed_form():
         O.compress(O.Config(O.DGC, use_ef=0), g, None)
 
 
+def test_sparse_payload_ends_with_a_directory_of_its_index_list():
+    """Entry t of the directory counts the kept entries with index below 4096 t (a library search over the index list is
+    the reference); payload size = header + 8 k + 4 (spans + 1).  Exact top-k, DGC, Rand-k and DGC with a capacity."""
+    n = 3 * 4096 + 77
+    g = rand_group(n, 71, 0.1)
+    g[4096:2 * 4096] *= 1e-4                      # a span with no kept entry
+    for cfg in (O.Config(O.TOPK, ratio_ppm=20000), O.Config(O.DGC, ratio_ppm=20000), O.Config(O.RANDK, ratio_ppm=20000, seed=3),
+                O.Config(O.DGC, ratio_ppm=20000, dgc_sample_ppm=100000, seed=5)):
+        pay, _ = O.compress(cfg, g, O.new_state(cfg, n), worker=1, it=2)
+        idx, _ = O.sparse_view(pay)
+        h = O.header(pay)
+        cap = h["levels"] or h["k"]
+        spans = (n + 4095) // 4096
+        assert pay.size == O.HDR + 8 * cap + 4 * (spans + 1) == O.payload_bytes(cfg, n)
+        d = O.sparse_directory(pay)
+        assert d.size == spans + 1 and d[0] == 0 and d[-1] == h["k"] == idx.size
+        assert np.array_equal(d, np.searchsorted(idx, np.arange(spans + 1) * 4096, side="left"))
+        if cfg.algo != O.RANDK and not cfg.dgc_sample_ppm:
+            assert d[2] == d[1]                       # nothing kept in the quiet span
+        # what a payload built from the lists alone looks like (the helper the GPU tests use)
+        if not cfg.dgc_sample_ppm:
+            assert np.array_equal(O.with_directory(cfg.algo, n, idx, O.sparse_view(pay)[1]), pay)
+
+
 # ================================================================= QSGD =====
 def test_qsgd_structure():
     n = 5000

@@ -40,7 +40,8 @@ def test_sampling_everything_is_the_exact_selection():
         assert O.header(pa)["k"] == O.header(pb)["k"] == 100
         assert np.array_equal(ia, ib) and np.array_equal(va, vb) and np.array_equal(sa, sb)
         assert O.header(pa)["levels"] == 200 and O.header(pb)["levels"] == 0
-        assert pa.size == O.HDR + 8 * 200 and pb.size == O.HDR + 8 * 100
+        dirb = 4 * ((n + 4095) // 4096 + 1)                            # the directory that ends a sparse payload
+        assert pa.size == O.HDR + 8 * 200 + dirb and pb.size == O.HDR + 8 * 100 + dirb
 
 
 @pytest.mark.parametrize("n,ratio,sppm,off,worker,it", [(50000, 10000, 10000, 0, 0, 0), (50000, 10000, 50000, 12345, 3, 9),
@@ -70,7 +71,9 @@ def test_threshold_is_the_quantile_of_the_strided_sample(n, ratio, sppm, off, wo
         assert h["k"] == cap
     assert np.array_equal(val, g[idx]) and (np.diff(idx.astype(np.int64)) > 0).all()
     # unused entries of the payload stay zero
-    assert not pay[O.HDR + 4 * h["k"]:O.HDR + 4 * cap].any() and not pay[O.HDR + 4 * cap + 4 * h["k"]:].any()
+    assert not pay[O.HDR + 4 * h["k"]:O.HDR + 4 * cap].any() and not pay[O.HDR + 4 * cap + 4 * h["k"]:O.HDR + 8 * cap].any()
+    # the directory of the index list follows the two lists
+    assert np.array_equal(O.sparse_directory(pay), np.searchsorted(idx, np.arange((n + 4095) // 4096 + 1) * 4096, side="left"))
     # momentum 0, zero state: what was sent plus what is remembered is g, exactly; kept entries left both accumulators
     back = st[:n].copy()
     back[idx] += val

@@ -162,5 +162,6 @@ def test_payload_sizes_follow_paper_settings(golden_dir):
     assert O.topk_count(n, ppm) == n // 100
     assert O.payload_bytes(O.Config(O.QSGD, qsgd_bits=f["qsgd_bits_per_element"]), n) == O.HDR + n  # 8 bits / element
     assert O.payload_bytes(O.Config(O.EFSIGN), n) == O.HDR + 4 * ((n + 31) // 32)                 # 1 bit / element
-    assert O.payload_bytes(O.Config(O.TOPK, ratio_ppm=ppm), n) == O.HDR + 8 * (n // 100)
+    # 99 % sparsity: an index and a value per kept entry, and the directory of the index list (one entry per 4096 elements and one more)
+    assert O.payload_bytes(O.Config(O.TOPK, ratio_ppm=ppm), n) == O.HDR + 8 * (n // 100) + 4 * ((n + 4095) // 4096 + 1)
     assert O.topk_count(50, 10000) == 1 and O.topk_count(0, 10000) == 0 and O.topk_count(3, 10 ** 6) == 3
