@@ -51,8 +51,13 @@
  *     QSGD      n int8 codes in [-s, s], zero-padded to a multiple of 4 bytes
  *     FP16      n binary16, zero-padded to a multiple of 4 bytes
  *     Top-k, DGC, Rand-k
- *               idx[k] uint32 ascending group-relative indices, then val[k] float
- *               (DGC with a sampled threshold: idx[c] then val[c], the first k of each in use, the rest zero)
+ *               idx[k] uint32 ascending group-relative indices, then val[k] float, then the directory of the
+ *               index list, dir[ceil(n/4096) + 1] uint32: dir[t] = number of entries with index below 4096 t
+ *               (dir[0] = 0, the last entry = k; no directory when n = 0).  It repeats what the index list says,
+ *               so that a receiver finds a payload's share of a 4096-element span without a search; a
+ *               directory that disagrees with its list makes the sums unspecified, never an access out of bounds
+ *               (DGC with a sampled threshold: idx[c] then val[c], the first k of each in use, the rest zero,
+ *               then the directory)
  *   Payload buffers must be 16-byte aligned; 128-byte alignment is what the kernels are fastest with
  *   (measured: FP16 decompress-sum of 8 payloads 81 us against 95 us with bodies 64 bytes off the lines).
  */

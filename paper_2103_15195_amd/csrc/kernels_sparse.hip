@@ -638,6 +638,14 @@ __global__ __launch_bounds__(kBlock) void cand_count_k(uint32_t n, uint32_t ntil
 //   (#kept before it) = (#above before it) + min(#equal before it, need).
 // Every block adds up the counts of the blocks before it; nothing waits.
 // ---------------------------------------------------------------------------
+// The directory that ends a sparse payload: entry t = kept entries with index below 4096 t, t = 0 .. tiles (the paper
+// gives no payload format; this one lets the receiver find a payload's share of a tile without searching).  It follows
+// the index and value lists, which have room for `cap` entries each.
+__device__ __forceinline__ uint32_t *payload_directory(PayloadHeader *hdr, uint64_t cap)
+{
+    return reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(hdr) + kHeaderBytes + 8u * cap);
+}
+
 // What the compaction does to the memory of an entry it keeps.  Top-k and DGC leave entries above the threshold key to the
 // next call's streaming pass (StateHeader::sent_key) and zero only kept entries equal to it; Rand-k, whose choice does not
 // depend on the values, zeroes in place.
@@ -756,6 +764,12 @@ __global__ __launch_bounds__(kBlock) void cand_emit_k(uint32_t n, uint32_t ntile
         if (ALGO == MC_ALGO_DGC || EF) reinterpret_cast<StateHeader *>(reinterpret_cast<uint8_t *>(st) - kHeaderBytes)->sent_key = 0xFFFFFFFFu;
     }
     if (s3.mode & kModeUniform) job.runs = job.tile < ntiles ? uniform_runs(job.tile, n) : 0ull;
+    if (lane == 0 && job.tile < ntiles) {
+        uint32_t *dir = payload_directory(hdr, k);
+        const uint64_t at = gt_before + (eq_before < need ? eq_before : need);      // CAPPED: there may be no room for all of them
+        dir[job.tile] = (uint32_t)(at < kept ? at : kept);
+        if (job.tile == ntiles - 1u) dir[ntiles] = (uint32_t)kept;
+    }
     emit_tile<ALGO, EF>(sc, job.tile, job.runs, n, k, st, idx, val, T, need, gt_before, eq_before);
 }
 
@@ -1126,6 +1140,11 @@ __device__ __forceinline__ void slow_routes(const GroupView &g, float *st, Paylo
             const uint32_t tile = r0 + p;
             const TileRuns tr = decode_runs(runs_of(tile));
             uint64_t gtb = base_gt + pfx[p], eqb = base_eq + pfx[kRoundTiles + p];
+            if (lane == 0) {
+                uint32_t *dir = payload_directory(hdr, k);
+                dir[tile] = (uint32_t)(gtb + (eqb < need ? eqb : need));
+                if (tile == ntiles - 1u) dir[ntiles] = (uint32_t)k;
+            }
             for (uint32_t f0 = 0; f0 < tr.total; f0 += 64 * kFewRounds) {
                 CandBatch<kFewRounds> c;
                 fetch_batch<kFewRounds, true>(sc, tile, tr, f0, c);
@@ -1405,7 +1424,6 @@ template <int ALGO, bool EF>
 __device__ __forceinline__ void emit_unit(const uint4 &bits, const uint2 &loc, uint32_t cnt, uint32_t v, uint32_t chunk, uint32_t n,
                                           uint64_t k, float *st, uint32_t *idx, float *val, uint32_t T, uint32_t need, uint64_t gt0, uint32_t eq0)
 {
-    const uint32_t lane = threadIdx.x & 63u;
     bool isg[4], ise[4];
     uint32_t mine = 0;                                    // this lane's keys above T | equal to T << 16
 #pragma unroll
@@ -1603,6 +1621,11 @@ __global__ __launch_bounds__(kEmitThreads) void lean_emit_k(uint32_t n, uint32_t
     }
     uint32_t *idx = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(hdr) + kHeaderBytes);
     float *val = reinterpret_cast<float *>(idx + k);
+    if (lane == 0) {
+        uint32_t *dir = payload_directory(hdr, k);
+        dir[tile] = (uint32_t)(gt0 + (eq0 < need ? eq0 : need));
+        if (tile == ntiles - 1u) dir[ntiles] = (uint32_t)k;              // (the selection keeps exactly k)
+    }
     if (tu.total == 0) {
         // the usual tile: no chunk holds more than 64 candidates, and they are all here
 #pragma unroll
@@ -1732,67 +1755,31 @@ void launch_sparse_compress(const LaunchCtx &lc, int algo, const GroupView &g, b
 
 // ---------------------------------------------------------------------------
 // Sparse decompress-and-sum.  Every worker's indices ascend, so a 4096-element
-// output tile owns one contiguous run of each list.  A first kernel records, per
-// worker and tile, where that run starts and ends (one thread per payload entry, no
-// search; entries are stamped with a per-call epoch instead of clearing the table);
-// the second accumulates each tile in LDS, one worker after the other in ascending
-// worker order -- the same order of fp32 additions as a dense sum, since adding
-// the +0 of an absent entry changes nothing -- and writes it once.  No atomics, no
-// pre-zeroed output, bit-reproducible.
+// output tile owns one contiguous run of each list, and the directory that ends a
+// payload says where that run starts and ends.  A block accumulates its tile in LDS,
+// one worker after the other in ascending worker order -- the same order of fp32
+// additions as a dense sum, since adding the +0 of an absent entry changes nothing --
+// and writes it once.  No atomics, no pre-zeroed output, bit-reproducible.
+// (The directory replaced a kernel that recorded the runs of all payloads in per-call
+// tables before this one could start: 5 of 38 us.)
 // ---------------------------------------------------------------------------
-// capped: the payloads hold up to k64 entries (their capacity, repeated in the header), the header says how many
-__global__ __launch_bounds__(kBlock) void sparse_index_k(int algo, uint32_t n, PayloadPtrs pl, int W, uint64_t k64,
-                                                         uint32_t ntiles, uint32_t epoch, uint64_t *tile_first,
-                                                         uint64_t *tile_last, int *status, int capped)
-{
-    const uint32_t w = blockIdx.y;
-    const PayloadHeader *h = reinterpret_cast<const PayloadHeader *>(pl.p[w]);
-    const uint64_t held = h->k;
-    const bool fits = capped ? held <= k64 && h->levels == (uint32_t)k64 : held == k64;
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        if (h->magic != kMagic || h->algo != (uint32_t)algo || h->n != (uint64_t)n || !fits) *status = 1;
-    }
-    const uint32_t k = fits ? (uint32_t)held : 0u;          // a payload that does not fit contributes nothing
-    const uint32_t *idx = reinterpret_cast<const uint32_t *>(pl.p[w] + kHeaderBytes);
-    // four consecutive entries per thread (one 16-byte load: the body of a payload is 16-byte aligned) and the
-    // entries before and after them
-    const uint32_t e0 = (blockIdx.x * kBlock + threadIdx.x) * 4u;
-    if (e0 >= k) return;
-    uint32_t v[6];
-    if (k - e0 >= 4u) {
-        const uint4 x = *reinterpret_cast<const uint4 *>(idx + e0);
-        v[1] = x.x; v[2] = x.y; v[3] = x.z; v[4] = x.w;
-    } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) v[1 + i] = e0 + i < k ? idx[e0 + i] : 0u;
-    }
-    v[0] = e0 > 0u ? idx[e0 - 1] : 0u;
-    v[5] = k - e0 > 4u ? idx[e0 + 4] : 0u;
-    // the first entry of a tile's run records where the run starts, the last one where it ends;
-    // both are stamped with this call's epoch, so tiles without entries need no clearing
-    const uint64_t stamp = (uint64_t)epoch << 32;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const uint32_t e = e0 + i;
-        if (e >= k) break;
-        const uint32_t tile = v[1 + i] >> 12;
-        if (tile >= ntiles) continue;
-        if (e == 0 || (v[i] >> 12) != tile) tile_first[(size_t)w * ntiles + tile] = stamp | e;
-        if (e == k - 1 || (v[2 + i] >> 12) != tile) tile_last[(size_t)w * ntiles + tile] = stamp | (e + 1);
-    }
-}
-
 constexpr int kSparseBatch = 8;    // workers whose entries are in flight together
 // rounds of 256 entries per worker fetched up front (with 4 the kernel needs 74 vector registers and 6 wavefronts
 // fit a SIMD; with 3, 58 and 8: measured 0.7 .. 1.9 us faster, 2 rounds no better)
 constexpr int kSparseRounds = 3;
 
-__global__ __launch_bounds__(kBlock) void sparse_decompress_k(GroupView out, PayloadPtrs pl, int W, float alpha,
-                                                              uint64_t k64, uint32_t ntiles, uint32_t epoch,
-                                                              const uint64_t *tile_first, const uint64_t *tile_last)
+// k64: entries a payload has room for (the exact k, or the capacity when DGC takes its threshold from a sample: the
+// header then says how many are in use and repeats the capacity)
+__global__ __launch_bounds__(kBlock) void sparse_decompress_k(int algo, GroupView out, PayloadPtrs pl, int W, float alpha,
+                                                              uint64_t k64, uint32_t ntiles, int *status, int capped)
 {
     __shared__ float acc[kTile];
     const uint32_t k = (uint32_t)k64;
+    if (blockIdx.x == 0 && (int)threadIdx.x < W) {
+        const PayloadHeader *h = reinterpret_cast<const PayloadHeader *>(pl.p[threadIdx.x]);
+        const bool fits = capped ? h->k <= k64 && h->levels == (uint32_t)k64 : h->k == k64;
+        if (h->magic != kMagic || h->algo != (uint32_t)algo || h->n != (uint64_t)out.n || !fits) *status = 1;
+    }
     const uint32_t tile = my_tile_index();
     const uint32_t tb = tile * (uint32_t)kTile;
     const uint32_t t = threadIdx.x;
@@ -1806,14 +1793,12 @@ __global__ __launch_bounds__(kBlock) void sparse_decompress_k(GroupView out, Pay
             lo[b] = hi[b] = 0;
             if (w0 + b < W) {
                 // block-uniform addresses, kept on the scalar path whatever the compiler makes of the rest
-                const uint64_t f = ld_uniform(tile_first + (size_t)(w0 + b) * ntiles + tile);
-                const uint64_t l = ld_uniform(tile_last + (size_t)(w0 + b) * ntiles + tile);
-                if ((uint32_t)(f >> 32) == epoch && (uint32_t)(l >> 32) == epoch) {      // else: no entry in this tile
-                    lo[b] = (uint32_t)f < k ? (uint32_t)f : k;
-                    hi[b] = (uint32_t)l < k ? (uint32_t)l : k;
-                    // inconsistent payload (indices not ascending): a tile holds at most 4096 entries
-                    if (hi[b] < lo[b] || hi[b] - lo[b] > (uint32_t)kTile) hi[b] = lo[b];
-                }
+                const uint32_t *dir = reinterpret_cast<const uint32_t *>(pl.p[w0 + b] + kHeaderBytes + 8u * k64);
+                const uint32_t f = ld_uniform(dir + tile), l = ld_uniform(dir + tile + 1u);
+                lo[b] = f < k ? f : k;
+                hi[b] = l < k ? l : k;
+                // inconsistent payload (a directory that does not ascend): a tile holds at most 4096 entries
+                if (hi[b] < lo[b] || hi[b] - lo[b] > (uint32_t)kTile) hi[b] = lo[b];
             }
         }
         if (W <= kSparseBatch) {          // most tiles hold no kept entry at all: they are just zero-filled
@@ -1914,18 +1899,12 @@ __global__ __launch_bounds__(kBlock) void sparse_decompress_k(GroupView out, Pay
 }
 
 void launch_sparse_decompress(const LaunchCtx &lc, int algo, const GroupView &out, const PayloadPtrs &pl, int W,
-                              float alpha, uint64_t k, uint32_t epoch, uint64_t *tile_first, uint64_t *tile_last, int *status,
-                              bool capped)
+                              float alpha, uint64_t k, int *status, bool capped)
 {
     if (out.n == 0) return;
     const uint32_t nt = tiles_of(out.n);
-    prof_begin(lc, K_SPARSE_INDEX);
-    MC_LAUNCH(sparse_index_k, dim3((uint32_t)((k + 4 * kBlock - 1) / (4 * kBlock)), W), dim3(kBlock), lc, algo,
-                       out.n, pl, W, k, nt, epoch, tile_first, tile_last, status, capped ? 1 : 0);
-    prof_end(lc, K_SPARSE_INDEX);
     prof_begin(lc, K_SPARSE_DECOMPRESS);
-    MC_LAUNCH(sparse_decompress_k, dim3(nt), dim3(kBlock), lc, out, pl, W, alpha, k, nt, epoch, tile_first,
-                       tile_last);
+    MC_LAUNCH(sparse_decompress_k, dim3(nt), dim3(kBlock), lc, algo, out, pl, W, alpha, k, nt, status, capped ? 1 : 0);
     prof_end(lc, K_SPARSE_DECOMPRESS);
 }
 

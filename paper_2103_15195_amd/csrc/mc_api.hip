@@ -92,7 +92,6 @@ struct mc_ctx {
     std::vector<PtrSlot> slots;
     std::vector<uintptr_t> want;        // the address list of the call in progress (reserved at creation)
     uint64_t clock = 0;
-    uint32_t epoch = 0;                 // stamps the sparse decompress tile table; 0 is never used
     uint32_t sync_blocks = 1;           // blocks of 1024 threads the device holds at once for sure: one per compute unit
     Profiler prof;
 };
@@ -131,7 +130,7 @@ void prof_end(const LaunchCtx &lc, int id)
 static const char *kKernelNames[K_COUNT] = {
     "upload_ptrs", "efsign_compress", "scalar_finalize", "accum_reduce", "qsgd_encode", "tern_encode",
     "fp16_compress", "dense_decompress", "sparse_accum", "sparse_seed", "cand_hist2", "cand_hist3", "cand_count",
-    "cand_emit", "sparse_index", "sparse_decompress", "state_convert", "lean_select", "lean_emit", "sparse_slow"};
+    "cand_emit", "sparse_decompress", "state_convert", "lean_select", "lean_emit", "sparse_slow"};
 
 static void prof_drain(Profiler &p)
 {
@@ -341,8 +340,8 @@ int mc_ctx_destroy(mc_ctx *ctx)
     }
     if (ctx->d_partial) (void)hipFree(ctx->d_partial);
     void *sparse_bufs[] = {ctx->sparse.hist, ctx->sparse.sel, ctx->d_hints, ctx->sparse.cand_bits, ctx->sparse.cand_loc,
-                           ctx->sparse.tile_runs, ctx->sparse.tile_cnt, ctx->sparse.blk_cnt, ctx->sparse.tile_first,
-                           ctx->sparse.tile_last, ctx->sparse.ulist, ctx->sparse.ucount, ctx->sparse.tile_base, ctx->sparse.sync};
+                           ctx->sparse.tile_runs, ctx->sparse.tile_cnt, ctx->sparse.blk_cnt, ctx->sparse.ulist, ctx->sparse.ucount,
+                           ctx->sparse.sync};
     for (void *b : sparse_bufs) if (b) (void)hipFree(b);
     if (ctx->d_status) (void)hipFree(ctx->d_status);
     if (switched) (void)hipSetDevice(prev);
@@ -420,7 +419,6 @@ int mc_ctx_create(mc_ctx **out, const mc_config *cfg, const int64_t *numel, int3
             SparseScratch &sp = ctx->sparse;
             const size_t hist_bytes = kHistWords * sizeof(uint32_t);
             const size_t chunks = tiles * kWavesPerBlock, slots = chunks * kChunk;
-            const size_t off_words = (size_t)kMaxWorkers * tiles;
             if (hipMalloc(&sp.hist, hist_bytes) != hipSuccess || hipMalloc(&sp.sel, 4 * sizeof(SelectState)) != hipSuccess ||
                 hipMalloc(&ctx->d_hints, (size_t)y * kHintWorkers * kHintWords * sizeof(uint32_t)) != hipSuccess ||
                 hipMalloc(&sp.cand_bits, slots * sizeof(uint32_t)) != hipSuccess ||
@@ -428,17 +426,12 @@ int mc_ctx_create(mc_ctx **out, const mc_config *cfg, const int64_t *numel, int3
                 hipMalloc(&sp.tile_runs, tiles * sizeof(uint64_t)) != hipSuccess ||
                 hipMalloc(&sp.tile_cnt, tiles * sizeof(uint32_t)) != hipSuccess ||
                 hipMalloc(&sp.blk_cnt, (tiles + kWavesPerBlock - 1) / kWavesPerBlock * sizeof(uint32_t)) != hipSuccess ||
-                hipMalloc(&sp.tile_first, off_words * sizeof(uint64_t)) != hipSuccess ||
-                hipMalloc(&sp.tile_last, off_words * sizeof(uint64_t)) != hipSuccess ||
                 hipMalloc(&sp.ulist, (size_t)kUSub * kUCap * sizeof(UEntry)) != hipSuccess ||
                 hipMalloc(&sp.ucount, (size_t)kUSub * kUCountStride * sizeof(uint32_t)) != hipSuccess ||
-                hipMalloc(&sp.tile_base, tiles * sizeof(uint2)) != hipSuccess ||
                 hipMalloc(&sp.sync, 64 * sizeof(uint32_t)) != hipSuccess) rc = MC_ERR_ALLOC;
             else if (hipMemset(sp.hist, 0, hist_bytes) != hipSuccess || hipMemset(sp.sel, 0, 4 * sizeof(SelectState)) != hipSuccess ||
                      hipMemset(ctx->d_hints, 0, (size_t)y * kHintWorkers * kHintWords * sizeof(uint32_t)) != hipSuccess ||
                      hipMemset(sp.tile_runs, 0, tiles * sizeof(uint64_t)) != hipSuccess ||
-                     hipMemset(sp.tile_first, 0, off_words * sizeof(uint64_t)) != hipSuccess ||
-                     hipMemset(sp.tile_last, 0, off_words * sizeof(uint64_t)) != hipSuccess ||
                      hipMemset(sp.ucount, 0, (size_t)kUSub * kUCountStride * sizeof(uint32_t)) != hipSuccess ||
                      hipMemset(sp.sync, 0, 64 * sizeof(uint32_t)) != hipSuccess) rc = MC_ERR_DEVICE;
             int cus = 0;
@@ -492,7 +485,7 @@ size_t mc_payload_bytes(const mc_ctx *ctx, int32_t group)
     case MC_ALGO_TERNGRAD: return kHeaderBytes + 8 * words;
     case MC_ALGO_QSGD: return kHeaderBytes + (n + 3) / 4 * 4;
     case MC_ALGO_FP16: return kHeaderBytes + (2 * n + 3) / 4 * 4;
-    default: return kHeaderBytes + 8 * g->k;
+    default: return kHeaderBytes + 8 * g->k + (n ? 4 * ((n + kTile - 1) / kTile + 1) : 0);      // index and value lists, directory
     }
 }
 
@@ -666,9 +659,7 @@ int mc_decompress_sum(mc_ctx *ctx, int32_t group, const void *const *payloads, i
     (void)hipGetLastError();
     GroupView gv = group_view(ctx, lc, group, G, reinterpret_cast<const void *const *>(out_ptrs));
     const mc_config &cfg = ctx->cfg;
-    if (is_sparse(cfg.algo) && ++ctx->epoch == 0) ctx->epoch = 1;
-    if (is_sparse(cfg.algo)) launch_sparse_decompress(lc, cfg.algo, gv, pl, W, alpha, G.k, ctx->epoch, ctx->sparse.tile_first,
-                                                    ctx->sparse.tile_last, ctx->d_status, cfg.dgc_sample_ppm != 0);
+    if (is_sparse(cfg.algo)) launch_sparse_decompress(lc, cfg.algo, gv, pl, W, alpha, G.k, ctx->d_status, cfg.dgc_sample_ppm != 0);
     else {
         const uint32_t levels = cfg.algo == MC_ALGO_QSGD ? (1u << (cfg.qsgd_bits - 1)) - 1u : 0u;
         launch_dense_decompress(lc, cfg.algo, gv, pl, W, alpha, levels, ctx->d_status);

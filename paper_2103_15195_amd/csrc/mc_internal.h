@@ -49,7 +49,7 @@ struct SelectState {
 enum KernelId {
     K_UPLOAD = 0, K_EFSIGN_COMPRESS, K_SCALAR_FINALIZE, K_ACCUM_REDUCE, K_QSGD_ENCODE, K_TERN_ENCODE,
     K_FP16_COMPRESS, K_DENSE_DECOMPRESS, K_SPARSE_ACCUM, K_SPARSE_SEED, K_CAND_HIST2, K_CAND_HIST3, K_CAND_COUNT,
-    K_CAND_EMIT, K_SPARSE_INDEX, K_SPARSE_DECOMPRESS, K_STATE_CONVERT, K_LEAN_SELECT, K_LEAN_EMIT, K_SPARSE_SLOW, K_COUNT
+    K_CAND_EMIT, K_SPARSE_DECOMPRESS, K_STATE_CONVERT, K_LEAN_SELECT, K_LEAN_EMIT, K_SPARSE_SLOW, K_COUNT
 };
 
 // reduction kinds of the two-pass quantizers
@@ -117,10 +117,8 @@ struct SparseScratch {
     uint64_t *tile_runs;   // candidates of the four chunks of every tile, 16 bits each
     uint32_t *tile_cnt;    // per tile: candidates above (low 16 bits) / equal to (high 16 bits) the threshold
     uint32_t *blk_cnt;     // the same per block of four tiles
-    uint64_t *tile_first, *tile_last;   // decompress: per worker and 4096-element tile, (epoch << 32 | entry) of its run
     UEntry *ulist;         // kUSub sublists of kUCap entries: the candidates in the threshold's window bin
     uint32_t *ucount;      // their lengths, kUCountStride words apart; cleared by the streaming pass of the next call
-    uint2 *tile_base;      // lean route: per tile, keys above / equal to the threshold before it (resolve kernel -> emit kernel)
     uint32_t *sync;        // [0]: arrivals at the grid-wide barriers of the slow routes (cleared by the select kernel); [32..36): calls per route
 };
 // sync_blocks: how many blocks of 1024 threads the device surely holds at once (one per compute unit): the slow routes
@@ -129,7 +127,6 @@ void launch_sparse_compress(const LaunchCtx &lc, int algo, const GroupView &g, b
                             uint64_t k, PayloadHeader *hdr, const SparseScratch &sc, uint64_t seed, uint32_t worker, uint32_t iter_lo,
                             uint32_t sample_stride, uint32_t sample_first, uint64_t sample_need, uint32_t sync_blocks, int *status);
 void launch_sparse_decompress(const LaunchCtx &lc, int algo, const GroupView &out, const PayloadPtrs &pl, int W,
-                              float alpha, uint64_t k, uint32_t epoch, uint64_t *tile_first, uint64_t *tile_last,
-                              int *status, bool capped);
+                              float alpha, uint64_t k, int *status, bool capped);
 
 }  // namespace mc

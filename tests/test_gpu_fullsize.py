@@ -52,13 +52,7 @@ def synthetic_sparse_payloads(algo_id, flats, lo, n, k, seed):
     for w, flat in enumerate(flats):
         x = flat[lo:lo + n]
         idx = np.sort(np.argpartition(np.abs(x), n - k)[n - k:]).astype(np.uint32)
-        pay = np.zeros(O.HDR + 8 * k, np.uint8)
-        pay[0:4] = np.frombuffer(np.uint32(0x3150434D).tobytes(), np.uint8)
-        pay[4:8] = np.frombuffer(np.uint32(algo_id).tobytes(), np.uint8)
-        pay[8:16] = np.frombuffer(np.uint64(n).tobytes(), np.uint8)
-        pay[16:24] = np.frombuffer(np.uint64(k).tobytes(), np.uint8)
-        pay[O.HDR:O.HDR + 4 * k] = idx.view(np.uint8)
-        pay[O.HDR + 4 * k:] = (x[idx] * np.float32(1 + 0.25 * w)).astype(np.float32).view(np.uint8)
+        pay = O.with_directory(algo_id, n, idx, (x[idx] * np.float32(1 + 0.25 * w)).astype(np.float32))
         pays.append(pay)
     return pays
 

@@ -127,6 +127,11 @@ def check_payload(algo, pay, hdr, opay_of, k_l):
         want_idx = (on_device(idx_l.astype(np.int64))[None, :] + (torch.arange(REPS, device=H.DEV, dtype=torch.int64) * L)[:, None])
         assert torch.equal(got_idx.view(REPS, k_l), want_idx), f"{algo}: indices differ"
         assert periods_equal(body[4 * k:8 * k], val_l), f"{algo}: values differ"
+        # the directory that ends the payload: entries of the (ascending) index list below each multiple of 4096
+        spans = (N + 4095) // 4096
+        got_dir = body[8 * k:8 * k + 4 * (spans + 1)].view(torch.int32).to(torch.int64) & 0xFFFFFFFF
+        want_dir = torch.searchsorted(got_idx.contiguous(), torch.arange(spans + 1, device=H.DEV, dtype=torch.int64) * 4096)
+        assert torch.equal(got_dir, want_dir), f"{algo}: directory differs"
         return
     if algo == "terngrad":
         nb, lb = N // 8, L // 8

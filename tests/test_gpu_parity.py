@@ -470,7 +470,7 @@ def test_selection_routes_are_all_taken_and_exact(algo):
         ctx.mc_compress(0, 5, it, H.device_tensors(g, tensors), st, pay)
         got = ctx.mc_last_select_route()
         op, _ = O.compress(ocfg, g, ost, group_off=0, worker=5, it=it)
-        T = int((op[O.HDR + 4 * k:].view(np.uint32) & 0x7FFFFFFF).min())          # k-th largest key
+        T = int((O.sparse_view(op)[1].view(np.uint32) & 0x7FFFFFFF).min())           # k-th largest key
         want = B.MC_SELECT_REFILL if T < hint else B.MC_SELECT_FAST if T - hint < 2047 * 2048 else B.MC_SELECT_ABOVE
         assert got == want, f"call {it}: route {got}, expected {want} (T {T:#x}, hint {hint:#x})"
         hint = T - (3 << 19) if T > (3 << 19) else 0
