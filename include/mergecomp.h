@@ -21,10 +21,8 @@
  *     (one stream, or streams the caller has ordered with events): the context
  *     scratch and its cached pointer tables are shared between calls.
  *     The calls are not meant to be recorded into a HIP graph: iteration and
- *     worker numbers, the tensor addresses and a per-call stamp of the sparse
- *     decompress travel as kernel arguments, so a replay would repeat the
- *     random stream of the recorded call, and a replayed sparse decompress
- *     would take tile entries of the previous replay for its own.
+ *     worker numbers and the tensor addresses travel as kernel arguments, so a
+ *     replay would repeat the random stream of the recorded call.
  *   - A group is addressed as the flat fp32 vector obtained by concatenating
  *     its tensors in list order, each tensor contiguous; nothing is copied to
  *     build it, kernels walk a segment table.  Flat index i of group j has the
@@ -177,8 +175,8 @@ int mc_partition_search(const int64_t *numel, const double *bwd_time, int32_t n_
  *   every algorithm   24 T bytes of reduction partials; up to 64 cached tensor-address lists with one
  *                     8-byte address per 1024 elements each (32 T bytes per list, 256 MiB at most in all)
  *   sparsifiers       6 bytes per element of the largest group for candidate values and positions
- *                     (24576 T; 153 MB for a 25.6 M element group), 1024 T + 16 T bytes of per-worker tile
- *                     tables for the decompress, histograms and counters of about 100 KB
+ *                     (24576 T; 153 MB for a 25.6 M element group), 12.25 T bytes of per-tile counts, 2 MiB for the
+ *                     list of keys in the threshold's histogram bin, histograms and counters of about 100 KB
  */
 int mc_ctx_create(mc_ctx **out, const mc_config *cfg, const int64_t *numel, int32_t n_tensors,
                   const int32_t *bounds, int32_t y);

@@ -195,3 +195,33 @@ def split(wl: Workload, flat: np.ndarray) -> List[np.ndarray]:
 def gradients(wl: Workload, worker: int, it: int, shared_fraction: float = 0.0) -> List[np.ndarray]:
     """One worker's fp32 gradient tensors (flattened, list order = wl.shapes)."""
     return split(wl, gradients_flat(wl, worker, it, shared_fraction))
+
+
+# --------------------------------------------------------------------------
+# inputs of the partition search (Section 4.3): a back-propagation timeline and
+# the communication cost, from the figures the paper prints
+# --------------------------------------------------------------------------
+PAPER_ITERATION_S = 64e-3        # Section 3.3: one ResNet50 / CIFAR10 iteration on a V100
+PAPER_COMM_S = 66e-3             # Section 3.3: communicating its 102 MB of fp32 gradients between two V100 over PCIe
+PAPER_MESSAGE_S = 50e-6          # fixed cost per message (a launch plus a PCIe round trip; the paper gives B_g no value)
+SENT_BYTES_PER_ELEM = {"fp16": 2.0, "qsgd": 1.0, "terngrad": 0.25, "efsign": 0.125, "signsgd": 0.125, "signum": 0.125,
+                       "onebit": 0.125}
+
+
+def sent_bytes_per_elem(algo: str, ratio_ppm: int) -> float:
+    """Bytes a compressor sends per gradient element (Table 1's payloads; a sparsifier sends an index and a value per
+    kept entry)."""
+    return SENT_BYTES_PER_ELEM.get(algo, 8.0 * ratio_ppm * 1e-6)
+
+
+def iteration_timeline(numel: Sequence[int], B_h_s: float, gamma_h_s: float, sent_bytes: float):
+    """Inputs of the iteration-time model F (Section 4.3) for a tensor list.
+
+    Returns (bwd, (fwd, B_h, gamma_h, B_g, gamma_g)): the forward pass takes a third of the paper's iteration and the
+    back-propagation of a tensor a share of the rest proportional to its size; g(x) is linear (Assumption 5), its slope
+    the paper's PCIe figure scaled to `sent_bytes` per element; h(x) = B_h_s + gamma_h_s x is the caller's (measured).
+    """
+    D = float(sum(int(m) for m in numel))
+    bwd = [(2.0 / 3.0) * PAPER_ITERATION_S * (int(m) / D) for m in numel]
+    gamma_g = PAPER_COMM_S / 25557032.0 * (sent_bytes / 4.0)
+    return bwd, (PAPER_ITERATION_S / 3.0, float(B_h_s), float(gamma_h_s), PAPER_MESSAGE_S, gamma_g)

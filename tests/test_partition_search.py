@@ -192,6 +192,25 @@ def test_library_search_on_a_model_sized_list():
     assert F <= B.mc_partition_cost(numel, bwd, bm, B.mc_partition(numel, y)) + 1e-15
 
 
+@pytest.mark.parametrize("algo,ppm,B_h,gD", [("efsign", 0, 4e-6, 54e-6), ("topk", 10000, 14e-6, 66e-6), ("dgc", 1000, 14e-6, 85e-6)])
+def test_search_on_the_benchmarks_timeline_matches_the_bruteforce(algo, ppm, B_h, gD):
+    """The inputs the benchmark feeds Algorithm 2 with (the paper's iteration and PCIe figures, an h(x) of the size the GPU
+    measures), on the last 24 tensors of the ResNet-50 list, where the oracle can still enumerate every partition."""
+    from paper_2103_15195_amd import workloads as WL
+    numel = WL.workload(2).numel.tolist()[-24:]
+    D = sum(numel)
+    bwd, mp = WL.iteration_timeline(numel, B_h, gD / D, WL.sent_bytes_per_elem(algo, ppm))
+    assert sum(bwd) == pytest.approx(2.0 / 3.0 * 64e-3) and mp[0] == pytest.approx(64e-3 / 3.0)
+    om, bm = O.TimeModel(*mp), B.McTimeModel(*mp)
+    for Y, alpha in [(4, 0.01), (4, 0.0), (3, 1e-4)]:
+        ob, oF = O.partition_search(numel, bwd, om, Y, alpha)
+        gb, gF = B.mc_partition_search(numel, bwd, bm, Y, alpha)
+        assert gF == pytest.approx(oF, rel=1e-12) and len(gb) == len(ob)
+        assert O.partition_cost(numel, bwd, om, gb) == pytest.approx(oF, rel=1e-12)
+        for pol in (B.MC_PART_EVEN_ELEMS, B.MC_PART_EVEN_COUNT):          # what the search returns is no worse than the naive splits
+            assert gF <= B.mc_partition_cost(numel, bwd, bm, B.mc_partition(numel, len(gb) - 1, pol)) * (1 + 1e-12)
+
+
 def test_library_argument_checks():
     _, bm = model(1.0)
     L = B.lib()
