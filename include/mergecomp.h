@@ -172,7 +172,7 @@ int mc_partition_search(const int64_t *numel, const double *bwd_time, int32_t n_
  * segment tables and scratch for every group, and reserves the host-side lists the
  * hot calls fill, so that those allocate nothing.
  * Device memory held by a context, with T = tiles of 4096 elements of its largest group:
- *   every algorithm   24 T bytes of reduction partials; up to 64 cached tensor-address lists with one
+ *   every algorithm   24 T bytes of reduction partials; up to 256 cached tensor-address lists with one
  *                     8-byte address per 1024 elements each (32 T bytes per list, 256 MiB at most in all)
  *   sparsifiers       6 bytes per element of the largest group for candidate values and positions
  *                     (24576 T; 153 MB for a 25.6 M element group), 12.25 T bytes of per-tile counts, 2 MiB for the

@@ -16,7 +16,7 @@ using namespace mc;
 namespace {
 
 constexpr uint64_t kMaxGroupElems = (1ull << 32) - (1ull << 24);
-constexpr int kPtrSlots = 64;            // cached device copies of per-call tensor address lists
+constexpr int kPtrSlots = 256;           // cached device copies of per-call tensor address lists
 
 struct Group {
     int32_t t0 = 0, t1 = 0;              // tensor range [t0, t1) of the model's list

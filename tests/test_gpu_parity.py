@@ -314,6 +314,25 @@ def test_state_calls_on_a_stateless_algorithm_touch_nothing():
     ctx.close()
 
 
+def test_more_address_lists_than_the_context_caches():
+    """A context keeps device copies of the tensor-address lists it has seen (256 of them); 300 different lists, then the
+    first ones again: every call must read the tensors it was given, also after its list's copy was replaced."""
+    numel = [1500, 700, 3000]                          # three tensors, one group: chunks that straddle tensors too
+    n = sum(numel)
+    ctx = B.Context("fp16", numel, [0, 3], use_ef=0)
+    ocfg = O.Config(H.ALGOS["fp16"], use_ef=0)
+    rng = np.random.default_rng(5)
+    flats = [rng.standard_normal(n).astype(np.float32) for _ in range(300)]
+    lists = [H.device_tensors(f, numel) for f in flats]
+    pay = torch.zeros(ctx.payload_bytes(0), dtype=torch.uint8, device=H.DEV)
+    for i in list(range(300)) + [0, 1, 2, 299, 150]:
+        ctx.mc_compress(0, 0, i, lists[i], None, pay)
+        opay, _ = O.compress(ocfg, flats[i], None)
+        assert np.array_equal(pay.cpu().numpy(), opay), i
+    assert ctx.mc_last_device_status() == B.MC_OK
+    ctx.close()
+
+
 def test_payload_mismatch_is_reported_not_fatal():
     n = 5000
     ctx = B.Context("efsign", [n], [0, 1])
