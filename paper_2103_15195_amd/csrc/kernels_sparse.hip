@@ -801,7 +801,6 @@ __global__ __launch_bounds__(kBlock) void cand_emit_k(uint32_t n, uint32_t ntile
 constexpr int kSelThreads = 1024, kSelWaves = kSelThreads / 64;      // select: 16 tiles per block (the window is read once per block)
 constexpr int kEmitThreads = kBlock, kEmitWaves = kWavesPerBlock;    // emit: 4 tiles per block
 constexpr int kSyncArrive = 0, kSyncRoutes = 32, kSyncLastBin = 40, kSyncLastCands = 41;     // words of SparseScratch::sync (mc_api.hip reads the last three)
-constexpr int kFewRounds = 4;          // a tile with at most 256 candidates is fetched whole
 
 struct TileRuns { uint32_t r0, r1, r2, total; };       // running sums of the candidates of a tile's four chunks
 __device__ __forceinline__ TileRuns decode_runs(uint64_t runs)
@@ -843,20 +842,22 @@ __device__ __forceinline__ void fetch_batch(const SparseScratch &sc, uint32_t ti
     }
 }
 
-// Walk of a tile's candidates, 256 at a time (the slow routes: one memory latency per batch).  body(valid, bits, at).
-template <bool WITH_AT, typename Body>
+// Walk of a tile's candidates, 64 ROUNDS at a time (the slow routes: one memory latency per batch, so a crowded
+// tile wants large batches).  body(valid, bits, at).
+template <bool WITH_AT, int ROUNDS, typename Body>
 __device__ __forceinline__ void walk_small(const SparseScratch &sc, uint32_t tile, uint64_t runs, Body body)
 {
     const TileRuns r = decode_runs(runs);
     const uint32_t lane = threadIdx.x & 63u;
-    for (uint32_t f0 = 0; f0 < r.total; f0 += 64 * kFewRounds) {
-        CandBatch<kFewRounds> c;
-        fetch_batch<kFewRounds, WITH_AT>(sc, tile, r, f0, c);
+    for (uint32_t f0 = 0; f0 < r.total; f0 += 64 * ROUNDS) {
+        CandBatch<ROUNDS> c;
+        fetch_batch<ROUNDS, WITH_AT>(sc, tile, r, f0, c);
 #pragma unroll
-        for (int u = 0; u < kFewRounds; ++u)
+        for (int u = 0; u < ROUNDS; ++u)
             if (f0 + 64 * u < r.total) body(f0 + 64 * u + lane < r.total, c.bits[u], c.at[u]);
     }
 }
+constexpr int kWalkRounds = 16, kCompactRounds = 8;      // candidates in flight per wavefront in the slow routes: 1024 when only read, 512 when placed
 
 // Select.  The keys inside the threshold's bin [lo, lo + 2048) -- rarely more than a few per tile -- are collected
 // in a buffer of the wavefront's own in LDS and appended to sublist `sub` with one atomic add per tile (per 64
@@ -875,31 +876,6 @@ __device__ __forceinline__ void flush_members(const SparseScratch &sc, MemberBuf
     if (lane < m.held && base + lane < kUCap) sc.ulist[(size_t)sub * kUCap + base + lane] = m.buf[lane];   // (always in range: the bin holds at most kUCap keys)
     __builtin_amdgcn_wave_barrier();
     m.held = 0u;
-}
-
-// One batch: counts the keys above the bin, buffers those inside it.
-template <int ROUNDS>
-__device__ __forceinline__ uint32_t select_apply(const SparseScratch &sc, const CandBatch<ROUNDS> &c, uint32_t total, uint32_t f0,
-                                                 uint32_t lo, uint32_t sub, MemberBuf &m)
-{
-    const uint32_t lane = threadIdx.x & 63u;
-    uint32_t above = 0;
-#pragma unroll
-    for (int u = 0; u < ROUNDS; ++u) {
-        if (f0 + 64 * u >= total) break;
-        const uint32_t key = c.bits[u] & 0x7FFFFFFFu;
-        const bool reach = f0 + 64 * u + lane < total && key >= lo;
-        const bool inside = reach && key - lo < (1u << kWindowShift);
-        const uint64_t mb = __builtin_amdgcn_ballot_w64(inside);
-        above += __popcll(__builtin_amdgcn_ballot_w64(reach && key - lo >= (1u << kWindowShift)));
-        if (mb) {
-            const uint32_t cnt = __popcll(mb);
-            if (m.held + cnt > (uint32_t)kMemberBuf) flush_members(sc, m, sub);
-            if (inside) { UEntry e; e.idx = c.at[u]; e.bits = c.bits[u]; m.buf[m.held + lanes_below(mb)] = e; }
-            m.held += cnt;
-        }
-    }
-    return above;
 }
 
 // Emit, one batch: a candidate is kept if its key is above T, or equal to T and among the first `need` such keys in
@@ -959,10 +935,13 @@ __device__ __forceinline__ bool grid_barrier(uint32_t *arrive, uint32_t blocks, 
         __hip_atomic_fetch_add(arrive, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
         const uint32_t target = round * blocks;
         uint32_t spins = 0;
-        while (__hip_atomic_load(arrive, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < target) {
-            __builtin_amdgcn_s_sleep(16);
+        // polled without acquire semantics: an acquire at agent scope invalidates the die's L2, and two hundred waiting
+        // blocks doing that every few hundred cycles starve the blocks still at work (phases of 60-120 us instead of 10)
+        while (__hip_atomic_load(arrive, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+            __builtin_amdgcn_s_sleep(32);
             if (++spins > (1u << 21)) { *dead = 1u; *status = 2; break; }
         }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     }
     __syncthreads();
     return *dead == 0u;
@@ -1011,7 +990,7 @@ __device__ __forceinline__ void slow_routes(const GroupView &g, float *st, Paylo
         // ---- level 1: bits 30..20 of key - lo
         if (!uniform) {
             for (uint32_t tile = gw; tile < ntiles; tile += nw)
-                walk_small<false>(sc, tile, runs_of(tile), [&](bool valid, uint32_t bits, uint32_t) {
+                walk_small<false, kWalkRounds>(sc, tile, runs_of(tile), [&](bool valid, uint32_t bits, uint32_t) {
                     const uint32_t key = bits & 0x7FFFFFFFu;
                     if (valid && key >= lo) atomicAdd(&hist[(key - lo) >> 20], 1u);
                 });
@@ -1054,7 +1033,7 @@ __device__ __forceinline__ void slow_routes(const GroupView &g, float *st, Paylo
         for (int b = t; b < kBins2; b += kSelThreads) hist[b] = 0u;
         __syncthreads();
         for (uint32_t tile = gw; tile < ntiles; tile += nw)
-            walk_small<false>(sc, tile, runs_of(tile), [&](bool valid, uint32_t bits, uint32_t) {
+            walk_small<false, kWalkRounds>(sc, tile, runs_of(tile), [&](bool valid, uint32_t bits, uint32_t) {
                 const uint32_t key = bits & 0x7FFFFFFFu;
                 if (valid && key >= lo && key - lo < (1u << 20)) atomicAdd(&hist[(key - lo) >> 10], 1u);
             });
@@ -1070,7 +1049,7 @@ __device__ __forceinline__ void slow_routes(const GroupView &g, float *st, Paylo
     // ---- level 3: the bits still open (10 after level 2, the 11 of a window bin otherwise)
     const uint32_t open = (mode & kModeFast) ? 1u << kWindowShift : 1u << 10;
     for (uint32_t tile = gw; tile < ntiles; tile += nw)
-        walk_small<false>(sc, tile, runs_of(tile), [&](bool valid, uint32_t bits, uint32_t) {
+        walk_small<false, kWalkRounds>(sc, tile, runs_of(tile), [&](bool valid, uint32_t bits, uint32_t) {
             const uint32_t key = bits & 0x7FFFFFFFu;
             if (valid && key >= lo && key - lo < open) atomicAdd(&hist[key - lo], 1u);
         });
@@ -1083,7 +1062,7 @@ __device__ __forceinline__ void slow_routes(const GroupView &g, float *st, Paylo
     // ---- kept candidates per tile
     for (uint32_t tile = gw; tile < ntiles; tile += nw) {
         uint32_t ngt = 0, neq = 0;
-        walk_small<false>(sc, tile, runs_of(tile), [&](bool valid, uint32_t bits, uint32_t) {
+        walk_small<false, kWalkRounds>(sc, tile, runs_of(tile), [&](bool valid, uint32_t bits, uint32_t) {
             const uint32_t key = bits & 0x7FFFFFFFu;
             ngt += __popcll(__builtin_amdgcn_ballot_w64(valid && key > T));
             neq += __popcll(__builtin_amdgcn_ballot_w64(valid && key == T));
@@ -1145,10 +1124,10 @@ __device__ __forceinline__ void slow_routes(const GroupView &g, float *st, Paylo
                 dir[tile] = (uint32_t)(gtb + (eqb < need ? eqb : need));
                 if (tile == ntiles - 1u) dir[ntiles] = (uint32_t)k;
             }
-            for (uint32_t f0 = 0; f0 < tr.total; f0 += 64 * kFewRounds) {
-                CandBatch<kFewRounds> c;
-                fetch_batch<kFewRounds, true>(sc, tile, tr, f0, c);
-                emit_apply<ALGO, EF, kFewRounds>(c, tr.total, f0, n, k, st, idx, val, T, need, gtb, eqb);
+            for (uint32_t f0 = 0; f0 < tr.total; f0 += 64 * kCompactRounds) {
+                CandBatch<kCompactRounds> c;
+                fetch_batch<kCompactRounds, true>(sc, tile, tr, f0, c);
+                emit_apply<ALGO, EF, kCompactRounds>(c, tr.total, f0, n, k, st, idx, val, T, need, gtb, eqb);
             }
         }
         base_gt += tg; base_eq += te;
