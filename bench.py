@@ -77,7 +77,10 @@ def parse():
                     help="skip the layer-wise comparison (y = number of tensors: one compress / decompress per tensor)")
     ap.add_argument("--no-other-configs", action="store_true", help="skip the ResNet-101 (W = 16) and Mask R-CNN secondary entries")
     ap.add_argument("--no-extras", action="store_true", help="skip the static-gradient line and the cold-call timing")
-    ap.add_argument("--algos", default="efsign,topk")
+    ap.add_argument("--algos", default=None, help="bench lines, comma separated (default: efsign,topk; efsign,topk-0.1 with --config 3)")
+    ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4],
+                    help="benchmark configuration of the main run: 2 ResNet-50 (W = 8, the headline), 3 ResNet-101 (W = 16, Top-k 0.1 %%), "
+                         "4 Mask R-CNN (W = 8); 3 and 4 are for profiling, the default run reports them under other_configs")
     ap.add_argument("--grad-layout", default="separate", choices=["separate", "views"],
                     help="separate: every gradient tensor its own allocation (a model's .grad tensors); views: the "
                          "tensors of a worker are views into one buffer (a bucketed gradient store)")
@@ -231,10 +234,12 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     B.lib()          # fails loudly if the HIP library has not been built
-    wl = WL.workload(2)
+    wl = WL.workload(args.config)
     numel = wl.numel.tolist()
     D, W = wl.total, wl.workers
-    algos = args.algos.split(",")
+    algos = (args.algos or ("efsign,topk-0.1" if args.config == 3 else "efsign,topk")).split(",")
+    if args.config != 2:
+        args.no_other_configs = True
     V = max(1, args.fresh)
 
     flats = [[WL.gradients_flat(wl, w, v) for v in range(V)] for w in range(W)]
@@ -304,7 +309,7 @@ def main():
     kern_us = 1e3 * prof["total_ms"] / prof["launches"]
     n_group = max(benches[dom_algo].ctx.group_numel(j) for j in range(args.y))
     launches_per_step = prof["launches"] / args.steps
-    alg_bytes = ALGO_BYTES[dom_kernel](D, W, 0.01) / launches_per_step
+    alg_bytes = ALGO_BYTES[dom_kernel](D, W, algo_config(dom_algo)[1] * 1e-6) / launches_per_step
     achieved = alg_bytes / kern_us * 1e-3      # GB/s
     grad_bytes = 4.0 * D * len(algos)
     value = grad_bytes / sec * 1e-9
@@ -491,14 +496,15 @@ def main():
                            "sample": f"one step of all {W} workers per algorithm: the {W} compress calls on {min(T, W)} threads, then one "
                                      f"decompress-sum over their payloads; {units} units, {t_par:.1f} s"}}
 
-    traffic = read_traffic()
+    traffic = read_traffic() if args.config == 2 else {}          # the file holds the ResNet-50 run's counters
     result = {
         "metric": "compress+decompress GB/s of fp32 gradient (EF-Sign, Top-k 1%) vs HBM peak",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "resnet50-shaped gradients, 161 tensors, 25557032 fp32, per-tensor std log-uniform [1e-4,1e-1]",
-                   "y": args.y, "workers": W, "grad_layout": args.grad_layout, "algorithms": algos, "topk_ratio_ppm": 10000,
+        "config": {"workload": f"{wl.name}-shaped gradients, {len(numel)} tensors, {D} fp32, "
+                               + ("Student-t(3) values, " if args.config == 4 else "") + "per-tensor std log-uniform [1e-4,1e-1]",
+                   "y": args.y, "workers": W, "grad_layout": args.grad_layout, "algorithms": algos, "topk_ratio_ppm": 1000 if args.config == 3 else 10000,
                    "gradients_per_worker": V,
                    "step": "per algorithm: one worker's mc_compress of its next gradient + one mc_decompress_sum over W payloads"},
         "roofline": {"bound": "hbm", "kernel": f"{dom_algo}:{dom_kernel}", "achieved": achieved, "peak": HBM_PEAK_GBS,

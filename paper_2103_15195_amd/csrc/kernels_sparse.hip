@@ -1764,6 +1764,24 @@ __global__ __launch_bounds__(kBlock) void sparse_decompress_k(int algo, GroupVie
     const uint32_t t = threadIdx.x;
     const Chunk c = my_chunk(out.n, tile);
     const uintptr_t entry = chunk_entry(out, c);        // needed last, asked for first: overlaps with the table loads
+    if (W > kSparseBatch) {
+        // more workers than one batch: the tiles that no worker has an entry for are found first, over all batches
+        // (the per-batch test below only sees its own eight), and zero-filled as with one batch
+        bool any = false;
+        for (int w = 0; w < W; ++w) {
+            const uint32_t *dir = reinterpret_cast<const uint32_t *>(pl.p[w] + kHeaderBytes + 8u * k64);
+            const uint32_t f = ld_uniform(dir + tile), l = ld_uniform(dir + tile + 1u);
+            any = any || (l < k ? l : k) > (f < k ? f : k);
+        }
+        if (!any) {
+            if (c.base >= out.n) return;
+            float z[kSteps];
+#pragma unroll
+            for (int j = 0; j < kSteps; ++j) z[j] = alpha * 0.0f;
+            store_seg_rot(out, c, z, entry, chunk_rotation(entry));
+            return;
+        }
+    }
     for (int w0 = 0; w0 < W; w0 += kSparseBatch) {
         // issue the loads of a batch of workers before the first LDS update
         uint32_t lo[kSparseBatch], hi[kSparseBatch];

@@ -7,7 +7,7 @@ S.csv is the kernel_stats file of a `rocprofv3 --kernel-trace --stats --output-f
 counter_collection files of two `--pmc` runs (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch) of bench.py with
 --calibrate-copy, which adds plain 256 MiB device copies: what the counters read for those gives the factor that turns
 the counters into bytes.  The traffic file holds one line per library kernel: profiler slot name, HBM bytes per launch
-(read + write), read bytes, write bytes.  Optional --counters C.csv adds a table of further per-dispatch counters.
+(read + write), read bytes, write bytes.  Every --counters C.csv adds a table of further per-dispatch counters.
 """
 from __future__ import annotations
 
@@ -49,7 +49,7 @@ def main():
     ap.add_argument("--trace", help="the kernel_trace file of the same run: adds the median duration and the register count")
     ap.add_argument("--fetch")
     ap.add_argument("--write")
-    ap.add_argument("--counters")
+    ap.add_argument("--counters", action="append", default=[], help="counter_collection file of a further --pmc run (may be given more than once)")
     ap.add_argument("--out", required=True)
     ap.add_argument("--traffic")
     ap.add_argument("--title", required=True)
@@ -101,13 +101,13 @@ def main():
                 for s, (rd, wr, n) in slots.items():
                     f.write(f"{s} {(rd + wr) / n:.0f} {rd / n:.0f} {wr / n:.0f} {n}\n")
 
-    if a.counters:
-        Cn = per_dispatch(a.counters)
+    for path in a.counters:
+        Cn = per_dispatch(path)
         names = sorted({c for (_, _, c) in Cn})
-        L += ["", "Further counters per launch (mean over launches; a pass of its own):",
-              "  " + f"{'kernel':62s} " + " ".join(f"{n:>22s}" for n in names)]
+        L += ["", "Further counters per launch (mean over launches; a pass of its own), by kernel and grid size:",
+              "  " + f"{'kernel':62s} {'grid':>9s} " + " ".join(f"{n:>22s}" for n in names)]
         for k, g in sorted({(k, g) for (k, g, _) in Cn if "mc::" in k}):
-            L.append("  " + f"{short_name(k):62s} " + " ".join(f"{mean(Cn[(k, g, n)]):22.0f}" if (k, g, n) in Cn else f"{'-':>22s}" for n in names))
+            L.append("  " + f"{short_name(k):62s} {g:9d} " + " ".join(f"{mean(Cn[(k, g, n)]):22.0f}" if (k, g, n) in Cn else f"{'-':>22s}" for n in names))
 
     text = "\n".join(L) + "\n"
     open(a.out, "w").write(text)
