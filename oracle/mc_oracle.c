@@ -29,7 +29,10 @@
  * library sign-of-sum, SigNUM with beta = 0 == SignSGD and the closed form of a
  * constant gradient, OneBit's two means against library means and the
  * least-squares property, Rand-k against a library stable argsort of the
- * pinned Philox draws, exact-k, value independence and uniformity.  Parity of
+ * pinned Philox draws, exact-k, value independence and uniformity.  Which
+ * Philox counter and word every element of QSGD and TernGrad draws from
+ * (worker, iteration, model-wide index: independent of the partition); the
+ * directory that ends a sparse payload against a library searchsorted.  Parity of
  * absolute values with the paper is unpinned: the paper prints no compressor
  * input/output pair.
  */
