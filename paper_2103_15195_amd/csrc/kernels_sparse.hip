@@ -1450,8 +1450,13 @@ __device__ __forceinline__ uint32_t count_unit(const uint4 &bits, uint32_t cnt, 
 // counts the list's kept keys that lie before each of its tiles, adds the keys above the bin in the tiles before,
 // and compacts its tiles' kept candidates into the payload.  The heads of the tile's chunks and the first entries
 // of every sublist are asked for together with everything else, so the usual tile costs one memory latency.
-constexpr int kUSpec = 4;              // entries of every sublist fetched before its length is known (one per thread of an emit block)
-static_assert(kUSpec * kUSub == kEmitThreads, "one speculative list entry per thread");
+// Consecutive entries that a thread of an emit block fetches before the sublists' lengths are known, four threads per
+// sublist: a list of a few hundred keys (9 per sublist) is then complete after the first level of loads.  Measured
+// with 1 / 2 / 4 / 8: emit 13.6 / 13.5 / 13.0 / 13.8 us on the bench's Top-k, whole compress 82.7 / 82.1 / 80.1 / 78.0
+// where the bin holds 2500 keys (tensors of one scale), DGC and Rand-k +1 us with 8 (68 registers instead of 60).
+constexpr int kUPer = 4;
+constexpr int kUSpec = 4 * kUPer;      // ... which covers the first kUSpec entries of every sublist
+static_assert(4 * kUSub == kEmitThreads, "four threads per sublist");
 
 template <int ALGO, bool EF>
 #ifdef MC_EMIT_WPE
@@ -1472,7 +1477,9 @@ __global__ __launch_bounds__(kEmitThreads) void lean_emit_k(uint32_t n, uint32_t
     const uint64_t runs = live ? sc.tile_runs[tile] : 0ull;
     const SelectState s0 = sc.sel[0];
     const uint32_t ucnt = wave == 0 ? sc.ucount[lane * kUCountStride] : 0u;
-    const UEntry spec = sc.ulist[(size_t)(t / kUSpec) * kUCap + (t % kUSpec)];      // entry t % 4 of sublist t / 4, if it has that many
+    UEntry spec[kUPer];                                    // entries (t % 4) kUPer ... of sublist t / 4, if it has that many
+#pragma unroll
+    for (int i = 0; i < kUPer; ++i) spec[i] = sc.ulist[(size_t)(t / 4u) * kUCap + (t % 4u) * kUPer + i];
     uint32_t hb[kWavesPerBlock], hl[kWavesPerBlock];
 #pragma unroll
     for (int q = 0; q < kWavesPerBlock; ++q) {
@@ -1517,7 +1524,7 @@ __global__ __launch_bounds__(kEmitThreads) void lean_emit_k(uint32_t n, uint32_t
     if (t < 64u) coarse[t] = 0u;
     if (t <= (uint32_t)kEmitWaves) { cgt[t] = 0u; ceq[t] = 0u; }
     __syncthreads();
-    const bool have_spec = (t % kUSpec) < ulen[t / kUSpec];
+    const uint32_t spec_n = ulen[t / 4u] > (t % 4u) * kUPer ? min(ulen[t / 4u] - (t % 4u) * kUPer, (uint32_t)kUPer) : 0u;      // of spec[], this many exist
     const uint32_t more = min(upre[kUSub], kUCap);       // (nothing, when no sublist holds more than four entries)
     // further entry e: entry kUSpec + (e - upre[s]) of the sublist s that is the last to start at or before e
     auto further = [&](uint32_t e) {
@@ -1530,7 +1537,8 @@ __global__ __launch_bounds__(kEmitThreads) void lean_emit_k(uint32_t n, uint32_t
         const uint32_t d = (bits & 0x7FFFFFFFu) - lo;
         if (d < (uint32_t)kBins3) { atomicAdd(&hist[d], 1u); atomicAdd(&coarse[d >> 5], 1u); }
     };
-    if (have_spec) tally(spec.bits);
+#pragma unroll
+    for (int i = 0; i < kUPer; ++i) if ((uint32_t)i < spec_n) tally(spec[i].bits);
     for (uint32_t e0 = t; e0 < more; e0 += 4 * kEmitThreads) {        // (four loads in flight)
         UEntry x[4];
 #pragma unroll
@@ -1574,7 +1582,8 @@ __global__ __launch_bounds__(kEmitThreads) void lean_emit_k(uint32_t n, uint32_t
             if (bucket <= (uint32_t)kEmitWaves) atomicAdd(key > T ? &cgt[bucket] : &ceq[bucket], 1u);
         }
     };
-    if (have_spec) classify(spec);
+#pragma unroll
+    for (int i = 0; i < kUPer; ++i) if ((uint32_t)i < spec_n) classify(spec[i]);
     for (uint32_t e0 = t; e0 < more; e0 += 4 * kEmitThreads) {
         UEntry x[4];
 #pragma unroll

@@ -465,6 +465,38 @@ def test_threshold_bin_too_full_to_list():
     ctx.close()
 
 
+@pytest.mark.parametrize("inbin", [40, 900, 3500])
+def test_long_list_of_keys_in_the_threshold_bin(inbin):
+    """The usual route with `inbin` different keys in the threshold's window bin (2048 consecutive keys): the emit kernel
+    asks for the first sixteen entries of each of the list's 64 sublists before it knows their lengths and fetches the
+    rest afterwards; 40 keys leave most sublists empty, 900 fill them unevenly around the sixteen, 3500 go far beyond."""
+    n, tensors = 400000, [150000, 250000]
+    k = 4000
+    ctx = B.Context("topk", tensors, [0, 2], ratio_ppm=10000, use_ef=0, seed=1)
+    ocfg = O.Config(O.TOPK, ratio_ppm=10000, use_ef=0, seed=1)
+    assert ctx.group_k(0) == k
+    pay = torch.zeros(ctx.payload_bytes(0), dtype=torch.uint8, device=H.DEV)
+    rng = np.random.default_rng(inbin)
+    routes, bins = [], []
+    for it in range(4):
+        g = (rng.standard_normal(n, dtype=np.float32) * np.float32(1e-3)).astype(np.float32)
+        # k - inbin / 2 values well above 1, and `inbin` values 1 + j ulp, j < 2048 (one bin of the window holds them all
+        # if it starts at a multiple of 2048 keys from the hint: two adjacent bins otherwise, which still makes long sublists)
+        pos = rng.choice(n, k - inbin // 2 + inbin, replace=False)
+        g[pos[:k - inbin // 2]] = (2.0 + rng.random(k - inbin // 2)).astype(np.float32) * np.where(rng.random(k - inbin // 2) < 0.5, 1, -1).astype(np.float32)
+        keys = np.uint32(0x3F800000) + rng.choice(2048, inbin, replace=inbin > 2048).astype(np.uint32)
+        g[pos[k - inbin // 2:]] = keys.view(np.float32) * np.where(rng.random(inbin) < 0.5, 1, -1).astype(np.float32)
+        ctx.mc_compress(0, 0, it, H.device_tensors(g, tensors), None, pay)
+        routes.append(ctx.mc_last_select_route())
+        bins.append(ctx.mc_select_stats()["last_bin_keys"])
+        op, _ = O.compress(ocfg, g, None, group_off=0, worker=0, it=it)
+        assert np.array_equal(pay.cpu().numpy(), op), f"call {it} (route {routes[-1]}): payload differs"
+    print("routes", routes, "keys in the bin", bins, flush=True)
+    assert routes[1:] == [B.MC_SELECT_FAST] * 3 and max(bins[1:]) >= inbin // 2
+    assert ctx.mc_last_device_status() == B.MC_OK
+    ctx.close()
+
+
 @pytest.mark.parametrize("algo", ["topk", "dgc"])
 def test_selection_routes_are_all_taken_and_exact(algo):
     """The exact selection has three routes: the threshold key T falls inside the histogram window that the
