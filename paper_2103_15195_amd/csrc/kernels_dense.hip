@@ -617,7 +617,7 @@ __global__ __launch_bounds__(kBlock) void dense_decompress_k(GroupView out, Payl
             float scale[kBatch];
 #pragma unroll
             for (int b = 0; b < kBatch; ++b)
-                scale[b] = w0 + b < W ? reinterpret_cast<const PayloadHeader *>(pl.p[w0 + b])->scale : 0.0f;
+                scale[b] = w0 + b < W ? ld_uniform(&reinterpret_cast<const PayloadHeader *>(pl.p[w0 + b])->scale) : 0.0f;
             uint32_t cw[kBatch][4];
 #pragma unroll
             for (int b = 0; b < kBatch; ++b) {
@@ -651,7 +651,7 @@ __global__ __launch_bounds__(kBlock) void dense_decompress_k(GroupView out, Payl
         float scale[kBatch];
 #pragma unroll
         for (int b = 0; b < kBatch; ++b)
-            scale[b] = w0 + b < W ? reinterpret_cast<const PayloadHeader *>(pl.p[w0 + b])->scale : 0.0f;
+            scale[b] = w0 + b < W ? ld_uniform(&reinterpret_cast<const PayloadHeader *>(pl.p[w0 + b])->scale) : 0.0f;
         if (ALGO == MC_ALGO_QSGD) {
             int8_t cd[kBatch][kSteps];
 #pragma unroll
@@ -732,8 +732,9 @@ __device__ __forceinline__ uint64_t gather_transpose(const uint32_t (&wd)[8], in
 // what a set / clear bit of worker w decodes to (one-plane schemes)
 __device__ __forceinline__ void plane_levels(const PayloadHeader *h, int kind, float &hi, float &lo)
 {
-    hi = kind == PLANE_VOTE ? 1.0f : h->scale;
-    lo = kind == PLANE_MEANS ? __uint_as_float(h->pad[0]) : -hi;
+    // (scalar loads: as vector loads they queue behind the compute unit's stores, and every block waits for them)
+    hi = kind == PLANE_VOTE ? 1.0f : ld_uniform(&h->scale);
+    lo = kind == PLANE_MEANS ? __uint_as_float(ld_uniform(&h->pad[0])) : -hi;
 }
 __device__ __forceinline__ float vote_of(float tally) { return tally > 0.0f ? 1.0f : (tally < 0.0f ? -1.0f : 0.0f); }
 
@@ -770,6 +771,21 @@ __global__ __launch_bounds__(kBlock) void plane_decompress_k(GroupView out, Payl
     if (blockIdx.x == 0 && (int)t < W)
         check_header(reinterpret_cast<const PayloadHeader *>(pl.p[t]), algo, out.n, status);
     const int Wt = W < 8 ? W : 8;
+    // the plane words are asked for before the table is built: the headers' scalars, which the table waits for, and
+    // the words then travel together (one-plane schemes 0.6 us, OneBit and TernGrad 1.0-1.5 us of 28-37)
+    const uint32_t wbase = my_tile_index() * (uint32_t)kSignTile + wave * (uint32_t)kSignWaveElems;
+    const uint32_t nwords = (out.n + 31u) >> 5;
+    const uint32_t wi = (wbase >> 5) + lane;
+    uint32_t wd[8], wn[8];
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+        wd[b] = 0u; wn[b] = 0u;
+        if (b < Wt && wi < nwords) {
+            const uint32_t *plane = reinterpret_cast<const uint32_t *>(pl.p[b] + kHeaderBytes);
+            wd[b] = ld_stream(plane + wi);
+            if (TERN) wn[b] = ld_stream(plane + nwords + wi);
+        }
+    }
     {
         if (!TERN) {
             float acc = 0.0f;
@@ -789,7 +805,7 @@ __global__ __launch_bounds__(kBlock) void plane_decompress_k(GroupView out, Payl
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 if (b < Wt) {
-                    const float sc = reinterpret_cast<const PayloadHeader *>(pl.p[b])->scale;
+                    const float sc = ld_uniform(&reinterpret_cast<const PayloadHeader *>(pl.p[b])->scale);
                     acc = acc + (((t >> b) & 1u) ? (((t >> (4 + b)) & 1u) ? -sc : sc) : 0.0f);
                 }
             }
@@ -799,23 +815,10 @@ __global__ __launch_bounds__(kBlock) void plane_decompress_k(GroupView out, Payl
     float s47[4] = {0.0f, 0.0f, 0.0f, 0.0f};               // TernGrad: scales of workers 4..7, added one by one
     if (TERN) {
 #pragma unroll
-        for (int b = 4; b < 8; ++b) if (b < Wt) s47[b - 4] = reinterpret_cast<const PayloadHeader *>(pl.p[b])->scale;
+        for (int b = 4; b < 8; ++b) if (b < Wt) s47[b - 4] = ld_uniform(&reinterpret_cast<const PayloadHeader *>(pl.p[b])->scale);
     }
     __syncthreads();
-    const uint32_t wbase = my_tile_index() * (uint32_t)kSignTile + wave * (uint32_t)kSignWaveElems;
     if (wbase >= out.n) return;
-    const uint32_t nwords = (out.n + 31u) >> 5;
-    const uint32_t wi = (wbase >> 5) + lane;
-    uint32_t wd[8], wn[8];
-#pragma unroll
-    for (int b = 0; b < 8; ++b) {
-        wd[b] = 0u; wn[b] = 0u;
-        if (b < Wt && wi < nwords) {
-            const uint32_t *plane = reinterpret_cast<const uint32_t *>(pl.p[b] + kHeaderBytes);
-            wd[b] = ld_stream(plane + wi);
-            if (TERN) wn[b] = ld_stream(plane + nwords + wi);
-        }
-    }
     float acc[32];
     // TernGrad: only workers 0..3 enter the transposes
     const uint32_t wlow[8] = {wd[0], wd[1], wd[2], wd[3], 0u, 0u, 0u, 0u}, nlow[8] = {wn[0], wn[1], wn[2], wn[3], 0u, 0u, 0u, 0u};
@@ -842,7 +845,7 @@ __global__ __launch_bounds__(kBlock) void plane_decompress_k(GroupView out, Payl
     }
     if (W > 8) {
         for (int w = 8; w < W; ++w) {
-            float sc = reinterpret_cast<const PayloadHeader *>(pl.p[w])->scale, sl = -sc;
+            float sc = ld_uniform(&reinterpret_cast<const PayloadHeader *>(pl.p[w])->scale), sl = -sc;
             if (!TERN) plane_levels(reinterpret_cast<const PayloadHeader *>(pl.p[w]), kind, sc, sl);
             const uint32_t *plane = reinterpret_cast<const uint32_t *>(pl.p[w] + kHeaderBytes);
             const uint32_t word = wi < nwords ? ld_stream(plane + wi) : 0u;
