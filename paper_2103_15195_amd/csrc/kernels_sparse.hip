@@ -1459,9 +1459,6 @@ constexpr int kUSpec = 4 * kUPer;      // ... which covers the first kUSpec entr
 static_assert(4 * kUSub == kEmitThreads, "four threads per sublist");
 
 template <int ALGO, bool EF>
-#ifdef MC_EMIT_WPE
-__attribute__((amdgpu_waves_per_eu(MC_EMIT_WPE, MC_EMIT_WPE)))
-#endif
 __global__ __launch_bounds__(kEmitThreads) void lean_emit_k(uint32_t n, uint32_t ntiles, float *st, PayloadHeader *hdr, uint64_t k,
                                                             SparseScratch sc)
 {
