@@ -68,7 +68,7 @@ def sparse_decompress_fullsize(wl, algo, y, W, grads, ppm):
         lo, n = int(offs[bounds[j]]), int(offs[bounds[j + 1]] - offs[bounds[j]])
         k = ctx.group_k(j)
         pays = synthetic_sparse_payloads(H.ALGOS[algo], flats, lo, n, k, seed=j)
-        for rep in range(2):             # twice: the tile table of the second call carries a new epoch
+        for rep in range(2):             # twice: the second call finds the context as the first one left it
             ctx.mc_decompress_sum(j, [torch.from_numpy(p).to(H.DEV) for p in pays], 0.125, outs[bounds[j]:bounds[j + 1]])
         assert ctx.mc_last_device_status() == B.MC_OK
         got = H.gather_flat(outs[bounds[j]:bounds[j + 1]])
