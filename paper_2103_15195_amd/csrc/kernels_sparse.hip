@@ -1847,10 +1847,13 @@ __global__ __launch_bounds__(kBlock) void sparse_decompress_k(int algo, GroupVie
                     if (b < W && local < (uint32_t)kChunk) mine[local] = mine[local] + vv[b];
                     __builtin_amdgcn_wave_barrier();
                 }
+                // read back in the mapping rotated onto the output's 128-byte lines (payloads spread thinly over all
+                // tiles: 37.2 -> 36.3 us; clustered ones: 32.3 -> 32.1; the same on the path below changes nothing)
                 float v[kSteps];
+                const uint32_t rot = chunk_rotation(entry);
 #pragma unroll
-                for (int j = 0; j < kSteps; ++j) v[j] = alpha * mine[64 * j + c.lane];
-                store_seg(out, c, v, entry);
+                for (int j = 0; j < kSteps; ++j) v[j] = alpha * mine[rotated(j, c.lane, rot)];
+                store_seg_rot(out, c, v, entry, rot);
                 return;
             }
         }
