@@ -99,7 +99,8 @@ typedef enum {
     MC_ERR_INVALID_ARG = -1, /* null pointer, unknown algo/policy, bad config value             */
     MC_ERR_RANGE = -2,       /* y > N, group with >= 2^32 - 2^24 elements, bounds not increasing */
     MC_ERR_ALLOC = -3,       /* host or device allocation failed in mc_ctx_create                */
-    MC_ERR_DEVICE = -4,      /* a HIP runtime call failed                                        */
+    MC_ERR_DEVICE = -4,      /* a HIP runtime call failed, or (mc_last_device_status) a bounded wait inside
+                                a kernel of the sparsifiers' rare selection routes ran out               */
     MC_ERR_PAYLOAD = -5      /* a payload header did not match the context (device-side check)   */
 } mc_status;
 
@@ -255,18 +256,36 @@ int mc_decompress_sum(mc_ctx *ctx, int32_t group, const void *const *payloads, i
 int mc_state_export_residual(mc_ctx *ctx, int32_t group, const void *state, float *e_out, void *stream);
 int mc_state_import_residual(mc_ctx *ctx, int32_t group, const float *e_in, void *state, void *stream);
 
-/* Synchronises the context's device and returns MC_OK or MC_ERR_PAYLOAD if any
- * mc_decompress_sum since the last call saw a mismatching header; clears the flag. */
+/* Synchronises the context's device and returns MC_OK, MC_ERR_PAYLOAD if any
+ * mc_decompress_sum since the last call saw a mismatching header, or MC_ERR_DEVICE if a
+ * sparsifier's mc_compress gave up waiting at a grid-wide barrier of its rare selection routes
+ * (the blocks of that kernel wait for each other, at most about two seconds, which needs them all
+ * resident: other work that holds the GPU's compute units for that long can cause it; the
+ * payload of that call is then incomplete and its error-feedback state unspecified -- import a
+ * residual again before the next call; the context itself stays usable).  Clears the flag. */
 int mc_last_device_status(mc_ctx *ctx);
 
-/* Diagnostic for the sparsifiers (Top-k, DGC; Section 5.1 names their selection as the
+/* For tests of the error path above: how often a block looks at a grid-wide barrier before it gives up
+ * (0 = the default, 2^21 looks of about a microsecond; 1 = after the first look, which makes every
+ * mc_compress that takes one of the rare routes on more than one block report MC_ERR_DEVICE while all its
+ * kernels still end normally).  Applies to the calls issued afterwards.  Errors: MC_ERR_INVALID_ARG
+ * (null, dense algorithm). */
+int mc_set_barrier_spin_limit(mc_ctx *ctx, uint32_t polls);
+
+/* Diagnostic for the sparsifiers (Top-k, DGC, Rand-k; Section 5.1 names their selection as the
  * costly step).  Synchronises the context's device and reports which route the exact
  * selection of the most recent mc_compress took:
- *   MC_SELECT_FAST    the threshold fell inside the histogram window kept around the
- *                     last threshold of this (group, worker): one more radix level
- *   MC_SELECT_ABOVE   it rose above that window (also the first call): three levels
- *   MC_SELECT_REFILL  fewer than k elements passed the candidate filter: the group was
- *                     streamed a second time
+ *   MC_SELECT_FAST    the threshold fell inside the histogram window kept from a margin below the
+ *                     last threshold of this (group, worker) upward, in a bin of at most 4096 keys:
+ *                     two short kernels after the streaming pass
+ *   MC_SELECT_DENSE   as FAST, but more than 4096 keys share that bin (many equal values): the bin
+ *                     is resolved as one more radix level
+ *   MC_SELECT_ABOVE   the threshold rose above the window (also a context's first call of a
+ *                     (group, worker)): three radix levels over the candidates
+ *   MC_SELECT_REFILL  fewer than k elements passed the candidate filter: the group is
+ *                     streamed a second time, every element a candidate
+ * The last three run as one kernel with grid-wide barriers and cost several times the first
+ * (measured on a 25.6 M element group: 60 / 160 / 180-260 / 410-450 us for the whole call).
  * The result of mc_compress is identical on all routes; only its cost differs.
  * Returns the route, or a negative mc_status (MC_ERR_INVALID_ARG for a dense algorithm). */
 enum { MC_SELECT_ABOVE = 0, MC_SELECT_FAST = 1, MC_SELECT_REFILL = 2, MC_SELECT_DENSE = 3 };

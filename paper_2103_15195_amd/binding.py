@@ -26,7 +26,7 @@ EXPORTS = [
     "mc_partition", "mc_partition_cost", "mc_partition_search", "mc_ctx_create", "mc_ctx_destroy", "mc_group_numel", "mc_group_k", "mc_group_tensors",
     "mc_payload_bytes", "mc_state_bytes", "mc_compress", "mc_compress_static", "mc_static_scratch_bytes", "mc_static_max_elems",
     "mc_decompress_sum", "mc_state_export_residual",
-    "mc_state_import_residual", "mc_last_device_status", "mc_last_select_route", "mc_select_stats", "mc_profile_enable", "mc_profile_select", "mc_profile_reset",
+    "mc_state_import_residual", "mc_last_device_status", "mc_last_select_route", "mc_select_stats", "mc_set_barrier_spin_limit", "mc_profile_enable", "mc_profile_select", "mc_profile_reset",
     "mc_profile_kernels", "mc_profile_read", "mc_strerror", "mc_version",
 ]
 
@@ -89,6 +89,7 @@ def lib():
         L.mc_last_device_status.argtypes = [vp]
         L.mc_last_select_route.argtypes = [vp]
         L.mc_select_stats.argtypes = [vp, C.POINTER(McSelectCounts), i32]
+        L.mc_set_barrier_spin_limit.argtypes = [vp, C.c_uint32]
         L.mc_profile_enable.argtypes = [vp, i32]
         L.mc_profile_select.argtypes = [vp, u64]
         L.mc_profile_reset.argtypes = [vp]
@@ -238,6 +239,9 @@ class Context:
         if r < 0:
             raise McError(r, "mc_last_select_route")
         return r
+
+    def mc_set_barrier_spin_limit(self, polls: int) -> None:
+        _check(lib().mc_set_barrier_spin_limit(self._h, polls), "mc_set_barrier_spin_limit")
 
     def mc_select_stats(self, reset: bool = False) -> dict:
         c = McSelectCounts()

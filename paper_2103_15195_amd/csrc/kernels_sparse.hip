@@ -142,6 +142,12 @@ __global__ __launch_bounds__(kBlock) void sparse_accum_k(GroupView g, float *st,
     // the emit kernel of the call before is done with the list of keys in the threshold's bin: its sublists are empty again
     if (blockIdx.x == 0 && threadIdx.x < (uint32_t)kUSub) sc.ucount[threadIdx.x * kUCountStride] = 0u;
     if (blockIdx.x == 0 && threadIdx.x == 0) sc.sync[0] = 0u;       // and nobody waits at a grid-wide barrier of that call any more
+    // The radix levels are cleared by the kernels that use them -- unless a call gave up at a barrier (MC_ERR_DEVICE):
+    // what it left behind must not enter this call's counts.
+    {
+        const uint32_t i = blockIdx.x * (uint32_t)kBlock + threadIdx.x;
+        if (i < (uint32_t)(kHistOpen - kHist1)) sc.hist[kHist1 + i] = 0u;
+    }
     uint32_t run = 0;
     if (c.base < g.n) {
         float p[kSteps];
@@ -928,7 +934,7 @@ __device__ __forceinline__ void publish_hint(const SparseScratch &sc, uint32_t T
 // block wrote before the barrier visible to every block after it.  The wait is bounded: should the count never
 // come (it always does when the blocks are resident together), the block flags the failure and leaves, and so
 // does every later wait.
-__device__ __forceinline__ bool grid_barrier(uint32_t *arrive, uint32_t blocks, uint32_t round, uint32_t *dead /* LDS */, int *status)
+__device__ __forceinline__ bool grid_barrier(uint32_t *arrive, uint32_t blocks, uint32_t round, uint32_t *dead /* LDS */, int *status, uint32_t limit)
 {
     __syncthreads();
     if (threadIdx.x == 0 && !*dead) {
@@ -939,7 +945,7 @@ __device__ __forceinline__ bool grid_barrier(uint32_t *arrive, uint32_t blocks, 
         // blocks doing that every few hundred cycles starve the blocks still at work (phases of 60-120 us instead of 10)
         while (__hip_atomic_load(arrive, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
             __builtin_amdgcn_s_sleep(32);
-            if (++spins > (1u << 21)) { *dead = 1u; *status = 2; break; }
+            if (spins++ >= limit) { *dead = 1u; *status = 2; break; }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     }
@@ -1026,7 +1032,7 @@ __device__ __forceinline__ void slow_routes(const GroupView &g, float *st, Paylo
         }
         __syncthreads();
         flush_fine(hist, sc.hist + kHist1, kBins1);
-        if (!grid_barrier(sc.sync + kSyncArrive, blocks, ++round, dead, status)) return;
+        if (!grid_barrier(sc.sync + kSyncArrive, blocks, ++round, dead, status, sc.spin_limit)) return;
         resolve_block<kBins1>(sc.hist + kHist1, need, bin, need, res);
         lo += bin << 20;
         // ---- level 2: bits 19..10
@@ -1039,7 +1045,7 @@ __device__ __forceinline__ void slow_routes(const GroupView &g, float *st, Paylo
             });
         __syncthreads();
         flush_fine(hist, sc.hist + kHist2, kBins2);
-        if (!grid_barrier(sc.sync + kSyncArrive, blocks, ++round, dead, status)) return;
+        if (!grid_barrier(sc.sync + kSyncArrive, blocks, ++round, dead, status, sc.spin_limit)) return;
         if (blockIdx.x == 0) for (int b = t; b < kBins1; b += kSelThreads) sc.hist[kHist1 + b] = 0u;    // every block has resolved level 1
         resolve_block<kBins2>(sc.hist + kHist2, need, bin, need, res);
         lo += bin << 10;
@@ -1055,7 +1061,7 @@ __device__ __forceinline__ void slow_routes(const GroupView &g, float *st, Paylo
         });
     __syncthreads();
     flush_fine(hist, sc.hist + kHist3, kBins3);
-    if (!grid_barrier(sc.sync + kSyncArrive, blocks, ++round, dead, status)) return;
+    if (!grid_barrier(sc.sync + kSyncArrive, blocks, ++round, dead, status, sc.spin_limit)) return;
     if (!(mode & kModeFast) && blockIdx.x == 0) for (int b = t; b < kBins2; b += kSelThreads) sc.hist[kHist2 + b] = 0u;
     resolve_block<kBins3>(sc.hist + kHist3, need, bin, need, res);
     T = lo + bin;
@@ -1069,7 +1075,7 @@ __device__ __forceinline__ void slow_routes(const GroupView &g, float *st, Paylo
         });
         if (lane == 0) sc.tile_cnt[tile] = ngt | (neq << 16);              // a tile holds at most 4096 candidates
     }
-    if (!grid_barrier(sc.sync + kSyncArrive, blocks, ++round, dead, status)) return;
+    if (!grid_barrier(sc.sync + kSyncArrive, blocks, ++round, dead, status, sc.spin_limit)) return;
     if (blockIdx.x == 0) for (int b = t; b < kBins3; b += kSelThreads) sc.hist[kHist3 + b] = 0u;
     uint32_t *idx = reinterpret_cast<uint32_t *>(reinterpret_cast<uint8_t *>(hdr) + kHeaderBytes);
     float *val = reinterpret_cast<float *>(idx + k);

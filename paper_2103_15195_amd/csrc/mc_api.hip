@@ -16,6 +16,7 @@ using namespace mc;
 namespace {
 
 constexpr uint64_t kMaxGroupElems = (1ull << 32) - (1ull << 24);
+constexpr uint32_t kBarrierSpinLimit = 1u << 21;     // polls (about a microsecond each) before a block of the slow selection routes gives up waiting
 constexpr int kPtrSlots = 256;           // cached device copies of per-call tensor address lists
 
 struct Group {
@@ -437,6 +438,7 @@ int mc_ctx_create(mc_ctx **out, const mc_config *cfg, const int64_t *numel, int3
             int cus = 0;
             if (rc == MC_OK && (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ctx->device) != hipSuccess || cus < 1)) rc = MC_ERR_DEVICE;
             ctx->sync_blocks = (uint32_t)std::max(cus, 1);
+            sp.spin_limit = kBarrierSpinLimit;
         }
         if (rc == MC_OK) {
             // the per-chunk address tables of all slots together stay below 256 MiB
@@ -726,6 +728,13 @@ int mc_select_stats(mc_ctx *ctx, mc_select_counts *out, int32_t reset)
     out->last_bin_keys = w[8];
     out->last_candidates = w[9];
     if (reset && hipMemset(ctx->sparse.sync + 32, 0, 4 * sizeof(uint32_t)) != hipSuccess) return MC_ERR_DEVICE;
+    return MC_OK;
+}
+
+int mc_set_barrier_spin_limit(mc_ctx *ctx, uint32_t polls)
+{
+    if (!ctx || !is_sparse(ctx->cfg.algo)) return MC_ERR_INVALID_ARG;
+    ctx->sparse.spin_limit = polls ? polls - 1u : kBarrierSpinLimit;       // polls = 1: give up after the first look
     return MC_OK;
 }
 

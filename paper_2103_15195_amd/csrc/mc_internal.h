@@ -119,7 +119,8 @@ struct SparseScratch {
     uint32_t *blk_cnt;     // the same per block of four tiles
     UEntry *ulist;         // kUSub sublists of kUCap entries: the candidates in the threshold's window bin
     uint32_t *ucount;      // their lengths, kUCountStride words apart; cleared by the streaming pass of the next call
-    uint32_t *sync;        // [0]: arrivals at the grid-wide barriers of the slow routes (cleared by the select kernel); [32..36): calls per route
+    uint32_t *sync;        // [0]: arrivals at the grid-wide barriers of the slow routes (cleared by the streaming pass); [32..36): calls per route
+    uint32_t spin_limit;   // polls after which a block gives up waiting at such a barrier (mc_set_barrier_spin_limit)
 };
 // sync_blocks: how many blocks of 1024 threads the device surely holds at once (one per compute unit): the slow routes
 // of the selection run on that many blocks with grid-wide barriers between their steps

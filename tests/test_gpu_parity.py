@@ -465,6 +465,31 @@ def test_threshold_bin_too_full_to_list():
     ctx.close()
 
 
+def test_a_barrier_that_is_not_passed_is_reported_and_nothing_hangs():
+    """The rare selection routes run as one kernel whose blocks wait for each other, a bounded number of looks.  With
+    the bound set to one look (from the host), the first call of a context -- which takes such a route, on four blocks
+    here -- gives up at its first barrier: every kernel still ends, the status says so, and with the default bound
+    restored the same call gives the oracle's payload."""
+    n, tensors = 200000, [120000, 80000]
+    ctx = B.Context("topk", tensors, [0, 2], ratio_ppm=10000, use_ef=0, seed=1)
+    ocfg = O.Config(O.TOPK, ratio_ppm=10000, use_ef=0, seed=1)
+    g = np.random.default_rng(11).standard_normal(n).astype(np.float32)
+    grads = H.device_tensors(g, tensors)
+    pay = torch.zeros(ctx.payload_bytes(0), dtype=torch.uint8, device=H.DEV)
+    ctx.mc_set_barrier_spin_limit(1)
+    ctx.mc_compress(0, 0, 0, grads, None, pay)
+    assert B.lib().mc_last_device_status(ctx._h) == B.MC_ERR_DEVICE
+    assert ctx.mc_last_device_status() == B.MC_OK                      # (the flag was cleared)
+    ctx.mc_set_barrier_spin_limit(0)
+    ctx.mc_compress(0, 0, 0, grads, None, pay)
+    assert ctx.mc_last_device_status() == B.MC_OK
+    op, _ = O.compress(ocfg, g, None, group_off=0, worker=0, it=0)
+    assert np.array_equal(pay.cpu().numpy(), op)
+    with pytest.raises(B.McError):
+        B.Context("efsign", tensors, [0, 2]).mc_set_barrier_spin_limit(1)
+    ctx.close()
+
+
 @pytest.mark.parametrize("inbin", [40, 900, 3500])
 def test_long_list_of_keys_in_the_threshold_bin(inbin):
     """The usual route with `inbin` different keys in the threshold's window bin (2048 consecutive keys): the emit kernel
