@@ -1408,13 +1408,13 @@ __device__ __forceinline__ void emit_head(uint32_t bits, uint32_t loc, bool vali
     gt0 += __popcll(bgt); eq0 += __popcll(beq);
 }
 
-// ... four consecutive candidates per lane (a unit)
+// ... four consecutive candidates per lane (a unit; it holds at most 256 keys above T and as many equal to it)
 template <int ALGO, bool EF>
 __device__ __forceinline__ void emit_unit(const uint4 &bits, const uint2 &loc, uint32_t cnt, uint32_t v, uint32_t chunk, uint32_t n,
-                                          uint64_t k, float *st, uint32_t *idx, float *val, uint32_t T, uint32_t need, uint64_t gt0, uint32_t eq0)
+                                          uint64_t k, float *st, uint32_t *idx, float *val, uint32_t T, uint32_t need, uint64_t &gt0, uint32_t &eq0)
 {
     bool isg[4], ise[4];
-    uint32_t mine = 0;                                    // this lane's keys above T | equal to T << 16
+    uint32_t mine = 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const uint32_t key = elem4(bits, j) & 0x7FFFFFFFu;
@@ -1422,7 +1422,8 @@ __device__ __forceinline__ void emit_unit(const uint4 &bits, const uint2 &loc, u
         isg[j] = valid && key > T; ise[j] = valid && key == T;
         mine += (isg[j] ? 1u : 0u) + (ise[j] ? 0x10000u : 0u);
     }
-    const uint32_t inc = wave_scan_incl(mine);            // (a unit holds at most 256 of each: the halves do not mix)
+    const uint32_t inc = wave_scan_incl(mine);
+    const uint32_t tot = wave_total(inc);
     uint64_t gtb = gt0 + ((inc - mine) & 0xFFFFu);
     uint32_t eqb = eq0 + ((inc - mine) >> 16);
 #pragma unroll
@@ -1439,20 +1440,7 @@ __device__ __forceinline__ void emit_unit(const uint4 &bits, const uint2 &loc, u
         }
         gtb += isg[j] ? 1u : 0u; eqb += ise[j] ? 1u : 0u;
     }
-}
-
-// keys above T | equal to T << 16 among one candidate per lane / in one unit
-__device__ __forceinline__ uint32_t count_head(uint32_t bits, bool valid, uint32_t T)
-{
-    const uint32_t key = bits & 0x7FFFFFFFu;
-    return __popcll(__builtin_amdgcn_ballot_w64(valid && key > T)) + (__popcll(__builtin_amdgcn_ballot_w64(valid && key == T)) << 16);
-}
-__device__ __forceinline__ uint32_t count_unit(const uint4 &bits, uint32_t cnt, uint32_t v, uint32_t T)
-{
-    uint32_t c = 0;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) c += count_head(elem4(bits, j), in_unit(cnt, v, j), T);
-    return c;
+    gt0 += tot & 0xFFFFu; eq0 += tot >> 16;
 }
 
 // Emit: four tiles per block, one wavefront each.  Every block reads the whole list of the keys in the threshold's
@@ -1628,56 +1616,37 @@ __global__ __launch_bounds__(kEmitThreads) void lean_emit_k(uint32_t n, uint32_t
             if (cnt[q]) emit_head<ALGO, EF>(hb[q], hl[q], lane < cnt[q], tile * kWavesPerBlock + q, n, k, st, idx, val, T, need, gt0, eq0);
         return;
     }
-    // a tile with crowded chunks: count the kept keys of every piece (lane 5 q: the head of chunk q, lane 5 q + 1 + v: its
-    // unit v), scan, then place piece by piece.  Up to four units -- nearly every such tile -- were fetched at the start and
-    // stay in registers between the two steps; beyond that the units are fetched four at a time, twice.
-    uint32_t piece = 0;
+    // A tile with crowded chunks: its pieces -- the head of chunk 0, its units, the head of chunk 1, ... -- are placed in
+    // index order, the counts of kept keys running along.  Up to four units, nearly every such tile, were fetched at
+    // the start; a tile with more fetches them four at a time.  One copy of the unit's code in a loop that is not
+    // unrolled: sixteen unrolled copies were 2 us slower (code size), and counting all pieces first, scanning the counts
+    // and fetching the units of a very crowded tile a second time 1.3 us slower (Top-k emit 13.0 -> 11.7 us).
+    uint32_t e = 0;                                         // next unit of the tile
 #pragma unroll
     for (int q = 0; q < kWavesPerBlock; ++q) {
-        const uint32_t c = cnt[q] ? count_head(hb[q], lane < cnt[q], T) : 0u;
-        if (lane == 5u * q) piece = c;
-    }
-    const bool kept_here = tu.total <= 4u;
-    for (uint32_t e0 = 0; e0 < tu.total; e0 += 4u) {
-        if (e0) {
+        const uint32_t cq = cnt[q];
+        if (!cq) continue;
+        emit_head<ALGO, EF>(hb[q], hl[q], lane < cq, tile * kWavesPerBlock + q, n, k, st, idx, val, T, need, gt0, eq0);
+        const uint32_t nu = tu.per[q];
+#pragma unroll 1
+        for (uint32_t v = 0; v < nu; ++v, ++e) {
+            if (e >= 4u && (e & 3u) == 0u) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                tu.locate(e0 + i < tu.total ? e0 + i : e0, kq[i], kv[i]);
-                kb[i] = load_bits4(sc, tile * kWavesPerBlock + kq[i], kv[i]);
+                for (int i = 0; i < 4; ++i) {
+                    tu.locate(e + i < tu.total ? e + i : e, kq[i], kv[i]);
+                    kb[i] = load_bits4(sc, tile * kWavesPerBlock + kq[i], kv[i]);
+                    kl[i] = load_loc4(sc, tile * kWavesPerBlock + kq[i], kv[i]);
+                }
             }
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            if (e0 + i >= tu.total) break;
-            const uint32_t c = count_unit(kb[i], pick4(cnt, kq[i]), kv[i], T);
-            if (lane == 5u * kq[i] + 1u + kv[i]) piece = c;
-        }
-    }
-    // inclusive scans over the twenty pieces (a tile holds at most 4096 of each)
-    const uint32_t ig = wave_scan_incl(piece & 0xFFFFu), ie = wave_scan_incl(piece >> 16);
-    const uint32_t xg = ig - (piece & 0xFFFFu), xe = ie - (piece >> 16);          // kept keys of the tile before each piece
-#pragma unroll
-    for (int q = 0; q < kWavesPerBlock; ++q) {
-        if (!cnt[q]) continue;
-        uint64_t g1 = gt0 + (uint32_t)__builtin_amdgcn_readlane((int)xg, 5 * q);
-        uint32_t e1 = eq0 + (uint32_t)__builtin_amdgcn_readlane((int)xe, 5 * q);
-        emit_head<ALGO, EF>(hb[q], hl[q], lane < cnt[q], tile * kWavesPerBlock + q, n, k, st, idx, val, T, need, g1, e1);
-    }
-    for (uint32_t e0 = 0; e0 < tu.total; e0 += 4u) {
-        if (!kept_here) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                tu.locate(e0 + i < tu.total ? e0 + i : e0, kq[i], kv[i]);
-                kb[i] = load_bits4(sc, tile * kWavesPerBlock + kq[i], kv[i]);
-                kl[i] = load_loc4(sc, tile * kWavesPerBlock + kq[i], kv[i]);
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            if (e0 + i >= tu.total) break;
-            const uint32_t u = 5u * kq[i] + 1u + kv[i];
-            emit_unit<ALGO, EF>(kb[i], kl[i], pick4(cnt, kq[i]), kv[i], tile * kWavesPerBlock + kq[i], n, k, st, idx, val, T, need,
-                                gt0 + (uint32_t)__builtin_amdgcn_readlane((int)xg, u), eq0 + (uint32_t)__builtin_amdgcn_readlane((int)xe, u));
+            // unit e % 4 of the four in registers, chosen word by word (an array indexed at run time would live in scratch memory)
+            const uint32_t s = e & 3u;
+            auto sel = [s](uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3) { return s == 0u ? a0 : s == 1u ? a1 : s == 2u ? a2 : a3; };
+            uint4 b;
+            b.x = sel(kb[0].x, kb[1].x, kb[2].x, kb[3].x); b.y = sel(kb[0].y, kb[1].y, kb[2].y, kb[3].y);
+            b.z = sel(kb[0].z, kb[1].z, kb[2].z, kb[3].z); b.w = sel(kb[0].w, kb[1].w, kb[2].w, kb[3].w);
+            uint2 l;
+            l.x = sel(kl[0].x, kl[1].x, kl[2].x, kl[3].x); l.y = sel(kl[0].y, kl[1].y, kl[2].y, kl[3].y);
+            emit_unit<ALGO, EF>(b, l, cq, v, tile * kWavesPerBlock + q, n, k, st, idx, val, T, need, gt0, eq0);
         }
     }
 }
