@@ -294,12 +294,18 @@ int mc_last_select_route(mc_ctx *ctx);
 /* Counts of mc_compress calls by the route their selection took (indexed by the MC_SELECT_ values) since
  * the context was created or the counts were last reset, for the sparsifiers without a sampled threshold;
  * and, of the most recent call, the number of keys that shared the threshold's window bin (the two-kernel
- * route lists them: at most 4096) and of elements that passed the candidate filter (modulo 2^32).
+ * route lists them: at most 4096) and of elements that passed the candidate filter (modulo 2^32); and where the
+ * candidate filter of that call's (group, worker) stands: the filter starts a margin below the last threshold,
+ * 3/16 of an octave halved margin_halvings times (0..4: the library halves it while many more than k elements
+ * pass, and starts over after a call whose threshold fell below the filter), at most margin_cap times for now
+ * (4, less for a while after such a call).  -1 for both before the first call.
  * Synchronises the context's device.  Errors: MC_ERR_INVALID_ARG (null, dense algorithm). */
 typedef struct {
     int64_t calls[4];
     int64_t last_bin_keys;
     int64_t last_candidates;
+    int64_t margin_halvings;
+    int64_t margin_cap;
 } mc_select_counts;
 int mc_select_stats(mc_ctx *ctx, mc_select_counts *out, int32_t reset);
 

@@ -42,7 +42,8 @@ class McTimeModel(C.Structure):
 
 
 class McSelectCounts(C.Structure):
-    _fields_ = [("calls", C.c_int64 * 4), ("last_bin_keys", C.c_int64), ("last_candidates", C.c_int64)]
+    _fields_ = [("calls", C.c_int64 * 4), ("last_bin_keys", C.c_int64), ("last_candidates", C.c_int64),
+                ("margin_halvings", C.c_int64), ("margin_cap", C.c_int64)]
 
 
 class McError(RuntimeError):
@@ -247,7 +248,8 @@ class Context:
         c = McSelectCounts()
         _check(lib().mc_select_stats(self._h, C.byref(c), 1 if reset else 0), "mc_select_stats")
         return {"above": c.calls[0], "fast": c.calls[1], "refill": c.calls[2], "dense": c.calls[3],
-                "last_bin_keys": c.last_bin_keys, "last_candidates": c.last_candidates}
+                "last_bin_keys": c.last_bin_keys, "last_candidates": c.last_candidates,
+                "margin_halvings": c.margin_halvings, "margin_cap": c.margin_cap}
 
     # profiling ------------------------------------------------------------------
     def profile_enable(self, on: bool, all_kernels: bool = False) -> None:

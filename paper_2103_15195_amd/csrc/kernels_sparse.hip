@@ -69,8 +69,38 @@ constexpr uint32_t kHintMargin = 3u << 19;   // 3/16 of an octave below the last
 // seed result (SelectState::mode)
 // hint record of a (group, worker): the filter key, how many times the margin below the threshold was halved,
 // and for how many calls it stays at the full margin after a miss
-constexpr int kHintShift = 1, kHintHold = 2;
+constexpr int kHintShift = 1, kHintHold = 2, kHintCap = 3;
 constexpr uint32_t kHintShiftMax = 4u, kHintHoldCalls = 8u;      // margin at least 3/256 of an octave (0.8 %)
+constexpr uint32_t kHintCapCalls = 64u;
+
+// How far below the threshold the next call starts filtering, after a call whose threshold lay inside the window.
+// Under error feedback the values pile up just below the threshold, in the long run those of every tensor, and a fixed
+// margin lets through many times k of them (each costs the streaming pass a store and the histogram an add): the
+// margin is halved while the filter passes more than 3 k (at most four times: 0.8 % below the threshold) and doubled
+// again when it passes fewer than 1.5 k.  (Measured, every worker on new gradients: 850 000 candidates with three
+// halvings and 4 k, 533 000 with four and 3 k; Top-k compress 80.2 -> 78.5 us, no miss in 200 calls either way.)
+// A call whose threshold fell below the filter (a miss: a second streaming pass) resets the margin, keeps it for
+// kHintHoldCalls calls, and caps the halvings below what the margin had been halved to when it missed, one step
+// more being allowed again after every kHintCapCalls calls: a threshold that jitters by more than the tightest margin
+// costs a miss every so many calls, not every few.  cap word: steps taken off kHintShiftMax | calls left << 8.
+__device__ __forceinline__ void margin_after_hit(uint32_t *hint, uint32_t shift, uint32_t hold, uint32_t capw, uint64_t cands, uint64_t k)
+{
+    uint32_t off = capw & 0xFFu, left = capw >> 8;
+    if (left) --left;
+    else if (off) { --off; left = off ? kHintCapCalls : 0u; }
+    const uint32_t cap = kHintShiftMax - (off < kHintShiftMax ? off : kHintShiftMax);
+    if (hold) --hold;
+    else if (cands > 3u * k && shift < cap) ++shift;
+    if (2u * cands < 3u * k && shift) --shift;
+    if (shift > cap) shift = cap;
+    hint[kHintShift] = shift; hint[kHintHold] = hold; hint[kHintCap] = off | (left << 8);
+}
+// below: the threshold fell below the filter (else it rose above the window, which no margin prevents)
+__device__ __forceinline__ void margin_after_miss(uint32_t *hint, uint32_t shift, bool below)
+{
+    hint[kHintShift] = 0u; hint[kHintHold] = kHintHoldCalls;
+    if (below && shift) hint[kHintCap] = (kHintShiftMax - (shift - 1u)) | (kHintCapCalls << 8);
+}
 constexpr uint32_t kModeFast = 1u;      // lo / need are those of level 3 already
 constexpr uint32_t kModeUniform = 2u;   // after a refill: every element is a candidate, chunk c holds 1024 c ...
 constexpr uint32_t kModeLean = 4u;      // fast, and the keys of the threshold's window bin were listed: the emit kernel finishes alone
@@ -418,7 +448,7 @@ __global__ __launch_bounds__(kSeedThreads) void sparse_seed_k(GroupView g, const
     __shared__ uint32_t verdict[6];              // found, bin, rest lo, rest hi, candidates lo, hi
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     // everything the verdict and its record need is asked for up front: one memory latency, not three in a row
-    const uint32_t hint = *sc.hint, hint_shift = sc.hint[kHintShift], hint_hold = sc.hint[kHintHold];
+    const uint32_t hint = *sc.hint, hint_shift = sc.hint[kHintShift], hint_hold = sc.hint[kHintHold], hint_cap = sc.hint[kHintCap];
     uint32_t open = wave == 0 ? sc.hist[kHistOpen + lane] : 0u;
     for (int b = t; b < kBinsW; b += kSeedThreads) {          // the window: the sum of its copies
         uint32_t sum = 0;
@@ -448,23 +478,12 @@ __global__ __launch_bounds__(kSeedThreads) void sparse_seed_k(GroupView g, const
             SelectState s;
             s.lo = hint + (bin << kWindowShift); s.mode = kModeFast; s.need = (uint64_t)verdict[2] | ((uint64_t)verdict[3] << 32);
             sc.sel[0] = s;
-            // How far below the threshold the next call starts filtering.  Under error feedback the values pile up just
-            // below the threshold, in the long run those of every tensor, and a fixed margin lets through many times k
-            // of them (each costs the streaming pass a store and the histogram an add): the margin is halved while the
-            // filter passes more than 3 k (at most four times: 0.8 % below the threshold) and doubled again when it passes fewer
-            // than 1.5 k; a miss resets it (below).  (Measured, every worker on new gradients: 850 000 candidates with three
-            // halvings and 4 k, 533 000 with four and 3 k; Top-k compress 80.2 -> 78.5 us, no miss in 200 calls either way.)
-            const uint64_t cands = (uint64_t)verdict[4] | ((uint64_t)verdict[5] << 32);
-            uint32_t shift = hint_shift, hold = hint_hold;
-            if (hold) --hold;
-            else if (cands > 3u * k && shift < kHintShiftMax) ++shift;
-            if (2u * cands < 3u * k && shift) --shift;
-            sc.hint[kHintShift] = shift; sc.hint[kHintHold] = hold;
+            margin_after_hit(sc.hint, hint_shift, hint_hold, hint_cap, (uint64_t)verdict[4] | ((uint64_t)verdict[5] << 32), k);
         }
         return;
     }
     // missed: the next calls filter with the full margin again, and keep it for a while
-    if (blockIdx.x == 0 && t == 0) { sc.hint[kHintShift] = 0u; sc.hint[kHintHold] = kHintHoldCalls; }
+    if (blockIdx.x == 0 && t == 0) margin_after_miss(sc.hint, hint_shift, !found);
     const uint32_t ntiles = (g.n + (uint32_t)kTile - 1u) / (uint32_t)kTile;
     const uint32_t uwave = __builtin_amdgcn_readfirstlane(wave), waves = kSeedThreads / 64;
     if (found) {
@@ -1277,7 +1296,7 @@ __global__ __launch_bounds__(kSelThreads) void lean_select_k(GroupView g, uint64
     // everything is asked for up front: what there is to know of the tile, the hint record, the window
     TileAhead a0;
     look_ahead(sc, tile, tile < ntiles, a0);
-    const uint32_t hint = *sc.hint, hint_shift = sc.hint[kHintShift], hint_hold = sc.hint[kHintHold];
+    const uint32_t hint = *sc.hint, hint_shift = sc.hint[kHintShift], hint_hold = sc.hint[kHintHold], hint_cap = sc.hint[kHintCap];
     uint32_t open = wave == kSelWaves - 1 ? sc.hist[kHistOpen + lane] : 0u;      // (the wavefront that holds the window's last bin)
     uint2 wsum = {0u, 0u};                       // window bins 2 t and 2 t + 1
 #pragma unroll
@@ -1325,18 +1344,7 @@ __global__ __launch_bounds__(kSelThreads) void lean_select_k(GroupView g, uint64
             SelectState s;
             s.lo = lo; s.mode = kModeFast | (lean ? kModeLean : kModeDense); s.need = (uint64_t)verdict[2] | ((uint64_t)verdict[3] << 32);
             sc.sel[0] = s;
-            // How far below the threshold the next call starts filtering.  Under error feedback the values pile up just
-            // below the threshold, in the long run those of every tensor, and a fixed margin lets through many times k
-            // of them (each costs the streaming pass a store and the histogram an add): the margin is halved while the
-            // filter passes more than 3 k (at most four times: 0.8 % below the threshold) and doubled again when it passes fewer
-            // than 1.5 k; a miss resets it (below).  (Measured, every worker on new gradients: 850 000 candidates with three
-            // halvings and 4 k, 533 000 with four and 3 k; Top-k compress 80.2 -> 78.5 us, no miss in 200 calls either way.)
-            const uint64_t cands = (uint64_t)verdict[4] | ((uint64_t)verdict[5] << 32);
-            uint32_t shift = hint_shift, hold = hint_hold;
-            if (hold) --hold;
-            else if (cands > 3u * k && shift < kHintShiftMax) ++shift;
-            if (2u * cands < 3u * k && shift) --shift;
-            sc.hint[kHintShift] = shift; sc.hint[kHintHold] = hold;
+            margin_after_hit(sc.hint, hint_shift, hint_hold, hint_cap, (uint64_t)verdict[4] | ((uint64_t)verdict[5] << 32), k);
             atomicAdd(&sc.sync[kSyncRoutes + (lean ? MC_SELECT_FAST : MC_SELECT_DENSE)], 1u);
         }
         if (!lean) return;               // dense bin: too many keys to list; the slow-route kernel takes its 2048 keys as a radix level
@@ -1360,7 +1368,7 @@ __global__ __launch_bounds__(kSelThreads) void lean_select_k(GroupView g, uint64
     }
     // missed: the next calls filter with the full margin again, and keep it for a while
     if (first) {
-        sc.hint[kHintShift] = 0u; sc.hint[kHintHold] = kHintHoldCalls;
+        margin_after_miss(sc.hint, hint_shift, !found);
         SelectState s;
         s.lo = found ? hint + (((uint32_t)kBinsW - 1u) << kWindowShift) : 0u; s.mode = found ? 0u : kModeUniform; s.need = k;
         sc.sel[0] = s;

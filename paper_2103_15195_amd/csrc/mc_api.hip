@@ -88,6 +88,7 @@ struct mc_ctx {
     double *d_partial = nullptr;
     SparseScratch sparse{};
     uint32_t *d_hints = nullptr;        // candidate-filter hints: kHintWorkers per group (worker id modulo that)
+    const uint32_t *last_hint = nullptr; // the record the most recent sparse mc_compress used (mc_select_stats)
     int *d_status = nullptr;
     void *static_scratch = nullptr;     // this device's copy of the file-scope scratch array (mc_compress_static)
     std::vector<PtrSlot> slots;
@@ -600,6 +601,7 @@ static int compress_impl(mc_ctx *ctx, int32_t group, uint32_t worker, uint64_t i
         SparseScratch sp = ctx->sparse;
         // a context may compress for several simulated workers whose thresholds differ: each keeps its own hint
         sp.hint = ctx->d_hints + ((size_t)group * kHintWorkers + worker % kHintWorkers) * kHintWords;
+        ctx->last_hint = sp.hint;
         uint32_t stride = 0, first = 0;
         uint64_t need = 0;
         if (cfg.dgc_sample_ppm) {       // sample: every stride-th element from `first`; threshold = its need-th largest key
@@ -727,6 +729,13 @@ int mc_select_stats(mc_ctx *ctx, mc_select_counts *out, int32_t reset)
     for (int r = 0; r < 4; ++r) out->calls[r] = w[r];
     out->last_bin_keys = w[8];
     out->last_candidates = w[9];
+    out->margin_halvings = out->margin_cap = -1;
+    if (ctx->last_hint) {
+        uint32_t h[kHintWords] = {};
+        if (hipMemcpy(h, ctx->last_hint, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return MC_ERR_DEVICE;
+        out->margin_halvings = h[1];
+        out->margin_cap = 4 - (int64_t)std::min<uint32_t>(h[3] & 0xFFu, 4u);
+    }
     if (reset && hipMemset(ctx->sparse.sync + 32, 0, 4 * sizeof(uint32_t)) != hipSuccess) return MC_ERR_DEVICE;
     return MC_OK;
 }

@@ -95,7 +95,7 @@ void launch_state_convert(const LaunchCtx &lc, int algo, bool to_residual, uint3
 
 // ---- sparse kernels (kernels_sparse.hip) ----------------------------------------
 constexpr int kHintWorkers = 64;                         // hints kept per group, one per worker id modulo this
-constexpr int kHintWords = 4;                            // words of a hint record (filter key, margin shift, hold, unused)
+constexpr int kHintWords = 4;                            // words of a hint record (filter key, halvings of the margin, calls it is held after a miss, cap on the halvings)
 constexpr int kWinCopies = 8;                                // copies of the window histogram (a block adds to the copy of its index)
 constexpr int kHistWords = 2048 * kWinCopies + 2048 + 1024 + 2048 + 64;   // bins of the window and of the three radix levels, copies of the window's open bin
 

@@ -490,6 +490,43 @@ def test_a_barrier_that_is_not_passed_is_reported_and_nothing_hangs():
     ctx.close()
 
 
+def test_filter_margin_tightens_and_backs_off_after_a_miss():
+    """The candidate filter starts a margin below the last threshold; the library halves the margin while many more than
+    k elements pass it (here 20 000 values sit 0.3 % below the threshold of k = 4000), down to 0.8 %.  A threshold that
+    then falls by 2 % is missed (a second streaming pass, the result as exact as ever); afterwards the margin may be
+    halved one time less than it had been, for 64 calls.  Every payload is compared with the oracle."""
+    n, tensors, k = 400000, [150000, 250000], 4000
+    ctx = B.Context("topk", tensors, [0, 2], ratio_ppm=10000, use_ef=0, seed=1)
+    ocfg = O.Config(O.TOPK, ratio_ppm=10000, use_ef=0, seed=1)
+    rng = np.random.default_rng(2)
+    g = (rng.standard_normal(n, dtype=np.float32) * np.float32(1e-3)).astype(np.float32)
+    pos = rng.choice(n, k + 20000, replace=False)
+    g[pos[:k]] = (2.0 + rng.random(k)).astype(np.float32)
+    g[pos[k:]] = np.float32(1.994) - rng.random(20000).astype(np.float32) * np.float32(1e-3)
+    pay = torch.zeros(ctx.payload_bytes(0), dtype=torch.uint8, device=H.DEV)
+    it = [0]
+
+    def call(grad):
+        ctx.mc_compress(0, 0, it[0], H.device_tensors(grad, tensors), None, pay)
+        op, _ = O.compress(ocfg, grad, None, group_off=0, worker=0, it=it[0])
+        assert np.array_equal(pay.cpu().numpy(), op), f"call {it[0]}"
+        it[0] += 1
+        s = ctx.mc_select_stats()
+        return ctx.mc_last_select_route(), s["margin_halvings"], s["margin_cap"]
+
+    assert ctx.mc_select_stats()["margin_halvings"] == -1
+    log = [call(g) for _ in range(16)]
+    assert log[-1] == (B.MC_SELECT_FAST, 4, 4), log                       # after the first call's hold: four halvings
+    g2 = (g * np.float32(0.98)).astype(np.float32)
+    assert call(g2) == (B.MC_SELECT_REFILL, 0, 3)                          # the miss: margin back to full, capped one step lower
+    log = [call(g2) for _ in range(30)]
+    assert all(r == B.MC_SELECT_FAST for r, _, _ in log) and max(h for _, h, _ in log) == 3 and log[-1][1:] == (3, 3), log
+    log = [call(g2) for _ in range(50)]                                    # 64 calls after the miss the cap is lifted
+    assert log[-1] == (B.MC_SELECT_FAST, 4, 4), log
+    assert ctx.mc_last_device_status() == B.MC_OK
+    ctx.close()
+
+
 @pytest.mark.parametrize("inbin", [40, 900, 3500])
 def test_long_list_of_keys_in_the_threshold_bin(inbin):
     """The usual route with `inbin` different keys in the threshold's window bin (2048 consecutive keys): the emit kernel
