@@ -306,6 +306,7 @@ def main():
             select_routes[a] = {r: int(s[r]) for r in ("fast", "dense", "above", "refill")}
             select_routes[a]["keys_in_threshold_bin_last_call"] = int(s["last_bin_keys"])
             select_routes[a]["candidates_last_call"] = int(s["last_candidates"])
+            select_routes[a]["filter_margin_halvings_last_call"] = int(s["margin_halvings"])
     kern_us = 1e3 * prof["total_ms"] / prof["launches"]
     n_group = max(benches[dom_algo].ctx.group_numel(j) for j in range(args.y))
     launches_per_step = prof["launches"] / args.steps
