@@ -121,6 +121,12 @@ class AlgoBench:
         self.grad_arr = [[[B.ptr_array(grads[w % len(grads)][v][b[j]:b[j + 1]]) for j in range(y)] for v in range(self.V)] for w in range(W)]
         self.out_arr = [B.ptr_array(self.outs[b[j]:b[j + 1]]) for j in range(y)]
         self.pay_arr = [(B.ptr_array([self.pay[w][j] for w in range(W)]), W) for j in range(y)]
+        # ... and for the calls that take all groups at once
+        self.grad_all = [[B.ptr_array(grads[w % len(grads)][v]) for v in range(self.V)] for w in range(W)]
+        self.state_all = [B.ptr_array(self.state[w]) for w in range(W)] if self.ctx.cfg.use_ef else [None] * W
+        self.pay_of = [B.ptr_array(self.pay[w]) for w in range(W)]
+        self.pay_all = B.ptr_array([self.pay[w][j] for w in range(W) for j in range(y)])
+        self.out_all = B.ptr_array(self.outs)
         self.it = 0
         self.turn = [0] * W            # how many gradients each worker has compressed: it takes number turn % V next
         # Every worker has a payload before the first decompress.  The sparsifiers also leave their start-up
@@ -140,6 +146,15 @@ class AlgoBench:
     def decompress(self):
         for j in range(self.y):
             self.ctx.mc_decompress_sum(j, self.pay_arr[j][0], 1.0, self.out_arr[j])
+
+    def compress_groups(self, w):
+        v = self.turn[w] % self.V
+        self.turn[w] += 1
+        self.it += 1
+        self.ctx.mc_compress_groups(w, self.it, self.grad_all[w][v], self.state_all[w], self.pay_of[w])
+
+    def decompress_groups(self):
+        self.ctx.mc_decompress_sum_groups(self.pay_all, self.W, 1.0, self.out_all)
 
     def step(self, i):
         self.compress(i % self.W)
@@ -262,8 +277,15 @@ def main():
             fl = [np.random.default_rng([77, w, v]).standard_normal(int(D), dtype=np.float32) * np.float32(0.01) for v in range(V)]
             grads_even.append(device_grads(torch, fl, numel, "separate"))
 
+    grads_shared = None
+    if any(a.endswith("-shared") for a in algos):
+        # half of every worker's gradient is a component common to all workers: their kept indices then largely coincide
+        # (the decompress-sum adds up to W values into the same element instead of W different ones)
+        grads_shared = [device_grads(torch, [WL.gradients_flat(wl, w, v, shared_fraction=0.5) for v in range(V)], numel, "separate")
+                        for w in range(W)]
+
     def grads_for(a):
-        return grads_even if a.endswith("-even") else grads
+        return grads_even if a.endswith("-even") else grads_shared if a.endswith("-shared") else grads
     benches = {a: AlgoBench(B, torch, a, numel, args.y, W, grads_for(a)) for a in algos}
 
     def step(i):
@@ -421,17 +443,22 @@ def main():
                 lb.compress(i % W)
             tc = timed(torch, lambda i: lb.compress(i % W), 10)
             td = timed(torch, lambda i: lb.decompress(), 10)
+            # the same 161 compressions / decompressions looped over inside the library: no Python between them
+            tcg = timed(torch, lambda i: lb.compress_groups(i % W), 10)
+            tdg = timed(torch, lambda i: lb.decompress_groups(), 10)
             lb.close()
             del lb
             torch.cuda.empty_cache()
             merged = per_algo[a]["compress_us"] + per_algo[a]["decompress_sum_us"]
             layerwise[a] = {"groups": N, "compress_us": tc * 1e6, "decompress_sum_us": td * 1e6,
-                            "merged_over_layerwise_speedup": (tc + td) * 1e6 / merged}
+                            "merged_over_layerwise_speedup": (tc + td) * 1e6 / merged,
+                            "looped_in_the_library": {"compress_us": tcg * 1e6, "decompress_sum_us": tdg * 1e6,
+                                                      "merged_over_layerwise_speedup": (tcg + tdg) * 1e6 / merged}}
 
     for b in benches.values():
         b.close()
     benches.clear()
-    del grads, grads_even
+    del grads, grads_even, grads_shared
     torch.cuda.empty_cache()
 
     # ---- the other two large configurations: ResNet-101 with W = 16, Mask R-CNN with W = 8 --------------------------------

@@ -249,6 +249,22 @@ int mc_decompress_sum(mc_ctx *ctx, int32_t group, const void *const *payloads, i
                       float *const *out_ptrs, void *stream);
 
 /*
+ * The loops of Algorithm 1 over all groups of the context in one call each, in group order, for a caller whose
+ * gradients are all there already (no overlap with back-propagation) -- the same kernels as y calls of
+ * mc_compress / mc_decompress_sum, without y trips through the caller's language binding.
+ *   grad_ptrs_all  host array, one DEVICE pointer per tensor of the MODEL (the list given to mc_ctx_create)
+ *   states         host array of y DEVICE pointers, states[j] as `state` of mc_compress for group j (NULL when use_ef = 0)
+ *   payloads_out   host array of y DEVICE pointers, payloads_out[j] receives group j's payload
+ *   payloads       host array of W * y DEVICE pointers: payloads[w * y + j] is worker w's payload of group j
+ *   out_ptrs_all   host array, one DEVICE pointer per tensor of the model
+ * Stops at the first group that returns an error and returns it.
+ */
+int mc_compress_groups(mc_ctx *ctx, uint32_t worker, uint64_t iter, const float *const *grad_ptrs_all, void *const *states,
+                       void *const *payloads_out, void *stream);
+int mc_decompress_sum_groups(mc_ctx *ctx, const void *const *payloads, int32_t W, float alpha, float *const *out_ptrs_all,
+                             void *stream);
+
+/*
  * Convert between the opaque state and plain error-feedback memory
  * (n floats e; DGC: v[n] then u[n]), both DEVICE pointers.  Import of a residual
  * followed by export returns the same bits.

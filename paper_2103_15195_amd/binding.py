@@ -26,7 +26,7 @@ EXPORTS = [
     "mc_partition", "mc_partition_cost", "mc_partition_search", "mc_ctx_create", "mc_ctx_destroy", "mc_group_numel", "mc_group_k", "mc_group_tensors",
     "mc_payload_bytes", "mc_state_bytes", "mc_compress", "mc_compress_static", "mc_static_scratch_bytes", "mc_static_max_elems",
     "mc_decompress_sum", "mc_state_export_residual",
-    "mc_state_import_residual", "mc_last_device_status", "mc_last_select_route", "mc_select_stats", "mc_set_barrier_spin_limit", "mc_profile_enable", "mc_profile_select", "mc_profile_reset",
+    "mc_state_import_residual", "mc_last_device_status", "mc_last_select_route", "mc_select_stats", "mc_set_barrier_spin_limit", "mc_compress_groups", "mc_decompress_sum_groups", "mc_profile_enable", "mc_profile_select", "mc_profile_reset",
     "mc_profile_kernels", "mc_profile_read", "mc_strerror", "mc_version",
 ]
 
@@ -90,6 +90,8 @@ def lib():
         L.mc_last_device_status.argtypes = [vp]
         L.mc_last_select_route.argtypes = [vp]
         L.mc_select_stats.argtypes = [vp, C.POINTER(McSelectCounts), i32]
+        L.mc_compress_groups.argtypes = [vp, C.c_uint32, C.c_uint64, vp, vp, vp, vp]
+        L.mc_decompress_sum_groups.argtypes = [vp, vp, i32, C.c_float, vp, vp]
         L.mc_set_barrier_spin_limit.argtypes = [vp, C.c_uint32]
         L.mc_profile_enable.argtypes = [vp, i32]
         L.mc_profile_select.argtypes = [vp, u64]
@@ -224,6 +226,17 @@ class Context:
                                        _stream_handle(stream)), "mc_decompress_sum")
 
     # state helpers --------------------------------------------------------------
+    def mc_compress_groups(self, worker: int, it: int, grads_all, states, payloads, stream=None) -> None:
+        """All groups of one worker in one call; tensor sequences (or ptr_array()s of them): the model's gradients,
+        one state and one payload per group."""
+        _check(lib().mc_compress_groups(self._h, worker, it, ptr_array(grads_all), None if states is None else ptr_array(states),
+                                        ptr_array(payloads), _stream_handle(stream)), "mc_compress_groups")
+
+    def mc_decompress_sum_groups(self, payloads, W: int, alpha: float, outs_all, stream=None) -> None:
+        """payloads: W * y entries, worker-major (payloads[w * y + j])."""
+        _check(lib().mc_decompress_sum_groups(self._h, ptr_array(payloads), W, alpha, ptr_array(outs_all), _stream_handle(stream)),
+               "mc_decompress_sum_groups")
+
     def mc_state_export_residual(self, group: int, state, e_out, stream=None) -> None:
         _check(lib().mc_state_export_residual(self._h, group, state.data_ptr(), e_out.data_ptr(),
                                               _stream_handle(stream)), "mc_state_export_residual")

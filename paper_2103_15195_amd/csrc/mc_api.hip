@@ -671,6 +671,33 @@ int mc_decompress_sum(mc_ctx *ctx, int32_t group, const void *const *payloads, i
     return check_launch();
 }
 
+int mc_compress_groups(mc_ctx *ctx, uint32_t worker, uint64_t iter, const float *const *grad_ptrs_all, void *const *states,
+                       void *const *payloads_out, void *stream)
+{
+    if (!ctx || !payloads_out || (ctx->cfg.use_ef && !states)) return MC_ERR_INVALID_ARG;
+    for (size_t j = 0; j < ctx->groups.size(); ++j) {
+        const Group &G = ctx->groups[j];
+        const int rc = compress_impl(ctx, (int32_t)j, worker, iter, grad_ptrs_all ? grad_ptrs_all + G.t0 : nullptr, states ? states[j] : nullptr,
+                                     payloads_out[j], stream, ctx->d_partial, &ctx->prof);
+        if (rc != MC_OK) return rc;
+    }
+    return MC_OK;
+}
+
+int mc_decompress_sum_groups(mc_ctx *ctx, const void *const *payloads, int32_t W, float alpha, float *const *out_ptrs_all, void *stream)
+{
+    if (!ctx || !payloads || W < 1) return MC_ERR_INVALID_ARG;
+    if (W > kMaxWorkers) return MC_ERR_RANGE;
+    const size_t y = ctx->groups.size();
+    const void *one[kMaxWorkers];
+    for (size_t j = 0; j < y; ++j) {
+        for (int32_t w = 0; w < W; ++w) one[w] = payloads[(size_t)w * y + j];
+        const int rc = mc_decompress_sum(ctx, (int32_t)j, one, W, alpha, out_ptrs_all ? out_ptrs_all + ctx->groups[j].t0 : nullptr, stream);
+        if (rc != MC_OK) return rc;
+    }
+    return MC_OK;
+}
+
 static int state_convert(mc_ctx *ctx, int32_t group, const void *src, void *dst, bool to_residual, void *stream)
 {
     const Group *g = group_of(ctx, group);

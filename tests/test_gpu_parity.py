@@ -314,6 +314,39 @@ def test_state_calls_on_a_stateless_algorithm_touch_nothing():
     ctx.close()
 
 
+@pytest.mark.parametrize("algo", ["efsign", "topk", "qsgd", "signsgd"])
+def test_all_groups_in_one_call(algo):
+    """mc_compress_groups / mc_decompress_sum_groups are the loops over the groups: same payloads, states and sums as
+    one call per group (which the other tests compare with the oracle)."""
+    numel = [3000, 17, 0, 5000, 1200, 64, 7000]
+    y, W = 3, 2
+    bounds = B.mc_partition(numel, y)
+    ctx = B.Context(algo, numel, bounds, ratio_ppm=20000, seed=5)
+    ef = algo != "signsgd"
+    rng = np.random.default_rng(8)
+    flats = [rng.standard_normal(sum(numel)).astype(np.float32) for _ in range(W)]
+    grads = [H.device_tensors(f, numel) for f in flats]
+    new = lambda fn: [[torch.zeros(fn(j), dtype=torch.uint8, device=H.DEV) for j in range(y)] for _ in range(W)]
+    st_a, st_b, pay_a, pay_b = new(ctx.state_bytes), new(ctx.state_bytes), new(ctx.payload_bytes), new(ctx.payload_bytes)
+    for it in range(2):
+        for w in range(W):
+            for j in range(y):
+                ctx.mc_compress(j, w, it, grads[w][bounds[j]:bounds[j + 1]], st_a[w][j] if ef else None, pay_a[w][j])
+            ctx.mc_compress_groups(w, it, grads[w], st_b[w] if ef else None, pay_b[w])
+    for w in range(W):
+        for j in range(y):
+            assert torch.equal(pay_a[w][j], pay_b[w][j]) and torch.equal(st_a[w][j], st_b[w][j]), (w, j)
+    out_a, out_b = H.empty_like_list(grads[0]), H.empty_like_list(grads[0])
+    for j in range(y):
+        ctx.mc_decompress_sum(j, [pay_a[w][j] for w in range(W)], 0.5, out_a[bounds[j]:bounds[j + 1]])
+    ctx.mc_decompress_sum_groups([pay_b[w][j] for w in range(W) for j in range(y)], W, 0.5, out_b)
+    assert H.same_bits(H.gather_flat(out_a), H.gather_flat(out_b))
+    assert ctx.mc_last_device_status() == B.MC_OK
+    with pytest.raises(B.McError):
+        ctx.mc_decompress_sum_groups([pay_b[0][0]] * (65 * y), 65, 1.0, out_b)
+    ctx.close()
+
+
 def test_more_address_lists_than_the_context_caches():
     """A context keeps device copies of the tensor-address lists it has seen (256 of them); 300 different lists, then the
     first ones again: every call must read the tensors it was given, also after its list's copy was replaced."""
