@@ -76,10 +76,11 @@ constexpr uint32_t kHintCapCalls = 64u;
 // How far below the threshold the next call starts filtering, after a call whose threshold lay inside the window.
 // Under error feedback the values pile up just below the threshold, in the long run those of every tensor, and a fixed
 // margin lets through many times k of them (each costs the streaming pass a store and the histogram an add): the
-// margin is halved while the filter passes more than 3 k (at most four times: 0.8 % below the threshold) and doubled
-// again when it passes fewer than 1.5 k.  (Measured, every worker on new gradients: with "more than 4 k" the bench's
-// Top-k stayed at the full margin, 12 %, and 850 000 candidates; with 3 k it settles at one halving, 6 %, and 533 000:
-// compress 80.2 -> 78.5 us, no miss in 200 calls either way.)
+// margin is halved while the filter passes more than 2 k (at most four times: 0.8 % below the threshold) and doubled
+// again when it passes fewer than 1.25 k.  (Measured, every worker on new gradients: with "more than 4 k" the bench's
+// Top-k stayed at the full margin, 12 %, and 850 000 candidates; with 3 k it settles at one halving and 533 000,
+// with 2 k at two, 3 %, and 396 000: Top-k compress went 80.2 -> 78.5 us with the second rule and 77.0 -> 75.5 us
+// with the third, no miss in 200 calls with any of them.)
 // A call whose threshold fell below the filter (a miss: a second streaming pass) resets the margin, keeps it for
 // kHintHoldCalls calls, and caps the halvings below what the margin had been halved to when it missed, one step
 // more being allowed again after every kHintCapCalls calls: a threshold that jitters by more than the tightest margin
@@ -91,8 +92,8 @@ __device__ __forceinline__ void margin_after_hit(uint32_t *hint, uint32_t shift,
     else if (off) { --off; left = off ? kHintCapCalls : 0u; }
     const uint32_t cap = kHintShiftMax - (off < kHintShiftMax ? off : kHintShiftMax);
     if (hold) --hold;
-    else if (cands > 3u * k && shift < cap) ++shift;
-    if (2u * cands < 3u * k && shift) --shift;
+    else if (cands > 2u * k && shift < cap) ++shift;
+    if (4u * cands < 5u * k && shift) --shift;
     if (shift > cap) shift = cap;
     hint[kHintShift] = shift; hint[kHintHold] = hold; hint[kHintCap] = off | (left << 8);
 }
